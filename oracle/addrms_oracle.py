@@ -1,0 +1,161 @@
+"""ctypes front end of the plain C oracle in ``addrms_oracle.c``.
+
+Test infrastructure only (see the header of the C file).  The wrapper does no
+arithmetic of the method: it compiles the C file with gcc when the shared
+object is missing or older than the source, marshals numpy arrays, and calls
+it.  16-bit formats travel as raw ``uint16`` bit patterns, fp32 as ``float32``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+BF16, FP16, FP16_RES32, FP32 = 0, 1, 2, 3
+VARIANTS = {"canonical": 0, "seq32": 1, "pair32": 2}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "addrms_oracle.c")
+_LIB = os.path.join(_HERE, "libaddrms_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no contraction, no fast-math)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+             "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"],
+            check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            lib = ctypes.CDLL(build())
+            vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+            lib.oracle_addrms.argtypes = [vp, vp, vp, ctypes.c_float, i64, i64, ci, ci, vp, vp, vp, ci]
+            lib.oracle_addrms.restype = ci
+            lib.oracle_addrms_y64.argtypes = [vp, vp, vp, ctypes.c_double, i64, i64, ci, vp]
+            lib.oracle_addrms_y64.restype = ci
+            lib.oracle_rstd_canonical.argtypes = [ctypes.c_double, i64, ctypes.c_float]
+            lib.oracle_rstd_canonical.restype = ctypes.c_float
+            lib.oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
+            lib.oracle_bf16_to_f32.restype = ctypes.c_float
+            lib.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
+            lib.oracle_f16_to_f32.restype = ctypes.c_float
+            lib.oracle_f32_to_bf16.argtypes = [ctypes.c_float]
+            lib.oracle_f32_to_bf16.restype = ctypes.c_uint16
+            lib.oracle_f32_to_f16.argtypes = [ctypes.c_float]
+            lib.oracle_f32_to_f16.restype = ctypes.c_uint16
+            for name in ("oracle_f32_to_bf16_array", "oracle_f32_to_f16_array",
+                         "oracle_bf16_to_f32_array", "oracle_f16_to_f32_array"):
+                getattr(lib, name).argtypes = [vp, vp, i64]
+                getattr(lib, name).restype = None
+            _lib = lib
+    return _lib
+
+
+def _x_np(dtype: int):
+    return np.float32 if dtype == FP32 else np.uint16
+
+
+def _r_np(dtype: int):
+    return np.float32 if dtype in (FP32, FP16_RES32) else np.uint16
+
+
+def _check(a: np.ndarray, want, shape, name: str) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != want:
+        raise TypeError(f"{name}: expected {np.dtype(want)}, got {a.dtype}")
+    if tuple(a.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {shape}, got {a.shape}")
+    return a
+
+
+def addrms(x, r, w, eps: float, dtype: int, variant: str = "canonical",
+           nthreads: int = 1, return_rstd: bool = False):
+    """Run the oracle.  Returns ``(y, residual_out)`` (and ``rstd`` if asked).
+
+    x, r: [M, N]; w: [N].  uint16 bit patterns for bf16/fp16 tensors, float32
+    for fp32 tensors (the residual of FP16_RES32, everything of FP32).
+    """
+    M, N = x.shape
+    x = _check(x, _x_np(dtype), (M, N), "x")
+    r = _check(r, _r_np(dtype), (M, N), "r")
+    w = _check(w, _x_np(dtype), (N,), "w")
+    y = np.empty((M, N), dtype=_x_np(dtype))
+    res = np.empty((M, N), dtype=_r_np(dtype))
+    rstd = np.empty((M,), dtype=np.float32)
+    rc = _load().oracle_addrms(
+        x.ctypes.data, r.ctypes.data, w.ctypes.data, float(eps), M, N, dtype,
+        VARIANTS[variant], y.ctypes.data, res.ctypes.data, rstd.ctypes.data, int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"oracle_addrms failed with {rc}")
+    return (y, res, rstd) if return_rstd else (y, res)
+
+
+def addrms_y64(x, r, w, eps: float, dtype: int) -> np.ndarray:
+    """Unrounded fp64 evaluation h*w/sqrt(mean(h^2)+eps) with h = x + r."""
+    M, N = x.shape
+    x = _check(x, _x_np(dtype), (M, N), "x")
+    r = _check(r, _r_np(dtype), (M, N), "r")
+    w = _check(w, _x_np(dtype), (N,), "w")
+    y64 = np.empty((M, N), dtype=np.float64)
+    rc = _load().oracle_addrms_y64(x.ctypes.data, r.ctypes.data, w.ctypes.data,
+                                   float(eps), M, N, dtype, y64.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_addrms_y64 failed with {rc}")
+    return y64
+
+
+def rstd_canonical(ss: float, N: int, eps: float) -> np.float32:
+    return np.float32(_load().oracle_rstd_canonical(float(ss), int(N), float(eps)))
+
+
+def _convert(name: str, a: np.ndarray, src, dst) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=src)
+    out = np.empty(a.shape, dtype=dst)
+    getattr(_load(), name)(a.ctypes.data, out.ctypes.data, a.size)
+    return out
+
+
+def f32_to_bf16_array(a):
+    return _convert("oracle_f32_to_bf16_array", a, np.float32, np.uint16)
+
+
+def f32_to_f16_array(a):
+    return _convert("oracle_f32_to_f16_array", a, np.float32, np.uint16)
+
+
+def bf16_to_f32_array(a):
+    return _convert("oracle_bf16_to_f32_array", a, np.uint16, np.float32)
+
+
+def f16_to_f32_array(a):
+    return _convert("oracle_f16_to_f32_array", a, np.uint16, np.float32)
+
+
+def bf16_to_f32(b: int) -> np.float32:
+    return np.float32(_load().oracle_bf16_to_f32(int(b)))
+
+
+def f16_to_f32(b: int) -> np.float32:
+    return np.float32(_load().oracle_f16_to_f32(int(b)))
+
+
+def f32_to_bf16(f) -> int:
+    return int(_load().oracle_f32_to_bf16(float(np.float32(f))))
+
+
+def f32_to_f16(f) -> int:
+    return int(_load().oracle_f32_to_f16(float(np.float32(f))))
