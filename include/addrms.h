@@ -1,0 +1,233 @@
+/*
+ * addrms -- fused residual-add + RMSNorm for AMD MI355X (gfx950), with the
+ * paper's two-stage tuner: an explicitly parameterised kernel template, a
+ * feasible-region deriver built on the hardware's resource limits, and a
+ * measured search over that region (Algorithm 1, Level 2; Section 3.3).
+ *
+ * C ABI.  Every function returns 0 (ADDRMS_OK) or a negative addrms_status;
+ * a message for the last failure on the calling thread is available from
+ * addrms_last_error().  No exception crosses this boundary.
+ *
+ * Pointer kinds are stated per argument: "device" = HIP device memory owned by
+ * the caller; "host" = ordinary host memory owned by the caller.  The library
+ * owns its compiled kernels, the configuration table and the error string.
+ *
+ * The operator (Section 4, "Kernels": fused_add_rmsnorm), per row of N elements:
+ *     h        = f32(x) + f32(residual)                    (one fp32 add)
+ *     residual <- round_nearest_even(h -> residual dtype)  (in place)
+ *     rstd     = fp32( 1 / sqrt( sum(h^2)/N + eps ) )      (sum of squares in fp64)
+ *     x        <- round_nearest_even((h*rstd)*f32(weight) -> x dtype)  (in place)
+ * Results do not depend on the configuration used to run it.
+ */
+#ifndef ADDRMS_H
+#define ADDRMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADDRMS_VERSION_STRING "0.1.0"
+
+/* ---- status codes ------------------------------------------------------- */
+typedef enum addrms_status {
+    ADDRMS_OK = 0,
+    ADDRMS_ERR_INVALID_ARG = -1,       /* null pointer, N <= 0, M < 0, bad enum, bad struct field */
+    ADDRMS_ERR_UNSUPPORTED_DTYPE = -2,
+    ADDRMS_ERR_INFEASIBLE_CFG = -3,    /* cfg outside the feasible region for (M, N, dtype) */
+    ADDRMS_ERR_MISALIGNED = -4,        /* a tensor base is not aligned to cfg's vector width */
+    ADDRMS_ERR_HIP = -5,               /* a HIP runtime call failed; text has the HIP error */
+    ADDRMS_ERR_IO = -6,                /* table/log file could not be read or written, or is malformed */
+    ADDRMS_ERR_NO_RESULT = -7,         /* budget ran out before any candidate was measured */
+    ADDRMS_ERR_UNSUPPORTED_SHAPE = -8  /* no configuration of the template covers this N */
+} addrms_status;
+
+/* ---- storage formats ----------------------------------------------------- */
+typedef enum addrms_dtype {
+    ADDRMS_BF16 = 0,        /* x, residual, weight: bfloat16                       */
+    ADDRMS_FP16 = 1,        /* x, residual, weight: IEEE binary16                  */
+    ADDRMS_FP16_RES32 = 2,  /* x, weight: binary16; residual stream: fp32          */
+    ADDRMS_FP32 = 3         /* x, residual, weight: fp32 (the paper's fp32 shapes) */
+} addrms_dtype;
+
+/* ---- the searchable parameter vector theta (Algorithm 1, Input) ------------ */
+enum { ADDRMS_REDUCE_WAVE = 0,   /* wave64 cross-lane butterfly, one LDS hop across waves */
+       ADDRMS_REDUCE_LDS = 1 };  /* LDS-staged tree reduction                             */
+enum { ADDRMS_FLAG_XCD_CONTIG = 1 };  /* workgroups of one XCD cover a contiguous row range */
+
+typedef struct addrms_cfg {
+    int32_t vec;              /* elements per thread per vector access: 1, 2, 4, 8        */
+    int32_t threads_per_row;  /* 8, 16, 32, or a multiple of 64 up to 1024                */
+    int32_t rows_per_wg;      /* 1, 2, 4, 8, 16; threads_per_row*rows_per_wg <= 1024      */
+    int32_t reduce;           /* ADDRMS_REDUCE_*                                          */
+    int32_t unroll;           /* 1, 2, 4, 8: chunks whose loads are in flight together    */
+    int32_t flags;            /* ADDRMS_FLAG_* bits                                       */
+    int32_t reserved[2];      /* must be 0                                                */
+} addrms_cfg;
+
+/* ---- run ------------------------------------------------------------------
+ * addrms_run: one launch of the operator, in place, asynchronous on `stream`.
+ *   x        device, [M, N] row-major (row stride N), x dtype.   in: x, out: y
+ *   residual device, [M, N] row-major, residual dtype.            in: r, out: round(x+r)
+ *   weight   device, [N], x dtype, read only
+ *   eps      added to the mean of squares
+ *   M, N     rows, row length.  M == 0 is a successful no-op; N <= 0 is INVALID_ARG
+ *   dtype    addrms_dtype
+ *   cfg      host; NULL = look (M, N, dtype) up in the specialised table
+ *            (nearest tuned M for the same N and dtype), else the default cfg
+ *   stream   a hipStream_t passed as void*; NULL = the default stream
+ * Never synchronises, never allocates device memory.  Arguments are checked
+ * before anything is launched (Section 3.3: invalid launches are pruned, not
+ * attempted).  x, residual and weight must not overlap.  Re-entrant.
+ */
+int addrms_run(void* x, void* residual, const void* weight, float eps,
+               int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, void* stream);
+
+/* The single untuned default configuration for (N, dtype): widest vector the
+ * row length admits, 256 threads per row where the template covers N with
+ * that, one row per workgroup, wave reduction. out: host. */
+int addrms_default_cfg(int64_t N, int dtype, addrms_cfg* out);
+
+/* ---- feasible region (Algorithm 1 line 18, DeriveFeasibleSpace; Section 3.3) */
+
+/* Resources of the kernel instance a cfg selects, read back from the compiler
+ * when the library was built, plus what the launch shape implies on one CU. */
+typedef struct addrms_resources {
+    int32_t chunks_per_thread;  /* ceil(N / (vec * threads_per_row))                   */
+    int32_t vgprs;              /* architected vector registers per lane               */
+    int32_t agprs;              /* accumulation registers per lane (same 512-entry file)*/
+    int32_t sgprs;
+    int32_t scratch_bytes;      /* per lane; nonzero means spills and is rejected      */
+    int32_t lds_bytes;          /* per workgroup for this launch shape                 */
+    int32_t max_threads;        /* workgroup-size bound the instance was compiled for  */
+    int32_t waves_per_wg;
+    int32_t waves_per_simd_regs;/* min(8, 512 / ceil8(vgprs + agprs))                  */
+    int32_t wgs_per_cu;         /* resident workgroups per CU (registers, LDS, slots)  */
+    int32_t waves_per_simd;     /* achieved = wgs_per_cu * waves_per_wg / 4 (rounded up)*/
+    int32_t reserved[5];
+} addrms_resources;
+
+/* 0 if cfg is in the feasible region for (M, N, dtype), else ADDRMS_ERR_INFEASIBLE_CFG
+ * (or INVALID_ARG / UNSUPPORTED_DTYPE).  `reason` (host, may be NULL) receives a
+ * NUL-terminated constraint rationale, truncated to reason_len.  `res` (host, may be
+ * NULL) receives the resources when the cfg got as far as selecting an instance. */
+int addrms_cfg_feasible(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype,
+                        char* reason, size_t reason_len, addrms_resources* res);
+
+/* Writes up to `cap` feasible cfgs into `out` (host, may be NULL when cap == 0)
+ * and returns how many exist (>= 0), or a negative status.  `n_grid` (host, may be
+ * NULL) receives the size of the knob grid that was pruned. Order is deterministic. */
+int64_t addrms_enumerate_feasible(int64_t M, int64_t N, int dtype,
+                                  addrms_cfg* out, int64_t cap, int64_t* n_grid);
+
+/* ---- search (Algorithm 1 lines 19-23: Search, BuildSpecialized) -------------- */
+enum { ADDRMS_SEARCH_GUIDED = 0, ADDRMS_SEARCH_EXHAUSTIVE = 1 };
+
+typedef struct addrms_budget {
+    double  max_wall_ms;     /* 0 = unlimited                                              */
+    int32_t max_candidates;  /* distinct cfgs that may be measured; 0 = unlimited          */
+    int32_t strategy;        /* ADDRMS_SEARCH_*                                            */
+    int32_t top_k;           /* candidates re-tested at the end; 0 = 5 (max 8)             */
+    int32_t warmup;          /* confirmation protocol; 0 = 20 (Section 4, "Performance     */
+    int32_t reps;            /*   Measurement": 20 warm-up runs, mean of 100); 0 = 100     */
+    int32_t coarse_warmup;   /* screening protocol of the guided search; 0 = 3             */
+    int32_t coarse_reps;     /* 0 = 15                                                     */
+    int32_t skip_validation; /* nonzero: do not gate candidates on correctness (tests only)*/
+    float   eps;             /* eps used for the tuning launches; 0 = 1e-6                 */
+    int32_t reserved0;
+    const char* log_path;    /* host; JSON-lines log of every candidate; NULL = none       */
+} addrms_budget;
+
+#define ADDRMS_MAX_TOPK 8
+typedef struct addrms_tune_report {
+    int64_t n_grid;          /* knob-grid points examined by the deriver                   */
+    int64_t n_feasible;      /* size of the feasible region                                */
+    int64_t n_measured;      /* distinct cfgs timed                                        */
+    int64_t n_failed;        /* cfgs that failed the correctness gate or a launch          */
+    int64_t best_found_at;   /* 1-based count of measured cfgs when the winner first ran   */
+    double  best_us;         /* confirmed mean time of the returned cfg                    */
+    double  default_us;      /* confirmed mean time of the default cfg                     */
+    double  wall_ms;         /* whole call                                                 */
+    double  time_to_best_ms; /* wall time until the winner was first measured              */
+    addrms_cfg best;
+    addrms_cfg default_cfg;
+    int32_t n_topk;
+    int32_t reserved0;
+    addrms_cfg topk[ADDRMS_MAX_TOPK];    /* confirmed candidates, fastest first            */
+    double  topk_us[ADDRMS_MAX_TOPK];
+} addrms_tune_report;
+
+/* addrms_tune: derive the feasible region for (M, N, dtype), search it on the
+ * current HIP device with measured kernel time, gate every candidate on
+ * agreement with the default configuration's output (bit-exact residual,
+ * y within 1 unit in the last place), re-test the Top-K with the confirmation
+ * protocol, store the winner in the specialised table and return it.
+ * Blocking.  Allocates and frees its own device buffers (rotated so that the
+ * timed launches stream from HBM rather than from cache).
+ *   budget  host, may be NULL (all defaults)
+ *   out_cfg host, required;  report host, may be NULL
+ */
+int addrms_tune(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
+                addrms_cfg* out_cfg, addrms_tune_report* report);
+
+/* The same search driven by caller-supplied measurement, so that its logic can
+ * be exercised without a GPU.  measure returns 0 and a time in microseconds, or
+ * nonzero if the candidate could not be run; validate returns 0 if the
+ * candidate's output is acceptable.  Does not touch the specialised table. */
+typedef struct addrms_backend {
+    void* user;
+    int (*validate)(void* user, const addrms_cfg* cfg);
+    int (*measure)(void* user, const addrms_cfg* cfg, int warmup, int reps, double* mean_us);
+} addrms_backend;
+
+int addrms_tune_with_backend(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
+                             const addrms_backend* backend,
+                             addrms_cfg* out_cfg, addrms_tune_report* report);
+
+/* addrms_measure: mean time in microseconds of `cfg` (NULL = table/default, as
+ * in addrms_run) on (M, N, dtype) over `reps` launches after `warmup`, on
+ * library-allocated synthetic buffers.  rotate != 0 cycles through enough
+ * buffer sets to exceed the last-level caches; rotate == 0 reuses one set
+ * (a cache-warm figure).  Blocking; allocates and frees device memory. */
+int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps,
+                   int warmup, int reps, int rotate, double* mean_us);
+
+/* ---- specialised table D_spec: (dtype, N, M) -> cfg (Algorithm 1 line 23) ---- */
+int addrms_table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, double mean_us);
+/* Exact (dtype, N, M) entry if present, else the entry of the same (dtype, N)
+ * whose M is nearest in ratio and whose cfg is feasible for the asked M.
+ * Returns 0 and fills out (host), or ADDRMS_ERR_NO_RESULT. */
+int addrms_table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out);
+int64_t addrms_table_size(void);
+void addrms_table_clear(void);
+/* Text file, one entry per line.  load replaces nothing on failure: a missing
+ * or malformed file returns ADDRMS_ERR_IO and leaves the table as it was. */
+int addrms_table_save(const char* path);
+int addrms_table_load(const char* path);
+
+/* ---- probes used by tests and by the measurement report ------------------- */
+
+/* rstd for each of n sums of squares: out[i] = fp32(1/sqrt(ss[i]/N + eps)),
+ * computed by the same device routine the kernel uses.  ss: device, fp64[n];
+ * out: device, fp32[n].  Asynchronous on stream. */
+int addrms_rstd_probe(const double* ss, int64_t n, int64_t N, float eps, float* out, void* stream);
+
+/* Calibration kernel with the operator's traffic and none of its arithmetic:
+ * reads [M,N] of x and of residual and writes both back (bitwise complemented),
+ * 16 bytes per lane.  Same argument meaning as addrms_run. */
+int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype, void* stream);
+
+/* Bytes the operator must move for (M, N, dtype): every x and residual element
+ * read once and written once, weight read once.  Negative on bad arguments. */
+int64_t addrms_algorithmic_bytes(int64_t M, int64_t N, int dtype);
+
+/* Static storage owned by the library; valid until the thread's next failing call. */
+const char* addrms_last_error(void);
+const char* addrms_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADDRMS_H */

@@ -1,0 +1,320 @@
+"""ctypes binding of ``libaddrms.so`` -- argument marshalling only.
+
+Every function here has the name of the C entry point it calls
+(``include/addrms.h``); no step of the operator, the deriver or the search is
+computed in Python.  Tensors are torch tensors used purely as device memory;
+``stream`` defaults to torch's current stream on the tensor's device.
+
+The library is loaded on first use.  If it has not been built the call raises
+:class:`AddrmsLibraryMissing` -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import (CFUNCTYPE, POINTER, Structure, byref, c_char_p, c_double, c_float, c_int, c_int32,
+                    c_int64, c_size_t, c_void_p)
+from typing import List, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaddrms.so")
+
+BF16, FP16, FP16_RES32, FP32 = 0, 1, 2, 3
+DTYPE_IDS = {"bf16": BF16, "fp16": FP16, "fp16_res32": FP16_RES32, "fp32": FP32}
+REDUCE_WAVE, REDUCE_LDS = 0, 1
+FLAG_XCD_CONTIG = 1
+SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
+MAX_TOPK = 8
+
+OK = 0
+ERR_INVALID_ARG, ERR_UNSUPPORTED_DTYPE, ERR_INFEASIBLE_CFG, ERR_MISALIGNED = -1, -2, -3, -4
+ERR_HIP, ERR_IO, ERR_NO_RESULT, ERR_UNSUPPORTED_SHAPE = -5, -6, -7, -8
+
+
+class AddrmsLibraryMissing(RuntimeError):
+    pass
+
+
+class AddrmsError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"addrms status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+class Cfg(Structure):
+    _fields_ = [("vec", c_int32), ("threads_per_row", c_int32), ("rows_per_wg", c_int32),
+                ("reduce", c_int32), ("unroll", c_int32), ("flags", c_int32), ("reserved", c_int32 * 2)]
+
+    def as_tuple(self) -> Tuple[int, int, int, int, int, int]:
+        return (self.vec, self.threads_per_row, self.rows_per_wg, self.reduce, self.unroll, self.flags)
+
+    def as_dict(self) -> dict:
+        return dict(vec=self.vec, threads_per_row=self.threads_per_row, rows_per_wg=self.rows_per_wg,
+                    reduce=self.reduce, unroll=self.unroll, flags=self.flags)
+
+    def __repr__(self) -> str:
+        return ("Cfg(vec=%d, threads_per_row=%d, rows_per_wg=%d, reduce=%d, unroll=%d, flags=%d)" % self.as_tuple())
+
+
+def make_cfg(vec: int, threads_per_row: int, rows_per_wg: int = 1, reduce: int = REDUCE_WAVE,
+             unroll: int = 1, flags: int = 0) -> Cfg:
+    c = Cfg()
+    c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags = (
+        vec, threads_per_row, rows_per_wg, reduce, unroll, flags)
+    return c
+
+
+class Resources(Structure):
+    _fields_ = [("chunks_per_thread", c_int32), ("vgprs", c_int32), ("agprs", c_int32), ("sgprs", c_int32),
+                ("scratch_bytes", c_int32), ("lds_bytes", c_int32), ("max_threads", c_int32),
+                ("waves_per_wg", c_int32), ("waves_per_simd_regs", c_int32), ("wgs_per_cu", c_int32),
+                ("waves_per_simd", c_int32), ("reserved", c_int32 * 5)]
+
+    def as_dict(self) -> dict:
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
+class Budget(Structure):
+    _fields_ = [("max_wall_ms", c_double), ("max_candidates", c_int32), ("strategy", c_int32),
+                ("top_k", c_int32), ("warmup", c_int32), ("reps", c_int32), ("coarse_warmup", c_int32),
+                ("coarse_reps", c_int32), ("skip_validation", c_int32), ("eps", c_float),
+                ("reserved0", c_int32), ("log_path", c_char_p)]
+
+
+class TuneReport(Structure):
+    _fields_ = [("n_grid", c_int64), ("n_feasible", c_int64), ("n_measured", c_int64), ("n_failed", c_int64),
+                ("best_found_at", c_int64), ("best_us", c_double), ("default_us", c_double),
+                ("wall_ms", c_double), ("time_to_best_ms", c_double), ("best", Cfg), ("default_cfg", Cfg),
+                ("n_topk", c_int32), ("reserved0", c_int32), ("topk", Cfg * MAX_TOPK),
+                ("topk_us", c_double * MAX_TOPK)]
+
+    def as_dict(self) -> dict:
+        return dict(n_grid=self.n_grid, n_feasible=self.n_feasible, n_measured=self.n_measured,
+                    n_failed=self.n_failed, best_found_at=self.best_found_at, best_us=self.best_us,
+                    default_us=self.default_us, wall_ms=self.wall_ms, time_to_best_ms=self.time_to_best_ms,
+                    best=self.best.as_dict(), default_cfg=self.default_cfg.as_dict(),
+                    topk=[(self.topk[i].as_dict(), self.topk_us[i]) for i in range(self.n_topk)])
+
+
+VALIDATE_FN = CFUNCTYPE(c_int, c_void_p, POINTER(Cfg))
+MEASURE_FN = CFUNCTYPE(c_int, c_void_p, POINTER(Cfg), c_int, c_int, POINTER(c_double))
+
+
+class Backend(Structure):
+    _fields_ = [("user", c_void_p), ("validate", VALIDATE_FN), ("measure", MEASURE_FN)]
+
+
+# name -> (restype, argtypes); mirrors include/addrms.h one to one
+SIGNATURES = {
+    "addrms_run": (c_int, [c_void_p, c_void_p, c_void_p, c_float, c_int64, c_int64, c_int, POINTER(Cfg), c_void_p]),
+    "addrms_default_cfg": (c_int, [c_int64, c_int, POINTER(Cfg)]),
+    "addrms_cfg_feasible": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_char_p, c_size_t, POINTER(Resources)]),
+    "addrms_enumerate_feasible": (c_int64, [c_int64, c_int64, c_int, POINTER(Cfg), c_int64, POINTER(c_int64)]),
+    "addrms_tune": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Cfg), POINTER(TuneReport)]),
+    "addrms_tune_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
+                                         POINTER(Cfg), POINTER(TuneReport)]),
+    "addrms_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_float, c_int, c_int, c_int, POINTER(c_double)]),
+    "addrms_table_insert": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg), c_double]),
+    "addrms_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
+    "addrms_table_size": (c_int64, []),
+    "addrms_table_clear": (None, []),
+    "addrms_table_save": (c_int, [c_char_p]),
+    "addrms_table_load": (c_int, [c_char_p]),
+    "addrms_rstd_probe": (c_int, [c_void_p, c_int64, c_int64, c_float, c_void_p, c_void_p]),
+    "addrms_stream_probe": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p]),
+    "addrms_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
+    "addrms_last_error": (c_char_p, []),
+    "addrms_version": (c_char_p, []),
+}
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libaddrms.so (once) and declare every entry point."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise AddrmsLibraryMissing(
+                f"{LIB_PATH} not found: build it with `python -m paper_2601_12698_amd.build` "
+                "(there is no fallback implementation)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int) -> int:
+    if status < 0:
+        raise AddrmsError(int(status), load().addrms_last_error().decode("utf-8", "replace"))
+    return status
+
+
+def _dtype_id(dtype) -> int:
+    return DTYPE_IDS[dtype] if isinstance(dtype, str) else int(dtype)
+
+
+def _stream_ptr(stream, tensor=None) -> Optional[int]:
+    if stream is not None:
+        return int(getattr(stream, "cuda_stream", stream))
+    import torch
+    return int(torch.cuda.current_stream(tensor.device if tensor is not None else None).cuda_stream)
+
+
+def _ptr(t) -> int:
+    return int(t.data_ptr())
+
+
+# ---- entry points --------------------------------------------------------------
+
+def addrms_version() -> str:
+    return load().addrms_version().decode()
+
+
+def addrms_last_error() -> str:
+    return load().addrms_last_error().decode("utf-8", "replace")
+
+
+def addrms_algorithmic_bytes(M: int, N: int, dtype) -> int:
+    return _check(load().addrms_algorithmic_bytes(M, N, _dtype_id(dtype)))
+
+
+def addrms_run(x, residual, weight, eps: float, M: int, N: int, dtype, cfg: Optional[Cfg] = None,
+               stream=None) -> None:
+    """In place: residual <- round(x + residual), x <- rmsnorm(x + residual) * weight."""
+    for name, t in (("x", x), ("residual", residual), ("weight", weight)):
+        if not t.is_cuda:
+            raise ValueError(f"{name} must be a device tensor")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if x.numel() != M * N or residual.numel() != M * N or weight.numel() != N:
+        raise ValueError("tensor sizes do not match M and N")
+    _check(load().addrms_run(_ptr(x), _ptr(residual), _ptr(weight), float(eps), M, N, _dtype_id(dtype),
+                             byref(cfg) if cfg is not None else None, _stream_ptr(stream, x)))
+
+
+def addrms_default_cfg(N: int, dtype) -> Cfg:
+    c = Cfg()
+    _check(load().addrms_default_cfg(N, _dtype_id(dtype), byref(c)))
+    return c
+
+
+def addrms_cfg_feasible(cfg: Cfg, M: int, N: int, dtype) -> Tuple[int, str, Resources]:
+    """Returns (status, reason, resources); status 0 means feasible."""
+    buf = ctypes.create_string_buffer(512)
+    res = Resources()
+    st = load().addrms_cfg_feasible(byref(cfg), M, N, _dtype_id(dtype), buf, len(buf), byref(res))
+    return int(st), buf.value.decode("utf-8", "replace"), res
+
+
+def addrms_enumerate_feasible(M: int, N: int, dtype) -> Tuple[List[Cfg], int]:
+    """Returns (feasible cfgs, knob-grid size)."""
+    lib = load()
+    grid = c_int64(0)
+    n = _check(lib.addrms_enumerate_feasible(M, N, _dtype_id(dtype), None, 0, byref(grid)))
+    arr = (Cfg * max(n, 1))()
+    _check(lib.addrms_enumerate_feasible(M, N, _dtype_id(dtype), arr, n, byref(grid)))
+    out = []
+    for i in range(n):
+        c = Cfg()
+        ctypes.memmove(byref(c), byref(arr[i]), ctypes.sizeof(Cfg))
+        out.append(c)
+    return out, int(grid.value)
+
+
+def make_budget(max_wall_ms: float = 0.0, max_candidates: int = 0, strategy: int = SEARCH_GUIDED, top_k: int = 0,
+                warmup: int = 0, reps: int = 0, coarse_warmup: int = 0, coarse_reps: int = 0,
+                skip_validation: bool = False, eps: float = 0.0, log_path: Optional[str] = None) -> Budget:
+    b = Budget()
+    b.max_wall_ms, b.max_candidates, b.strategy, b.top_k = max_wall_ms, max_candidates, strategy, top_k
+    b.warmup, b.reps, b.coarse_warmup, b.coarse_reps = warmup, reps, coarse_warmup, coarse_reps
+    b.skip_validation, b.eps = int(skip_validation), eps
+    b.log_path = log_path.encode() if log_path else None
+    return b
+
+
+def addrms_tune(M: int, N: int, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, TuneReport]:
+    c, rep = Cfg(), TuneReport()
+    _check(load().addrms_tune(M, N, _dtype_id(dtype), byref(budget) if budget is not None else None,
+                              byref(c), byref(rep)))
+    return c, rep
+
+
+def addrms_tune_with_backend(M: int, N: int, dtype, budget: Optional[Budget], measure, validate=None
+                             ) -> Tuple[Cfg, TuneReport]:
+    """``measure(cfg, warmup, reps) -> microseconds`` (raise or return None to
+    signal a failed candidate); ``validate(cfg) -> bool``."""
+    def _m(_user, cfg_p, warmup, reps, out):
+        try:
+            us = measure(cfg_p.contents, warmup, reps)
+        except Exception:
+            return 1
+        if us is None:
+            return 1
+        out[0] = float(us)
+        return 0
+
+    def _v(_user, cfg_p):
+        try:
+            return 0 if validate(cfg_p.contents) else 1
+        except Exception:
+            return 1
+
+    be = Backend()
+    be.user = None
+    be.measure = MEASURE_FN(_m)
+    be.validate = VALIDATE_FN(_v) if validate is not None else VALIDATE_FN()
+    c, rep = Cfg(), TuneReport()
+    _check(load().addrms_tune_with_backend(M, N, _dtype_id(dtype), byref(budget) if budget is not None else None,
+                                           byref(be), byref(c), byref(rep)))
+    return c, rep
+
+
+def addrms_measure(cfg: Optional[Cfg], M: int, N: int, dtype, eps: float = 1e-6, warmup: int = 20,
+                   reps: int = 100, rotate: bool = True) -> float:
+    us = c_double(0.0)
+    _check(load().addrms_measure(byref(cfg) if cfg is not None else None, M, N, _dtype_id(dtype), float(eps),
+                                 warmup, reps, int(rotate), byref(us)))
+    return float(us.value)
+
+
+def addrms_table_insert(M: int, N: int, dtype, cfg: Cfg, mean_us: float = 0.0) -> None:
+    _check(load().addrms_table_insert(M, N, _dtype_id(dtype), byref(cfg), float(mean_us)))
+
+
+def addrms_table_lookup(M: int, N: int, dtype) -> Optional[Cfg]:
+    c = Cfg()
+    st = load().addrms_table_lookup(M, N, _dtype_id(dtype), byref(c))
+    if st == ERR_NO_RESULT:
+        return None
+    _check(st)
+    return c
+
+
+def addrms_table_size() -> int:
+    return int(load().addrms_table_size())
+
+
+def addrms_table_clear() -> None:
+    load().addrms_table_clear()
+
+
+def addrms_table_save(path: str) -> None:
+    _check(load().addrms_table_save(path.encode()))
+
+
+def addrms_table_load(path: str) -> None:
+    _check(load().addrms_table_load(path.encode()))
+
+
+def addrms_rstd_probe(ss, N: int, eps: float, out, stream=None) -> None:
+    """ss: device fp64 [n]; out: device fp32 [n]."""
+    _check(load().addrms_rstd_probe(_ptr(ss), ss.numel(), N, float(eps), _ptr(out), _stream_ptr(stream, ss)))
+
+
+def addrms_stream_probe(x, residual, M: int, N: int, dtype, stream=None) -> None:
+    _check(load().addrms_stream_probe(_ptr(x), _ptr(residual), M, N, _dtype_id(dtype), _stream_ptr(stream, x)))

@@ -1,0 +1,363 @@
+// Feasible-region deriver (Algorithm 1 line 18, DeriveFeasibleSpace; Section 3.3:
+// ranges and candidate sets are derived from the hardware's resource limits, and
+// combinations that would fail to compile, launch invalidly or be obviously
+// inefficient are pruned, each with a stated rationale).
+//
+// Host-only: no HIP call is made here, so the region can be derived on a machine
+// without a GPU.  Register, scratch and LDS figures of every kernel instance
+// come from the compiler's resource report captured when the library was built.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <mutex>
+#include <unordered_map>
+
+#include "addrms_internal.h"
+
+namespace addrms_host {
+
+// ---- error text -------------------------------------------------------------
+static thread_local std::string g_error;
+
+int fail(int status, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_error = buf;
+    return status;
+}
+void clear_error() { g_error.clear(); }
+static const char* last_error() { return g_error.c_str(); }
+
+// ---- hardware ---------------------------------------------------------------
+const HwLimits& hw()
+{
+    static const HwLimits limits;
+    return limits;
+}
+
+// ---- instances ----------------------------------------------------------------
+static const Instance kInstances[] = {
+#include "gen_instances.inc"
+};
+static const InstanceRes kInstanceRes[] = {
+#include "gen_resources.inc"
+};
+static_assert(sizeof(kInstances) / sizeof(kInstances[0]) == sizeof(kInstanceRes) / sizeof(kInstanceRes[0]),
+              "instance list and resource report disagree");
+
+int n_instances() { return static_cast<int>(sizeof(kInstances) / sizeof(kInstances[0])); }
+const Instance& instance(int idx) { return kInstances[idx]; }
+const InstanceRes& instance_res(int idx) { return kInstanceRes[idx]; }
+
+static uint32_t inst_key(int dt, int vec, int cpt, int unr)
+{
+    return (static_cast<uint32_t>(dt) << 24) | (static_cast<uint32_t>(vec) << 16) |
+           (static_cast<uint32_t>(cpt) << 8) | static_cast<uint32_t>(unr);
+}
+
+int find_instance(int dt, int vec, int cpt, int unr)
+{
+    static const std::unordered_map<uint32_t, int> index = [] {
+        std::unordered_map<uint32_t, int> m;
+        for (int i = 0; i < n_instances(); ++i)
+            m[inst_key(kInstances[i].dt, kInstances[i].vec, kInstances[i].cpt, kInstances[i].unr)] = i;
+        return m;
+    }();
+    auto it = index.find(inst_key(dt, vec, cpt, unr));
+    return it == index.end() ? -1 : it->second;
+}
+
+bool cpt_supported(int cpt)
+{
+    for (int i = 0; i < n_instances(); ++i)
+        if (kInstances[i].cpt == cpt) return true;
+    return false;
+}
+
+// ---- formats -------------------------------------------------------------------
+bool dtype_valid(int dtype) { return dtype >= ADDRMS_BF16 && dtype <= ADDRMS_FP32; }
+int x_bytes(int dtype) { return dtype == ADDRMS_FP32 ? 4 : 2; }
+int r_bytes(int dtype) { return (dtype == ADDRMS_FP32 || dtype == ADDRMS_FP16_RES32) ? 4 : 2; }
+const char* dtype_name(int dtype)
+{
+    switch (dtype) {
+    case ADDRMS_BF16: return "bf16";
+    case ADDRMS_FP16: return "fp16";
+    case ADDRMS_FP16_RES32: return "fp16_res32";
+    case ADDRMS_FP32: return "fp32";
+    default: return "?";
+    }
+}
+
+// ---- small helpers -----------------------------------------------------------
+static const int kVecs[] = {8, 4, 2, 1};
+static const int kRows[] = {1, 2, 4, 8, 16};
+static const int kUnrolls[] = {1, 2, 4, 8};
+
+static bool in_set(int v, const int* set, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        if (set[i] == v) return true;
+    return false;
+}
+static bool tpr_valid(int t) { return t == 8 || t == 16 || t == 32 || (t >= 64 && t <= 1024 && t % 64 == 0); }
+static int round_up(int v, int g) { return (v + g - 1) / g * g; }
+
+bool cfg_equal(const addrms_cfg& a, const addrms_cfg& b)
+{
+    return a.vec == b.vec && a.threads_per_row == b.threads_per_row && a.rows_per_wg == b.rows_per_wg &&
+           a.reduce == b.reduce && a.unroll == b.unroll && a.flags == b.flags;
+}
+uint64_t cfg_key(const addrms_cfg& c)
+{
+    return (static_cast<uint64_t>(c.vec) << 40) | (static_cast<uint64_t>(c.threads_per_row) << 24) |
+           (static_cast<uint64_t>(c.rows_per_wg) << 16) | (static_cast<uint64_t>(c.reduce) << 12) |
+           (static_cast<uint64_t>(c.unroll) << 4) | static_cast<uint64_t>(c.flags & 0xf);
+}
+std::string cfg_json(const addrms_cfg& c)
+{
+    char buf[192];
+    snprintf(buf, sizeof buf,
+             "{\"vec\":%d,\"threads_per_row\":%d,\"rows_per_wg\":%d,\"reduce\":%d,\"unroll\":%d,\"flags\":%d}",
+             c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags);
+    return buf;
+}
+
+int lds_bytes_for(const addrms_cfg& c)
+{
+    if (c.reduce == ADDRMS_REDUCE_LDS) return c.threads_per_row * c.rows_per_wg * 8;
+    return c.threads_per_row > 64 ? c.rows_per_wg * 16 * 8 : 0;   // one fp64 slot per wave of a row
+}
+int64_t n_workgroups(const addrms_cfg& c, int64_t M) { return (M + c.rows_per_wg - 1) / c.rows_per_wg; }
+
+// ---- the rules ------------------------------------------------------------------
+static Feas infeasible(const char* rule, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+static Feas infeasible(const char* rule, const char* fmt, ...)
+{
+    char buf[384];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    Feas f;
+    f.status = ADDRMS_ERR_INFEASIBLE_CFG;
+    f.rule = rule;
+    f.reason = buf;
+    return f;
+}
+
+Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
+{
+    const HwLimits& L = hw();
+    Feas f;
+    if (!dtype_valid(dtype)) {
+        f.status = ADDRMS_ERR_UNSUPPORTED_DTYPE;
+        f.reason = "dtype is not one of bf16, fp16, fp16_res32, fp32";
+        return f;
+    }
+    if (M < 0 || N <= 0) {
+        f.status = ADDRMS_ERR_INVALID_ARG;
+        f.reason = "M must be >= 0 and N must be > 0";
+        return f;
+    }
+    // -- the knob grid itself
+    if (!in_set(c.vec, kVecs, 4)) return infeasible("grid", "vec=%d: vector width must be 1, 2, 4 or 8 elements", c.vec);
+    if (!tpr_valid(c.threads_per_row))
+        return infeasible("grid", "threads_per_row=%d: a row is reduced either inside one wave64 (8, 16 or 32 lanes) or by "
+                          "whole waves (a multiple of 64 up to %d)", c.threads_per_row, L.max_threads_per_wg);
+    if (!in_set(c.rows_per_wg, kRows, 5)) return infeasible("grid", "rows_per_wg=%d: must be 1, 2, 4, 8 or 16", c.rows_per_wg);
+    if (c.reduce != ADDRMS_REDUCE_WAVE && c.reduce != ADDRMS_REDUCE_LDS)
+        return infeasible("grid", "reduce=%d: must be wave (0) or lds (1)", c.reduce);
+    if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
+    if (c.flags & ~ADDRMS_FLAG_XCD_CONTIG) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
+    if (c.reserved[0] || c.reserved[1]) return infeasible("grid", "reserved fields must be zero");
+
+    const int xb = x_bytes(dtype), rb = r_bytes(dtype);
+    // -- vectorisation and alignment
+    if (N % c.vec != 0)
+        return infeasible("vec_divides_n", "vec=%d does not divide N=%lld: rows after the first would start misaligned and the last "
+                          "vector of a row would straddle two rows", c.vec, (long long)N);
+    if (c.vec * xb > L.max_access_bytes)
+        return infeasible("access_width", "vec=%d x %d-byte elements is %d bytes per lane: wider than the %d-byte global access",
+                          c.vec, xb, c.vec * xb, L.max_access_bytes);
+    (void)rb;   // the residual stream may take two accesses (fp32 residual at vec=8)
+
+    // -- launch validity
+    const int threads = c.threads_per_row * c.rows_per_wg;
+    if (threads > L.max_threads_per_wg)
+        return infeasible("wg_size", "workgroup of %d x %d = %d threads exceeds the %d-thread limit (invalid launch)",
+                          c.threads_per_row, c.rows_per_wg, threads, L.max_threads_per_wg);
+    if (threads % L.wave_size != 0)
+        return infeasible("whole_waves", "workgroup of %d threads is not a whole number of %d-lane waves: the cross-lane reduction "
+                          "needs full waves", threads, L.wave_size);
+
+    // -- register row cache: the row slice of a thread must fit in registers
+    const int64_t per_pass = static_cast<int64_t>(c.vec) * c.threads_per_row;
+    const int64_t need = (N + per_pass - 1) / per_pass;
+    if (need * c.vec > kMaxElemsPerThread)
+        return infeasible("row_cache", "N=%lld over %d threads at vec=%d needs %lld values per thread in registers; the row cache "
+                          "holds %d (more would spill or leave under %d waves per SIMD)",
+                          (long long)N, c.threads_per_row, c.vec, (long long)(need * c.vec), kMaxElemsPerThread,
+                          kMinWavesPerSimd);
+    if (!cpt_supported(static_cast<int>(need)))
+        return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (1-8, 10, 12, 14, 16 exist)", (long long)need);
+    f.res.chunks_per_thread = static_cast<int>(need);
+    const double util = static_cast<double>(N) / static_cast<double>(per_pass * need);
+    if (util <= 0.5)
+        return infeasible("lane_utilisation", "only %.0f%% of the %lld lane slots of a row would carry data (obviously inefficient: a "
+                          "narrower row does the same work)", util * 100.0, (long long)(per_pass * need));
+    if (c.unroll > need)
+        return infeasible("unroll_gt_chunks", "unroll=%d exceeds the %lld chunks a thread has", c.unroll, (long long)need);
+
+    // -- problem-size rules
+    const int min_rows = std::max(1, L.wave_size / c.threads_per_row);
+    if (c.rows_per_wg > std::max<int64_t>(M, min_rows) && c.rows_per_wg > min_rows)
+        return infeasible("rows_gt_m", "rows_per_wg=%d exceeds the %lld rows there are", c.rows_per_wg, (long long)M);
+    if ((c.flags & ADDRMS_FLAG_XCD_CONTIG) && n_workgroups(c, M) < 2 * L.xcds)
+        return infeasible("xcd_identity", "XCD-contiguous mapping with fewer than %d workgroups is the identity mapping",
+                          2 * L.xcds);
+
+    // -- compiled instance and its resources
+    const int idx = find_instance(dtype, c.vec, static_cast<int>(need), c.unroll);
+    if (idx < 0)
+        return infeasible("no_instance", "no compiled instance for dtype=%s vec=%d chunks=%lld unroll=%d", dtype_name(dtype), c.vec,
+                          (long long)need, c.unroll);
+    f.inst = idx;
+    const Instance& in = kInstances[idx];
+    const InstanceRes& r = kInstanceRes[idx];
+    addrms_resources& o = f.res;
+    o.vgprs = r.vgprs; o.agprs = r.agprs; o.sgprs = r.sgprs; o.scratch_bytes = r.scratch;
+    o.max_threads = in.maxt;
+    o.lds_bytes = lds_bytes_for(c) + r.lds_static;
+    o.waves_per_wg = threads / L.wave_size;
+    if (r.scratch > 0)
+        return infeasible("scratch", "instance spills %d bytes per lane to scratch memory", r.scratch);
+    if (threads > in.maxt)
+        return infeasible("wg_bound", "instance holds %d values per thread and was compiled for workgroups of at most %d threads; "
+                          "%d requested", c.vec * static_cast<int>(need), in.maxt, threads);
+
+    // -- occupancy on one CU
+    const int regs = round_up(std::max(1, r.vgprs + r.agprs), L.reg_granule);
+    o.waves_per_simd_regs = std::min(L.max_waves_per_simd, L.regs_per_lane / regs);
+    const int waves_cu_regs = o.waves_per_simd_regs * L.simds_per_cu;
+    int wgs = waves_cu_regs / o.waves_per_wg;
+    if (o.lds_bytes > 0) wgs = std::min(wgs, L.lds_bytes_per_cu / round_up(o.lds_bytes, L.lds_granule));
+    wgs = std::min(wgs, o.waves_per_wg > 1 ? L.max_multiwave_wgs_per_cu : L.max_wgs_per_cu);
+    o.wgs_per_cu = wgs;
+    if (wgs < 1)
+        return infeasible("occupancy", "workgroup of %d waves at %d registers per lane does not fit one CU (%d wave slots by "
+                          "registers, %d bytes of LDS)", o.waves_per_wg, regs, waves_cu_regs, o.lds_bytes);
+    o.waves_per_simd = (wgs * o.waves_per_wg + L.simds_per_cu - 1) / L.simds_per_cu;
+    if (o.waves_per_simd < kMinWavesPerSimd)
+        return infeasible("occupancy", "only %d wave per SIMD would be resident (%d registers per lane, %d-wave workgroups): too "
+                          "few loads in flight to cover HBM latency", o.waves_per_simd, regs, o.waves_per_wg);
+    return f;
+}
+
+void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid)
+{
+    int64_t grid = 0;
+    std::vector<int> tprs = {8, 16, 32};
+    for (int t = 64; t <= hw().max_threads_per_wg; t += 64) tprs.push_back(t);
+    for (int vec : kVecs)
+        for (int tpr : tprs)
+            for (int rows : kRows)
+                for (int red = 0; red < 2; ++red)
+                    for (int unr : kUnrolls)
+                        for (int flags = 0; flags < 2; ++flags) {
+                            ++grid;
+                            addrms_cfg c{};
+                            c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;
+                            c.reduce = red; c.unroll = unr; c.flags = flags;
+                            if (check_cfg(c, M, N, dtype).status == ADDRMS_OK && out) out->push_back(c);
+                        }
+    if (n_grid) *n_grid = grid;
+}
+
+int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why)
+{
+    if (!dtype_valid(dtype)) { if (why) *why = "unsupported dtype"; return ADDRMS_ERR_UNSUPPORTED_DTYPE; }
+    if (N <= 0) { if (why) *why = "N must be > 0"; return ADDRMS_ERR_INVALID_ARG; }
+    // Preference order: widest vector; 256 threads per row, then wider, then
+    // narrower rows; one row per workgroup (more only to fill a wave).
+    static const int tprs[] = {256, 512, 1024, 384, 768, 128, 192, 320, 448, 576, 640, 704, 832, 896, 960,
+                               64, 32, 16, 8};
+    const int64_t big_m = 1 << 20;   // feasibility of the default must not depend on M
+    for (int vec : kVecs)
+        for (int tpr : tprs) {
+            addrms_cfg c{};
+            c.vec = vec; c.threads_per_row = tpr;
+            c.rows_per_wg = std::max(1, hw().wave_size / tpr);
+            c.reduce = ADDRMS_REDUCE_WAVE;
+            const int64_t need = (N + static_cast<int64_t>(vec) * tpr - 1) / (static_cast<int64_t>(vec) * tpr);
+            c.unroll = need >= 2 ? 2 : 1;
+            if (check_cfg(c, big_m, N, dtype).status == ADDRMS_OK) { *out = c; return ADDRMS_OK; }
+        }
+    if (why) {
+        char buf[160];
+        snprintf(buf, sizeof buf, "no configuration of the template covers N=%lld for %s (row cache holds %d values "
+                 "per thread, %d threads per row at most)", (long long)N, dtype_name(dtype), kMaxElemsPerThread,
+                 hw().max_threads_per_wg);
+        *why = buf;
+    }
+    return ADDRMS_ERR_UNSUPPORTED_SHAPE;
+}
+
+}  // namespace addrms_host
+
+// ---- C ABI -------------------------------------------------------------------------
+using namespace addrms_host;
+
+extern "C" {
+
+const char* addrms_last_error(void) { return last_error(); }
+const char* addrms_version(void) { return ADDRMS_VERSION_STRING " (gfx950)"; }
+
+int64_t addrms_algorithmic_bytes(int64_t M, int64_t N, int dtype)
+{
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
+    return M * N * (2 * x_bytes(dtype) + 2 * r_bytes(dtype)) + N * x_bytes(dtype);
+}
+
+int addrms_default_cfg(int64_t N, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    std::string why;
+    const int st = default_cfg(N, dtype, out, &why);
+    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
+}
+
+int addrms_cfg_feasible(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype,
+                        char* reason, size_t reason_len, addrms_resources* res)
+{
+    if (reason && reason_len) reason[0] = '\0';
+    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
+    const Feas f = check_cfg(*cfg, M, N, dtype);
+    if (res) *res = f.res;
+    if (f.status != ADDRMS_OK) {
+        if (reason && reason_len) snprintf(reason, reason_len, "%s", f.reason.c_str());
+        return fail(f.status, "%s", f.reason.c_str());
+    }
+    return ADDRMS_OK;
+}
+
+int64_t addrms_enumerate_feasible(int64_t M, int64_t N, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid)
+{
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
+    if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
+    std::vector<addrms_cfg> v;
+    enumerate(M, N, dtype, &v, n_grid);
+    const int64_t n = static_cast<int64_t>(v.size());
+    for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
+    return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+// Internal declarations shared by the host-side translation units of libaddrms.
+// Nothing here is part of the ABI.
+#pragma once
+#include <stdarg.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "addrms.h"
+
+namespace addrms_host {
+
+// ---- r(h): resource upper bounds of the target (Algorithm 1, Input) --------
+// MI355X / gfx950 (CDNA4), public figures.
+struct HwLimits {
+    int compute_units = 256;
+    int xcds = 8;
+    int simds_per_cu = 4;
+    int wave_size = 64;
+    int max_waves_per_simd = 8;
+    int regs_per_lane = 512;        // unified VGPR+AGPR file entries per lane per SIMD
+    int reg_granule = 8;            // allocation granularity of that file
+    int lds_bytes_per_cu = 160 * 1024;
+    int lds_granule = 1280;         // LDS allocation granularity in bytes
+    int max_threads_per_wg = 1024;
+    int max_wgs_per_cu = 32;        // workgroup slots per CU (16 when a workgroup has several waves)
+    int max_multiwave_wgs_per_cu = 16;
+    int max_access_bytes = 16;      // widest single global load/store per lane
+    double hbm_bytes_per_s = 8.0e12;
+    int64_t last_level_cache_bytes = 256ll << 20;  // Infinity Cache
+    int64_t l2_bytes_per_xcd = 4ll << 20;
+};
+const HwLimits& hw();
+
+// Floors below which a launch shape is pruned as obviously inefficient.
+constexpr int kMinWavesPerSimd = 2;
+constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
+
+// ---- kernel instances ------------------------------------------------------
+struct Instance { int dt, vec, cpt, unr, maxt; };
+struct InstanceRes { int vgprs, agprs, sgprs, scratch, lds_static, occupancy; };
+
+int n_instances();
+const Instance& instance(int idx);
+const InstanceRes& instance_res(int idx);
+// Index of the instance with exactly these knob values, or -1.
+int find_instance(int dt, int vec, int cpt, int unr);
+bool cpt_supported(int cpt);
+
+// ---- storage formats -------------------------------------------------------
+bool dtype_valid(int dtype);
+int x_bytes(int dtype);
+int r_bytes(int dtype);
+const char* dtype_name(int dtype);
+
+// ---- feasibility -----------------------------------------------------------
+struct Feas {
+    int status = ADDRMS_OK;
+    const char* rule = "";      // short tag of the rule that rejected the cfg
+    std::string reason;
+    int inst = -1;              // instance index when one was selected
+    addrms_resources res{};
+};
+Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype);
+void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid);
+int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why);
+int lds_bytes_for(const addrms_cfg& c);
+int64_t n_workgroups(const addrms_cfg& c, int64_t M);
+
+bool cfg_equal(const addrms_cfg& a, const addrms_cfg& b);
+uint64_t cfg_key(const addrms_cfg& c);
+std::string cfg_json(const addrms_cfg& c);
+
+// ---- specialised table -----------------------------------------------------
+int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out);
+
+// ---- search ----------------------------------------------------------------
+int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
+               const addrms_backend& be, addrms_cfg* out_cfg, addrms_tune_report* report);
+
+// ---- error text ------------------------------------------------------------
+int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+}  // namespace addrms_host

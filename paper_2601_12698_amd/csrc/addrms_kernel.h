@@ -1,0 +1,339 @@
+// Device-side template of the fused residual-add + RMSNorm kernel for gfx950.
+//
+// This is the "parameterizable template" of the paper's Level 2 (Algorithm 1,
+// Templatize; Section 3.3 lists the knob families: thread-level granularity,
+// loop scheduling/unrolling, vectorisation/alignment, organisation of shared
+// memory and registers).  The knobs are
+//
+//   VEC   elements per thread per chunk (one vector load of x, one of residual)
+//   CPT   chunks per thread = ceil(N / (VEC * threads_per_row)); the whole row
+//         slice lives in registers between the two passes (register row cache)
+//   UNR   chunks whose loads are in flight before the first one is consumed
+//   threads_per_row, rows_per_wg : launch shape (blockDim.x, blockDim.y)
+//   reduce  : wave64 cross-lane butterfly + one LDS hop across waves, or an
+//             LDS-staged tree
+//   flags   : XCD-contiguous mapping of workgroups to rows
+//
+// VEC, CPT and UNR are compile-time; the rest are launch-time and uniform
+// over the workgroup.
+//
+// Arithmetic per row (what every instantiation must reproduce bit for bit):
+//   h = f32(x) + f32(r)                       one fp32 add
+//   residual <- RNE(h -> residual dtype)      in place
+//   ss = sum h^2  accumulated in fp64 (each h^2 is exact in fp64), any order
+//   rstd = fp32( rsqrt(ss * (1/N) + eps) )    fp64, refined to fp64 accuracy
+//   x <- RNE((h * rstd) * f32(w) -> x dtype)  two fp32 multiplies, in place
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace addrms {
+
+enum : int { DT_BF16 = 0, DT_FP16 = 1, DT_FP16_RES32 = 2, DT_FP32 = 3 };
+enum : int { RED_WAVE = 0, RED_LDS = 1 };
+enum : uint32_t { FLAG_XCD_CONTIG = 1u };
+
+template <int DT> struct dt_traits;
+template <> struct dt_traits<DT_BF16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = true;  };
+template <> struct dt_traits<DT_FP16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = false; };
+template <> struct dt_traits<DT_FP16_RES32> { static constexpr int XB = 2, RB = 4; static constexpr bool BF = false; };
+template <> struct dt_traits<DT_FP32>       { static constexpr int XB = 4, RB = 4; static constexpr bool BF = false; };
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Raw register image of one vector access of BYTES bytes (2..32).
+template <int BYTES> struct raw_t { uint32_t d[(BYTES + 3) / 4]; };
+
+template <int BYTES>
+__device__ __forceinline__ void ld_raw(const char* p, raw_t<BYTES>& v)
+{
+    if constexpr (BYTES == 2) {
+        v.d[0] = *reinterpret_cast<const uint16_t*>(p);
+    } else if constexpr (BYTES == 4) {
+        v.d[0] = *reinterpret_cast<const uint32_t*>(p);
+    } else if constexpr (BYTES == 8) {
+        u32x2 t = *reinterpret_cast<const u32x2*>(p);
+        v.d[0] = t.x; v.d[1] = t.y;
+    } else if constexpr (BYTES == 16) {
+        u32x4 t = *reinterpret_cast<const u32x4*>(p);
+        v.d[0] = t.x; v.d[1] = t.y; v.d[2] = t.z; v.d[3] = t.w;
+    } else {
+        static_assert(BYTES == 32, "vector access must be 2, 4, 8, 16 or 32 bytes");
+        u32x4 a = *reinterpret_cast<const u32x4*>(p);
+        u32x4 b = *reinterpret_cast<const u32x4*>(p + 16);
+        v.d[0] = a.x; v.d[1] = a.y; v.d[2] = a.z; v.d[3] = a.w;
+        v.d[4] = b.x; v.d[5] = b.y; v.d[6] = b.z; v.d[7] = b.w;
+    }
+}
+
+template <int BYTES>
+__device__ __forceinline__ void st_raw(char* p, const raw_t<BYTES>& v)
+{
+    if constexpr (BYTES == 2) {
+        *reinterpret_cast<uint16_t*>(p) = static_cast<uint16_t>(v.d[0]);
+    } else if constexpr (BYTES == 4) {
+        *reinterpret_cast<uint32_t*>(p) = v.d[0];
+    } else if constexpr (BYTES == 8) {
+        u32x2 t = {v.d[0], v.d[1]};
+        *reinterpret_cast<u32x2*>(p) = t;
+    } else if constexpr (BYTES == 16) {
+        u32x4 t = {v.d[0], v.d[1], v.d[2], v.d[3]};
+        *reinterpret_cast<u32x4*>(p) = t;
+    } else {
+        static_assert(BYTES == 32, "vector access must be 2, 4, 8, 16 or 32 bytes");
+        u32x4 a = {v.d[0], v.d[1], v.d[2], v.d[3]};
+        u32x4 b = {v.d[4], v.d[5], v.d[6], v.d[7]};
+        *reinterpret_cast<u32x4*>(p) = a;
+        *reinterpret_cast<u32x4*>(p + 16) = b;
+    }
+}
+
+// Element e of a raw vector of ES-byte elements, widened to fp32 (exact).
+template <int ES, bool BF, int BYTES>
+__device__ __forceinline__ float get_elem(const raw_t<BYTES>& v, int e)
+{
+    if constexpr (ES == 4) {
+        return __uint_as_float(v.d[e]);
+    } else {
+        const uint32_t dw = v.d[e >> 1];
+        if constexpr (BF) {
+            return __uint_as_float((e & 1) ? (dw & 0xffff0000u) : (dw << 16));
+        } else {
+            f16x2 hh = __builtin_bit_cast(f16x2, dw);
+            return (e & 1) ? static_cast<float>(hh.y) : static_cast<float>(hh.x);
+        }
+    }
+}
+
+// Two fp32 values rounded to nearest-even into one dword of 16-bit storage.
+template <bool BF>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    f32x2 f = {lo, hi};
+    if constexpr (BF) {
+        bf16x2 b = __builtin_convertvector(f, bf16x2);
+        return __builtin_bit_cast(uint32_t, b);
+    } else {
+        f16x2 b = __builtin_convertvector(f, f16x2);
+        return __builtin_bit_cast(uint32_t, b);
+    }
+}
+
+// VEC fp32 values -> raw vector of ES-byte elements.
+template <int ES, bool BF, int VEC>
+__device__ __forceinline__ void pack_vec(const float (&f)[VEC], raw_t<ES * VEC>& out)
+{
+    if constexpr (ES == 4) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) out.d[e] = __float_as_uint(f[e]);
+    } else if constexpr (VEC == 1) {
+        out.d[0] = pack2<BF>(f[0], 0.0f) & 0xffffu;
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; e += 2) out.d[e >> 1] = pack2<BF>(f[e], f[e + 1]);
+    }
+}
+
+// ---- cross-lane movement of one dword ------------------------------------
+// xor-butterfly partner fetch.  Steps 1, 2 use DPP quad permutes; 4 and 8 use
+// the DPP half-row and row mirrors (valid as butterfly steps because the
+// lanes being mirrored already hold equal sub-sums); 16 uses the LDS crossbar
+// swizzle; 32 uses a wave-wide bpermute.
+template <int STEP>
+__device__ __forceinline__ uint32_t lane_partner(uint32_t v)
+{
+    if constexpr (STEP == 1) {
+        return __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+    } else if constexpr (STEP == 2) {
+        return __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    } else if constexpr (STEP == 4) {
+        return __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);  // row_half_mirror
+    } else if constexpr (STEP == 8) {
+        return __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);  // row_mirror
+    } else if constexpr (STEP == 16) {
+        return __builtin_amdgcn_ds_swizzle(v, 0x401F);                    // lane ^ 16 within 32
+    } else {
+        static_assert(STEP == 32, "butterfly step");
+        const uint32_t self = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        return __builtin_amdgcn_ds_bpermute(static_cast<int>((self ^ 32u) << 2), v);
+    }
+}
+
+template <int STEP>
+__device__ __forceinline__ double butterfly_add(double v)
+{
+    const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = lane_partner<STEP>(static_cast<uint32_t>(bits));
+    const uint32_t hi = lane_partner<STEP>(static_cast<uint32_t>(bits >> 32));
+    const double other = __builtin_bit_cast(double, (static_cast<uint64_t>(hi) << 32) | lo);
+    return v + other;       // a+b on one side, b+a on the other: identical bits
+}
+
+// Sum over aligned groups of `width` lanes (8, 16, 32 or 64); every lane of a
+// group ends with the same bits.
+__device__ __forceinline__ double wave_group_sum(double v, uint32_t width)
+{
+    v = butterfly_add<1>(v);
+    v = butterfly_add<2>(v);
+    v = butterfly_add<4>(v);
+    if (width >= 16) v = butterfly_add<8>(v);
+    if (width >= 32) v = butterfly_add<16>(v);
+    if (width >= 64) v = butterfly_add<32>(v);
+    return v;
+}
+
+// Row sum of per-thread partials; result identical in all threads of the row.
+// lds: RED_WAVE needs rows_per_wg * 16 doubles, RED_LDS needs one double per thread.
+__device__ __forceinline__ double row_sum(double part, int reduce, uint32_t tpr, uint32_t lane, uint32_t ry,
+                                          double* lds)
+{
+    if (reduce == RED_WAVE) {
+        if (tpr <= 64u) return wave_group_sum(part, tpr);
+        const double wsum = wave_group_sum(part, 64u);
+        const uint32_t nw = tpr >> 6;
+        double* slot = lds + ry * 16u;
+        if ((lane & 63u) == 0u) slot[lane >> 6] = wsum;
+        __syncthreads();
+        double total = slot[0];
+        for (uint32_t i = 1; i < nw; ++i) total += slot[i];
+        return total;
+    }
+    double* buf = lds + ry * tpr;
+    buf[lane] = part;
+    __syncthreads();
+    uint32_t cur = tpr;
+    while (cur > 1u) {
+        const uint32_t half = (cur + 1u) >> 1;
+        if (lane + half < cur) buf[lane] += buf[lane + half];
+        __syncthreads();
+        cur = half;
+    }
+    return buf[0];
+}
+
+// fp32 rounding of 1/sqrt(d) for d > 0 in fp64: hardware estimate refined by
+// two Newton steps, which leaves an error of a few fp64 ulps -- 2^29 times
+// finer than the fp32 cell the result is rounded into.
+__device__ __forceinline__ float rsqrt_to_f32(double d)
+{
+    double y = __builtin_amdgcn_rsq(d);
+    if (d > 0.0 && d < __builtin_huge_val()) {
+        const double hd = 0.5 * d;
+        y = y * __builtin_fma(-hd * y, y, 1.5);
+        y = y * __builtin_fma(-hd * y, y, 1.5);
+    }
+    return static_cast<float>(y);
+}
+
+// Workgroup b of nb -> position in row order such that the workgroups that
+// land on one XCD (dispatch is round-robin over 8 XCDs) cover one contiguous
+// range of rows.  Bijective for any nb.
+__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t nb)
+{
+    const uint32_t xcd = b & 7u, idx = b >> 3;
+    const uint32_t q = nb >> 3, rem = nb & 7u;
+    return xcd * q + (xcd < rem ? xcd : rem) + idx;
+}
+
+template <int DT, int VEC, int CPT, int UNR>
+__device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restrict__ rp,
+                                            const void* __restrict__ wp, float eps, double inv_n,
+                                            int64_t M, int32_t N, uint32_t flags, int32_t reduce)
+{
+    using T = dt_traits<DT>;
+    constexpr int XB = T::XB, RB = T::RB;
+    constexpr bool BF = T::BF;
+    extern __shared__ double lds[];
+
+    const uint32_t tpr = blockDim.x, rpw = blockDim.y;
+    const uint32_t lane = threadIdx.x, ry = threadIdx.y;
+    uint32_t bid = blockIdx.x;
+    if (flags & FLAG_XCD_CONTIG) bid = xcd_contiguous(bid, gridDim.x);
+
+    // Workgroup base is wave-uniform; the per-thread part fits 32 bits.
+    const int64_t row0 = static_cast<int64_t>(bid) * rpw;
+    const int64_t left = M - row0;                        // rows available to this workgroup (>= 1)
+    const bool row_ok = static_cast<int64_t>(ry) < left;
+    const uint32_t ryc = row_ok ? ry : static_cast<uint32_t>(left - 1);
+    char* xbase = static_cast<char*>(xp) + row0 * N * XB;
+    char* rbase = static_cast<char*>(rp) + row0 * N * RB;
+    const char* wbase = static_cast<const char*>(wp);
+    const uint32_t rowoff = ryc * static_cast<uint32_t>(N);   // elements
+    const uint32_t col0 = lane * VEC;
+    const uint32_t stride = tpr * VEC;
+    const uint32_t nlast = static_cast<uint32_t>(N) - VEC;
+
+    float h[CPT][VEC];
+    double acc = 0.0;
+
+#pragma unroll
+    for (int g = 0; g < CPT; g += UNR) {
+        raw_t<XB * VEC> xv[UNR];
+        raw_t<RB * VEC> rv[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (g + u < CPT) {
+                const uint32_t col = col0 + static_cast<uint32_t>(g + u) * stride;
+                const uint32_t colc = col < nlast ? col : nlast;      // clamp: tail lanes re-read valid data
+                ld_raw<XB * VEC>(xbase + static_cast<uint64_t>((rowoff + colc) * XB), xv[u]);
+                ld_raw<RB * VEC>(rbase + static_cast<uint64_t>((rowoff + colc) * RB), rv[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (g + u < CPT) {
+                const int c = g + u;
+                const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    h[c][e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                if (row_ok && col <= nlast) {
+                    raw_t<RB * VEC> out;
+                    pack_vec<RB, BF, VEC>(h[c], out);
+                    st_raw<RB * VEC>(rbase + static_cast<uint64_t>((rowoff + col) * RB), out);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const double hd = static_cast<double>(h[c][e]);
+                        acc = __builtin_fma(hd, hd, acc);
+                    }
+                }
+            }
+        }
+        if (g + UNR < CPT) __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // Weights: tiny, L2-resident after the first workgroups; issue before the
+    // reduction so their latency hides behind it.
+    raw_t<XB * VEC> wv[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+        const uint32_t colc = col < nlast ? col : nlast;
+        ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(colc * XB), wv[c]);
+    }
+
+    const double ss = row_sum(acc, reduce, tpr, lane, ry, lds);
+    const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
+
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+        float y[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float t = h[c][e] * rstd;
+            y[e] = t * get_elem<XB, BF>(wv[c], e);
+        }
+        if (row_ok && col <= nlast) {
+            raw_t<XB * VEC> out;
+            pack_vec<XB, BF, VEC>(y, out);
+            st_raw<XB * VEC>(xbase + static_cast<uint64_t>((rowoff + col) * XB), out);
+        }
+    }
+}
+
+}  // namespace addrms

@@ -1,0 +1,418 @@
+// HIP side of libaddrms: kernel dispatch (addrms_run), the measurement harness
+// and correctness gate used by the search (Algorithm 1: Validate, Search,
+// EvaluatePerformance), and the probe kernels.
+#include <hip/hip_runtime.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <mutex>
+#include <vector>
+
+#include "addrms_internal.h"
+#include "addrms_kernel.h"
+
+// Declarations of every kernel instance and the table of their addresses, in
+// the order of the instance list the deriver uses.
+#include "gen_dispatch_decl.inc"
+struct DispatchEntry { int dt, vec, cpt, unr; const void* fn; };
+static const DispatchEntry kDispatch[] = {
+#include "gen_dispatch_rows.inc"
+};
+
+using namespace addrms_host;
+
+namespace {
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return fail(ADDRMS_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));            \
+    } while (0)
+
+bool dispatch_consistent()
+{
+    static const bool ok = [] {
+        if (static_cast<int>(sizeof(kDispatch) / sizeof(kDispatch[0])) != n_instances()) return false;
+        for (int i = 0; i < n_instances(); ++i) {
+            const Instance& in = instance(i);
+            const DispatchEntry& d = kDispatch[i];
+            if (d.dt != in.dt || d.vec != in.vec || d.cpt != in.cpt || d.unr != in.unr) return false;
+        }
+        return true;
+    }();
+    return ok;
+}
+
+bool aligned(const void* p, int bytes) { return (reinterpret_cast<uintptr_t>(p) % static_cast<uintptr_t>(bytes)) == 0; }
+
+// Launch with every check already done.
+int launch(const Feas& f, const addrms_cfg& c, void* x, void* r, const void* w, float eps, int64_t M, int64_t N,
+           hipStream_t stream)
+{
+    double inv_n = 1.0 / static_cast<double>(N);
+    long long m = M;
+    int n = static_cast<int>(N);
+    unsigned flags = static_cast<unsigned>(c.flags);
+    int reduce = c.reduce;
+    void* args[] = {&x, &r, &w, &eps, &inv_n, &m, &n, &flags, &reduce};
+    const dim3 grid(static_cast<unsigned>(n_workgroups(c, M)));
+    const dim3 block(static_cast<unsigned>(c.threads_per_row), static_cast<unsigned>(c.rows_per_wg));
+    HIP_TRY(hipLaunchKernel(kDispatch[f.inst].fn, grid, block, args, static_cast<size_t>(lds_bytes_for(c)), stream));
+    return ADDRMS_OK;
+}
+
+int resolve_cfg(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, addrms_cfg* out)
+{
+    if (cfg) { *out = *cfg; return ADDRMS_OK; }
+    if (table_lookup(M, N, dtype, out) == ADDRMS_OK) return ADDRMS_OK;
+    std::string why;
+    const int st = default_cfg(N, dtype, out, &why);
+    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
+}
+
+// ---- probe and harness kernels ---------------------------------------------------
+
+__global__ void rstd_probe_kernel(const double* ss, long long n, double inv_n, float eps, float* out)
+{
+    const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = addrms::rsqrt_to_f32(__builtin_fma(ss[i], inv_n, static_cast<double>(eps)));
+}
+
+// Reads two streams and writes both back complemented: the operator's traffic
+// pattern (one read and one write of every byte, both streams touched by the
+// same lane) with no arithmetic to speak of.
+__global__ __launch_bounds__(256) void stream_probe_kernel(addrms::u32x4* a, addrms::u32x4* b, long long n, int b_per_a)
+{
+    const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    addrms::u32x4 va = a[i];
+    if (b_per_a == 1) {
+        addrms::u32x4 vb = b[i];
+        a[i] = ~va; b[i] = ~vb;
+    } else {
+        addrms::u32x4 vb0 = b[2 * i], vb1 = b[2 * i + 1];
+        a[i] = ~va; b[2 * i] = ~vb0; b[2 * i + 1] = ~vb1;
+    }
+}
+
+// Synthetic activations for the tuner's own buffers: a counter-based hash mapped
+// to a roughly unit-variance symmetric distribution (sum of four uniforms).
+__device__ __forceinline__ uint32_t mix32(uint32_t v)
+{
+    v ^= v >> 16; v *= 0x7feb352du; v ^= v >> 15; v *= 0x846ca68bu; v ^= v >> 16;
+    return v;
+}
+__device__ __forceinline__ float synth_value(uint64_t i, uint32_t seed, float lo, float hi, bool bell)
+{
+    const uint32_t a = mix32(static_cast<uint32_t>(i) ^ seed);
+    const uint32_t b = mix32(a ^ static_cast<uint32_t>(i >> 32) ^ 0x9e3779b9u);
+    if (!bell) return lo + (hi - lo) * (static_cast<float>(a >> 8) * (1.0f / 16777216.0f));
+    const float u = static_cast<float>(a & 0xffffu) + static_cast<float>(a >> 16) +
+                    static_cast<float>(b & 0xffffu) + static_cast<float>(b >> 16);
+    return (u * (1.0f / 65536.0f) - 2.0f) * 1.7320508f;   // variance 4/12 -> 1
+}
+template <int ES, bool BF>
+__global__ void fill_kernel(void* p, long long n, uint32_t seed, float lo, float hi, int bell)
+{
+    const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float v = synth_value(static_cast<uint64_t>(i), seed, lo, hi, bell != 0);
+    if constexpr (ES == 4) static_cast<float*>(p)[i] = v;
+    else static_cast<uint16_t*>(p)[i] = static_cast<uint16_t>(addrms::pack2<BF>(v, 0.0f) & 0xffffu);
+}
+
+// Correctness gate d(S~(x), S(x)) <= eps (Section 3.1): residual must match bit
+// for bit; y may differ by at most `tol` units in the last place of its format.
+// counts[0] = residual mismatches, counts[1] = y elements beyond tol, counts[2] = max y distance.
+template <int ES>
+__device__ __forceinline__ long long ordered_bits(const void* p, long long i)
+{
+    if constexpr (ES == 4) {
+        const uint32_t u = static_cast<const uint32_t*>(p)[i];
+        const long long mag = u & 0x7fffffffu;
+        return (u >> 31) ? -mag : mag;
+    } else {
+        const uint32_t u = static_cast<const uint16_t*>(p)[i];
+        const long long mag = u & 0x7fffu;
+        return (u >> 15) ? -mag : mag;
+    }
+}
+template <int XB, int RB>
+__global__ void compare_kernel(const void* y, const void* y_ref, const void* r, const void* r_ref, long long n,
+                               unsigned tol, unsigned* counts)
+{
+    const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    bool rbad;
+    if constexpr (RB == 4) rbad = static_cast<const uint32_t*>(r)[i] != static_cast<const uint32_t*>(r_ref)[i];
+    else rbad = static_cast<const uint16_t*>(r)[i] != static_cast<const uint16_t*>(r_ref)[i];
+    if (rbad) atomicAdd(&counts[0], 1u);
+    long long d = ordered_bits<XB>(y, i) - ordered_bits<XB>(y_ref, i);
+    if (d < 0) d = -d;
+    if (d > 0) {
+        const unsigned du = d > 0xffffffffll ? 0xffffffffu : static_cast<unsigned>(d);
+        if (du > tol) atomicAdd(&counts[1], 1u);
+        atomicMax(&counts[2], du);
+    }
+}
+
+int fill(void* p, int64_t n, int es, bool bf, uint32_t seed, float lo, float hi, bool bell, hipStream_t st)
+{
+    if (n == 0) return ADDRMS_OK;
+    const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
+    if (es == 4) hipLaunchKernelGGL((fill_kernel<4, false>), grid, block, 0, st, p, (long long)n, seed, lo, hi, bell ? 1 : 0);
+    else if (bf) hipLaunchKernelGGL((fill_kernel<2, true>), grid, block, 0, st, p, (long long)n, seed, lo, hi, bell ? 1 : 0);
+    else hipLaunchKernelGGL((fill_kernel<2, false>), grid, block, 0, st, p, (long long)n, seed, lo, hi, bell ? 1 : 0);
+    HIP_TRY(hipGetLastError());
+    return ADDRMS_OK;
+}
+
+// ---- measurement harness ------------------------------------------------------------
+// Owns: one pristine input set, one reference-output set, and `nsets` working
+// sets that the timed launches rotate through so that their combined footprint
+// exceeds the last-level caches.
+struct Harness {
+    int64_t M = 0, N = 0;
+    int dtype = 0;
+    float eps = 1e-6f;
+    int nsets = 0;
+    size_t xbytes = 0, rbytes = 0, wbytes = 0;
+    char* pool = nullptr;
+    char *x0 = nullptr, *r0 = nullptr, *yref = nullptr, *rref = nullptr, *w = nullptr;
+    std::vector<char*> xs, rs;
+    unsigned* counts = nullptr;
+    hipStream_t stream = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    bool have_ref = false;
+    addrms_cfg ref_cfg{};
+
+    static size_t pad(size_t b) { return (b + 255) / 256 * 256; }
+
+    int init(int64_t m, int64_t n, int dt, float e, bool rotate)
+    {
+        M = m; N = n; dtype = dt; eps = e;
+        xbytes = static_cast<size_t>(M) * N * x_bytes(dt);
+        rbytes = static_cast<size_t>(M) * N * r_bytes(dt);
+        wbytes = static_cast<size_t>(N) * x_bytes(dt);
+        const size_t set = pad(xbytes) + pad(rbytes);
+        // enough rotating sets that two laps exceed twice the last-level cache plus the L2s
+        const size_t want = 2 * (static_cast<size_t>(hw().last_level_cache_bytes) +
+                                 static_cast<size_t>(hw().l2_bytes_per_xcd) * hw().xcds);
+        nsets = rotate ? static_cast<int>(std::min<size_t>(32, std::max<size_t>(2, (want + set - 1) / set))) : 1;
+        const size_t total = set * (nsets + 2) + pad(wbytes) + 256;
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), total));
+        char* p = pool;
+        auto take = [&](size_t b) { char* q = p; p += pad(b); return q; };
+        x0 = take(xbytes); r0 = take(rbytes); yref = take(xbytes); rref = take(rbytes); w = take(wbytes);
+        counts = reinterpret_cast<unsigned*>(take(256));
+        for (int i = 0; i < nsets; ++i) { xs.push_back(take(xbytes)); rs.push_back(take(rbytes)); }
+        HIP_TRY(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
+        HIP_TRY(hipEventCreate(&ev0));
+        HIP_TRY(hipEventCreate(&ev1));
+        const bool bf = dt == ADDRMS_BF16;
+        int st = fill(x0, M * N, x_bytes(dt), bf, 0x1234567u, 0, 0, true, stream);
+        if (st == ADDRMS_OK) st = fill(r0, M * N, r_bytes(dt), bf, 0x89abcdeu, 0, 0, true, stream);
+        if (st == ADDRMS_OK) st = fill(w, N, x_bytes(dt), bf, 0x5555aaau, 0.5f, 1.5f, false, stream);
+        if (st != ADDRMS_OK) return st;
+        for (int i = 0; i < nsets; ++i) {
+            HIP_TRY(hipMemcpyAsync(xs[i], x0, xbytes, hipMemcpyDeviceToDevice, stream));
+            HIP_TRY(hipMemcpyAsync(rs[i], r0, rbytes, hipMemcpyDeviceToDevice, stream));
+        }
+        HIP_TRY(hipStreamSynchronize(stream));
+        return ADDRMS_OK;
+    }
+
+    ~Harness()
+    {
+        if (ev0) (void)hipEventDestroy(ev0);
+        if (ev1) (void)hipEventDestroy(ev1);
+        if (stream) (void)hipStreamDestroy(stream);
+        if (pool) (void)hipFree(pool);
+    }
+
+    int run_on(const addrms_cfg& c, const Feas& f, int set) { return launch(f, c, xs[set], rs[set], w, eps, M, N, stream); }
+
+    int make_reference(const addrms_cfg& c)
+    {
+        const Feas f = check_cfg(c, M, N, dtype);
+        if (f.status != ADDRMS_OK) return fail(f.status, "reference cfg infeasible: %s", f.reason.c_str());
+        HIP_TRY(hipMemcpyAsync(yref, x0, xbytes, hipMemcpyDeviceToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(rref, r0, rbytes, hipMemcpyDeviceToDevice, stream));
+        const int st = launch(f, c, yref, rref, w, eps, M, N, stream);
+        if (st != ADDRMS_OK) return st;
+        HIP_TRY(hipStreamSynchronize(stream));
+        have_ref = true;
+        ref_cfg = c;
+        return ADDRMS_OK;
+    }
+
+    // 0 if cfg reproduces the reference output on the pristine inputs.
+    int validate(const addrms_cfg& c)
+    {
+        const Feas f = check_cfg(c, M, N, dtype);
+        if (f.status != ADDRMS_OK) return f.status;
+        HIP_TRY(hipMemcpyAsync(xs[0], x0, xbytes, hipMemcpyDeviceToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(rs[0], r0, rbytes, hipMemcpyDeviceToDevice, stream));
+        int st = run_on(c, f, 0);
+        if (st != ADDRMS_OK) return st;
+        {
+            const long long n = static_cast<long long>(M) * N;
+            const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
+            HIP_TRY(hipMemsetAsync(counts, 0, 16, stream));
+            const int xb = x_bytes(dtype), rb = r_bytes(dtype);
+            if (xb == 2 && rb == 2) hipLaunchKernelGGL((compare_kernel<2, 2>), grid, block, 0, stream, xs[0], yref, rs[0], rref, n, 1u, counts);
+            else if (xb == 2) hipLaunchKernelGGL((compare_kernel<2, 4>), grid, block, 0, stream, xs[0], yref, rs[0], rref, n, 1u, counts);
+            else hipLaunchKernelGGL((compare_kernel<4, 4>), grid, block, 0, stream, xs[0], yref, rs[0], rref, n, 1u, counts);
+            HIP_TRY(hipGetLastError());
+        }
+        unsigned h[4] = {0, 0, 0, 0};
+        HIP_TRY(hipMemcpyAsync(h, counts, 16, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        if (h[0] != 0 || h[1] != 0)
+            return fail(ADDRMS_ERR_INFEASIBLE_CFG, "candidate %s disagrees with the reference: %u residual elements "
+                        "differ, %u outputs beyond 1 ulp (max distance %u)", cfg_json(c).c_str(), h[0], h[1], h[2]);
+        return ADDRMS_OK;
+    }
+
+    int measure(const addrms_cfg& c, int warmup, int reps, double* mean_us)
+    {
+        const Feas f = check_cfg(c, M, N, dtype);
+        if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+        int set = 0;
+        for (int i = 0; i < warmup; ++i) {
+            const int st = run_on(c, f, set);
+            if (st != ADDRMS_OK) return st;
+            set = (set + 1) % nsets;
+        }
+        HIP_TRY(hipEventRecord(ev0, stream));
+        for (int i = 0; i < reps; ++i) {
+            const int st = run_on(c, f, set);
+            if (st != ADDRMS_OK) return st;
+            set = (set + 1) % nsets;
+        }
+        HIP_TRY(hipEventRecord(ev1, stream));
+        HIP_TRY(hipEventSynchronize(ev1));
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, ev0, ev1));
+        *mean_us = static_cast<double>(ms) * 1000.0 / reps;
+        return ADDRMS_OK;
+    }
+};
+
+int backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<Harness*>(user)->validate(*cfg); }
+int backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
+{
+    return static_cast<Harness*>(user)->measure(*cfg, warmup, reps, us);
+}
+
+std::mutex g_tune_mu;
+
+}  // namespace
+
+extern "C" {
+
+int addrms_run(void* x, void* residual, const void* weight, float eps, int64_t M, int64_t N, int dtype,
+               const addrms_cfg* cfg, void* stream)
+{
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0 (got M=%lld N=%lld)",
+                                     (long long)M, (long long)N);
+    if (M == 0) return ADDRMS_OK;
+    if (!x || !residual || !weight) return fail(ADDRMS_ERR_INVALID_ARG, "x, residual and weight must not be NULL");
+    if (M > (1ll << 31) - 1) return fail(ADDRMS_ERR_INVALID_ARG, "M=%lld exceeds the 2^31-1 row limit", (long long)M);
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    addrms_cfg c{};
+    int st = resolve_cfg(cfg, M, N, dtype, &c);
+    if (st != ADDRMS_OK) return st;
+    const Feas f = check_cfg(c, M, N, dtype);
+    if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+    const int xa = c.vec * x_bytes(dtype), ra = std::min(16, c.vec * r_bytes(dtype));
+    if (!aligned(x, xa) || !aligned(weight, xa) || !aligned(residual, ra))
+        return fail(ADDRMS_ERR_MISALIGNED, "x and weight must be %d-byte aligned and residual %d-byte aligned for vec=%d",
+                    xa, ra, c.vec);
+    return launch(f, c, x, residual, weight, eps, M, N, static_cast<hipStream_t>(stream));
+}
+
+int addrms_tune(int64_t M, int64_t N, int dtype, const addrms_budget* budget, addrms_cfg* out_cfg,
+                addrms_tune_report* report)
+{
+    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M <= 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs M > 0 and N > 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_cfg dflt{};
+    std::string why;
+    int st = default_cfg(N, dtype, &dflt, &why);
+    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
+    Harness h;
+    const float eps = (budget && budget->eps > 0.0f) ? budget->eps : 1e-6f;
+    st = h.init(M, N, dtype, eps, true);
+    if (st != ADDRMS_OK) return st;
+    // S_ref: the default configuration's output on the pristine inputs.
+    if (check_cfg(dflt, M, N, dtype).status != ADDRMS_OK) {
+        std::vector<addrms_cfg> v;
+        enumerate(M, N, dtype, &v, nullptr);
+        if (v.empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
+        dflt = v.front();
+    }
+    st = h.make_reference(dflt);
+    if (st != ADDRMS_OK) return st;
+    addrms_backend be{&h, backend_validate, backend_measure};
+    addrms_tune_report local{};
+    st = run_search(M, N, dtype, budget, be, out_cfg, &local);
+    if (st != ADDRMS_OK) return st;
+    if (report) *report = local;
+    return addrms_table_insert(M, N, dtype, out_cfg, local.best_us);
+}
+
+int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,
+                   int rotate, double* mean_us)
+{
+    if (!mean_us) return fail(ADDRMS_ERR_INVALID_ARG, "mean_us is NULL");
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M <= 0 || N <= 0 || reps <= 0 || warmup < 0) return fail(ADDRMS_ERR_INVALID_ARG, "need M, N, reps > 0 and warmup >= 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    addrms_cfg c{};
+    int st = resolve_cfg(cfg, M, N, dtype, &c);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    Harness h;
+    st = h.init(M, N, dtype, eps, rotate != 0);
+    if (st != ADDRMS_OK) return st;
+    return h.measure(c, warmup, reps, mean_us);
+}
+
+int addrms_rstd_probe(const double* ss, int64_t n, int64_t N, float eps, float* out, void* stream)
+{
+    if (n < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "need n >= 0 and N > 0");
+    if (n == 0) return ADDRMS_OK;
+    if (!ss || !out) return fail(ADDRMS_ERR_INVALID_ARG, "ss and out must not be NULL");
+    const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
+    hipLaunchKernelGGL(rstd_probe_kernel, grid, block, 0, static_cast<hipStream_t>(stream), ss, (long long)n,
+                       1.0 / static_cast<double>(N), eps, out);
+    HIP_TRY(hipGetLastError());
+    return ADDRMS_OK;
+}
+
+int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype, void* stream)
+{
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
+    if (M == 0) return ADDRMS_OK;
+    if (!x || !residual) return fail(ADDRMS_ERR_INVALID_ARG, "x and residual must not be NULL");
+    const int64_t xb = M * N * x_bytes(dtype), rb = M * N * r_bytes(dtype);
+    if (xb % 16 != 0 || !aligned(x, 16) || !aligned(residual, 16))
+        return fail(ADDRMS_ERR_MISALIGNED, "the probe moves 16 bytes per lane: M*N*element size must be a multiple of 16 "
+                    "and both bases 16-byte aligned");
+    const long long n = xb / 16;
+    const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
+    hipLaunchKernelGGL(stream_probe_kernel, grid, block, 0, static_cast<hipStream_t>(stream),
+                       static_cast<addrms::u32x4*>(x), static_cast<addrms::u32x4*>(residual), n, static_cast<int>(rb / xb));
+    HIP_TRY(hipGetLastError());
+    return ADDRMS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,407 @@
+// Search over the feasible region (Algorithm 1 lines 19-21: for each input x,
+// theta*(x) = argmin over Theta_feasible of measured runtime; Section 3.2, Tuning
+// agent: candidates are compiled, run and timed, ranked, and the Top-K are
+// submitted for re-testing; Testing agent: every candidate passes a correctness
+// gate first).
+//
+// The search only sees a backend with two calls, validate(cfg) and
+// measure(cfg, warmup, reps), so the same code runs against the GPU and against
+// a synthetic cost function in the CPU tests.
+//
+// Strategies:
+//   exhaustive  the plain definition: time every feasible cfg with the
+//               confirmation protocol, then re-test the Top-K;
+//   guided      (1) coarse sweep: one representative launch shape per
+//               (vec, threads_per_row) class, short protocol;
+//               (2) descent: from the best few classes, move one knob at a time
+//               to the best unmeasured neighbour, trying first the moves that
+//               the static signals favour (more resident waves when the kernel
+//               is register-limited, more workgroups when the grid underfills
+//               the chip);
+//               (3) Top-K re-test with the confirmation protocol, interleaved
+//               so that clock drift hits all candidates alike.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <chrono>
+#include <map>
+#include <unordered_map>
+
+#include "addrms_internal.h"
+
+namespace addrms_host {
+namespace {
+
+using Clock = std::chrono::steady_clock;
+
+struct Cand {
+    addrms_cfg cfg{};
+    addrms_resources res{};
+    bool tried = false;      // validate and/or measure was attempted
+    bool failed = false;     // gate or launch failure: never ranked
+    double us = -1.0;        // screening time
+    int64_t order = 0;       // 1-based count of measured cfgs when first timed
+    double at_ms = 0.0;      // wall time of the first measurement
+};
+
+struct Searcher {
+    int64_t M, N;
+    int dtype;
+    addrms_budget b;
+    const addrms_backend& be;
+    std::vector<Cand> cands;
+    std::unordered_map<uint64_t, int> index;
+    int64_t n_measured = 0, n_failed = 0;
+    Clock::time_point t0 = Clock::now();
+    FILE* log = nullptr;
+    double bytes = 0.0;
+
+    Searcher(int64_t m, int64_t n, int dt, const addrms_budget& bud, const addrms_backend& backend)
+        : M(m), N(n), dtype(dt), b(bud), be(backend) {}
+
+    double elapsed_ms() const { return std::chrono::duration<double, std::milli>(Clock::now() - t0).count(); }
+    bool budget_left() const
+    {
+        if (b.max_candidates > 0 && n_measured >= b.max_candidates) return false;
+        if (b.max_wall_ms > 0.0 && elapsed_ms() >= b.max_wall_ms) return false;
+        return true;
+    }
+    int find(const addrms_cfg& c) const
+    {
+        auto it = index.find(cfg_key(c));
+        return it == index.end() ? -1 : it->second;
+    }
+
+    void log_eval(const char* phase, const Cand& c, bool pass, double us, int warmup, int reps)
+    {
+        if (!log) return;
+        fprintf(log,
+                "{\"event\":\"eval\",\"phase\":\"%s\",\"cfg\":%s,\"pass\":%s,\"us\":%.4f,\"gbps\":%.2f,"
+                "\"warmup\":%d,\"reps\":%d,\"signals\":{\"chunks_per_thread\":%d,\"vgprs\":%d,\"agprs\":%d,"
+                "\"lds_bytes\":%d,\"waves_per_wg\":%d,\"wgs_per_cu\":%d,\"waves_per_simd\":%d,\"workgroups\":%lld},"
+                "\"n_measured\":%lld,\"t_ms\":%.3f}\n",
+                phase, cfg_json(c.cfg).c_str(), pass ? "true" : "false", us, us > 0 ? bytes / us * 1e-3 : 0.0,
+                warmup, reps, c.res.chunks_per_thread, c.res.vgprs, c.res.agprs, c.res.lds_bytes, c.res.waves_per_wg,
+                c.res.wgs_per_cu, c.res.waves_per_simd, (long long)n_workgroups(c.cfg, M),
+                (long long)n_measured, elapsed_ms());
+    }
+
+    // Gate + screening measurement of candidate i.  Returns true if it now has a time.
+    bool eval(int i, const char* phase, int warmup, int reps)
+    {
+        Cand& c = cands[i];
+        if (c.tried) return !c.failed;
+        c.tried = true;
+        if (!b.skip_validation && be.validate && be.validate(be.user, &c.cfg) != 0) {
+            c.failed = true;
+            ++n_failed;
+            log_eval(phase, c, false, -1.0, 0, 0);
+            return false;
+        }
+        double us = 0.0;
+        if (be.measure(be.user, &c.cfg, warmup, reps, &us) != 0 || !(us > 0.0)) {
+            c.failed = true;
+            ++n_failed;
+            log_eval(phase, c, false, -1.0, warmup, reps);
+            return false;
+        }
+        ++n_measured;
+        c.us = us;
+        c.order = n_measured;
+        c.at_ms = elapsed_ms();
+        log_eval(phase, c, true, us, warmup, reps);
+        return true;
+    }
+
+    std::vector<int> ranked() const
+    {
+        std::vector<int> v;
+        for (int i = 0; i < static_cast<int>(cands.size()); ++i)
+            if (cands[i].tried && !cands[i].failed) v.push_back(i);
+        std::stable_sort(v.begin(), v.end(), [&](int a, int c) { return cands[a].us < cands[c].us; });
+        return v;
+    }
+
+    // ---- guided: stage 1 -------------------------------------------------------
+    // One representative per (vec, threads_per_row): wave reduction, identity
+    // mapping, workgroup nearest 256 threads, two chunks in flight.
+    std::vector<int> class_representatives() const
+    {
+        std::map<std::pair<int, int>, std::pair<double, int>> best;   // class -> (score, index)
+        for (int i = 0; i < static_cast<int>(cands.size()); ++i) {
+            const addrms_cfg& c = cands[i].cfg;
+            const double threads = static_cast<double>(c.threads_per_row) * c.rows_per_wg;
+            const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
+            const double score = fabs(log2(threads / 256.0)) + (c.reduce == ADDRMS_REDUCE_LDS ? 10.0 : 0.0) +
+                                 (c.flags ? 10.0 : 0.0) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
+            auto key = std::make_pair(-c.vec, c.threads_per_row);       // widest vector first
+            auto it = best.find(key);
+            if (it == best.end() || score < it->second.first) best[key] = {score, i};
+        }
+        std::vector<int> out;
+        for (auto& kv : best) out.push_back(kv.second.second);
+        return out;
+    }
+
+    // ---- guided: stage 2 -------------------------------------------------------
+    std::vector<int> neighbours(int i) const
+    {
+        const addrms_cfg c = cands[i].cfg;
+        std::vector<addrms_cfg> raw;
+        auto push = [&](addrms_cfg n) { raw.push_back(n); };
+        { addrms_cfg n = c; n.rows_per_wg *= 2; push(n); }
+        { addrms_cfg n = c; n.rows_per_wg /= 2; if (n.rows_per_wg >= 1) push(n); }
+        { addrms_cfg n = c; n.unroll *= 2; push(n); }
+        { addrms_cfg n = c; n.unroll /= 2; if (n.unroll >= 1) push(n); }
+        { addrms_cfg n = c; n.reduce ^= 1; push(n); }
+        { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_XCD_CONTIG; push(n); }
+        // threads_per_row: nearest feasible values above and below at this vec
+        int up = 0, down = 0;
+        for (const Cand& o : cands) {
+            if (o.cfg.vec != c.vec) continue;
+            const int t = o.cfg.threads_per_row;
+            if (t > c.threads_per_row && (up == 0 || t < up)) up = t;
+            if (t < c.threads_per_row && t > down) down = t;
+        }
+        for (int t : {up, down}) {
+            if (t == 0) continue;
+            addrms_cfg n = c; n.threads_per_row = t; push(n);
+            // keep the workgroup size when the row gets wider or narrower
+            n.rows_per_wg = std::max(1, c.rows_per_wg * c.threads_per_row / t); push(n);
+        }
+        // vec: same threads (more or fewer chunks), or same chunks (threads scaled)
+        for (int v : {c.vec * 2, c.vec / 2}) {
+            if (v < 1 || v > 8) continue;
+            addrms_cfg n = c; n.vec = v; push(n);
+            n.threads_per_row = c.threads_per_row * c.vec / v; push(n);
+        }
+        std::vector<int> out;
+        for (addrms_cfg n : raw) {
+            int j = find(n);
+            if (j < 0) {   // the unroll may no longer fit the new chunk count: clamp down once
+                for (int u = n.unroll / 2; u >= 1 && j < 0; u /= 2) { n.unroll = u; j = find(n); }
+            }
+            if (j >= 0 && j != i && std::find(out.begin(), out.end(), j) == out.end()) out.push_back(j);
+        }
+        return out;
+    }
+
+    // Static signals decide which neighbours are tried first.
+    int move_priority(const Cand& from, const Cand& to) const
+    {
+        int p = 0;
+        if (from.res.waves_per_simd < 4 && to.res.waves_per_simd > from.res.waves_per_simd) p += 2;
+        const int64_t resident = static_cast<int64_t>(hw().compute_units) * std::max(1, from.res.wgs_per_cu);
+        if (n_workgroups(from.cfg, M) < resident && n_workgroups(to.cfg, M) > n_workgroups(from.cfg, M)) p += 2;
+        if (to.cfg.vec > from.cfg.vec) p += 1;
+        return p;
+    }
+
+    void descend(int seed, int warmup, int reps)
+    {
+        int cur = seed;
+        for (int step = 0; step < 64 && budget_left(); ++step) {
+            std::vector<int> nb = neighbours(cur);
+            std::stable_sort(nb.begin(), nb.end(), [&](int a, int c) {
+                return move_priority(cands[cur], cands[a]) > move_priority(cands[cur], cands[c]);
+            });
+            int best = -1;
+            for (int j : nb) {
+                if (!cands[j].tried) {
+                    if (!budget_left()) break;
+                    eval(j, "descent", warmup, reps);
+                }
+                if (cands[j].tried && !cands[j].failed && (best < 0 || cands[j].us < cands[best].us)) best = j;
+            }
+            if (best < 0 || !(cands[best].us < cands[cur].us * 0.995)) break;
+            cur = best;
+        }
+    }
+};
+
+void fill_defaults(addrms_budget* b)
+{
+    if (b->top_k <= 0) b->top_k = 5;
+    if (b->top_k > ADDRMS_MAX_TOPK) b->top_k = ADDRMS_MAX_TOPK;
+    if (b->warmup <= 0) b->warmup = 20;
+    if (b->reps <= 0) b->reps = 100;
+    if (b->coarse_warmup <= 0) b->coarse_warmup = 3;
+    if (b->coarse_reps <= 0) b->coarse_reps = 15;
+    if (!(b->eps > 0.0f)) b->eps = 1e-6f;
+}
+
+}  // namespace
+
+int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, const addrms_backend& be,
+               addrms_cfg* out_cfg, addrms_tune_report* report)
+{
+    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
+    if (!be.measure) return fail(ADDRMS_ERR_INVALID_ARG, "backend has no measure function");
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M <= 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs M > 0 and N > 0");
+    addrms_budget b{};
+    if (budget) b = *budget;
+    if (b.strategy != ADDRMS_SEARCH_GUIDED && b.strategy != ADDRMS_SEARCH_EXHAUSTIVE)
+        return fail(ADDRMS_ERR_INVALID_ARG, "unknown search strategy %d", b.strategy);
+    fill_defaults(&b);
+
+    Searcher s(M, N, dtype, b, be);
+    s.bytes = static_cast<double>(addrms_algorithmic_bytes(M, N, dtype));
+    std::vector<addrms_cfg> feasible;
+    int64_t n_grid = 0;
+    enumerate(M, N, dtype, &feasible, &n_grid);
+    addrms_cfg dflt{};
+    std::string why;
+    const int dst = default_cfg(N, dtype, &dflt, &why);
+    if (dst != ADDRMS_OK || feasible.empty())
+        return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty for M=%lld N=%lld %s: %s", (long long)M,
+                    (long long)N, dtype_name(dtype), why.c_str());
+    // The default is feasible for any M except that a wave-filling row count may exceed a tiny M; keep it anyway.
+    if (check_cfg(dflt, M, N, dtype).status != ADDRMS_OK) {
+        bool found = false;
+        for (const addrms_cfg& c : feasible)
+            if (c.vec == dflt.vec && c.threads_per_row == dflt.threads_per_row) { dflt = c; found = true; break; }
+        if (!found) dflt = feasible.front();
+    }
+    s.cands.reserve(feasible.size());
+    for (const addrms_cfg& c : feasible) {
+        Cand cd;
+        cd.cfg = c;
+        cd.res = check_cfg(c, M, N, dtype).res;
+        s.index[cfg_key(c)] = static_cast<int>(s.cands.size());
+        s.cands.push_back(cd);
+    }
+    const int i_default = s.find(dflt);
+
+    if (b.log_path) {
+        s.log = fopen(b.log_path, "a");
+        if (!s.log) return fail(ADDRMS_ERR_IO, "cannot open log %s", b.log_path);
+        // prune histogram: which rule removed how many grid points
+        std::map<std::string, int64_t> pruned;
+        {
+            std::vector<int> tprs = {8, 16, 32};
+            for (int t = 64; t <= hw().max_threads_per_wg; t += 64) tprs.push_back(t);
+            for (int vec : {8, 4, 2, 1}) for (int tpr : tprs) for (int rows : {1, 2, 4, 8, 16})
+                for (int red = 0; red < 2; ++red) for (int unr : {1, 2, 4, 8}) for (int fl = 0; fl < 2; ++fl) {
+                    addrms_cfg c{};
+                    c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows; c.reduce = red; c.unroll = unr; c.flags = fl;
+                    const Feas f = check_cfg(c, M, N, dtype);
+                    if (f.status != ADDRMS_OK) ++pruned[f.rule];
+                }
+        }
+        fprintf(s.log, "{\"event\":\"begin\",\"M\":%lld,\"N\":%lld,\"dtype\":\"%s\",\"strategy\":\"%s\",\"n_grid\":%lld,"
+                       "\"n_feasible\":%lld,\"default\":%s,\"pruned\":{",
+                (long long)M, (long long)N, dtype_name(dtype), b.strategy == ADDRMS_SEARCH_GUIDED ? "guided" : "exhaustive",
+                (long long)n_grid, (long long)feasible.size(), cfg_json(dflt).c_str());
+        bool first = true;
+        for (auto& kv : pruned) { fprintf(s.log, "%s\"%s\":%lld", first ? "" : ",", kv.first.c_str(), (long long)kv.second); first = false; }
+        fprintf(s.log, "}}\n");
+    }
+
+    // ---- screening ---------------------------------------------------------------
+    if (b.strategy == ADDRMS_SEARCH_EXHAUSTIVE) {
+        if (i_default >= 0) s.eval(i_default, "default", b.warmup, b.reps);
+        for (int i = 0; i < static_cast<int>(s.cands.size()) && s.budget_left(); ++i)
+            s.eval(i, "exhaustive", b.warmup, b.reps);
+    } else {
+        if (i_default >= 0) s.eval(i_default, "default", b.coarse_warmup, b.coarse_reps);
+        for (int i : s.class_representatives()) {
+            if (!s.budget_left()) break;
+            s.eval(i, "sweep", b.coarse_warmup, b.coarse_reps);
+        }
+        std::vector<int> seeds = s.ranked();
+        // descend from the best three classes (distinct (vec, threads_per_row))
+        std::vector<int> starts;
+        for (int i : seeds) {
+            bool dup = false;
+            for (int j : starts)
+                dup = dup || (s.cands[j].cfg.vec == s.cands[i].cfg.vec &&
+                              s.cands[j].cfg.threads_per_row == s.cands[i].cfg.threads_per_row);
+            if (!dup) starts.push_back(i);
+            if (starts.size() == 3) break;
+        }
+        for (int i : starts) s.descend(i, b.coarse_warmup, b.coarse_reps);
+    }
+
+    std::vector<int> order = s.ranked();
+    if (order.empty()) {
+        if (s.log) { fprintf(s.log, "{\"event\":\"end\",\"status\":\"no_result\"}\n"); fclose(s.log); }
+        return fail(ADDRMS_ERR_NO_RESULT, "no candidate could be measured within the budget (%lld failed)",
+                    (long long)s.n_failed);
+    }
+
+    // ---- Top-K confirmation re-test ----------------------------------------------
+    std::vector<int> top(order.begin(), order.begin() + std::min<size_t>(order.size(), b.top_k));
+    bool default_in_top = std::find(top.begin(), top.end(), i_default) != top.end();
+    std::vector<int> confirm = top;
+    if (i_default >= 0 && !default_in_top && s.cands[i_default].tried && !s.cands[i_default].failed)
+        confirm.push_back(i_default);
+    std::vector<double> sum(confirm.size(), 0.0);
+    std::vector<int> cnt(confirm.size(), 0);
+    const int rounds = 2;
+    for (int r = 0; r < rounds; ++r)
+        for (size_t k = 0; k < confirm.size(); ++k) {
+            double us = 0.0;
+            if (be.measure(be.user, &s.cands[confirm[k]].cfg, b.warmup, b.reps, &us) == 0 && us > 0.0) {
+                sum[k] += us;
+                ++cnt[k];
+                s.log_eval("confirm", s.cands[confirm[k]], true, us, b.warmup, b.reps);
+            }
+        }
+    std::vector<std::pair<double, int>> confirmed;   // (mean us, cand index)
+    double default_us = -1.0;
+    for (size_t k = 0; k < confirm.size(); ++k) {
+        if (cnt[k] == 0) continue;
+        const double mean = sum[k] / cnt[k];
+        if (confirm[k] == i_default) default_us = mean;
+        if (k < top.size()) confirmed.push_back({mean, confirm[k]});
+    }
+    if (confirmed.empty()) {
+        if (s.log) { fprintf(s.log, "{\"event\":\"end\",\"status\":\"no_result\"}\n"); fclose(s.log); }
+        return fail(ADDRMS_ERR_NO_RESULT, "confirmation re-test failed for every Top-K candidate");
+    }
+    std::stable_sort(confirmed.begin(), confirmed.end());
+    const Cand& win = s.cands[confirmed.front().second];
+    *out_cfg = win.cfg;
+
+    if (report) {
+        memset(report, 0, sizeof *report);
+        report->n_grid = n_grid;
+        report->n_feasible = static_cast<int64_t>(feasible.size());
+        report->n_measured = s.n_measured;
+        report->n_failed = s.n_failed;
+        report->best_found_at = win.order;
+        report->best_us = confirmed.front().first;
+        report->default_us = default_us;
+        report->time_to_best_ms = win.at_ms;
+        report->best = win.cfg;
+        report->default_cfg = dflt;
+        report->n_topk = static_cast<int32_t>(confirmed.size());
+        for (size_t k = 0; k < confirmed.size(); ++k) {
+            report->topk[k] = s.cands[confirmed[k].second].cfg;
+            report->topk_us[k] = confirmed[k].first;
+        }
+        report->wall_ms = s.elapsed_ms();
+    }
+    if (s.log) {
+        fprintf(s.log, "{\"event\":\"end\",\"status\":\"ok\",\"best\":%s,\"best_us\":%.4f,\"default_us\":%.4f,"
+                       "\"n_measured\":%lld,\"n_failed\":%lld,\"best_found_at\":%lld,\"time_to_best_ms\":%.3f,"
+                       "\"wall_ms\":%.3f}\n",
+                cfg_json(win.cfg).c_str(), confirmed.front().first, default_us, (long long)s.n_measured,
+                (long long)s.n_failed, (long long)win.order, win.at_ms, s.elapsed_ms());
+        fclose(s.log);
+    }
+    return ADDRMS_OK;
+}
+
+}  // namespace addrms_host
+
+extern "C" int addrms_tune_with_backend(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
+                                        const addrms_backend* backend, addrms_cfg* out_cfg,
+                                        addrms_tune_report* report)
+{
+    if (!backend) return addrms_host::fail(ADDRMS_ERR_INVALID_ARG, "backend is NULL");
+    return addrms_host::run_search(M, N, dtype, budget, *backend, out_cfg, report);
+}

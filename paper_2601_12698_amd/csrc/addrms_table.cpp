@@ -1,0 +1,148 @@
+// Specialised configuration table D_spec (Algorithm 1 line 23, BuildSpecialized):
+// (dtype, N, M) -> configuration, with a nearest-M fallback for row counts that
+// were never tuned, and a plain-text file form so a tuning run can be reused.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <map>
+#include <mutex>
+#include <tuple>
+
+#include "addrms_internal.h"
+
+namespace addrms_host {
+
+struct Entry { addrms_cfg cfg; double us; };
+using Key = std::tuple<int, int64_t, int64_t>;   // dtype, N, M
+
+static std::mutex g_mu;
+static std::map<Key, Entry>& table()
+{
+    static std::map<Key, Entry> t;
+    return t;
+}
+
+int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    auto& t = table();
+    auto it = t.find(Key(dtype, N, M));
+    if (it != t.end()) { *out = it->second.cfg; return ADDRMS_OK; }
+    // Same (dtype, N): nearest M in ratio whose cfg is still feasible at this M.
+    double best = 0.0;
+    const Entry* pick = nullptr;
+    for (auto lo = t.lower_bound(Key(dtype, N, INT64_MIN)); lo != t.end(); ++lo) {
+        if (std::get<0>(lo->first) != dtype || std::get<1>(lo->first) != N) break;
+        const double d = fabs(log(static_cast<double>(std::max<int64_t>(std::get<2>(lo->first), 1)) /
+                                  static_cast<double>(std::max<int64_t>(M, 1))));
+        if (pick && d >= best) continue;
+        if (check_cfg(lo->second.cfg, M, N, dtype).status != ADDRMS_OK) continue;
+        best = d;
+        pick = &lo->second;
+    }
+    if (!pick) return ADDRMS_ERR_NO_RESULT;
+    *out = pick->cfg;
+    return ADDRMS_OK;
+}
+
+static const char kMagic[] = "addrms-table 1 gfx950";
+
+}  // namespace addrms_host
+
+using namespace addrms_host;
+
+extern "C" {
+
+int addrms_table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, double mean_us)
+{
+    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
+    const Feas f = check_cfg(*cfg, M, N, dtype);
+    if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+    std::lock_guard<std::mutex> lock(g_mu);
+    table()[Key(dtype, N, M)] = Entry{*cfg, mean_us};
+    return ADDRMS_OK;
+}
+
+int addrms_table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    const int st = table_lookup(M, N, dtype, out);
+    return st == ADDRMS_OK ? st : fail(st, "no table entry usable for M=%lld N=%lld dtype=%d",
+                                       (long long)M, (long long)N, dtype);
+}
+
+int64_t addrms_table_size(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    return static_cast<int64_t>(table().size());
+}
+
+void addrms_table_clear(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    table().clear();
+}
+
+int addrms_table_save(const char* path)
+{
+    if (!path) return fail(ADDRMS_ERR_INVALID_ARG, "path is NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    FILE* f = fopen(path, "w");
+    if (!f) return fail(ADDRMS_ERR_IO, "cannot open %s for writing", path);
+    fprintf(f, "%s\n# dtype M N vec threads_per_row rows_per_wg reduce unroll flags mean_us\n", kMagic);
+    for (const auto& kv : table()) {
+        const addrms_cfg& c = kv.second.cfg;
+        fprintf(f, "%d %lld %lld %d %d %d %d %d %d %.6f\n", std::get<0>(kv.first),
+                (long long)std::get<2>(kv.first), (long long)std::get<1>(kv.first), c.vec, c.threads_per_row,
+                c.rows_per_wg, c.reduce, c.unroll, c.flags, kv.second.us);
+    }
+    const bool bad = ferror(f) != 0;
+    if (fclose(f) != 0 || bad) return fail(ADDRMS_ERR_IO, "write to %s failed", path);
+    return ADDRMS_OK;
+}
+
+int addrms_table_load(const char* path)
+{
+    if (!path) return fail(ADDRMS_ERR_INVALID_ARG, "path is NULL");
+    FILE* f = fopen(path, "r");
+    if (!f) return fail(ADDRMS_ERR_IO, "cannot open %s", path);
+    char line[512];
+    std::map<Key, Entry> staged;
+    int lineno = 0;
+    bool have_magic = false;
+    while (fgets(line, sizeof line, f)) {
+        ++lineno;
+        size_t len = strlen(line);
+        while (len && (line[len - 1] == '\n' || line[len - 1] == '\r')) line[--len] = '\0';
+        if (!have_magic) {
+            if (strcmp(line, kMagic) != 0) {
+                fclose(f);
+                return fail(ADDRMS_ERR_IO, "%s: not an addrms table for gfx950 (bad first line)", path);
+            }
+            have_magic = true;
+            continue;
+        }
+        if (len == 0 || line[0] == '#') continue;
+        int dtype; long long M, N; addrms_cfg c{}; double us; int used = 0;
+        const int got = sscanf(line, "%d %lld %lld %d %d %d %d %d %d %lf %n", &dtype, &M, &N, &c.vec,
+                               &c.threads_per_row, &c.rows_per_wg, &c.reduce, &c.unroll, &c.flags, &us, &used);
+        if (got != 10 || static_cast<size_t>(used) != len) {
+            fclose(f);
+            return fail(ADDRMS_ERR_IO, "%s:%d: malformed entry", path, lineno);
+        }
+        const Feas fe = check_cfg(c, M, N, dtype);
+        if (fe.status != ADDRMS_OK) {
+            fclose(f);
+            return fail(ADDRMS_ERR_IO, "%s:%d: entry is not feasible: %s", path, lineno, fe.reason.c_str());
+        }
+        staged[Key(dtype, N, M)] = Entry{c, us};
+    }
+    fclose(f);
+    if (!have_magic) return fail(ADDRMS_ERR_IO, "%s: empty file", path);
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (const auto& kv : staged) table()[kv.first] = kv.second;
+    return ADDRMS_OK;
+}
+
+}  // extern "C"

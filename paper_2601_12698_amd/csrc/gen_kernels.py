@@ -1,0 +1,83 @@
+"""Writes the instantiation list of the kernel template.
+
+The template in ``addrms_kernel.h`` has three compile-time knobs (VEC, CPT,
+UNR) per storage format.  This script emits, into a build directory:
+
+  kern_d<DT>_v<VEC>.hip   one translation unit per (format, vector width),
+                          each kernel an ``extern "C"`` wrapper with a readable
+                          name so the compiler's resource remarks can be
+                          matched back to knob values;
+  gen_dispatch_decl.inc   declarations of every kernel, and
+  gen_dispatch_rows.inc   the rows of the table of their addresses, both
+                          included by the runtime;
+  gen_instances.inc       the list of instances (knob values, workgroup bound),
+                          included by the host-only deriver.
+
+The set must agree with the index arithmetic in ``addrms_internal.h``.
+"""
+from __future__ import annotations
+
+import os
+import sys
+
+DTS = (0, 1, 2, 3)                      # bf16, fp16, fp16+fp32 residual, fp32
+VECS = (1, 2, 4, 8)
+CPTS = (1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16)
+UNRS = (1, 2, 4, 8)
+MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 values per thread
+BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
+
+
+def instances():
+    for dt in DTS:
+        for vec in VECS:
+            for cpt in CPTS:
+                if vec * cpt > MAX_ELEMS:
+                    continue
+                for unr in UNRS:
+                    if unr > cpt:
+                        continue
+                    maxt = 1024 if vec * cpt <= BIG_ELEMS else 256
+                    yield dt, vec, cpt, unr, maxt
+
+
+def name(dt, vec, cpt, unr):
+    return f"addrms_k_d{dt}_v{vec}_c{cpt}_u{unr}"
+
+
+ARGS = ("void* x, void* r, const void* w, float eps, double inv_n, "
+        "long long M, int N, unsigned flags, int reduce")
+
+
+def main(outdir: str) -> None:
+    os.makedirs(outdir, exist_ok=True)
+    units = {}
+    for dt, vec, cpt, unr, maxt in instances():
+        units.setdefault((dt, vec), []).append((cpt, unr, maxt))
+    for (dt, vec), lst in units.items():
+        lines = ['#include "addrms_kernel.h"', ""]
+        for cpt, unr, maxt in lst:
+            lines.append(
+                f'extern "C" __global__ __launch_bounds__({maxt}) void {name(dt, vec, cpt, unr)}({ARGS})\n'
+                f"{{ addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}>(x, r, w, eps, inv_n, M, N, flags, reduce); }}")
+        _write(os.path.join(outdir, f"kern_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")
+    decl, table, inst = [], [], []
+    for dt, vec, cpt, unr, maxt in instances():
+        n = name(dt, vec, cpt, unr)
+        decl.append(f'extern "C" __global__ void {n}({ARGS});')
+        table.append(f"    {{{dt}, {vec}, {cpt}, {unr}, reinterpret_cast<const void*>(&{n})}},")
+        inst.append(f"    {{{dt}, {vec}, {cpt}, {unr}, {maxt}}},")
+    _write(os.path.join(outdir, "gen_dispatch_decl.inc"), "\n".join(decl) + "\n")
+    _write(os.path.join(outdir, "gen_dispatch_rows.inc"), "\n".join(table) + "\n")
+    _write(os.path.join(outdir, "gen_instances.inc"), "\n".join(inst) + "\n")
+
+
+def _write(path: str, text: str) -> None:
+    if os.path.exists(path) and open(path).read() == text:
+        return
+    with open(path, "w") as f:
+        f.write(text)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1])
