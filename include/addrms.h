@@ -219,6 +219,14 @@ int addrms_rstd_probe(const double* ss, int64_t n, int64_t N, float eps, float* 
  * 16 bytes per lane.  Same argument meaning as addrms_run. */
 int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype, void* stream);
 
+/* What the HIP runtime on the current device reports for the kernel instance and
+ * launch shape a cfg selects: registers and scratch from the loaded code object,
+ * resident workgroups per CU from the runtime's occupancy query.  Fills vgprs
+ * (architected + accumulation registers as the runtime counts them), scratch_bytes,
+ * lds_bytes, max_threads, waves_per_wg, wgs_per_cu and waves_per_simd of `out` (host);
+ * other fields are zero.  Used to pin the deriver's model against the device. */
+int addrms_device_resources(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, addrms_resources* out);
+
 /* Bytes the operator must move for (M, N, dtype): every x and residual element
  * read once and written once, weight read once.  Negative on bad arguments. */
 int64_t addrms_algorithmic_bytes(int64_t M, int64_t N, int dtype);

@@ -121,6 +121,7 @@ SIGNATURES = {
     "addrms_table_clear": (None, []),
     "addrms_table_save": (c_int, [c_char_p]),
     "addrms_table_load": (c_int, [c_char_p]),
+    "addrms_device_resources": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, POINTER(Resources)]),
     "addrms_rstd_probe": (c_int, [c_void_p, c_int64, c_int64, c_float, c_void_p, c_void_p]),
     "addrms_stream_probe": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p]),
     "addrms_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
@@ -309,6 +310,12 @@ def addrms_table_save(path: str) -> None:
 
 def addrms_table_load(path: str) -> None:
     _check(load().addrms_table_load(path.encode()))
+
+
+def addrms_device_resources(cfg: Cfg, M: int, N: int, dtype) -> Resources:
+    res = Resources()
+    _check(load().addrms_device_resources(byref(cfg), M, N, _dtype_id(dtype), byref(res)))
+    return res
 
 
 def addrms_rstd_probe(ss, N: int, eps: float, out, stream=None) -> None:

@@ -25,7 +25,10 @@ LIB = os.path.join(HERE, "libaddrms.so")
 ARCH = "gfx950"
 
 # -packed-fp32-ops off: packed fp32 instruction selection stays disabled for all device code.
-DEVICE_FLAGS = [f"--offload-arch={ARCH}", "-O3", "-fPIC", "-std=c++17",
+# -ffp-contract=off: the operator rounds every fp32 product before the next step (and before the
+# conversion to storage); contraction would fuse multiply+convert into one mixed-precision
+# instruction with a single rounding, which is a different result on exact ties.
+DEVICE_FLAGS = [f"--offload-arch={ARCH}", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off",
                 "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                 "-Wno-unused-command-line-argument"]
 HOST_FLAGS = ["-O2", "-fPIC", "-std=c++17", "-Wall", "-Wextra"]

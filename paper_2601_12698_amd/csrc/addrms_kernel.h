@@ -110,9 +110,14 @@ __device__ __forceinline__ float get_elem(const raw_t<BYTES>& v, int e)
 }
 
 // Two fp32 values rounded to nearest-even into one dword of 16-bit storage.
+// The empty asm pins both values in registers as finished fp32 results: without
+// it the compiler may fold the preceding fp32 multiply and this conversion into
+// one mixed-precision multiply that rounds once, which differs from rounding
+// the fp32 product first whenever that product is an exact tie of the format.
 template <bool BF>
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 {
+    asm volatile("" : "+v"(lo), "+v"(hi));
     f32x2 f = {lo, hi};
     if constexpr (BF) {
         bf16x2 b = __builtin_convertvector(f, bf16x2);

@@ -385,6 +385,30 @@ int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float
     return h.measure(c, warmup, reps, mean_us);
 }
 
+int addrms_device_resources(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, addrms_resources* out)
+{
+    if (!cfg || !out) return fail(ADDRMS_ERR_INVALID_ARG, "cfg and out must not be NULL");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    const Feas f = check_cfg(*cfg, M, N, dtype);
+    if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+    memset(out, 0, sizeof *out);
+    hipFuncAttributes attr;
+    HIP_TRY(hipFuncGetAttributes(&attr, kDispatch[f.inst].fn));
+    const int threads = cfg->threads_per_row * cfg->rows_per_wg;
+    int wgs = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs, kDispatch[f.inst].fn, threads,
+                                                         static_cast<size_t>(lds_bytes_for(*cfg))));
+    out->chunks_per_thread = f.res.chunks_per_thread;
+    out->vgprs = attr.numRegs;
+    out->scratch_bytes = static_cast<int32_t>(attr.localSizeBytes);
+    out->lds_bytes = static_cast<int32_t>(attr.sharedSizeBytes) + lds_bytes_for(*cfg);
+    out->max_threads = attr.maxThreadsPerBlock;
+    out->waves_per_wg = threads / hw().wave_size;
+    out->wgs_per_cu = wgs;
+    out->waves_per_simd = (wgs * out->waves_per_wg + hw().simds_per_cu - 1) / hw().simds_per_cu;
+    return ADDRMS_OK;
+}
+
 int addrms_rstd_probe(const double* ss, int64_t n, int64_t N, float eps, float* out, void* stream)
 {
     if (n < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "need n >= 0 and N > 0");

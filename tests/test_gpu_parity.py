@@ -1,0 +1,199 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI (needs an MI355X).
+
+Bar: residual output bit-exact; normalised output within 1 unit in the last
+place of its storage format AND within 2e-2 absolute.  Because both sides
+form the sum of squares in fp64 and round rstd to fp32 once, the outputs are
+expected to be identical; the few-ulp allowance only covers the (about 1e-7
+per row) chance that the two fp64 summation orders straddle an fp32 rounding
+boundary of rstd.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import DeviceCase, compare, oracle_outputs
+from paper_2601_12698_amd import binding as B
+from paper_2601_12698_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(M, N, dtype, seed, eps=1e-6, **kw):
+    return W.Workload(f"t_{M}x{N}_{dtype}", M, N, dtype, eps, seed, **kw)
+
+
+def test_smoke_shape_default_cfg(oracle):
+    wl = W.SMOKE
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    y, res = case.run(None)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    st = compare(y, res, y_ref, res_ref, wl.dtype, wl.name)
+    assert st["n_diff"] == 0
+
+
+# Small shapes that still span several chunks, ragged row tails (N not a
+# multiple of vec*threads) and a ragged last workgroup (M not a multiple of
+# rows_per_wg).
+SMALL = [
+    ("bf16", 37, 4096, 0), ("bf16", 5, 8192, 1), ("bf16", 70, 7168, 2),
+    ("fp16", 19, 1000, 3), ("fp16_res32", 21, 2880, 4), ("fp16_res32", 9, 5120, 5),
+    ("fp16_res32", 33, 1000, 6), ("fp32", 13, 1536, 7), ("fp32", 3, 11008, 8), ("bf16", 130, 512, 9),
+]
+
+
+@pytest.mark.parametrize("dtype,M,N,seed", SMALL)
+def test_every_feasible_cfg_matches_oracle(oracle, dtype, M, N, seed):
+    wl = _wl(M, N, dtype, seed, x_std=1.3, r_std=0.9)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    cfgs, grid = B.addrms_enumerate_feasible(M, N, dtype)
+    assert len(cfgs) > 50
+    print(f"{wl.name}: {len(cfgs)} feasible of {grid}", flush=True)
+    total_diff = 0
+    for c in cfgs:
+        y, res = case.run(c)
+        st = compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")
+        total_diff += st["n_diff"]
+    # identical everywhere is the expectation, across all configurations
+    assert total_diff == 0
+
+
+def test_results_do_not_depend_on_cfg_and_are_repeatable(oracle):
+    wl = _wl(257, 4096, "bf16", 21)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    cfgs, _ = B.addrms_enumerate_feasible(wl.M, wl.N, wl.dtype)
+    y0, r0 = case.run(cfgs[0])
+    for c in cfgs[:: max(1, len(cfgs) // 40)]:
+        for _ in range(2):
+            y, r = case.run(c)
+            assert np.array_equal(y, y0) and np.array_equal(r, r0), str(c)
+
+
+@pytest.mark.parametrize("N", [8, 24, 1001, 333, 2050])
+def test_narrow_and_odd_widths(oracle, N):
+    """Widths that force narrow vectors (odd N needs vec=1) and rows shorter than a wave."""
+    for dtype in ("bf16", "fp16_res32"):
+        wl = _wl(11, N, dtype, 30 + N)
+        d = W.generate(wl)
+        case = DeviceCase(d, wl)
+        y_ref, res_ref = oracle_outputs(oracle, d, wl)
+        cfgs, _ = B.addrms_enumerate_feasible(wl.M, N, dtype)
+        assert cfgs, f"no feasible cfg for N={N}"
+        for c in [None] + cfgs[::7]:
+            y, res = case.run(c)
+            assert compare(y, res, y_ref, res_ref, dtype, f"N={N} {c}")["n_diff"] == 0
+
+
+def test_degenerate_rows(oracle):
+    """Zero rows, signed zeros, rounding ties, subnormal sums, large magnitudes."""
+    N = 1024
+    wl = _wl(8, N, "bf16", 40)
+    d = W.generate(wl)
+    x = d["x"].clone()
+    r = d["r"].clone()
+    x[0].zero_(); r[0].zero_()                                   # zero row: rstd = 1/sqrt(eps)
+    x[1] = -0.0; r[1] = 0.0                                      # (-0) + (+0) = +0
+    x[2] = -0.0; r[2] = -0.0                                     # stays -0
+    x[3] = 1.0; r[3] = 2.0 ** -8                                 # exact tie in bf16: rounds to even
+    x[4] = 1.0; r[4] = 3 * 2.0 ** -8                             # tie the other way
+    x[5] = 2.0 ** -120; r[5] = 2.0 ** -127                       # subnormal fp32 partial sums
+    x[6] = 1e18; r[6] = -3e17                                    # large finite values (h^2 ~ 1e36)
+    x[7, ::2] = 0.0                                              # half zeros
+    d2 = {"x": x.contiguous(), "r": r.contiguous(), "w": d["w"]}
+    case = DeviceCase(d2, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d2, wl)
+    cfgs, _ = B.addrms_enumerate_feasible(wl.M, N, "bf16")
+    for c in [None] + cfgs[::11]:
+        y, res = case.run(c)
+        assert compare(y, res, y_ref, res_ref, "bf16", f"degenerate {c}")["n_diff"] == 0
+    assert np.all(res_ref[0] == 0) and np.all(y_ref[0] == 0)
+
+
+def test_fp16_ties_and_subnormal_outputs(oracle):
+    N = 512
+    wl = _wl(4, N, "fp16", 41, eps=1e-6)
+    d = W.generate(wl)
+    x = d["x"].clone(); r = d["r"].clone()
+    x[0] = 1.0; r[0] = 2.0 ** -11                                # tie in fp16
+    x[1] = 2.0 ** -14; r[1] = 2.0 ** -24                         # sums near the fp16 subnormal boundary
+    x[2, :] = 0.0; x[2, 0] = 6e-5; r[2] = 0.0                    # y has fp16-subnormal entries? (others 0)
+    d2 = {"x": x.contiguous(), "r": r.contiguous(), "w": d["w"]}
+    case = DeviceCase(d2, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d2, wl)
+    cfgs, _ = B.addrms_enumerate_feasible(wl.M, N, "fp16")
+    for c in [None] + cfgs[::13]:
+        y, res = case.run(c)
+        assert compare(y, res, y_ref, res_ref, "fp16", f"fp16 edge {c}")["n_diff"] == 0
+
+
+def test_rstd_probe_matches_oracle(oracle):
+    rng = np.random.default_rng(50)
+    for N, eps in ((4096, 1e-6), (7168, 1e-6), (1000, 1e-5), (8192, 1e-5)):
+        ss = np.concatenate([np.exp(rng.uniform(-30, 40, 200000)), rng.uniform(0.5, 2.0, 100000) * N,
+                             np.array([0.0, 1e-300, 1e300])])
+        ss_d = torch.from_numpy(ss).cuda()
+        out = torch.empty(ss.size, dtype=torch.float32, device="cuda")
+        B.addrms_rstd_probe(ss_d, N, eps, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        want = np.array([oracle.rstd_canonical(float(v), N, eps) for v in ss[:5000]], dtype=np.float32)
+        assert np.array_equal(got[:5000], want)
+        # vectorised check of the rest with numpy fp64 (same formula, correctly rounded ops)
+        want_all = (1.0 / np.sqrt(ss / N + np.float64(np.float32(eps)))).astype(np.float32)
+        assert np.array_equal(got, want_all)
+
+
+def test_m_zero_is_noop_and_m_one_works(oracle):
+    wl = _wl(1, 8192, "bf16", 60, eps=1e-5, x_std=2.0, r_std=2.0)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    cfgs, _ = B.addrms_enumerate_feasible(1, 8192, "bf16")
+    for c in [None] + cfgs[::5]:
+        y, res = case.run(c)
+        assert compare(y, res, y_ref, res_ref, "bf16", f"M=1 {c}")["n_diff"] == 0
+    x = case.x0.clone(); r = case.r0.clone()
+    B.load().addrms_run(x.data_ptr(), r.data_ptr(), case.w.data_ptr(), 1e-5, 0, 8192, B.BF16, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(x, case.x0) and torch.equal(r, case.r0)
+
+
+def test_argument_errors_launch_nothing():
+    wl = _wl(4, 4096, "bf16", 61)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    case.x.copy_(case.x0); case.r.copy_(case.r0)
+    lib = B.load()
+    xp, rp, wp = case.x.data_ptr(), case.r.data_ptr(), case.w.data_ptr()
+    bad = B.make_cfg(8, 1024, 1)                                  # half the lanes idle: pruned
+    assert lib.addrms_run(xp, rp, wp, 1e-6, 4, 4096, B.BF16, bad, None) == B.ERR_INFEASIBLE_CFG
+    assert "lane slots" in B.addrms_last_error()
+    ok = B.make_cfg(8, 256, 1, unroll=2)
+    assert lib.addrms_run(xp + 2, rp, wp, 1e-6, 4, 4096, B.BF16, ok, None) == B.ERR_MISALIGNED
+    assert lib.addrms_run(xp, rp + 4, wp, 1e-6, 4, 4096, B.BF16, ok, None) == B.ERR_MISALIGNED
+    assert lib.addrms_run(None, rp, wp, 1e-6, 4, 4096, B.BF16, ok, None) == B.ERR_INVALID_ARG
+    assert lib.addrms_run(xp, rp, wp, 1e-6, 4, 0, B.BF16, ok, None) == B.ERR_INVALID_ARG
+    assert lib.addrms_run(xp, rp, wp, 1e-6, -1, 4096, B.BF16, ok, None) == B.ERR_INVALID_ARG
+    assert lib.addrms_run(xp, rp, wp, 1e-6, 4, 4096, 9, ok, None) == B.ERR_UNSUPPORTED_DTYPE
+    assert lib.addrms_run(xp, rp, wp, 1e-6, 4, 4100, B.BF16, ok, None) == B.ERR_INFEASIBLE_CFG   # 8 does not divide 4100
+    torch.cuda.synchronize()
+    assert torch.equal(case.x, case.x0) and torch.equal(case.r, case.r0)
+
+
+def test_runs_on_a_side_stream(oracle):
+    wl = _wl(64, 4096, "bf16", 62)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    s = torch.cuda.Stream()
+    case.x.copy_(case.x0); case.r.copy_(case.r0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        B.addrms_run(case.x, case.r, case.w, wl.eps, wl.M, wl.N, wl.dtype, None, stream=s)
+    s.synchronize()
+    compare(W.to_bits(case.x), W.to_bits(case.r), y_ref, res_ref, "bf16", "side stream")
