@@ -99,10 +99,10 @@ def build(force: bool = False, jobs: int = 8, verbose: bool = False) -> str:
     for text in remarks:
         res.update(parse_remarks(text))
     rows = []
-    for dt, vec, cpt, unr, _maxt in gen_kernels.instances():
-        r = res.get(gen_kernels.name(dt, vec, cpt, unr))
+    for dt, vec, cpt, unr, nt, _maxt in gen_kernels.instances():
+        r = res.get(gen_kernels.name(dt, vec, cpt, unr, nt))
         if r is None or any(k not in r for k in ("vgprs", "agprs", "sgprs", "scratch", "lds", "occupancy")):
-            raise RuntimeError(f"no resource report for {gen_kernels.name(dt, vec, cpt, unr)}")
+            raise RuntimeError(f"no resource report for {gen_kernels.name(dt, vec, cpt, unr, nt)}")
         rows.append(f"    {{{r['vgprs']}, {r['agprs']}, {r['sgprs']}, {r['scratch']}, {r['lds']}, {r['occupancy']}}},")
     gen_kernels._write(os.path.join(BUILD, "gen_resources.inc"), "\n".join(rows) + "\n")
 

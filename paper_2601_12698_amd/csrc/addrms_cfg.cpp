@@ -55,21 +55,21 @@ int n_instances() { return static_cast<int>(sizeof(kInstances) / sizeof(kInstanc
 const Instance& instance(int idx) { return kInstances[idx]; }
 const InstanceRes& instance_res(int idx) { return kInstanceRes[idx]; }
 
-static uint32_t inst_key(int dt, int vec, int cpt, int unr)
+static uint32_t inst_key(int dt, int vec, int cpt, int unr, int nt)
 {
     return (static_cast<uint32_t>(dt) << 24) | (static_cast<uint32_t>(vec) << 16) |
-           (static_cast<uint32_t>(cpt) << 8) | static_cast<uint32_t>(unr);
+           (static_cast<uint32_t>(cpt) << 8) | (static_cast<uint32_t>(unr) << 1) | static_cast<uint32_t>(nt);
 }
 
-int find_instance(int dt, int vec, int cpt, int unr)
+int find_instance(int dt, int vec, int cpt, int unr, int nt)
 {
     static const std::unordered_map<uint32_t, int> index = [] {
         std::unordered_map<uint32_t, int> m;
         for (int i = 0; i < n_instances(); ++i)
-            m[inst_key(kInstances[i].dt, kInstances[i].vec, kInstances[i].cpt, kInstances[i].unr)] = i;
+            m[inst_key(kInstances[i].dt, kInstances[i].vec, kInstances[i].cpt, kInstances[i].unr, kInstances[i].nt)] = i;
         return m;
     }();
-    auto it = index.find(inst_key(dt, vec, cpt, unr));
+    auto it = index.find(inst_key(dt, vec, cpt, unr, nt));
     return it == index.end() ? -1 : it->second;
 }
 
@@ -175,7 +175,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     if (c.reduce != ADDRMS_REDUCE_WAVE && c.reduce != ADDRMS_REDUCE_LDS)
         return infeasible("grid", "reduce=%d: must be wave (0) or lds (1)", c.reduce);
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
-    if (c.flags & ~ADDRMS_FLAG_XCD_CONTIG) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
+    if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL)) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
     if (c.reserved[0] || c.reserved[1]) return infeasible("grid", "reserved fields must be zero");
 
     const int xb = x_bytes(dtype), rb = r_bytes(dtype);
@@ -224,7 +224,8 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
                           2 * L.xcds);
 
     // -- compiled instance and its resources
-    const int idx = find_instance(dtype, c.vec, static_cast<int>(need), c.unroll);
+    const int idx = find_instance(dtype, c.vec, static_cast<int>(need), c.unroll,
+                                  (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0);
     if (idx < 0)
         return infeasible("no_instance", "no compiled instance for dtype=%s vec=%d chunks=%lld unroll=%d", dtype_name(dtype), c.vec,
                           (long long)need, c.unroll);
@@ -270,7 +271,7 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
             for (int rows : kRows)
                 for (int red = 0; red < 2; ++red)
                     for (int unr : kUnrolls)
-                        for (int flags = 0; flags < 2; ++flags) {
+                        for (int flags = 0; flags < 4; ++flags) {
                             ++grid;
                             addrms_cfg c{};
                             c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;

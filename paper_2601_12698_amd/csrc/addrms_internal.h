@@ -38,14 +38,14 @@ constexpr int kMinWavesPerSimd = 2;
 constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
 
 // ---- kernel instances ------------------------------------------------------
-struct Instance { int dt, vec, cpt, unr, maxt; };
+struct Instance { int dt, vec, cpt, unr, nt, maxt; };
 struct InstanceRes { int vgprs, agprs, sgprs, scratch, lds_static, occupancy; };
 
 int n_instances();
 const Instance& instance(int idx);
 const InstanceRes& instance_res(int idx);
 // Index of the instance with exactly these knob values, or -1.
-int find_instance(int dt, int vec, int cpt, int unr);
+int find_instance(int dt, int vec, int cpt, int unr, int nt);
 bool cpt_supported(int cpt);
 
 // ---- storage formats -------------------------------------------------------

@@ -12,9 +12,11 @@
 //   threads_per_row, rows_per_wg : launch shape (blockDim.x, blockDim.y)
 //   reduce  : wave64 cross-lane butterfly + one LDS hop across waves, or an
 //             LDS-staged tree
+//   NT    non-temporal (streaming) cache policy on the x and residual loads
+//         and stores; the weight vector always uses the default policy
 //   flags   : XCD-contiguous mapping of workgroups to rows
 //
-// VEC, CPT and UNR are compile-time; the rest are launch-time and uniform
+// VEC, CPT, UNR and NT are compile-time; the rest are launch-time and uniform
 // over the workgroup.
 //
 // Arithmetic per row (what every instantiation must reproduce bit for bit):
@@ -31,7 +33,7 @@ namespace addrms {
 
 enum : int { DT_BF16 = 0, DT_FP16 = 1, DT_FP16_RES32 = 2, DT_FP32 = 3 };
 enum : int { RED_WAVE = 0, RED_LDS = 1 };
-enum : uint32_t { FLAG_XCD_CONTIG = 1u };
+enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u };
 
 template <int DT> struct dt_traits;
 template <> struct dt_traits<DT_BF16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = true;  };
@@ -48,47 +50,60 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // Raw register image of one vector access of BYTES bytes (2..32).
 template <int BYTES> struct raw_t { uint32_t d[(BYTES + 3) / 4]; };
 
-template <int BYTES>
+template <bool NT, typename T>
+__device__ __forceinline__ T ld_as(const char* p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const T*>(p));
+    else return *reinterpret_cast<const T*>(p);
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st_as(char* p, T v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<T*>(p));
+    else *reinterpret_cast<T*>(p) = v;
+}
+
+template <int BYTES, bool NT = false>
 __device__ __forceinline__ void ld_raw(const char* p, raw_t<BYTES>& v)
 {
     if constexpr (BYTES == 2) {
-        v.d[0] = *reinterpret_cast<const uint16_t*>(p);
+        v.d[0] = ld_as<NT, uint16_t>(p);
     } else if constexpr (BYTES == 4) {
-        v.d[0] = *reinterpret_cast<const uint32_t*>(p);
+        v.d[0] = ld_as<NT, uint32_t>(p);
     } else if constexpr (BYTES == 8) {
-        u32x2 t = *reinterpret_cast<const u32x2*>(p);
+        u32x2 t = ld_as<NT, u32x2>(p);
         v.d[0] = t.x; v.d[1] = t.y;
     } else if constexpr (BYTES == 16) {
-        u32x4 t = *reinterpret_cast<const u32x4*>(p);
+        u32x4 t = ld_as<NT, u32x4>(p);
         v.d[0] = t.x; v.d[1] = t.y; v.d[2] = t.z; v.d[3] = t.w;
     } else {
         static_assert(BYTES == 32, "vector access must be 2, 4, 8, 16 or 32 bytes");
-        u32x4 a = *reinterpret_cast<const u32x4*>(p);
-        u32x4 b = *reinterpret_cast<const u32x4*>(p + 16);
+        u32x4 a = ld_as<NT, u32x4>(p);
+        u32x4 b = ld_as<NT, u32x4>(p + 16);
         v.d[0] = a.x; v.d[1] = a.y; v.d[2] = a.z; v.d[3] = a.w;
         v.d[4] = b.x; v.d[5] = b.y; v.d[6] = b.z; v.d[7] = b.w;
     }
 }
 
-template <int BYTES>
+template <int BYTES, bool NT = false>
 __device__ __forceinline__ void st_raw(char* p, const raw_t<BYTES>& v)
 {
     if constexpr (BYTES == 2) {
-        *reinterpret_cast<uint16_t*>(p) = static_cast<uint16_t>(v.d[0]);
+        st_as<NT, uint16_t>(p, static_cast<uint16_t>(v.d[0]));
     } else if constexpr (BYTES == 4) {
-        *reinterpret_cast<uint32_t*>(p) = v.d[0];
+        st_as<NT, uint32_t>(p, v.d[0]);
     } else if constexpr (BYTES == 8) {
         u32x2 t = {v.d[0], v.d[1]};
-        *reinterpret_cast<u32x2*>(p) = t;
+        st_as<NT, u32x2>(p, t);
     } else if constexpr (BYTES == 16) {
         u32x4 t = {v.d[0], v.d[1], v.d[2], v.d[3]};
-        *reinterpret_cast<u32x4*>(p) = t;
+        st_as<NT, u32x4>(p, t);
     } else {
         static_assert(BYTES == 32, "vector access must be 2, 4, 8, 16 or 32 bytes");
         u32x4 a = {v.d[0], v.d[1], v.d[2], v.d[3]};
         u32x4 b = {v.d[4], v.d[5], v.d[6], v.d[7]};
-        *reinterpret_cast<u32x4*>(p) = a;
-        *reinterpret_cast<u32x4*>(p + 16) = b;
+        st_as<NT, u32x4>(p, a);
+        st_as<NT, u32x4>(p + 16, b);
     }
 }
 
@@ -244,7 +259,7 @@ __device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t nb)
     return xcd * q + (xcd < rem ? xcd : rem) + idx;
 }
 
-template <int DT, int VEC, int CPT, int UNR>
+template <int DT, int VEC, int CPT, int UNR, bool NT>
 __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restrict__ rp,
                                             const void* __restrict__ wp, float eps, double inv_n,
                                             int64_t M, int32_t N, uint32_t flags, int32_t reduce)
@@ -284,8 +299,8 @@ __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restr
             if (g + u < CPT) {
                 const uint32_t col = col0 + static_cast<uint32_t>(g + u) * stride;
                 const uint32_t colc = col < nlast ? col : nlast;      // clamp: tail lanes re-read valid data
-                ld_raw<XB * VEC>(xbase + static_cast<uint64_t>((rowoff + colc) * XB), xv[u]);
-                ld_raw<RB * VEC>(rbase + static_cast<uint64_t>((rowoff + colc) * RB), rv[u]);
+                ld_raw<XB * VEC, NT>(xbase + static_cast<uint64_t>((rowoff + colc) * XB), xv[u]);
+                ld_raw<RB * VEC, NT>(rbase + static_cast<uint64_t>((rowoff + colc) * RB), rv[u]);
             }
         }
 #pragma unroll
@@ -299,7 +314,7 @@ __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restr
                 if (row_ok && col <= nlast) {
                     raw_t<RB * VEC> out;
                     pack_vec<RB, BF, VEC>(h[c], out);
-                    st_raw<RB * VEC>(rbase + static_cast<uint64_t>((rowoff + col) * RB), out);
+                    st_raw<RB * VEC, NT>(rbase + static_cast<uint64_t>((rowoff + col) * RB), out);
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
                         const double hd = static_cast<double>(h[c][e]);
@@ -336,7 +351,7 @@ __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restr
         if (row_ok && col <= nlast) {
             raw_t<XB * VEC> out;
             pack_vec<XB, BF, VEC>(y, out);
-            st_raw<XB * VEC>(xbase + static_cast<uint64_t>((rowoff + col) * XB), out);
+            st_raw<XB * VEC, NT>(xbase + static_cast<uint64_t>((rowoff + col) * XB), out);
         }
     }
 }

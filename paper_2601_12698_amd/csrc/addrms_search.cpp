@@ -157,6 +157,7 @@ struct Searcher {
         { addrms_cfg n = c; n.unroll /= 2; if (n.unroll >= 1) push(n); }
         { addrms_cfg n = c; n.reduce ^= 1; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_XCD_CONTIG; push(n); }
+        { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_NONTEMPORAL; push(n); }
         // threads_per_row: nearest feasible values above and below at this vec
         int up = 0, down = 0;
         for (const Cand& o : cands) {
@@ -284,7 +285,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
             std::vector<int> tprs = {8, 16, 32};
             for (int t = 64; t <= hw().max_threads_per_wg; t += 64) tprs.push_back(t);
             for (int vec : {8, 4, 2, 1}) for (int tpr : tprs) for (int rows : {1, 2, 4, 8, 16})
-                for (int red = 0; red < 2; ++red) for (int unr : {1, 2, 4, 8}) for (int fl = 0; fl < 2; ++fl) {
+                for (int red = 0; red < 2; ++red) for (int unr : {1, 2, 4, 8}) for (int fl = 0; fl < 4; ++fl) {
                     addrms_cfg c{};
                     c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows; c.reduce = red; c.unroll = unr; c.flags = fl;
                     const Feas f = check_cfg(c, M, N, dtype);

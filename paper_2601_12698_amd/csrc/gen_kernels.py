@@ -1,7 +1,7 @@
 """Writes the instantiation list of the kernel template.
 
-The template in ``addrms_kernel.h`` has three compile-time knobs (VEC, CPT,
-UNR) per storage format.  This script emits, into a build directory:
+The template in ``addrms_kernel.h`` has four compile-time knobs (VEC, CPT,
+UNR, NT) per storage format.  This script emits, into a build directory:
 
   kern_d<DT>_v<VEC>.hip   one translation unit per (format, vector width),
                           each kernel an ``extern "C"`` wrapper with a readable
@@ -38,11 +38,12 @@ def instances():
                     if unr > cpt:
                         continue
                     maxt = 1024 if vec * cpt <= BIG_ELEMS else 256
-                    yield dt, vec, cpt, unr, maxt
+                    for nt in (0, 1):
+                        yield dt, vec, cpt, unr, nt, maxt
 
 
-def name(dt, vec, cpt, unr):
-    return f"addrms_k_d{dt}_v{vec}_c{cpt}_u{unr}"
+def name(dt, vec, cpt, unr, nt):
+    return f"addrms_k_d{dt}_v{vec}_c{cpt}_u{unr}_n{nt}"
 
 
 ARGS = ("void* x, void* r, const void* w, float eps, double inv_n, "
@@ -52,21 +53,22 @@ ARGS = ("void* x, void* r, const void* w, float eps, double inv_n, "
 def main(outdir: str) -> None:
     os.makedirs(outdir, exist_ok=True)
     units = {}
-    for dt, vec, cpt, unr, maxt in instances():
-        units.setdefault((dt, vec), []).append((cpt, unr, maxt))
+    for dt, vec, cpt, unr, nt, maxt in instances():
+        units.setdefault((dt, vec), []).append((cpt, unr, nt, maxt))
     for (dt, vec), lst in units.items():
         lines = ['#include "addrms_kernel.h"', ""]
-        for cpt, unr, maxt in lst:
+        for cpt, unr, nt, maxt in lst:
             lines.append(
-                f'extern "C" __global__ __launch_bounds__({maxt}) void {name(dt, vec, cpt, unr)}({ARGS})\n'
-                f"{{ addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}>(x, r, w, eps, inv_n, M, N, flags, reduce); }}")
+                f'extern "C" __global__ __launch_bounds__({maxt}) void {name(dt, vec, cpt, unr, nt)}({ARGS})\n'
+                f"{{ addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}, {'true' if nt else 'false'}>"
+                f"(x, r, w, eps, inv_n, M, N, flags, reduce); }}")
         _write(os.path.join(outdir, f"kern_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")
     decl, table, inst = [], [], []
-    for dt, vec, cpt, unr, maxt in instances():
-        n = name(dt, vec, cpt, unr)
+    for dt, vec, cpt, unr, nt, maxt in instances():
+        n = name(dt, vec, cpt, unr, nt)
         decl.append(f'extern "C" __global__ void {n}({ARGS});')
-        table.append(f"    {{{dt}, {vec}, {cpt}, {unr}, reinterpret_cast<const void*>(&{n})}},")
-        inst.append(f"    {{{dt}, {vec}, {cpt}, {unr}, {maxt}}},")
+        table.append(f"    {{{dt}, {vec}, {cpt}, {unr}, {nt}, reinterpret_cast<const void*>(&{n})}},")
+        inst.append(f"    {{{dt}, {vec}, {cpt}, {unr}, {nt}, {maxt}}},")
     _write(os.path.join(outdir, "gen_dispatch_decl.inc"), "\n".join(decl) + "\n")
     _write(os.path.join(outdir, "gen_dispatch_rows.inc"), "\n".join(table) + "\n")
     _write(os.path.join(outdir, "gen_instances.inc"), "\n".join(inst) + "\n")
