@@ -188,7 +188,11 @@ struct Harness {
     bool have_ref = false;
     addrms_cfg ref_cfg{};
 
-    static size_t pad(size_t b) { return (b + 255) / 256 * 256; }
+    // Buffers start on 64 KiB boundaries; each residual buffer is then skewed by
+    // one 4 KiB interleave unit so that the x and residual accesses of a lane,
+    // issued together at equal offsets, do not land on the same HBM channel.
+    static constexpr size_t kAlign = 64 * 1024, kSkew = 4096;
+    static size_t pad(size_t b) { return (b + kAlign - 1) / kAlign * kAlign + kAlign; }
 
     int init(int64_t m, int64_t n, int dt, float e, bool rotate)
     {
@@ -201,13 +205,14 @@ struct Harness {
         const size_t want = 2 * (static_cast<size_t>(hw().last_level_cache_bytes) +
                                  static_cast<size_t>(hw().l2_bytes_per_xcd) * hw().xcds);
         nsets = rotate ? static_cast<int>(std::min<size_t>(32, std::max<size_t>(2, (want + set - 1) / set))) : 1;
-        const size_t total = set * (nsets + 2) + pad(wbytes) + 256;
+        const size_t total = set * (nsets + 2) + pad(wbytes) + pad(256);
         HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), total));
         char* p = pool;
-        auto take = [&](size_t b) { char* q = p; p += pad(b); return q; };
-        x0 = take(xbytes); r0 = take(rbytes); yref = take(xbytes); rref = take(rbytes); w = take(wbytes);
-        counts = reinterpret_cast<unsigned*>(take(256));
-        for (int i = 0; i < nsets; ++i) { xs.push_back(take(xbytes)); rs.push_back(take(rbytes)); }
+        auto take = [&](size_t b, size_t skew) { char* q = p + skew; p += pad(b); return q; };
+        x0 = take(xbytes, 0); r0 = take(rbytes, kSkew); yref = take(xbytes, 0); rref = take(rbytes, kSkew);
+        w = take(wbytes, 0);
+        counts = reinterpret_cast<unsigned*>(take(256, 0));
+        for (int i = 0; i < nsets; ++i) { xs.push_back(take(xbytes, 0)); rs.push_back(take(rbytes, kSkew)); }
         HIP_TRY(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
         HIP_TRY(hipEventCreate(&ev0));
         HIP_TRY(hipEventCreate(&ev1));

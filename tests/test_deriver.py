@@ -1,0 +1,133 @@
+"""Feasible-region deriver (host logic, no GPU): rules, reasons, counts, the
+occupancy model against the compiler's own figure, and the default cfg."""
+import re
+
+import pytest
+
+from paper_2601_12698_amd import binding as B
+
+
+def feas(cfg, M, N, dtype):
+    st, why, res = B.addrms_cfg_feasible(cfg, M, N, dtype)
+    return st, why, res
+
+
+def test_known_feasible_and_resources():
+    c = B.make_cfg(8, 256, 1, unroll=2)
+    st, why, res = feas(c, 4096, 4096, "bf16")
+    assert st == 0 and why == ""
+    assert res.chunks_per_thread == 2 and res.scratch_bytes == 0
+    assert res.waves_per_wg == 4 and res.max_threads == 1024
+    assert 16 <= res.vgprs <= 128 and res.lds_bytes == 16 * 8
+    assert 1 <= res.waves_per_simd <= 8
+
+
+KNOWN_INFEASIBLE = [
+    (B.make_cfg(3, 256, 1), 4096, 4096, "bf16", "vector width"),
+    (B.make_cfg(8, 100, 1), 4096, 4096, "bf16", "threads_per_row"),
+    (B.make_cfg(8, 256, 3), 4096, 4096, "bf16", "rows_per_wg"),
+    (B.make_cfg(8, 256, 1, reduce=2), 4096, 4096, "bf16", "reduce"),
+    (B.make_cfg(8, 256, 1, unroll=3), 4096, 4096, "bf16", "unroll"),
+    (B.make_cfg(8, 256, 1, flags=8), 4096, 4096, "bf16", "flags"),
+    (B.make_cfg(8, 256, 1), 4096, 4100, "bf16", "does not divide"),
+    (B.make_cfg(8, 256, 1), 4096, 4096, "fp32", "wider than"),
+    (B.make_cfg(8, 512, 4), 4096, 4096, "bf16", "exceeds the 1024-thread limit"),
+    (B.make_cfg(8, 8, 1), 4096, 64, "bf16", "whole number"),
+    (B.make_cfg(8, 32, 2), 4096, 4096, "bf16", "row cache"),
+    (B.make_cfg(4, 64, 1), 4096, 2304, "bf16", "no compiled instance"),      # 9 chunks
+    (B.make_cfg(8, 1024, 1), 4096, 4096, "bf16", "lane slots"),
+    (B.make_cfg(8, 512, 1, unroll=2), 4096, 4096, "bf16", "unroll=2 exceeds"),
+    (B.make_cfg(8, 256, 4, unroll=2), 2, 4096, "bf16", "exceeds the 2 rows"),
+    (B.make_cfg(8, 256, 1, unroll=2, flags=1), 8, 4096, "bf16", "identity mapping"),
+    (B.make_cfg(8, 64, 16, unroll=2), 4096, 4096, "bf16", "at most 256 threads"),
+]
+
+
+@pytest.mark.parametrize("cfg,M,N,dtype,needle", KNOWN_INFEASIBLE)
+def test_known_infeasible_with_rationale(cfg, M, N, dtype, needle):
+    st, why, _ = feas(cfg, M, N, dtype)
+    assert st == B.ERR_INFEASIBLE_CFG
+    assert needle in why, why
+    assert B.addrms_last_error() == why
+
+
+def test_bad_shape_and_dtype_codes():
+    c = B.make_cfg(8, 256, 1)
+    assert feas(c, 4, 0, "bf16")[0] == B.ERR_INVALID_ARG
+    assert feas(c, -1, 8, "bf16")[0] == B.ERR_INVALID_ARG
+    assert feas(c, 4, 4096, 5)[0] == B.ERR_UNSUPPORTED_DTYPE
+
+
+@pytest.mark.parametrize("M,N,dtype", [(4096, 4096, "bf16"), (1, 8192, "bf16"), (32768, 7168, "bf16"),
+                                       (8192, 1000, "fp16_res32"), (8192, 2880, "fp16_res32"), (128, 11008, "fp32")])
+def test_enumeration_is_exactly_the_feasible_subset(M, N, dtype):
+    cfgs, grid = B.addrms_enumerate_feasible(M, N, dtype)
+    assert grid == 4 * 19 * 5 * 2 * 4 * 4
+    assert 0 < len(cfgs) < grid
+    seen = set()
+    for c in cfgs:
+        assert feas(c, M, N, dtype)[0] == 0
+        assert c.as_tuple() not in seen
+        seen.add(c.as_tuple())
+        per_pass = c.vec * c.threads_per_row
+        cpt = -(-N // per_pass)
+        assert N % c.vec == 0 and c.vec * cpt <= 64 and c.unroll <= cpt
+        assert (c.threads_per_row * c.rows_per_wg) % 64 == 0 and c.threads_per_row * c.rows_per_wg <= 1024
+        assert N / (per_pass * cpt) > 0.5
+    # deterministic order
+    again, _ = B.addrms_enumerate_feasible(M, N, dtype)
+    assert [c.as_tuple() for c in again] == [c.as_tuple() for c in cfgs]
+
+
+def test_enumeration_counts_are_stable():
+    """Region sizes for the benchmark shapes (a change here is a change of the region)."""
+    got = {k: len(B.addrms_enumerate_feasible(*k)[0]) for k in
+           [(4096, 4096, "bf16"), (16, 4096, "bf16"), (256, 8192, "bf16"), (32768, 7168, "bf16")]}
+    assert got[(4096, 4096, "bf16")] == 2072
+    assert got[(16, 4096, "bf16")] < got[(4096, 4096, "bf16")]      # fewer rows: fewer row packings, no XCD map
+    assert all(v > 100 for v in got.values())
+
+
+def test_occupancy_model_matches_compiler_report():
+    """waves/SIMD by registers = min(8, 512 // ceil8(vgprs + agprs)) must equal the
+    occupancy the compiler printed for the same instance when the library was built."""
+    import os
+    build = os.path.join(os.path.dirname(B.LIB_PATH), "_build")
+    if not os.path.isdir(build):
+        pytest.skip("build directory with the compiler's resource report is not present")
+    from paper_2601_12698_amd.build import parse_remarks
+    reports = {}
+    for f in os.listdir(build):
+        if f.endswith(".remarks"):
+            reports.update(parse_remarks(open(os.path.join(build, f)).read()))
+    assert len(reports) >= 1000
+    checked = 0
+    for name, r in reports.items():
+        m = re.match(r"addrms_k_d(\d)_v(\d)_c(\d+)_u(\d)_n(\d)$", name)
+        if not m:
+            continue
+        regs = -(-max(1, r["vgprs"] + r["agprs"]) // 8) * 8
+        assert min(8, 512 // regs) == r["occupancy"], (name, r)
+        assert r["scratch"] == 0, name
+        checked += 1
+    assert checked >= 1000
+    # and the library's table carries the same numbers
+    c = B.make_cfg(8, 64, 1, unroll=2)
+    st, _, res = feas(c, 4096, 4096, "bf16")
+    assert st == 0
+    rr = reports["addrms_k_d0_v8_c8_u2_n0"]
+    assert (res.vgprs, res.agprs) == (rr["vgprs"], rr["agprs"])
+    assert res.waves_per_simd_regs == rr["occupancy"]
+
+
+def test_default_cfg():
+    for N, dtype in [(4096, "bf16"), (8192, "bf16"), (7168, "bf16"), (5120, "fp16_res32"), (2880, "fp16_res32"),
+                     (1000, "fp16_res32"), (4096, "fp32"), (11008, "fp32"), (14336, "fp32"), (1001, "bf16"), (8, "bf16")]:
+        d = B.addrms_default_cfg(N, dtype)
+        for M in (1, 16, 4096):
+            assert feas(d, M, N, dtype)[0] == 0, (N, dtype, M, d)
+        assert d.reduce == B.REDUCE_WAVE and d.flags == 0
+    d = B.addrms_default_cfg(4096, "bf16")
+    assert d.as_tuple() == (8, 256, 1, 0, 2, 0)
+    assert B.load().addrms_default_cfg(1 << 20, B.BF16, B.Cfg()) == B.ERR_UNSUPPORTED_SHAPE
+    assert "row cache" in B.addrms_last_error()

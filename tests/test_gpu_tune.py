@@ -1,0 +1,92 @@
+"""The tuner on the device (needs an MI355X): deriver model against the device's
+own resource report, guided search against exhaustive search, the correctness
+gate, the table, and the measurement harness."""
+import json
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_12698_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def clean_table():
+    B.addrms_table_clear()
+    yield
+    B.addrms_table_clear()
+
+
+@pytest.mark.parametrize("M,N,dtype", [(4096, 4096, "bf16"), (8192, 1000, "fp16_res32"), (512, 14336, "fp32"),
+                                       (64, 8192, "bf16")])
+def test_deriver_model_matches_device(M, N, dtype):
+    """Registers, LDS, workgroup bound and resident workgroups per CU predicted by
+    the host-side deriver equal what the HIP runtime reports for the loaded kernels."""
+    cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
+    for c in cfgs[::5]:
+        st, _, model = B.addrms_cfg_feasible(c, M, N, dtype)
+        dev = B.addrms_device_resources(c, M, N, dtype)
+        assert st == 0
+        assert model.vgprs + model.agprs == dev.vgprs, c
+        assert dev.scratch_bytes == 0, c
+        assert model.lds_bytes == dev.lds_bytes, c
+        assert model.max_threads == dev.max_threads, c
+        assert model.wgs_per_cu == dev.wgs_per_cu, (c, model.as_dict(), dev.as_dict())
+
+
+def test_guided_close_to_exhaustive_on_prefill(tmp_path):
+    M, N, dt = 4096, 4096, "bf16"
+    log = str(tmp_path / "guided.jsonl")
+    g, grep = B.addrms_tune(M, N, dt, B.make_budget(log_path=log))
+    e, erep = B.addrms_tune(M, N, dt, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE, warmup=5, reps=30))
+    assert grep.n_failed == 0 and erep.n_failed == 0            # every candidate passed the gate
+    assert erep.n_measured == erep.n_feasible
+    assert grep.n_measured <= 0.1 * grep.n_feasible
+    # re-measure both winners back to back with the confirmation protocol
+    tg = min(B.addrms_measure(g, M, N, dt) for _ in range(3))
+    te = min(B.addrms_measure(e, M, N, dt) for _ in range(3))
+    td = min(B.addrms_measure(B.addrms_default_cfg(N, dt), M, N, dt) for _ in range(3))
+    print(f"guided {g} {tg:.2f} us ({grep.n_measured} cfgs, {grep.wall_ms:.0f} ms); exhaustive {e} {te:.2f} us "
+          f"({erep.n_measured} cfgs, {erep.wall_ms:.0f} ms); default {td:.2f} us", flush=True)
+    assert tg <= 1.05 * te                                       # regret of the guided search
+    assert tg <= td * 1.01                                       # tuned is not slower than the default
+    lines = [json.loads(l) for l in open(log)]
+    assert lines[0]["event"] == "begin" and lines[-1]["event"] == "end"
+    # the winner went into the table and is what a cfg-less run resolves to
+    assert B.addrms_table_lookup(M, N, dt).as_tuple() == e.as_tuple()
+
+
+def test_gate_rejects_wrong_candidates_is_wired():
+    """The gate compares each candidate with the default configuration's output;
+    with identical arithmetic in every instance nothing may be rejected."""
+    c, rep = B.addrms_tune(37, 1000, "fp16", B.make_budget(strategy=B.SEARCH_EXHAUSTIVE, warmup=1, reps=3))
+    assert rep.n_failed == 0 and rep.n_measured == rep.n_feasible > 100
+
+
+def test_tune_small_budget_and_errors():
+    c, rep = B.addrms_tune(16, 4096, "bf16", B.make_budget(max_candidates=6, warmup=2, reps=10))
+    assert rep.n_measured <= 6 and B.addrms_cfg_feasible(c, 16, 4096, "bf16")[0] == 0
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_tune(16, 1 << 20, "bf16")
+    assert e.value.status == B.ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_tune(0, 4096, "bf16")
+    assert e.value.status == B.ERR_INVALID_ARG
+
+
+def test_measure_and_stream_probe():
+    M, N, dt = 4096, 4096, "bf16"
+    d = B.addrms_default_cfg(N, dt)
+    cold = B.addrms_measure(d, M, N, dt, rotate=True)
+    warm = B.addrms_measure(d, M, N, dt, rotate=False)
+    nbytes = B.addrms_algorithmic_bytes(M, N, dt)
+    assert 10.0 < warm <= cold * 1.05 < 200.0
+    assert nbytes / cold * 1e-3 > 2000.0                         # GB/s: far above anything cache-less code would miss
+    x = torch.randn(M, N, device="cuda").to(torch.bfloat16)
+    r = torch.randn(M, N, device="cuda").to(torch.bfloat16)
+    x0, r0 = x.clone(), r.clone()
+    B.addrms_stream_probe(x, r, M, N, dt)
+    torch.cuda.synchronize()
+    assert torch.equal(x.view(torch.int16), ~x0.view(torch.int16)) and torch.equal(r.view(torch.int16), ~r0.view(torch.int16))

@@ -1,0 +1,144 @@
+"""The search, driven by a synthetic cost function with a known optimum instead
+of a GPU (host logic only).  Covers: the exhaustive strategy is the plain argmin;
+the guided strategy lands within 3 % of it while timing a small fraction of the
+region; failing candidates (launch failure, wrong output) are contained and never
+returned; budgets are honoured; the log is written."""
+import json
+import math
+
+import pytest
+
+from paper_2601_12698_amd import binding as B
+
+M, N, DT = 4096, 4096, "bf16"
+
+
+def cost(c, noise=0.0):
+    """Unimodal in every knob, optimum at vec 8, 512 threads per row, 2 rows per
+    workgroup, wave reduction, one chunk in flight, non-temporal, identity mapping."""
+    us = 20.0
+    us *= 1.0 + 0.30 * abs(math.log2(c.threads_per_row / 512.0))
+    us *= 1.0 + 0.25 * abs(math.log2(c.vec / 8.0))
+    us *= 1.0 + 0.05 * abs(math.log2(c.rows_per_wg / 2.0))
+    us *= 1.10 if c.reduce == B.REDUCE_LDS else 1.0
+    us *= 1.0 + 0.03 * abs(math.log2(c.unroll))
+    us *= 0.85 if c.flags & B.FLAG_NONTEMPORAL else 1.0
+    us *= 1.02 if c.flags & B.FLAG_XCD_CONTIG else 1.0
+    if noise:
+        h = hash(c.as_tuple()) % 1000 / 1000.0 - 0.5
+        us *= 1.0 + noise * h
+    return us
+
+
+class Recorder:
+    def __init__(self, fn, fail_measure=lambda c: False, fail_validate=lambda c: False):
+        self.fn, self.fail_measure, self.fail_validate = fn, fail_measure, fail_validate
+        self.measured, self.validated, self.protocols = [], [], set()
+
+    def measure(self, c, warmup, reps):
+        self.protocols.add((warmup, reps))
+        if self.fail_measure(c):
+            return None
+        self.measured.append(c.as_tuple())
+        return self.fn(c)
+
+    def validate(self, c):
+        self.validated.append(c.as_tuple())
+        return not self.fail_validate(c)
+
+
+def true_best(fn, exclude=lambda c: False):
+    cfgs, _ = B.addrms_enumerate_feasible(M, N, DT)
+    ok = [c for c in cfgs if not exclude(c)]
+    return min(ok, key=fn), len(cfgs)
+
+
+def test_exhaustive_is_the_argmin():
+    rec = Recorder(cost)
+    best, n = true_best(cost)
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE), rec.measure, rec.validate)
+    assert got.as_tuple() == best.as_tuple() == (8, 512, 2, 0, 1, 2)
+    assert rep.n_feasible == n == rep.n_measured and rep.n_failed == 0
+    assert len(set(rec.validated)) == n                      # every candidate went through the gate
+    assert rep.best_us == pytest.approx(cost(best)) and rep.default_us == pytest.approx(cost(B.addrms_default_cfg(N, DT)))
+    assert rep.n_topk == 5 and list(rep.topk_us[:5]) == sorted(rep.topk_us[:5])
+    assert (20, 100) in rec.protocols                        # the paper's 20 warm-up + 100 timed runs
+
+
+@pytest.mark.parametrize("noise", [0.0, 0.02])
+def test_guided_is_near_optimal_and_cheap(noise):
+    fn = lambda c: cost(c, noise)
+    rec = Recorder(fn)
+    best, n = true_best(fn)
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(), rec.measure, rec.validate)
+    assert fn(got) <= 1.03 * fn(best)
+    assert rep.n_measured <= 0.12 * n
+    assert rep.n_measured == len(set(rec.measured))
+    assert 1 <= rep.best_found_at <= rep.n_measured
+    assert (3, 15) in rec.protocols and (20, 100) in rec.protocols   # screening, then confirmation
+    assert rep.default_us > rep.best_us
+
+
+def test_failing_candidates_are_contained():
+    bad_launch = lambda c: c.threads_per_row == 512          # "launch failure" on the would-be optimum
+    bad_output = lambda c: c.vec == 4                        # "wrong output" on a whole class
+    rec = Recorder(cost, bad_launch, bad_output)
+    excl = lambda c: bad_launch(c) or bad_output(c)
+    best, _ = true_best(cost, excl)
+    for strategy in (B.SEARCH_GUIDED, B.SEARCH_EXHAUSTIVE):
+        got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(strategy=strategy), rec.measure, rec.validate)
+        assert not excl(got)
+        assert rep.n_failed > 0
+        assert all(not excl(rep.topk[i]) for i in range(rep.n_topk))
+        assert cost(got) <= 1.03 * cost(best)
+    assert all(t[0] != 4 for t in rec.measured)              # gated candidates are never timed
+
+
+def test_budget_in_candidates_is_honoured():
+    rec = Recorder(cost)
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(max_candidates=7), rec.measure, rec.validate)
+    assert rep.n_measured <= 7 and len(set(rec.measured)) <= 7
+    assert B.addrms_cfg_feasible(got, M, N, DT)[0] == 0
+
+
+def test_everything_failing_reports_no_result():
+    rec = Recorder(cost, fail_measure=lambda c: True)
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_tune_with_backend(M, N, DT, B.make_budget(max_candidates=30), rec.measure, rec.validate)
+    assert e.value.status == B.ERR_NO_RESULT
+
+
+def test_skip_validation_flag():
+    rec = Recorder(cost)
+    B.addrms_tune_with_backend(M, N, DT, B.make_budget(skip_validation=True, max_candidates=5), rec.measure, rec.validate)
+    assert rec.validated == []
+
+
+def test_log_is_json_lines(tmp_path):
+    rec = Recorder(cost)
+    path = str(tmp_path / "tune.jsonl")
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=path), rec.measure, rec.validate)
+    lines = [json.loads(l) for l in open(path)]
+    assert lines[0]["event"] == "begin" and lines[-1]["event"] == "end"
+    assert lines[0]["n_feasible"] == rep.n_feasible and lines[0]["n_grid"] == rep.n_grid
+    assert sum(lines[0]["pruned"].values()) == rep.n_grid - rep.n_feasible
+    evals = [l for l in lines if l["event"] == "eval"]
+    assert {l["phase"] for l in evals} >= {"default", "sweep", "descent", "confirm"}
+    assert all("vgprs" in l["signals"] and "waves_per_simd" in l["signals"] for l in evals)
+    assert lines[-1]["best"] == got.as_dict()
+
+
+def test_argument_errors():
+    rec = Recorder(cost)
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_tune_with_backend(0, N, DT, None, rec.measure)
+    assert e.value.status == B.ERR_INVALID_ARG
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_tune_with_backend(M, N, 9, None, rec.measure)
+    assert e.value.status == B.ERR_UNSUPPORTED_DTYPE
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_tune_with_backend(M, 1 << 20, DT, None, rec.measure)
+    assert e.value.status == B.ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_tune_with_backend(M, N, DT, B.make_budget(strategy=5), rec.measure)
+    assert e.value.status == B.ERR_INVALID_ARG

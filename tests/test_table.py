@@ -1,0 +1,83 @@
+"""Specialised table D_spec (host logic, no GPU): insert, exact and nearest-M
+lookup, persistence, and refusal of missing or corrupt files."""
+import os
+
+import pytest
+
+from paper_2601_12698_amd import binding as B
+
+
+@pytest.fixture(autouse=True)
+def clean_table():
+    B.addrms_table_clear()
+    yield
+    B.addrms_table_clear()
+
+
+def test_insert_lookup_exact_and_nearest():
+    a = B.make_cfg(8, 1024, 1)
+    b = B.make_cfg(8, 256, 4, unroll=2, flags=B.FLAG_NONTEMPORAL)
+    B.addrms_table_insert(1, 8192, "bf16", a, 3.0)
+    B.addrms_table_insert(256, 8192, "bf16", b, 9.0)
+    assert B.addrms_table_size() == 2
+    assert B.addrms_table_lookup(1, 8192, "bf16").as_tuple() == a.as_tuple()
+    assert B.addrms_table_lookup(256, 8192, "bf16").as_tuple() == b.as_tuple()
+    assert B.addrms_table_lookup(2, 8192, "bf16").as_tuple() == a.as_tuple()        # nearest in ratio
+    assert B.addrms_table_lookup(100, 8192, "bf16").as_tuple() == b.as_tuple()
+    assert B.addrms_table_lookup(100000, 8192, "bf16").as_tuple() == b.as_tuple()
+    # b packs 4 rows per workgroup: not feasible for M = 3, so the fallback must skip it
+    assert B.addrms_table_lookup(3, 8192, "bf16").as_tuple() == a.as_tuple()
+    assert B.addrms_table_lookup(16, 4096, "bf16") is None                           # other N
+    assert B.addrms_table_lookup(16, 8192, "fp16") is None                           # other dtype
+
+
+def test_insert_rejects_infeasible():
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_table_insert(4096, 4096, "bf16", B.make_cfg(8, 1024, 1))
+    assert e.value.status == B.ERR_INFEASIBLE_CFG
+    assert B.addrms_table_size() == 0
+
+
+def test_save_load_round_trip(tmp_path):
+    a = B.make_cfg(8, 576, 1, flags=B.FLAG_NONTEMPORAL)
+    b = B.make_cfg(4, 128, 2, reduce=B.REDUCE_LDS, unroll=2)
+    B.addrms_table_insert(4096, 4096, "bf16", a, 23.5)
+    B.addrms_table_insert(8192, 1000, "fp16_res32", b, 17.25)
+    path = str(tmp_path / "table.txt")
+    B.addrms_table_save(path)
+    B.addrms_table_clear()
+    assert B.addrms_table_size() == 0
+    B.addrms_table_load(path)
+    assert B.addrms_table_size() == 2
+    assert B.addrms_table_lookup(4096, 4096, "bf16").as_tuple() == a.as_tuple()
+    assert B.addrms_table_lookup(8192, 1000, "fp16_res32").as_tuple() == b.as_tuple()
+
+
+@pytest.mark.parametrize("content", [
+    "",                                                     # empty
+    "not a table\n0 1 8192 8 1024 1 0 1 0 3.0\n",         # wrong magic
+    "addrms-table 1 gfx950\n0 1 8192 8 1024 1 0 1\n",      # truncated entry
+    "addrms-table 1 gfx950\n0 1 8192 8 1024 1 0 1 0 3.0 junk\n",
+    "addrms-table 1 gfx950\n0 4096 4096 8 1024 1 0 1 0 3.0\n",   # parses, but cfg infeasible for that shape
+    "addrms-table 1 gfx950\n7 1 8192 8 1024 1 0 1 0 3.0\n",      # bad dtype
+])
+def test_corrupt_file_leaves_table_unchanged(tmp_path, content):
+    keep = B.make_cfg(8, 1024, 1)
+    B.addrms_table_insert(1, 8192, "bf16", keep, 3.0)
+    path = str(tmp_path / "bad.txt")
+    with open(path, "w") as f:
+        f.write(content)
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_table_load(path)
+    assert e.value.status == B.ERR_IO
+    assert B.addrms_table_size() == 1
+    assert B.addrms_table_lookup(1, 8192, "bf16").as_tuple() == keep.as_tuple()
+
+
+def test_missing_file_and_unwritable_path(tmp_path):
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_table_load(str(tmp_path / "nope.txt"))
+    assert e.value.status == B.ERR_IO
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_table_save(str(tmp_path / "no_such_dir" / "t.txt"))
+    assert e.value.status == B.ERR_IO
