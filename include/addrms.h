@@ -65,7 +65,10 @@ typedef struct addrms_cfg {
     int32_t reduce;           /* ADDRMS_REDUCE_*                                          */
     int32_t unroll;           /* 1, 2, 4, 8: chunks whose loads are in flight together    */
     int32_t flags;            /* ADDRMS_FLAG_* bits                                       */
-    int32_t reserved[2];      /* must be 0                                                */
+    int32_t max_waves_per_simd; /* 0 = as many as fit; 1..7 = cap on resident waves per SIMD,
+                                 imposed by padding the workgroup's LDS allocation (fewer
+                                 requests in flight can raise mixed read/write HBM efficiency) */
+    int32_t reserved;         /* must be 0                                                */
 } addrms_cfg;
 
 /* ---- run ------------------------------------------------------------------
@@ -101,11 +104,11 @@ typedef struct addrms_resources {
     int32_t agprs;              /* accumulation registers per lane (same 512-entry file)*/
     int32_t sgprs;
     int32_t scratch_bytes;      /* per lane; nonzero means spills and is rejected      */
-    int32_t lds_bytes;          /* per workgroup for this launch shape                 */
+    int32_t lds_bytes;          /* per workgroup for this launch shape, occupancy padding included */
     int32_t max_threads;        /* workgroup-size bound the instance was compiled for  */
     int32_t waves_per_wg;
     int32_t waves_per_simd_regs;/* min(8, 512 / ceil8(vgprs + agprs))                  */
-    int32_t wgs_per_cu;         /* resident workgroups per CU (registers, LDS, slots)  */
+    int32_t wgs_per_cu;         /* resident workgroups per CU (registers, LDS, slots, cap) */
     int32_t waves_per_simd;     /* achieved = wgs_per_cu * waves_per_wg / 4 (rounded up)*/
     int32_t reserved[5];
 } addrms_resources;

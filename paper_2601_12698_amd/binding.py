@@ -45,24 +45,28 @@ class AddrmsError(RuntimeError):
 
 class Cfg(Structure):
     _fields_ = [("vec", c_int32), ("threads_per_row", c_int32), ("rows_per_wg", c_int32),
-                ("reduce", c_int32), ("unroll", c_int32), ("flags", c_int32), ("reserved", c_int32 * 2)]
+                ("reduce", c_int32), ("unroll", c_int32), ("flags", c_int32),
+                ("max_waves_per_simd", c_int32), ("reserved", c_int32)]
 
-    def as_tuple(self) -> Tuple[int, int, int, int, int, int]:
-        return (self.vec, self.threads_per_row, self.rows_per_wg, self.reduce, self.unroll, self.flags)
+    def as_tuple(self) -> Tuple[int, int, int, int, int, int, int]:
+        return (self.vec, self.threads_per_row, self.rows_per_wg, self.reduce, self.unroll, self.flags,
+                self.max_waves_per_simd)
 
     def as_dict(self) -> dict:
         return dict(vec=self.vec, threads_per_row=self.threads_per_row, rows_per_wg=self.rows_per_wg,
-                    reduce=self.reduce, unroll=self.unroll, flags=self.flags)
+                    reduce=self.reduce, unroll=self.unroll, flags=self.flags,
+                    max_waves_per_simd=self.max_waves_per_simd)
 
     def __repr__(self) -> str:
-        return ("Cfg(vec=%d, threads_per_row=%d, rows_per_wg=%d, reduce=%d, unroll=%d, flags=%d)" % self.as_tuple())
+        return ("Cfg(vec=%d, threads_per_row=%d, rows_per_wg=%d, reduce=%d, unroll=%d, flags=%d, "
+                "max_waves_per_simd=%d)" % self.as_tuple())
 
 
 def make_cfg(vec: int, threads_per_row: int, rows_per_wg: int = 1, reduce: int = REDUCE_WAVE,
-             unroll: int = 1, flags: int = 0) -> Cfg:
+             unroll: int = 1, flags: int = 0, max_waves_per_simd: int = 0) -> Cfg:
     c = Cfg()
-    c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags = (
-        vec, threads_per_row, rows_per_wg, reduce, unroll, flags)
+    c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd = (
+        vec, threads_per_row, rows_per_wg, reduce, unroll, flags, max_waves_per_simd)
     return c
 
 

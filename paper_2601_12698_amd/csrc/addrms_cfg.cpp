@@ -11,6 +11,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <map>
 #include <mutex>
 #include <unordered_map>
 
@@ -112,27 +113,58 @@ static int round_up(int v, int g) { return (v + g - 1) / g * g; }
 bool cfg_equal(const addrms_cfg& a, const addrms_cfg& b)
 {
     return a.vec == b.vec && a.threads_per_row == b.threads_per_row && a.rows_per_wg == b.rows_per_wg &&
-           a.reduce == b.reduce && a.unroll == b.unroll && a.flags == b.flags;
+           a.reduce == b.reduce && a.unroll == b.unroll && a.flags == b.flags &&
+           a.max_waves_per_simd == b.max_waves_per_simd;
 }
 uint64_t cfg_key(const addrms_cfg& c)
 {
     return (static_cast<uint64_t>(c.vec) << 40) | (static_cast<uint64_t>(c.threads_per_row) << 24) |
            (static_cast<uint64_t>(c.rows_per_wg) << 16) | (static_cast<uint64_t>(c.reduce) << 12) |
-           (static_cast<uint64_t>(c.unroll) << 4) | static_cast<uint64_t>(c.flags & 0xf);
+           (static_cast<uint64_t>(c.unroll) << 8) | (static_cast<uint64_t>(c.max_waves_per_simd & 0xf) << 4) |
+           static_cast<uint64_t>(c.flags & 0xf);
 }
 std::string cfg_json(const addrms_cfg& c)
 {
-    char buf[192];
+    char buf[224];
     snprintf(buf, sizeof buf,
-             "{\"vec\":%d,\"threads_per_row\":%d,\"rows_per_wg\":%d,\"reduce\":%d,\"unroll\":%d,\"flags\":%d}",
-             c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags);
+             "{\"vec\":%d,\"threads_per_row\":%d,\"rows_per_wg\":%d,\"reduce\":%d,\"unroll\":%d,\"flags\":%d,"
+             "\"max_waves_per_simd\":%d}",
+             c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd);
     return buf;
+}
+
+int reduction_lds_bytes(const addrms_cfg& c)
+{
+    if (c.reduce == ADDRMS_REDUCE_LDS) return c.threads_per_row * c.rows_per_wg * 8;
+    return c.threads_per_row > 64 ? c.rows_per_wg * 16 * 8 : 0;   // one fp64 slot per wave of a row
+}
+
+int capped_wgs_per_cu(const addrms_cfg& c)
+{
+    if (c.max_waves_per_simd <= 0) return 0;
+    const int waves_per_wg = std::max(1, c.threads_per_row * c.rows_per_wg / hw().wave_size);
+    return c.max_waves_per_simd * hw().simds_per_cu / waves_per_wg;   // 0: one workgroup already exceeds the cap
+}
+
+// LDS padding such that exactly `wgs` workgroups fit the CU's LDS: the largest
+// whole number of allocation granules g with wgs * g <= total; it binds only if
+// (wgs + 1) * g exceeds the total.  Returns 0 if no such padding exists.
+static int lds_padding_for_wgs(int wgs)
+{
+    const int total = hw().lds_bytes_per_cu / hw().lds_granule;
+    const int g = total / wgs;
+    if (g < 1 || (wgs + 1) * g <= total) return 0;
+    return g * hw().lds_granule;
 }
 
 int lds_bytes_for(const addrms_cfg& c)
 {
-    if (c.reduce == ADDRMS_REDUCE_LDS) return c.threads_per_row * c.rows_per_wg * 8;
-    return c.threads_per_row > 64 ? c.rows_per_wg * 16 * 8 : 0;   // one fp64 slot per wave of a row
+    const int need = reduction_lds_bytes(c);
+    const int wgs = capped_wgs_per_cu(c);
+    if (c.max_waves_per_simd <= 0) return need;
+    if (wgs == 0) return 0;
+    const int pad = lds_padding_for_wgs(wgs);
+    return pad == 0 ? 0 : std::max(need, pad);
 }
 int64_t n_workgroups(const addrms_cfg& c, int64_t M) { return (M + c.rows_per_wg - 1) / c.rows_per_wg; }
 
@@ -176,7 +208,10 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
         return infeasible("grid", "reduce=%d: must be wave (0) or lds (1)", c.reduce);
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
     if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL)) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
-    if (c.reserved[0] || c.reserved[1]) return infeasible("grid", "reserved fields must be zero");
+    if (c.max_waves_per_simd < 0 || c.max_waves_per_simd >= L.max_waves_per_simd)
+        return infeasible("grid", "max_waves_per_simd=%d: must be 0 (no cap) or 1..%d", c.max_waves_per_simd,
+                          L.max_waves_per_simd - 1);
+    if (c.reserved) return infeasible("grid", "reserved field must be zero");
 
     const int xb = x_bytes(dtype), rb = r_bytes(dtype);
     // -- vectorisation and alignment
@@ -235,7 +270,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     addrms_resources& o = f.res;
     o.vgprs = r.vgprs; o.agprs = r.agprs; o.sgprs = r.sgprs; o.scratch_bytes = r.scratch;
     o.max_threads = in.maxt;
-    o.lds_bytes = lds_bytes_for(c) + r.lds_static;
+    o.lds_bytes = reduction_lds_bytes(c) + r.lds_static;
     o.waves_per_wg = threads / L.wave_size;
     if (r.scratch > 0)
         return infeasible("scratch", "instance spills %d bytes per lane to scratch memory", r.scratch);
@@ -250,6 +285,24 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     int wgs = waves_cu_regs / o.waves_per_wg;
     if (o.lds_bytes > 0) wgs = std::min(wgs, L.lds_bytes_per_cu / round_up(o.lds_bytes, L.lds_granule));
     wgs = std::min(wgs, o.waves_per_wg > 1 ? L.max_multiwave_wgs_per_cu : L.max_wgs_per_cu);
+    // -- requested occupancy cap: must bind, and must be imposable by LDS padding
+    if (c.max_waves_per_simd > 0) {
+        const int cap = capped_wgs_per_cu(c);
+        if (cap < 1)
+            return infeasible("cap_below_one_wg", "max_waves_per_simd=%d is less than one %d-wave workgroup spread over "
+                              "%d SIMDs", c.max_waves_per_simd, o.waves_per_wg, L.simds_per_cu);
+        if ((c.max_waves_per_simd - 1) * L.simds_per_cu / o.waves_per_wg == cap)
+            return infeasible("cap_redundant", "max_waves_per_simd=%d and %d both leave %d workgroups per CU",
+                              c.max_waves_per_simd, c.max_waves_per_simd - 1, cap);
+        if (cap >= wgs)
+            return infeasible("cap_not_binding", "max_waves_per_simd=%d allows %d workgroups per CU but only %d fit anyway: "
+                              "the cap changes nothing", c.max_waves_per_simd, cap, wgs);
+        const int pad = lds_padding_for_wgs(cap);
+        if (pad == 0 || pad < o.lds_bytes)
+            return infeasible("cap_not_imposable", "no LDS padding leaves exactly %d workgroups per CU", cap);
+        o.lds_bytes = pad;
+        wgs = cap;
+    }
     o.wgs_per_cu = wgs;
     if (wgs < 1)
         return infeasible("occupancy", "workgroup of %d waves at %d registers per lane does not fit one CU (%d wave slots by "
@@ -261,7 +314,8 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     return f;
 }
 
-void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid)
+void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid,
+               std::map<std::string, int64_t>* pruned)
 {
     int64_t grid = 0;
     std::vector<int> tprs = {8, 16, 32};
@@ -271,13 +325,16 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
             for (int rows : kRows)
                 for (int red = 0; red < 2; ++red)
                     for (int unr : kUnrolls)
-                        for (int flags = 0; flags < 4; ++flags) {
-                            ++grid;
-                            addrms_cfg c{};
-                            c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;
-                            c.reduce = red; c.unroll = unr; c.flags = flags;
-                            if (check_cfg(c, M, N, dtype).status == ADDRMS_OK && out) out->push_back(c);
-                        }
+                        for (int flags = 0; flags < 4; ++flags)
+                            for (int cap = 0; cap < hw().max_waves_per_simd; ++cap) {
+                                ++grid;
+                                addrms_cfg c{};
+                                c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;
+                                c.reduce = red; c.unroll = unr; c.flags = flags; c.max_waves_per_simd = cap;
+                                const Feas f = check_cfg(c, M, N, dtype);
+                                if (f.status == ADDRMS_OK) { if (out) out->push_back(c); }
+                                else if (pruned) ++(*pruned)[f.rule];
+                            }
     if (n_grid) *n_grid = grid;
 }
 
@@ -355,7 +412,7 @@ int64_t addrms_enumerate_feasible(int64_t M, int64_t N, int dtype, addrms_cfg* o
     if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
     if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
     std::vector<addrms_cfg> v;
-    enumerate(M, N, dtype, &v, n_grid);
+    enumerate(M, N, dtype, &v, n_grid, nullptr);
     const int64_t n = static_cast<int64_t>(v.size());
     for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
     return n;

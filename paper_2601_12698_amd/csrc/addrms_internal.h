@@ -4,6 +4,7 @@
 #include <stdarg.h>
 #include <stdint.h>
 
+#include <map>
 #include <string>
 #include <vector>
 
@@ -63,9 +64,16 @@ struct Feas {
     addrms_resources res{};
 };
 Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype);
-void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid);
+// Walks the whole knob grid; `pruned` (optional) counts rejected points by rule tag.
+void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid,
+               std::map<std::string, int64_t>* pruned = nullptr);
 int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why);
+// Dynamic LDS bytes of a launch: what the reduction needs, raised to the padding that
+// imposes cfg.max_waves_per_simd (0 if the cap cannot be imposed; check_cfg rejects that).
 int lds_bytes_for(const addrms_cfg& c);
+int reduction_lds_bytes(const addrms_cfg& c);
+// Workgroups per CU that cfg.max_waves_per_simd allows (0 = no cap requested).
+int capped_wgs_per_cu(const addrms_cfg& c);
 int64_t n_workgroups(const addrms_cfg& c, int64_t M);
 
 bool cfg_equal(const addrms_cfg& a, const addrms_cfg& b);

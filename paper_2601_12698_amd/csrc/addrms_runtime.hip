@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -45,6 +46,9 @@ bool dispatch_consistent()
     return ok;
 }
 
+constexpr int kDefaultDynamicLdsLimit = 64 * 1024;
+std::atomic<bool> g_big_lds_enabled[sizeof(kDispatch) / sizeof(kDispatch[0])];
+
 bool aligned(const void* p, int bytes) { return (reinterpret_cast<uintptr_t>(p) % static_cast<uintptr_t>(bytes)) == 0; }
 
 // Launch with every check already done.
@@ -59,7 +63,17 @@ int launch(const Feas& f, const addrms_cfg& c, void* x, void* r, const void* w, 
     void* args[] = {&x, &r, &w, &eps, &inv_n, &m, &n, &flags, &reduce};
     const dim3 grid(static_cast<unsigned>(n_workgroups(c, M)));
     const dim3 block(static_cast<unsigned>(c.threads_per_row), static_cast<unsigned>(c.rows_per_wg));
-    HIP_TRY(hipLaunchKernel(kDispatch[f.inst].fn, grid, block, args, static_cast<size_t>(lds_bytes_for(c)), stream));
+    const int lds = lds_bytes_for(c);
+    if (lds > kDefaultDynamicLdsLimit) {
+        // Occupancy padding beyond the default per-launch limit has to be enabled once per kernel.
+        std::atomic<bool>& done = g_big_lds_enabled[f.inst];
+        if (!done.load(std::memory_order_acquire)) {
+            HIP_TRY(hipFuncSetAttribute(kDispatch[f.inst].fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        hw().lds_bytes_per_cu));
+            done.store(true, std::memory_order_release);
+        }
+    }
+    HIP_TRY(hipLaunchKernel(kDispatch[f.inst].fn, grid, block, args, static_cast<size_t>(lds), stream));
     return ADDRMS_OK;
 }
 
@@ -359,7 +373,7 @@ int addrms_tune(int64_t M, int64_t N, int dtype, const addrms_budget* budget, ad
     // S_ref: the default configuration's output on the pristine inputs.
     if (check_cfg(dflt, M, N, dtype).status != ADDRMS_OK) {
         std::vector<addrms_cfg> v;
-        enumerate(M, N, dtype, &v, nullptr);
+        enumerate(M, N, dtype, &v, nullptr, nullptr);
         if (v.empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
         dflt = v.front();
     }

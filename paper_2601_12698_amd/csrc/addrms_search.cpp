@@ -135,7 +135,7 @@ struct Searcher {
             const double threads = static_cast<double>(c.threads_per_row) * c.rows_per_wg;
             const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
             const double score = fabs(log2(threads / 256.0)) + (c.reduce == ADDRMS_REDUCE_LDS ? 10.0 : 0.0) +
-                                 (c.flags ? 10.0 : 0.0) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
+                                 (c.flags ? 10.0 : 0.0) + (c.max_waves_per_simd ? 10.0 : 0.0) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
             auto key = std::make_pair(-c.vec, c.threads_per_row);       // widest vector first
             auto it = best.find(key);
             if (it == best.end() || score < it->second.first) best[key] = {score, i};
@@ -158,6 +158,21 @@ struct Searcher {
         { addrms_cfg n = c; n.reduce ^= 1; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_XCD_CONTIG; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_NONTEMPORAL; push(n); }
+        // occupancy cap: one step tighter, one step looser (0 = uncapped sits above the natural occupancy)
+        {
+            const int natural = cands[i].res.waves_per_simd;
+            const int cur = c.max_waves_per_simd == 0 ? natural + 1 : c.max_waves_per_simd;
+            for (int k = cur - 1; k >= 1; --k) {            // next tighter cap that is feasible
+                addrms_cfg n = c; n.max_waves_per_simd = k;
+                if (find(n) >= 0) { push(n); break; }
+            }
+            bool found = false;
+            for (int k = cur + 1; k < hw().max_waves_per_simd && !found; ++k) {
+                addrms_cfg n = c; n.max_waves_per_simd = k;
+                if (find(n) >= 0) { push(n); found = true; }
+            }
+            if (!found && c.max_waves_per_simd != 0) { addrms_cfg n = c; n.max_waves_per_simd = 0; push(n); }
+        }
         // threads_per_row: nearest feasible values above and below at this vec
         int up = 0, down = 0;
         for (const Cand& o : cands) {
@@ -252,7 +267,8 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     s.bytes = static_cast<double>(addrms_algorithmic_bytes(M, N, dtype));
     std::vector<addrms_cfg> feasible;
     int64_t n_grid = 0;
-    enumerate(M, N, dtype, &feasible, &n_grid);
+    std::map<std::string, int64_t> pruned;   // which rule removed how many grid points
+    enumerate(M, N, dtype, &feasible, &n_grid, &pruned);
     addrms_cfg dflt{};
     std::string why;
     const int dst = default_cfg(N, dtype, &dflt, &why);
@@ -279,19 +295,6 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     if (b.log_path) {
         s.log = fopen(b.log_path, "a");
         if (!s.log) return fail(ADDRMS_ERR_IO, "cannot open log %s", b.log_path);
-        // prune histogram: which rule removed how many grid points
-        std::map<std::string, int64_t> pruned;
-        {
-            std::vector<int> tprs = {8, 16, 32};
-            for (int t = 64; t <= hw().max_threads_per_wg; t += 64) tprs.push_back(t);
-            for (int vec : {8, 4, 2, 1}) for (int tpr : tprs) for (int rows : {1, 2, 4, 8, 16})
-                for (int red = 0; red < 2; ++red) for (int unr : {1, 2, 4, 8}) for (int fl = 0; fl < 4; ++fl) {
-                    addrms_cfg c{};
-                    c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows; c.reduce = red; c.unroll = unr; c.flags = fl;
-                    const Feas f = check_cfg(c, M, N, dtype);
-                    if (f.status != ADDRMS_OK) ++pruned[f.rule];
-                }
-        }
         fprintf(s.log, "{\"event\":\"begin\",\"M\":%lld,\"N\":%lld,\"dtype\":\"%s\",\"strategy\":\"%s\",\"n_grid\":%lld,"
                        "\"n_feasible\":%lld,\"default\":%s,\"pruned\":{",
                 (long long)M, (long long)N, dtype_name(dtype), b.strategy == ADDRMS_SEARCH_GUIDED ? "guided" : "exhaustive",

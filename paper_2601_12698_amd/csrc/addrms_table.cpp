@@ -46,7 +46,7 @@ int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out)
     return ADDRMS_OK;
 }
 
-static const char kMagic[] = "addrms-table 1 gfx950";
+static const char kMagic[] = "addrms-table 2 gfx950";
 
 }  // namespace addrms_host
 
@@ -90,12 +90,12 @@ int addrms_table_save(const char* path)
     std::lock_guard<std::mutex> lock(g_mu);
     FILE* f = fopen(path, "w");
     if (!f) return fail(ADDRMS_ERR_IO, "cannot open %s for writing", path);
-    fprintf(f, "%s\n# dtype M N vec threads_per_row rows_per_wg reduce unroll flags mean_us\n", kMagic);
+    fprintf(f, "%s\n# dtype M N vec threads_per_row rows_per_wg reduce unroll flags max_waves_per_simd mean_us\n", kMagic);
     for (const auto& kv : table()) {
         const addrms_cfg& c = kv.second.cfg;
-        fprintf(f, "%d %lld %lld %d %d %d %d %d %d %.6f\n", std::get<0>(kv.first),
+        fprintf(f, "%d %lld %lld %d %d %d %d %d %d %d %.6f\n", std::get<0>(kv.first),
                 (long long)std::get<2>(kv.first), (long long)std::get<1>(kv.first), c.vec, c.threads_per_row,
-                c.rows_per_wg, c.reduce, c.unroll, c.flags, kv.second.us);
+                c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd, kv.second.us);
     }
     const bool bad = ferror(f) != 0;
     if (fclose(f) != 0 || bad) return fail(ADDRMS_ERR_IO, "write to %s failed", path);
@@ -125,9 +125,10 @@ int addrms_table_load(const char* path)
         }
         if (len == 0 || line[0] == '#') continue;
         int dtype; long long M, N; addrms_cfg c{}; double us; int used = 0;
-        const int got = sscanf(line, "%d %lld %lld %d %d %d %d %d %d %lf %n", &dtype, &M, &N, &c.vec,
-                               &c.threads_per_row, &c.rows_per_wg, &c.reduce, &c.unroll, &c.flags, &us, &used);
-        if (got != 10 || static_cast<size_t>(used) != len) {
+        const int got = sscanf(line, "%d %lld %lld %d %d %d %d %d %d %d %lf %n", &dtype, &M, &N, &c.vec,
+                               &c.threads_per_row, &c.rows_per_wg, &c.reduce, &c.unroll, &c.flags,
+                               &c.max_waves_per_simd, &us, &used);
+        if (got != 11 || static_cast<size_t>(used) != len) {
             fclose(f);
             return fail(ADDRMS_ERR_IO, "%s:%d: malformed entry", path, lineno);
         }

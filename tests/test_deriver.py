@@ -40,6 +40,10 @@ KNOWN_INFEASIBLE = [
     (B.make_cfg(8, 256, 4, unroll=2), 2, 4096, "bf16", "exceeds the 2 rows"),
     (B.make_cfg(8, 256, 1, unroll=2, flags=1), 8, 4096, "bf16", "identity mapping"),
     (B.make_cfg(8, 64, 16, unroll=2), 4096, 4096, "bf16", "at most 256 threads"),
+    (B.make_cfg(8, 256, 1, unroll=2, max_waves_per_simd=8), 4096, 4096, "bf16", "max_waves_per_simd"),
+    (B.make_cfg(8, 576, 1, max_waves_per_simd=6), 4096, 4096, "bf16", "both leave"),   # 9-wave groups: caps 5 and 6 both leave 2
+    (B.make_cfg(8, 576, 1, max_waves_per_simd=2), 4096, 4096, "bf16", "less than one"),
+    (B.make_cfg(8, 576, 1, max_waves_per_simd=7), 4096, 4096, "bf16", "changes nothing"),
 ]
 
 
@@ -62,7 +66,7 @@ def test_bad_shape_and_dtype_codes():
                                        (8192, 1000, "fp16_res32"), (8192, 2880, "fp16_res32"), (128, 11008, "fp32")])
 def test_enumeration_is_exactly_the_feasible_subset(M, N, dtype):
     cfgs, grid = B.addrms_enumerate_feasible(M, N, dtype)
-    assert grid == 4 * 19 * 5 * 2 * 4 * 4
+    assert grid == 4 * 19 * 5 * 2 * 4 * 4 * 8
     assert 0 < len(cfgs) < grid
     seen = set()
     for c in cfgs:
@@ -83,7 +87,7 @@ def test_enumeration_counts_are_stable():
     """Region sizes for the benchmark shapes (a change here is a change of the region)."""
     got = {k: len(B.addrms_enumerate_feasible(*k)[0]) for k in
            [(4096, 4096, "bf16"), (16, 4096, "bf16"), (256, 8192, "bf16"), (32768, 7168, "bf16")]}
-    assert got[(4096, 4096, "bf16")] == 2072
+    assert got[(4096, 4096, "bf16")] == 6904
     assert got[(16, 4096, "bf16")] < got[(4096, 4096, "bf16")]      # fewer rows: fewer row packings, no XCD map
     assert all(v > 100 for v in got.values())
 
@@ -120,14 +124,30 @@ def test_occupancy_model_matches_compiler_report():
     assert res.waves_per_simd_regs == rr["occupancy"]
 
 
+def test_occupancy_cap_is_modelled():
+    """max_waves_per_simd lowers the resident workgroups per CU by LDS padding."""
+    base = B.make_cfg(8, 256, 1, unroll=2)
+    st, _, r0 = feas(base, 4096, 4096, "bf16")
+    assert st == 0 and r0.wgs_per_cu == 8 and r0.lds_bytes == 128
+    for cap, wgs in ((6, 6), (5, 5), (4, 4), (3, 3), (2, 2)):
+        c = B.make_cfg(8, 256, 1, unroll=2, max_waves_per_simd=cap)
+        st, why, r = feas(c, 4096, 4096, "bf16")
+        assert st == 0, why
+        assert r.wgs_per_cu == wgs and r.waves_per_simd == wgs
+        # the padding admits exactly `wgs` workgroups in 160 KB
+        assert wgs * r.lds_bytes <= 160 * 1024 < (wgs + 1) * r.lds_bytes
+    st, why, _ = feas(B.make_cfg(8, 256, 1, unroll=2, max_waves_per_simd=1), 4096, 4096, "bf16")
+    assert st == B.ERR_INFEASIBLE_CFG and "too few loads in flight" in why
+
+
 def test_default_cfg():
     for N, dtype in [(4096, "bf16"), (8192, "bf16"), (7168, "bf16"), (5120, "fp16_res32"), (2880, "fp16_res32"),
                      (1000, "fp16_res32"), (4096, "fp32"), (11008, "fp32"), (14336, "fp32"), (1001, "bf16"), (8, "bf16")]:
         d = B.addrms_default_cfg(N, dtype)
         for M in (1, 16, 4096):
             assert feas(d, M, N, dtype)[0] == 0, (N, dtype, M, d)
-        assert d.reduce == B.REDUCE_WAVE and d.flags == 0
+        assert d.reduce == B.REDUCE_WAVE and d.flags == 0 and d.max_waves_per_simd == 0
     d = B.addrms_default_cfg(4096, "bf16")
-    assert d.as_tuple() == (8, 256, 1, 0, 2, 0)
+    assert d.as_tuple() == (8, 256, 1, 0, 2, 0, 0)
     assert B.load().addrms_default_cfg(1 << 20, B.BF16, B.Cfg()) == B.ERR_UNSUPPORTED_SHAPE
     assert "row cache" in B.addrms_last_error()

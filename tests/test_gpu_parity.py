@@ -54,6 +54,8 @@ def test_every_feasible_cfg_matches_oracle(oracle, dtype, M, N, seed):
     assert len(cfgs) > 50
     print(f"{wl.name}: {len(cfgs)} feasible of {grid}", flush=True)
     total_diff = 0
+    # occupancy-capped variants run the same kernel with more LDS: cover every uncapped cfg, a third of the capped
+    cfgs = [c for i, c in enumerate(cfgs) if c.max_waves_per_simd == 0 or i % 3 == 0]
     for c in cfgs:
         y, res = case.run(c)
         st = compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")

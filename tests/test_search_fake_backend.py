@@ -15,7 +15,8 @@ M, N, DT = 4096, 4096, "bf16"
 
 def cost(c, noise=0.0):
     """Unimodal in every knob, optimum at vec 8, 512 threads per row, 2 rows per
-    workgroup, wave reduction, one chunk in flight, non-temporal, identity mapping."""
+    workgroup, wave reduction, one chunk in flight, non-temporal, identity mapping,
+    4 resident waves per SIMD."""
     us = 20.0
     us *= 1.0 + 0.30 * abs(math.log2(c.threads_per_row / 512.0))
     us *= 1.0 + 0.25 * abs(math.log2(c.vec / 8.0))
@@ -24,6 +25,7 @@ def cost(c, noise=0.0):
     us *= 1.0 + 0.03 * abs(math.log2(c.unroll))
     us *= 0.85 if c.flags & B.FLAG_NONTEMPORAL else 1.0
     us *= 1.02 if c.flags & B.FLAG_XCD_CONTIG else 1.0
+    us *= 1.0 + 0.02 * abs((c.max_waves_per_simd or 8) - 4)
     if noise:
         h = hash(c.as_tuple()) % 1000 / 1000.0 - 0.5
         us *= 1.0 + noise * h
@@ -57,7 +59,7 @@ def test_exhaustive_is_the_argmin():
     rec = Recorder(cost)
     best, n = true_best(cost)
     got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE), rec.measure, rec.validate)
-    assert got.as_tuple() == best.as_tuple() == (8, 512, 2, 0, 1, 2)
+    assert got.as_tuple() == best.as_tuple() == (8, 512, 2, 0, 1, 2, 4)
     assert rep.n_feasible == n == rep.n_measured and rep.n_failed == 0
     assert len(set(rec.validated)) == n                      # every candidate went through the gate
     assert rep.best_us == pytest.approx(cost(best)) and rep.default_us == pytest.approx(cost(B.addrms_default_cfg(N, DT)))

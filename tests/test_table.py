@@ -39,7 +39,7 @@ def test_insert_rejects_infeasible():
 
 
 def test_save_load_round_trip(tmp_path):
-    a = B.make_cfg(8, 576, 1, flags=B.FLAG_NONTEMPORAL)
+    a = B.make_cfg(8, 576, 1, flags=B.FLAG_NONTEMPORAL, max_waves_per_simd=5)
     b = B.make_cfg(4, 128, 2, reduce=B.REDUCE_LDS, unroll=2)
     B.addrms_table_insert(4096, 4096, "bf16", a, 23.5)
     B.addrms_table_insert(8192, 1000, "fp16_res32", b, 17.25)
@@ -55,11 +55,12 @@ def test_save_load_round_trip(tmp_path):
 
 @pytest.mark.parametrize("content", [
     "",                                                     # empty
-    "not a table\n0 1 8192 8 1024 1 0 1 0 3.0\n",         # wrong magic
-    "addrms-table 1 gfx950\n0 1 8192 8 1024 1 0 1\n",      # truncated entry
-    "addrms-table 1 gfx950\n0 1 8192 8 1024 1 0 1 0 3.0 junk\n",
-    "addrms-table 1 gfx950\n0 4096 4096 8 1024 1 0 1 0 3.0\n",   # parses, but cfg infeasible for that shape
-    "addrms-table 1 gfx950\n7 1 8192 8 1024 1 0 1 0 3.0\n",      # bad dtype
+    "not a table\n0 1 8192 8 1024 1 0 1 0 0 3.0\n",         # wrong magic
+    "addrms-table 1 gfx950\n0 1 8192 8 1024 1 0 1 0 3.0\n",  # older format version
+    "addrms-table 2 gfx950\n0 1 8192 8 1024 1 0 1 0\n",      # truncated entry
+    "addrms-table 2 gfx950\n0 1 8192 8 1024 1 0 1 0 0 3.0 junk\n",
+    "addrms-table 2 gfx950\n0 4096 4096 8 1024 1 0 1 0 0 3.0\n",   # parses, but cfg infeasible for that shape
+    "addrms-table 2 gfx950\n7 1 8192 8 1024 1 0 1 0 0 3.0\n",      # bad dtype
 ])
 def test_corrupt_file_leaves_table_unchanged(tmp_path, content):
     keep = B.make_cfg(8, 1024, 1)
