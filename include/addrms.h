@@ -56,7 +56,9 @@ typedef enum addrms_dtype {
 enum { ADDRMS_REDUCE_WAVE = 0,   /* wave64 cross-lane butterfly, one LDS hop across waves */
        ADDRMS_REDUCE_LDS = 1 };  /* LDS-staged tree reduction                             */
 enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguous row range       */
-       ADDRMS_FLAG_NONTEMPORAL = 2 }; /* streaming cache policy on x/residual loads and stores    */
+       ADDRMS_FLAG_NONTEMPORAL = 2,   /* streaming cache policy on x/residual loads and stores    */
+       ADDRMS_FLAG_PERSISTENT = 4 };  /* grid = resident workgroups only; each walks several row
+                                         blocks and prefetches the next block before reducing   */
 
 typedef struct addrms_cfg {
     int32_t vec;              /* elements per thread per vector access: 1, 2, 4, 8        */

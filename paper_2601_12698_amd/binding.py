@@ -24,6 +24,7 @@ DTYPE_IDS = {"bf16": BF16, "fp16": FP16, "fp16_res32": FP16_RES32, "fp32": FP32}
 REDUCE_WAVE, REDUCE_LDS = 0, 1
 FLAG_XCD_CONTIG = 1
 FLAG_NONTEMPORAL = 2
+FLAG_PERSISTENT = 4
 SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
 MAX_TOPK = 8
 

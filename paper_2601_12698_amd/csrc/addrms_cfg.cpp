@@ -135,8 +135,10 @@ std::string cfg_json(const addrms_cfg& c)
 
 int reduction_lds_bytes(const addrms_cfg& c)
 {
-    if (c.reduce == ADDRMS_REDUCE_LDS) return c.threads_per_row * c.rows_per_wg * 8;
-    return c.threads_per_row > 64 ? c.rows_per_wg * 16 * 8 : 0;   // one fp64 slot per wave of a row
+    // a persistent workgroup alternates between two regions from one row block to the next
+    const int regions = (c.flags & ADDRMS_FLAG_PERSISTENT) ? 2 : 1;
+    if (c.reduce == ADDRMS_REDUCE_LDS) return regions * c.threads_per_row * c.rows_per_wg * 8;
+    return c.threads_per_row > 64 ? regions * c.rows_per_wg * 16 * 8 : 0;   // one fp64 slot per wave of a row
 }
 
 int capped_wgs_per_cu(const addrms_cfg& c)
@@ -166,7 +168,13 @@ int lds_bytes_for(const addrms_cfg& c)
     const int pad = lds_padding_for_wgs(wgs);
     return pad == 0 ? 0 : std::max(need, pad);
 }
-int64_t n_workgroups(const addrms_cfg& c, int64_t M) { return (M + c.rows_per_wg - 1) / c.rows_per_wg; }
+int64_t n_row_blocks(const addrms_cfg& c, int64_t M) { return (M + c.rows_per_wg - 1) / c.rows_per_wg; }
+int64_t n_workgroups(const addrms_cfg& c, int64_t M, int wgs_per_cu)
+{
+    const int64_t blocks = n_row_blocks(c, M);
+    if (!(c.flags & ADDRMS_FLAG_PERSISTENT)) return blocks;
+    return std::min<int64_t>(blocks, static_cast<int64_t>(hw().compute_units) * std::max(1, wgs_per_cu));
+}
 
 // ---- the rules ------------------------------------------------------------------
 static Feas infeasible(const char* rule, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
@@ -207,7 +215,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     if (c.reduce != ADDRMS_REDUCE_WAVE && c.reduce != ADDRMS_REDUCE_LDS)
         return infeasible("grid", "reduce=%d: must be wave (0) or lds (1)", c.reduce);
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
-    if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL)) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
+    if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT)) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
     if (c.max_waves_per_simd < 0 || c.max_waves_per_simd >= L.max_waves_per_simd)
         return infeasible("grid", "max_waves_per_simd=%d: must be 0 (no cap) or 1..%d", c.max_waves_per_simd,
                           L.max_waves_per_simd - 1);
@@ -254,7 +262,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     const int min_rows = std::max(1, L.wave_size / c.threads_per_row);
     if (c.rows_per_wg > std::max<int64_t>(M, min_rows) && c.rows_per_wg > min_rows)
         return infeasible("rows_gt_m", "rows_per_wg=%d exceeds the %lld rows there are", c.rows_per_wg, (long long)M);
-    if ((c.flags & ADDRMS_FLAG_XCD_CONTIG) && n_workgroups(c, M) < 2 * L.xcds)
+    if ((c.flags & ADDRMS_FLAG_XCD_CONTIG) && n_row_blocks(c, M) < 2 * L.xcds)
         return infeasible("xcd_identity", "XCD-contiguous mapping with fewer than %d workgroups is the identity mapping",
                           2 * L.xcds);
 
@@ -308,6 +316,9 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
         return infeasible("occupancy", "workgroup of %d waves at %d registers per lane does not fit one CU (%d wave slots by "
                           "registers, %d bytes of LDS)", o.waves_per_wg, regs, waves_cu_regs, o.lds_bytes);
     o.waves_per_simd = (wgs * o.waves_per_wg + L.simds_per_cu - 1) / L.simds_per_cu;
+    if ((c.flags & ADDRMS_FLAG_PERSISTENT) && n_row_blocks(c, M) <= static_cast<int64_t>(L.compute_units) * wgs)
+        return infeasible("persistent_identity", "all %lld row blocks are resident at once (%d CUs x %d workgroups): a "
+                          "persistent grid is the ordinary grid", (long long)n_row_blocks(c, M), L.compute_units, wgs);
     if (o.waves_per_simd < kMinWavesPerSimd)
         return infeasible("occupancy", "only %d wave per SIMD would be resident (%d registers per lane, %d-wave workgroups): too "
                           "few loads in flight to cover HBM latency", o.waves_per_simd, regs, o.waves_per_wg);
@@ -325,7 +336,7 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
             for (int rows : kRows)
                 for (int red = 0; red < 2; ++red)
                     for (int unr : kUnrolls)
-                        for (int flags = 0; flags < 4; ++flags)
+                        for (int flags = 0; flags < 8; ++flags)
                             for (int cap = 0; cap < hw().max_waves_per_simd; ++cap) {
                                 ++grid;
                                 addrms_cfg c{};

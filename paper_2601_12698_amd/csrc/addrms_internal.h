@@ -74,7 +74,10 @@ int lds_bytes_for(const addrms_cfg& c);
 int reduction_lds_bytes(const addrms_cfg& c);
 // Workgroups per CU that cfg.max_waves_per_simd allows (0 = no cap requested).
 int capped_wgs_per_cu(const addrms_cfg& c);
-int64_t n_workgroups(const addrms_cfg& c, int64_t M);
+// Blocks of rows_per_wg rows; and the grid size: one workgroup per block, or for a
+// persistent cfg the number of workgroups resident on the chip (wgs_per_cu from check_cfg).
+int64_t n_row_blocks(const addrms_cfg& c, int64_t M);
+int64_t n_workgroups(const addrms_cfg& c, int64_t M, int wgs_per_cu);
 
 bool cfg_equal(const addrms_cfg& a, const addrms_cfg& b);
 uint64_t cfg_key(const addrms_cfg& c);

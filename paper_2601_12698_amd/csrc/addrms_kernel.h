@@ -14,7 +14,9 @@
 //             LDS-staged tree
 //   NT    non-temporal (streaming) cache policy on the x and residual loads
 //         and stores; the weight vector always uses the default policy
-//   flags   : XCD-contiguous mapping of workgroups to rows
+//   flags   : XCD-contiguous mapping of workgroups to rows; persistent grid
+//             (set by the host through the grid size: fewer workgroups than
+//             row blocks makes each workgroup loop with a prefetch)
 //
 // VEC, CPT, UNR and NT are compile-time; the rest are launch-time and uniform
 // over the workgroup.
@@ -33,7 +35,7 @@ namespace addrms {
 
 enum : int { DT_BF16 = 0, DT_FP16 = 1, DT_FP16_RES32 = 2, DT_FP32 = 3 };
 enum : int { RED_WAVE = 0, RED_LDS = 1 };
-enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u };
+enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u, FLAG_PERSISTENT = 4u };
 
 template <int DT> struct dt_traits;
 template <> struct dt_traits<DT_BF16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = true;  };
@@ -259,10 +261,58 @@ __device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t nb)
     return xcd * q + (xcd < rem ? xcd : rem) + idx;
 }
 
+// Per-workgroup-iteration addressing: base pointers are wave-uniform (SGPRs), the
+// per-thread part fits 32 bits.
+struct RowAddr {
+    char* xbase;
+    char* rbase;
+    uint32_t rowoff;   // elements from the workgroup's first row to this thread's row
+    uint32_t row_ok;   // 1 if this thread's row exists (the last workgroup may be ragged)
+};
+
+template <int XB, int RB>
+__device__ __forceinline__ RowAddr row_addr(void* xp, void* rp, uint32_t blk, uint32_t rpw, uint32_t ry,
+                                            int64_t M, int32_t N)
+{
+    RowAddr a;
+    const int64_t row0 = static_cast<int64_t>(blk) * rpw;
+    const int64_t left = M - row0;                          // rows available to this block (>= 1)
+    a.row_ok = static_cast<int64_t>(ry) < left ? 1u : 0u;
+    const uint32_t ryc = a.row_ok ? ry : static_cast<uint32_t>(left - 1);   // ghost threads re-read the last row
+    a.xbase = static_cast<char*>(xp) + row0 * N * XB;
+    a.rbase = static_cast<char*>(rp) + row0 * N * RB;
+    a.rowoff = ryc * static_cast<uint32_t>(N);
+    return a;
+}
+
+// Issues the loads of chunk group g (UNR chunks starting at chunk g) of one row.
+template <int XB, int RB, int VEC, int CPT, int UNR, bool NT>
+__device__ __forceinline__ void load_group(const char* xbase, const char* rbase, uint32_t rowoff, uint32_t col0,
+                                           uint32_t stride, uint32_t nlast, int g,
+                                           raw_t<XB * VEC> (&xv)[UNR], raw_t<RB * VEC> (&rv)[UNR])
+{
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+        if (g + u < CPT) {
+            const uint32_t col = col0 + static_cast<uint32_t>(g + u) * stride;
+            const uint32_t colc = col < nlast ? col : nlast;      // clamp: tail lanes re-read valid data
+            ld_raw<XB * VEC, NT>(xbase + static_cast<uint64_t>((rowoff + colc) * XB), xv[u]);
+            ld_raw<RB * VEC, NT>(rbase + static_cast<uint64_t>((rowoff + colc) * RB), rv[u]);
+        }
+    }
+}
+
+// The grid has either one workgroup per block of rows_per_wg rows, or fewer
+// (a persistent grid sized to what is resident on the chip): a workgroup then
+// walks blocks blk, blk + gridDim.x, ... and issues the first loads of its
+// next block before reducing the current one, so that it always has requests
+// in flight.  Every workgroup leaves the loop after its last block; there is
+// no waiting between workgroups.
 template <int DT, int VEC, int CPT, int UNR, bool NT>
 __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restrict__ rp,
                                             const void* __restrict__ wp, float eps, double inv_n,
-                                            int64_t M, int32_t N, uint32_t flags, int32_t reduce)
+                                            int64_t M, int32_t N, uint32_t flags, int32_t reduce,
+                                            uint32_t nblocks)
 {
     using T = dt_traits<DT>;
     constexpr int XB = T::XB, RB = T::RB;
@@ -271,88 +321,97 @@ __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restr
 
     const uint32_t tpr = blockDim.x, rpw = blockDim.y;
     const uint32_t lane = threadIdx.x, ry = threadIdx.y;
-    uint32_t bid = blockIdx.x;
-    if (flags & FLAG_XCD_CONTIG) bid = xcd_contiguous(bid, gridDim.x);
+    uint32_t blk = blockIdx.x;
+    if (flags & FLAG_XCD_CONTIG) blk = xcd_contiguous(blk, gridDim.x);
 
-    // Workgroup base is wave-uniform; the per-thread part fits 32 bits.
-    const int64_t row0 = static_cast<int64_t>(bid) * rpw;
-    const int64_t left = M - row0;                        // rows available to this workgroup (>= 1)
-    const bool row_ok = static_cast<int64_t>(ry) < left;
-    const uint32_t ryc = row_ok ? ry : static_cast<uint32_t>(left - 1);
-    char* xbase = static_cast<char*>(xp) + row0 * N * XB;
-    char* rbase = static_cast<char*>(rp) + row0 * N * RB;
     const char* wbase = static_cast<const char*>(wp);
-    const uint32_t rowoff = ryc * static_cast<uint32_t>(N);   // elements
     const uint32_t col0 = lane * VEC;
     const uint32_t stride = tpr * VEC;
     const uint32_t nlast = static_cast<uint32_t>(N) - VEC;
+    // LDS region of one reduction; consecutive iterations alternate between two regions
+    const uint32_t lds_region = (reduce == RED_WAVE) ? rpw * 16u : rpw * tpr;
 
-    float h[CPT][VEC];
-    double acc = 0.0;
+    raw_t<XB * VEC> xv[UNR];
+    raw_t<RB * VEC> rv[UNR];
+    RowAddr ra = row_addr<XB, RB>(xp, rp, blk, rpw, ry, M, N);
+    load_group<XB, RB, VEC, CPT, UNR, NT>(ra.xbase, ra.rbase, ra.rowoff, col0, stride, nlast, 0, xv, rv);
 
+    uint32_t parity = 0;
+    const uint32_t col_first = col0;
+    for (;;) {
+        // Column offsets are recomputed in every iteration on purpose: hoisting them out of
+        // the row loop would keep several registers per chunk alive across the whole loop.
+        uint32_t col0 = col_first;
+        asm volatile("" : "+v"(col0));
+        float h[CPT][VEC];
+        double acc = 0.0;
 #pragma unroll
-    for (int g = 0; g < CPT; g += UNR) {
-        raw_t<XB * VEC> xv[UNR];
-        raw_t<RB * VEC> rv[UNR];
+        for (int g = 0; g < CPT; g += UNR) {
+            if (g > 0)    // group 0 was issued ahead (prologue or previous iteration)
+                load_group<XB, RB, VEC, CPT, UNR, NT>(ra.xbase, ra.rbase, ra.rowoff, col0, stride, nlast, g, xv, rv);
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            if (g + u < CPT) {
-                const uint32_t col = col0 + static_cast<uint32_t>(g + u) * stride;
-                const uint32_t colc = col < nlast ? col : nlast;      // clamp: tail lanes re-read valid data
-                ld_raw<XB * VEC, NT>(xbase + static_cast<uint64_t>((rowoff + colc) * XB), xv[u]);
-                ld_raw<RB * VEC, NT>(rbase + static_cast<uint64_t>((rowoff + colc) * RB), rv[u]);
-            }
-        }
+            for (int u = 0; u < UNR; ++u) {
+                if (g + u < CPT) {
+                    const int c = g + u;
+                    const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            if (g + u < CPT) {
-                const int c = g + u;
-                const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+                    for (int e = 0; e < VEC; ++e)
+                        h[c][e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                    if (ra.row_ok && col <= nlast) {
+                        raw_t<RB * VEC> out;
+                        pack_vec<RB, BF, VEC>(h[c], out);
+                        st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), out);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e)
-                    h[c][e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
-                if (row_ok && col <= nlast) {
-                    raw_t<RB * VEC> out;
-                    pack_vec<RB, BF, VEC>(h[c], out);
-                    st_raw<RB * VEC, NT>(rbase + static_cast<uint64_t>((rowoff + col) * RB), out);
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) {
-                        const double hd = static_cast<double>(h[c][e]);
-                        acc = __builtin_fma(hd, hd, acc);
+                        for (int e = 0; e < VEC; ++e) {
+                            const double hd = static_cast<double>(h[c][e]);
+                            acc = __builtin_fma(hd, hd, acc);
+                        }
                     }
                 }
             }
+            if (g + UNR < CPT) __builtin_amdgcn_sched_barrier(0);
         }
-        if (g + UNR < CPT) __builtin_amdgcn_sched_barrier(0);
-    }
 
-    // Weights: tiny, L2-resident after the first workgroups; issue before the
-    // reduction so their latency hides behind it.
-    raw_t<XB * VEC> wv[CPT];
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-        const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
-        const uint32_t colc = col < nlast ? col : nlast;
-        ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(colc * XB), wv[c]);
-    }
-
-    const double ss = row_sum(acc, reduce, tpr, lane, ry, lds);
-    const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
-
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-        const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
-        float y[VEC];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const float t = h[c][e] * rstd;
-            y[e] = t * get_elem<XB, BF>(wv[c], e);
+        const uint32_t next = blk + gridDim.x;
+        const bool more = next < nblocks;         // uniform over the workgroup
+        RowAddr rn = ra;
+        if (more) {
+            rn = row_addr<XB, RB>(xp, rp, next, rpw, ry, M, N);
+            load_group<XB, RB, VEC, CPT, UNR, NT>(rn.xbase, rn.rbase, rn.rowoff, col0, stride, nlast, 0, xv, rv);
         }
-        if (row_ok && col <= nlast) {
-            raw_t<XB * VEC> out;
-            pack_vec<XB, BF, VEC>(y, out);
-            st_raw<XB * VEC, NT>(xbase + static_cast<uint64_t>((rowoff + col) * XB), out);
+
+        // Weights: tiny and L2/L1-resident after the first workgroups; issued before the
+        // reduction so their latency hides behind it.
+        raw_t<XB * VEC> wv[CPT];
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+            const uint32_t colc = col < nlast ? col : nlast;
+            ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(colc * XB), wv[c]);
         }
+
+        const double ss = row_sum(acc, reduce, tpr, lane, ry, lds + parity * lds_region);
+        const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
+
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+            float y[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float t = h[c][e] * rstd;
+                y[e] = t * get_elem<XB, BF>(wv[c], e);
+            }
+            if (ra.row_ok && col <= nlast) {
+                raw_t<XB * VEC> out;
+                pack_vec<XB, BF, VEC>(y, out);
+                st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), out);
+            }
+        }
+        if (!more) break;
+        ra = rn;
+        blk = next;
+        parity ^= 1u;
     }
 }
 

@@ -60,8 +60,9 @@ int launch(const Feas& f, const addrms_cfg& c, void* x, void* r, const void* w, 
     int n = static_cast<int>(N);
     unsigned flags = static_cast<unsigned>(c.flags);
     int reduce = c.reduce;
-    void* args[] = {&x, &r, &w, &eps, &inv_n, &m, &n, &flags, &reduce};
-    const dim3 grid(static_cast<unsigned>(n_workgroups(c, M)));
+    unsigned nblocks = static_cast<unsigned>(n_row_blocks(c, M));
+    void* args[] = {&x, &r, &w, &eps, &inv_n, &m, &n, &flags, &reduce, &nblocks};
+    const dim3 grid(static_cast<unsigned>(n_workgroups(c, M, f.res.wgs_per_cu)));
     const dim3 block(static_cast<unsigned>(c.threads_per_row), static_cast<unsigned>(c.rows_per_wg));
     const int lds = lds_bytes_for(c);
     if (lds > kDefaultDynamicLdsLimit) {

@@ -12,7 +12,9 @@
 //   exhaustive  the plain definition: time every feasible cfg with the
 //               confirmation protocol, then re-test the Top-K;
 //   guided      (1) coarse sweep: one representative launch shape per
-//               (vec, threads_per_row) class, short protocol;
+//               (vec, threads_per_row) class, short protocol, in up to three
+//               modes (plain, streaming, persistent) because those corners are
+//               not connected by single-knob moves;
 //               (2) descent: from the best few classes, move one knob at a time
 //               to the best unmeasured neighbour, trying first the moves that
 //               the static signals favour (more resident waves when the kernel
@@ -84,7 +86,7 @@ struct Searcher {
                 "\"n_measured\":%lld,\"t_ms\":%.3f}\n",
                 phase, cfg_json(c.cfg).c_str(), pass ? "true" : "false", us, us > 0 ? bytes / us * 1e-3 : 0.0,
                 warmup, reps, c.res.chunks_per_thread, c.res.vgprs, c.res.agprs, c.res.lds_bytes, c.res.waves_per_wg,
-                c.res.wgs_per_cu, c.res.waves_per_simd, (long long)n_workgroups(c.cfg, M),
+                c.res.wgs_per_cu, c.res.waves_per_simd, (long long)n_workgroups(c.cfg, M, c.res.wgs_per_cu),
                 (long long)n_measured, elapsed_ms());
     }
 
@@ -125,17 +127,29 @@ struct Searcher {
     }
 
     // ---- guided: stage 1 -------------------------------------------------------
-    // One representative per (vec, threads_per_row): wave reduction, identity
-    // mapping, workgroup nearest 256 threads, two chunks in flight.
-    std::vector<int> class_representatives() const
+    // One representative per (vec, threads_per_row) class and per mode.  The modes are
+    // the corners of the space that one-knob moves do not connect well:
+    //   plain       default cache policy, workgroup nearest 256 threads, two chunks in flight
+    //   streaming   the same launch shape with the non-temporal policy
+    //   persistent  non-temporal, persistent grid (XCD-contiguous when available), the
+    //               largest workgroup and the deepest load batching the class admits
+    enum Mode { kPlain = 0, kStreaming = 1, kPersistent = 2 };
+    std::vector<int> class_representatives(Mode mode) const
     {
         std::map<std::pair<int, int>, std::pair<double, int>> best;   // class -> (score, index)
         for (int i = 0; i < static_cast<int>(cands.size()); ++i) {
             const addrms_cfg& c = cands[i].cfg;
+            if (c.reduce != ADDRMS_REDUCE_WAVE || c.max_waves_per_simd != 0) continue;
             const double threads = static_cast<double>(c.threads_per_row) * c.rows_per_wg;
-            const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
-            const double score = fabs(log2(threads / 256.0)) + (c.reduce == ADDRMS_REDUCE_LDS ? 10.0 : 0.0) +
-                                 (c.flags ? 10.0 : 0.0) + (c.max_waves_per_simd ? 10.0 : 0.0) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
+            double score;
+            if (mode == kPersistent) {
+                if (!(c.flags & ADDRMS_FLAG_PERSISTENT) || !(c.flags & ADDRMS_FLAG_NONTEMPORAL)) continue;
+                score = -threads - 0.1 * c.unroll - ((c.flags & ADDRMS_FLAG_XCD_CONTIG) ? 0.01 : 0.0);
+            } else {
+                if (c.flags != (mode == kStreaming ? ADDRMS_FLAG_NONTEMPORAL : 0)) continue;
+                const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
+                score = fabs(log2(threads / 256.0)) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
+            }
             auto key = std::make_pair(-c.vec, c.threads_per_row);       // widest vector first
             auto it = best.find(key);
             if (it == best.end() || score < it->second.first) best[key] = {score, i};
@@ -158,6 +172,7 @@ struct Searcher {
         { addrms_cfg n = c; n.reduce ^= 1; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_XCD_CONTIG; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_NONTEMPORAL; push(n); }
+        { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_PERSISTENT; push(n); }
         // occupancy cap: one step tighter, one step looser (0 = uncapped sits above the natural occupancy)
         {
             const int natural = cands[i].res.waves_per_simd;
@@ -210,7 +225,7 @@ struct Searcher {
         int p = 0;
         if (from.res.waves_per_simd < 4 && to.res.waves_per_simd > from.res.waves_per_simd) p += 2;
         const int64_t resident = static_cast<int64_t>(hw().compute_units) * std::max(1, from.res.wgs_per_cu);
-        if (n_workgroups(from.cfg, M) < resident && n_workgroups(to.cfg, M) > n_workgroups(from.cfg, M)) p += 2;
+        if (n_row_blocks(from.cfg, M) < resident && n_row_blocks(to.cfg, M) > n_row_blocks(from.cfg, M)) p += 2;
         if (to.cfg.vec > from.cfg.vec) p += 1;
         return p;
     }
@@ -311,18 +326,35 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
             s.eval(i, "exhaustive", b.warmup, b.reps);
     } else {
         if (i_default >= 0) s.eval(i_default, "default", b.coarse_warmup, b.coarse_reps);
-        for (int i : s.class_representatives()) {
+        // plain mode for every class; the other modes only for classes within a factor two of the best plain time
+        std::map<std::pair<int, int>, double> plain_us;
+        double best_plain = 0.0;
+        for (int i : s.class_representatives(Searcher::kPlain)) {
             if (!s.budget_left()) break;
-            s.eval(i, "sweep", b.coarse_warmup, b.coarse_reps);
+            if (s.eval(i, "sweep", b.coarse_warmup, b.coarse_reps)) {
+                const addrms_cfg& c = s.cands[i].cfg;
+                plain_us[{c.vec, c.threads_per_row}] = s.cands[i].us;
+                if (best_plain == 0.0 || s.cands[i].us < best_plain) best_plain = s.cands[i].us;
+            }
         }
+        for (Searcher::Mode mode : {Searcher::kStreaming, Searcher::kPersistent})
+            for (int i : s.class_representatives(mode)) {
+                if (!s.budget_left()) break;
+                const addrms_cfg& c = s.cands[i].cfg;
+                auto it = plain_us.find({c.vec, c.threads_per_row});
+                if (it != plain_us.end() && it->second > 2.0 * best_plain) continue;
+                s.eval(i, mode == Searcher::kStreaming ? "sweep_streaming" : "sweep_persistent", b.coarse_warmup,
+                       b.coarse_reps);
+            }
         std::vector<int> seeds = s.ranked();
-        // descend from the best three classes (distinct (vec, threads_per_row))
+        // descend from the best three distinct (vec, threads_per_row, persistent) corners
         std::vector<int> starts;
         for (int i : seeds) {
             bool dup = false;
             for (int j : starts)
                 dup = dup || (s.cands[j].cfg.vec == s.cands[i].cfg.vec &&
-                              s.cands[j].cfg.threads_per_row == s.cands[i].cfg.threads_per_row);
+                              s.cands[j].cfg.threads_per_row == s.cands[i].cfg.threads_per_row &&
+                              ((s.cands[j].cfg.flags ^ s.cands[i].cfg.flags) & ADDRMS_FLAG_PERSISTENT) == 0);
             if (!dup) starts.push_back(i);
             if (starts.size() == 3) break;
         }

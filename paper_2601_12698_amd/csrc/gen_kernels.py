@@ -24,6 +24,7 @@ DTS = (0, 1, 2, 3)                      # bf16, fp16, fp16+fp32 residual, fp32
 VECS = (1, 2, 4, 8)
 CPTS = (1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16)
 UNRS = (1, 2, 4, 8)
+X_BYTES = {0: 2, 1: 2, 2: 2, 3: 4}      # bytes per x element of each format
 MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 values per thread
 BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
 
@@ -31,6 +32,8 @@ BIG_ELEMS = 32                          # above this the instance is compiled fo
 def instances():
     for dt in DTS:
         for vec in VECS:
+            if vec * X_BYTES[dt] > 16:           # wider than one global access: never selectable
+                continue
             for cpt in CPTS:
                 if vec * cpt > MAX_ELEMS:
                     continue
@@ -47,7 +50,7 @@ def name(dt, vec, cpt, unr, nt):
 
 
 ARGS = ("void* x, void* r, const void* w, float eps, double inv_n, "
-        "long long M, int N, unsigned flags, int reduce")
+        "long long M, int N, unsigned flags, int reduce, unsigned nblocks")
 
 
 def main(outdir: str) -> None:
@@ -61,7 +64,7 @@ def main(outdir: str) -> None:
             lines.append(
                 f'extern "C" __global__ __launch_bounds__({maxt}) void {name(dt, vec, cpt, unr, nt)}({ARGS})\n'
                 f"{{ addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}, {'true' if nt else 'false'}>"
-                f"(x, r, w, eps, inv_n, M, N, flags, reduce); }}")
+                f"(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks); }}")
         _write(os.path.join(outdir, f"kern_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")
     decl, table, inst = [], [], []
     for dt, vec, cpt, unr, nt, maxt in instances():

@@ -32,6 +32,20 @@ def cost(c, noise=0.0):
     return us
 
 
+def cost_with_corner(c):
+    """A landscape with a corner that single-knob moves do not reach from the plain
+    configurations: the persistent grid only pays with the largest workgroup, all chunks of
+    a row in flight and the non-temporal policy together (what the device shows on
+    mid-size shapes); on its own every one of those changes is neutral or harmful."""
+    us = cost(c)
+    cpt = -(-N // (c.vec * c.threads_per_row))
+    if c.flags & B.FLAG_PERSISTENT:
+        full = (c.threads_per_row * c.rows_per_wg == 1024 and c.unroll >= min(cpt, 4)
+                and c.flags & B.FLAG_NONTEMPORAL and c.threads_per_row == 128)
+        us = 14.0 * (1.02 if c.flags & B.FLAG_XCD_CONTIG else 1.0) * (1.05 if c.reduce else 1.0) if full else us * 1.06
+    return us
+
+
 class Recorder:
     def __init__(self, fn, fail_measure=lambda c: False, fail_validate=lambda c: False):
         self.fn, self.fail_measure, self.fail_validate = fn, fail_measure, fail_validate
@@ -81,6 +95,16 @@ def test_guided_is_near_optimal_and_cheap(noise):
     assert rep.default_us > rep.best_us
 
 
+def test_guided_reaches_the_persistent_corner():
+    rec = Recorder(cost_with_corner)
+    best, n = true_best(cost_with_corner)
+    assert best.flags & B.FLAG_PERSISTENT and best.threads_per_row == 128 and best.rows_per_wg == 8
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(), rec.measure, rec.validate)
+    assert cost_with_corner(got) <= 1.03 * cost_with_corner(best)
+    assert got.flags & B.FLAG_PERSISTENT
+    assert rep.n_measured <= 0.05 * n
+
+
 def test_failing_candidates_are_contained():
     bad_launch = lambda c: c.threads_per_row == 512          # "launch failure" on the would-be optimum
     bad_output = lambda c: c.vec == 4                        # "wrong output" on a whole class
@@ -125,7 +149,7 @@ def test_log_is_json_lines(tmp_path):
     assert lines[0]["n_feasible"] == rep.n_feasible and lines[0]["n_grid"] == rep.n_grid
     assert sum(lines[0]["pruned"].values()) == rep.n_grid - rep.n_feasible
     evals = [l for l in lines if l["event"] == "eval"]
-    assert {l["phase"] for l in evals} >= {"default", "sweep", "descent", "confirm"}
+    assert {l["phase"] for l in evals} >= {"default", "sweep", "sweep_streaming", "sweep_persistent", "descent", "confirm"}
     assert all("vgprs" in l["signals"] and "waves_per_simd" in l["signals"] for l in evals)
     assert lines[-1]["best"] == got.as_dict()
 
