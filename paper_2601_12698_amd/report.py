@@ -1,0 +1,101 @@
+"""Tuned-versus-default report over the benchmark configurations (needs an MI355X).
+
+    python -m paper_2601_12698_amd.report [--exhaustive-prefill] [--table PATH]
+
+For every configuration it runs the library's guided search (the paper's Level 2:
+feasible region, search, Top-K re-test), then prints one markdown row with the
+four forms the measurement plan asks for: absolute GB/s and tokens/s, fraction
+of the 8 TB/s HBM roofline, default versus tuned configuration, and what the
+search cost (wall time, candidates timed).  The calibration kernel (same traffic,
+no arithmetic) is timed beside each shape as the attainable ceiling.  The
+specialised table built on the way can be saved with --table.
+
+All compute runs in libaddrms.so; this module only loops over shapes and formats text.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+import time
+
+import torch
+
+from . import binding as B
+from . import workloads as W
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def shapes():
+    yield W.SMOKE
+    yield W.PREFILL
+    for m in W.DECODE_M:
+        yield W.DECODE.with_rows(m)
+    yield W.LARGE_PREFILL
+    for n in W.ODD_WIDTH_N:
+        yield W.ODD_WIDTH.with_cols(n)
+
+
+def probe_us(wl, reps=50) -> float:
+    """Mean time of the calibration kernel over rotated buffers (0 if the shape
+    does not meet its 16-byte granularity)."""
+    xb, rb = W.x_bytes(wl.dtype), W.r_bytes(wl.dtype)
+    if (wl.M * wl.N * xb) % 16:
+        return 0.0
+    set_bytes = wl.M * wl.N * (xb + rb)
+    nsets = int(max(2, min(32, -(-2 * (288 << 20) // set_bytes))))
+    xs = [torch.zeros(wl.M * wl.N * xb, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    rs = [torch.zeros(wl.M * wl.N * rb, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    for i in range(10):
+        B.addrms_stream_probe(xs[i % nsets], rs[i % nsets], wl.M, wl.N, wl.dtype)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(reps):
+        B.addrms_stream_probe(xs[i % nsets], rs[i % nsets], wl.M, wl.N, wl.dtype)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--exhaustive-prefill", action="store_true",
+                    help="also run the exhaustive search on the prefill shape and report the guided search's regret")
+    ap.add_argument("--table", default=None, help="save the specialised table here")
+    a = ap.parse_args(argv)
+    if not torch.cuda.is_available():
+        print("needs a GPU", file=sys.stderr)
+        return 2
+    B.addrms_table_clear()
+    print("| workload | M x N | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tokens/s | probe GB/s | "
+          "tuned cfg (vec, threads/row, rows/wg, reduce, unroll, flags, cap) | feasible | timed | search ms |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    for wl in shapes():
+        nbytes = B.addrms_algorithmic_bytes(wl.M, wl.N, wl.dtype)
+        t0 = time.perf_counter()
+        cfg, rep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
+        wall = (time.perf_counter() - t0) * 1e3
+        p = probe_us(wl)
+        moved = 2 * wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
+        gbps = nbytes / rep.best_us * 1e-3
+        print(f"| {wl.name} | {wl.M} x {wl.N} | {rep.default_us:.2f} | {rep.best_us:.2f} | "
+              f"{rep.default_us / rep.best_us:.3f} | {gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | "
+              f"{wl.M / rep.best_us * 1e6:.3g} | {(moved / p * 1e-3) if p else float('nan'):.0f} | "
+              f"{cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
+    if a.exhaustive_prefill:
+        wl = W.PREFILL
+        g, grep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
+        e, erep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps, strategy=B.SEARCH_EXHAUSTIVE))
+        tg = min(B.addrms_measure(g, wl.M, wl.N, wl.dtype) for _ in range(3))
+        te = min(B.addrms_measure(e, wl.M, wl.N, wl.dtype) for _ in range(3))
+        print(f"\nprefill: guided {g.as_tuple()} {tg:.2f} us after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
+              f"exhaustive {e.as_tuple()} {te:.2f} us after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms; "
+              f"regret {tg / te:.4f}")
+    if a.table:
+        B.addrms_table_save(a.table)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
