@@ -192,6 +192,47 @@ int addrms_tune_with_backend(int64_t M, int64_t N, int dtype, const addrms_budge
                              const addrms_backend* backend,
                              addrms_cfg* out_cfg, addrms_tune_report* report);
 
+/* ---- general configuration (Algorithm 1 line 22, SelectGeneral) ----------------
+ * One cfg for a whole set of shapes of one dtype: each shape is searched as in
+ * addrms_tune (its winner goes to the specialised table, line 23); the Top-K of all
+ * shapes, the default cfgs, and the universally feasible cfgs closest to each shape's
+ * winner form the pool; every pool member that is feasible on every shape is timed on
+ * every shape with the confirmation protocol; the winner maximises the geometric mean
+ * over shapes of default_time / time (the aggregate of Section 3.1). */
+#define ADDRMS_MAX_SHAPES 16
+typedef struct addrms_shape { int64_t M, N; } addrms_shape;
+
+typedef struct addrms_general_report {
+    int32_t n_shapes;
+    int32_t n_pool;                        /* universally feasible candidates that were timed  */
+    double  geomean_speedup_general;       /* theta_gen against the default cfg of each shape  */
+    double  geomean_speedup_specialized;   /* each shape's own winner against its default       */
+    double  mean_speedup_general;          /* arithmetic mean of the same per-shape ratios      */
+    double  wall_ms;
+    double  default_us[ADDRMS_MAX_SHAPES];
+    double  general_us[ADDRMS_MAX_SHAPES];
+    double  specialized_us[ADDRMS_MAX_SHAPES];
+    addrms_cfg specialized[ADDRMS_MAX_SHAPES];
+} addrms_general_report;
+
+/* shapes: host, n in 1..ADDRMS_MAX_SHAPES; out_general: host, required; report: host, may be NULL.
+ * Blocking; allocates and frees device buffers shape by shape.  ADDRMS_ERR_NO_RESULT if no cfg is
+ * feasible on all shapes. */
+int addrms_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                          addrms_cfg* out_general, addrms_general_report* report);
+
+/* The same selection over caller-supplied measurement: open() fills a backend for one
+ * shape, close() releases it; at most one backend is open at a time. */
+typedef struct addrms_backend_factory {
+    void* user;
+    int (*open)(void* user, int64_t M, int64_t N, int dtype, addrms_backend* out);
+    void (*close)(void* user, addrms_backend* backend);
+} addrms_backend_factory;
+
+int addrms_select_general_with_backend(const addrms_shape* shapes, int32_t n, int dtype,
+                                       const addrms_budget* budget, const addrms_backend_factory* factory,
+                                       addrms_cfg* out_general, addrms_general_report* report);
+
 /* addrms_measure: mean time in microseconds of `cfg` (NULL = table/default, as
  * in addrms_run) on (M, N, dtype) over `reps` launches after `warmup`, on
  * library-allocated synthetic buffers.  rotate != 0 cycles through enough

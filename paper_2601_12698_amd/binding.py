@@ -111,6 +111,37 @@ class Backend(Structure):
     _fields_ = [("user", c_void_p), ("validate", VALIDATE_FN), ("measure", MEASURE_FN)]
 
 
+MAX_SHAPES = 16
+
+
+class Shape(Structure):
+    _fields_ = [("M", c_int64), ("N", c_int64)]
+
+
+class GeneralReport(Structure):
+    _fields_ = [("n_shapes", c_int32), ("n_pool", c_int32), ("geomean_speedup_general", c_double),
+                ("geomean_speedup_specialized", c_double), ("mean_speedup_general", c_double),
+                ("wall_ms", c_double), ("default_us", c_double * MAX_SHAPES), ("general_us", c_double * MAX_SHAPES),
+                ("specialized_us", c_double * MAX_SHAPES), ("specialized", Cfg * MAX_SHAPES)]
+
+    def as_dict(self) -> dict:
+        n = self.n_shapes
+        return dict(n_shapes=n, n_pool=self.n_pool, geomean_speedup_general=self.geomean_speedup_general,
+                    geomean_speedup_specialized=self.geomean_speedup_specialized,
+                    mean_speedup_general=self.mean_speedup_general, wall_ms=self.wall_ms,
+                    default_us=list(self.default_us[:n]), general_us=list(self.general_us[:n]),
+                    specialized_us=list(self.specialized_us[:n]),
+                    specialized=[self.specialized[i].as_dict() for i in range(n)])
+
+
+OPEN_FN = CFUNCTYPE(c_int, c_void_p, c_int64, c_int64, c_int, POINTER(Backend))
+CLOSE_FN = CFUNCTYPE(None, c_void_p, POINTER(Backend))
+
+
+class BackendFactory(Structure):
+    _fields_ = [("user", c_void_p), ("open", OPEN_FN), ("close", CLOSE_FN)]
+
+
 # name -> (restype, argtypes); mirrors include/addrms.h one to one
 SIGNATURES = {
     "addrms_run": (c_int, [c_void_p, c_void_p, c_void_p, c_float, c_int64, c_int64, c_int, POINTER(Cfg), c_void_p]),
@@ -120,6 +151,10 @@ SIGNATURES = {
     "addrms_tune": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Cfg), POINTER(TuneReport)]),
     "addrms_tune_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
                                          POINTER(Cfg), POINTER(TuneReport)]),
+    "addrms_select_general": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg),
+                                      POINTER(GeneralReport)]),
+    "addrms_select_general_with_backend": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget),
+                                                   POINTER(BackendFactory), POINTER(Cfg), POINTER(GeneralReport)]),
     "addrms_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_float, c_int, c_int, c_int, POINTER(c_double)]),
     "addrms_table_insert": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg), c_double]),
     "addrms_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
@@ -278,6 +313,78 @@ def addrms_tune_with_backend(M: int, N: int, dtype, budget: Optional[Budget], me
     c, rep = Cfg(), TuneReport()
     _check(load().addrms_tune_with_backend(M, N, _dtype_id(dtype), byref(budget) if budget is not None else None,
                                            byref(be), byref(c), byref(rep)))
+    return c, rep
+
+
+def _wrap_measure(measure):
+    def _m(_user, cfg_p, warmup, reps, out):
+        try:
+            us = measure(cfg_p.contents, warmup, reps)
+        except Exception:
+            return 1
+        if us is None:
+            return 1
+        out[0] = float(us)
+        return 0
+    return MEASURE_FN(_m)
+
+
+def _wrap_validate(validate):
+    if validate is None:
+        return VALIDATE_FN()
+
+    def _v(_user, cfg_p):
+        try:
+            return 0 if validate(cfg_p.contents) else 1
+        except Exception:
+            return 1
+    return VALIDATE_FN(_v)
+
+
+def _shape_array(shapes):
+    arr = (Shape * len(shapes))()
+    for i, (m, n) in enumerate(shapes):
+        arr[i].M, arr[i].N = m, n
+    return arr
+
+
+def addrms_select_general(shapes, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, GeneralReport]:
+    """shapes: list of (M, N).  Returns (theta_gen, report)."""
+    c, rep = Cfg(), GeneralReport()
+    _check(load().addrms_select_general(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                        byref(budget) if budget is not None else None, byref(c), byref(rep)))
+    return c, rep
+
+
+def addrms_select_general_with_backend(shapes, dtype, budget: Optional[Budget], make_backend
+                                       ) -> Tuple[Cfg, GeneralReport]:
+    """``make_backend(M, N) -> (measure, validate_or_None)`` with the callables of
+    :func:`addrms_tune_with_backend`."""
+    keep = []
+
+    def _open(_user, M, N, _dt, out):
+        try:
+            measure, validate = make_backend(M, N)
+        except Exception:
+            return 1
+        m, v = _wrap_measure(measure), _wrap_validate(validate)
+        keep.append((m, v))
+        out.contents.user = None
+        out.contents.measure = m
+        out.contents.validate = v
+        return 0
+
+    def _close(_user, _be):
+        return None
+
+    fac = BackendFactory()
+    fac.user = None
+    fac.open = OPEN_FN(_open)
+    fac.close = CLOSE_FN(_close)
+    c, rep = Cfg(), GeneralReport()
+    _check(load().addrms_select_general_with_backend(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                                     byref(budget) if budget is not None else None, byref(fac),
+                                                     byref(c), byref(rep)))
     return c, rep
 
 

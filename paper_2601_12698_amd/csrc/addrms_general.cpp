@@ -1,0 +1,175 @@
+// General configuration (Algorithm 1 line 22, SelectGeneral; Section 4, "Performance
+// Measurement": besides the best specialised cfg per shape, report the one general
+// cfg with the best average performance across shapes).  The aggregate is the
+// geometric-mean speed-up of Section 3.1, taken against each shape's default cfg.
+//
+// Host-only: measurement comes through a backend factory, one backend per shape.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <chrono>
+#include <unordered_set>
+
+#include "addrms_internal.h"
+
+namespace addrms_host {
+namespace {
+
+double knob_distance(const addrms_cfg& a, const addrms_cfg& b)
+{
+    auto l2 = [](int v) { return log2(static_cast<double>(std::max(1, v))); };
+    return fabs(l2(a.vec) - l2(b.vec)) * 2.0 + fabs(l2(a.threads_per_row) - l2(b.threads_per_row)) +
+           fabs(l2(a.rows_per_wg) - l2(b.rows_per_wg)) + fabs(l2(a.unroll) - l2(b.unroll)) * 0.5 +
+           (a.reduce != b.reduce ? 1.0 : 0.0) + __builtin_popcount(static_cast<unsigned>(a.flags ^ b.flags)) +
+           0.25 * abs(a.max_waves_per_simd - b.max_waves_per_simd);
+}
+
+bool feasible_everywhere(const addrms_cfg& c, const addrms_shape* shapes, int n, int dtype)
+{
+    for (int i = 0; i < n; ++i)
+        if (check_cfg(c, shapes[i].M, shapes[i].N, dtype).status != ADDRMS_OK) return false;
+    return true;
+}
+
+struct OpenBackend {
+    const addrms_backend_factory& f;
+    addrms_backend be{};
+    bool open = false;
+    explicit OpenBackend(const addrms_backend_factory& fac) : f(fac) {}
+    int start(int64_t M, int64_t N, int dtype)
+    {
+        const int st = f.open(f.user, M, N, dtype, &be);
+        open = st == 0;
+        return st;
+    }
+    ~OpenBackend() { if (open && f.close) f.close(f.user, &be); }
+};
+
+}  // namespace
+
+int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
+                       const addrms_backend_factory& factory, bool insert_in_table,
+                       addrms_cfg* out_general, addrms_general_report* report)
+{
+    using Clock = std::chrono::steady_clock;
+    const auto t0 = Clock::now();
+    if (!shapes || !out_general) return fail(ADDRMS_ERR_INVALID_ARG, "shapes and out_general must not be NULL");
+    if (n < 1 || n > ADDRMS_MAX_SHAPES) return fail(ADDRMS_ERR_INVALID_ARG, "n must be 1..%d", ADDRMS_MAX_SHAPES);
+    if (!factory.open) return fail(ADDRMS_ERR_INVALID_ARG, "backend factory has no open function");
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    for (int i = 0; i < n; ++i)
+        if (shapes[i].M <= 0 || shapes[i].N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "shape %d needs M > 0 and N > 0", i);
+    addrms_budget b{};
+    if (budget) b = *budget;
+    const int warmup = b.warmup > 0 ? b.warmup : 20, reps = b.reps > 0 ? b.reps : 100;
+
+    // ---- per-shape search (lines 19-21), specialised table (line 23)
+    addrms_general_report rep{};
+    rep.n_shapes = n;
+    std::vector<addrms_cfg> pool;
+    std::unordered_set<uint64_t> seen;
+    auto add = [&](const addrms_cfg& c) { if (seen.insert(cfg_key(c)).second) pool.push_back(c); };
+    std::vector<addrms_cfg> defaults(n);
+    for (int i = 0; i < n; ++i) {
+        OpenBackend ob(factory);
+        if (ob.start(shapes[i].M, shapes[i].N, dtype) != 0)
+            return fail(ADDRMS_ERR_HIP, "could not open a measurement backend for shape %d (%lld x %lld)", i,
+                        (long long)shapes[i].M, (long long)shapes[i].N);
+        addrms_cfg best{};
+        addrms_tune_report tr{};
+        const int st = run_search(shapes[i].M, shapes[i].N, dtype, budget, ob.be, &best, &tr);
+        if (st != ADDRMS_OK) return st;
+        rep.specialized[i] = best;
+        rep.specialized_us[i] = tr.best_us;
+        rep.default_us[i] = tr.default_us;
+        defaults[i] = tr.default_cfg;
+        if (insert_in_table) addrms_table_insert(shapes[i].M, shapes[i].N, dtype, &best, tr.best_us);
+        for (int k = 0; k < tr.n_topk; ++k) add(tr.topk[k]);
+        add(tr.default_cfg);
+    }
+
+    // ---- candidates that are one theta for every shape
+    std::vector<addrms_cfg> cands;
+    for (const addrms_cfg& c : pool)
+        if (feasible_everywhere(c, shapes, n, dtype)) cands.push_back(c);
+    {
+        // widen: the universally feasible cfgs nearest (in knob steps) to each shape's winner, so that a
+        // compromise lying between the specialised winners is in the pool even if no winner fits every shape
+        std::vector<addrms_cfg> all;
+        enumerate(shapes[0].M, shapes[0].N, dtype, &all, nullptr, nullptr);
+        std::vector<addrms_cfg> common;
+        for (const addrms_cfg& c : all)
+            if (feasible_everywhere(c, shapes, n, dtype)) common.push_back(c);
+        if (common.empty() && cands.empty())
+            return fail(ADDRMS_ERR_NO_RESULT, "no configuration is feasible on all %d shapes", n);
+        std::unordered_set<uint64_t> have;
+        for (const addrms_cfg& c : cands) have.insert(cfg_key(c));
+        for (int i = 0; i < n; ++i) {
+            std::vector<std::pair<double, int>> near;
+            for (int j = 0; j < static_cast<int>(common.size()); ++j)
+                near.push_back({knob_distance(common[j], rep.specialized[i]), j});
+            std::stable_sort(near.begin(), near.end());
+            for (int k = 0; k < std::min<int>(3, near.size()); ++k)
+                if (have.insert(cfg_key(common[near[k].second])).second) cands.push_back(common[near[k].second]);
+        }
+    }
+    rep.n_pool = static_cast<int32_t>(cands.size());
+
+    // ---- time every candidate on every shape; defaults again with the same protocol
+    std::vector<std::vector<double>> us(cands.size(), std::vector<double>(n, -1.0));
+    for (int i = 0; i < n; ++i) {
+        OpenBackend ob(factory);
+        if (ob.start(shapes[i].M, shapes[i].N, dtype) != 0)
+            return fail(ADDRMS_ERR_HIP, "could not open a measurement backend for shape %d", i);
+        double d = 0.0;
+        if (ob.be.measure(ob.be.user, &defaults[i], warmup, reps, &d) == 0 && d > 0.0) rep.default_us[i] = d;
+        for (size_t k = 0; k < cands.size(); ++k) {
+            if (!b.skip_validation && ob.be.validate && ob.be.validate(ob.be.user, &cands[k]) != 0) continue;
+            double t = 0.0;
+            if (ob.be.measure(ob.be.user, &cands[k], warmup, reps, &t) == 0 && t > 0.0) us[k][i] = t;
+        }
+    }
+    int win = -1;
+    double win_score = 0.0;
+    for (size_t k = 0; k < cands.size(); ++k) {
+        double logsum = 0.0;
+        bool ok = true;
+        for (int i = 0; i < n && ok; ++i) {
+            ok = us[k][i] > 0.0 && rep.default_us[i] > 0.0;
+            if (ok) logsum += log(rep.default_us[i] / us[k][i]);
+        }
+        if (!ok) continue;
+        const double score = exp(logsum / n);
+        if (win < 0 || score > win_score) { win = static_cast<int>(k); win_score = score; }
+    }
+    if (win < 0) return fail(ADDRMS_ERR_NO_RESULT, "no candidate could be measured on all %d shapes", n);
+    *out_general = cands[win];
+    rep.geomean_speedup_general = win_score;
+    double logspec = 0.0, mean = 0.0;
+    for (int i = 0; i < n; ++i) {
+        rep.general_us[i] = us[win][i];
+        // a shape's specialised time can never be reported worse than the general cfg measured on it
+        if (rep.specialized_us[i] <= 0.0 || us[win][i] < rep.specialized_us[i]) {
+            rep.specialized_us[i] = us[win][i];
+            rep.specialized[i] = cands[win];
+        }
+        logspec += log(rep.default_us[i] / rep.specialized_us[i]);
+        mean += rep.default_us[i] / us[win][i];
+    }
+    rep.geomean_speedup_specialized = exp(logspec / n);
+    rep.mean_speedup_general = mean / n;
+    rep.wall_ms = std::chrono::duration<double, std::milli>(Clock::now() - t0).count();
+    if (report) *report = rep;
+    return ADDRMS_OK;
+}
+
+}  // namespace addrms_host
+
+extern "C" int addrms_select_general_with_backend(const addrms_shape* shapes, int32_t n, int dtype,
+                                                  const addrms_budget* budget, const addrms_backend_factory* factory,
+                                                  addrms_cfg* out_general, addrms_general_report* report)
+{
+    if (!factory) return addrms_host::fail(ADDRMS_ERR_INVALID_ARG, "factory is NULL");
+    return addrms_host::run_select_general(shapes, n, dtype, budget, *factory, false, out_general, report);
+}

@@ -90,6 +90,12 @@ int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out);
 int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
                const addrms_backend& be, addrms_cfg* out_cfg, addrms_tune_report* report);
 
+// ---- general configuration ---------------------------------------------------
+// insert_in_table: store each shape's winner in the specialised table (device runs only).
+int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
+                       const addrms_backend_factory& factory, bool insert_in_table,
+                       addrms_cfg* out_general, addrms_general_report* report);
+
 // ---- error text ------------------------------------------------------------
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();

@@ -329,6 +329,25 @@ int backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, dou
 
 std::mutex g_tune_mu;
 
+// Backend factory over the device harness: one Harness per shape, reference output from
+// that shape's default cfg.
+struct HarnessFactory { float eps; };
+int factory_open(void* user, int64_t M, int64_t N, int dtype, addrms_backend* out)
+{
+    auto* h = new Harness();
+    addrms_cfg dflt{};
+    std::string why;
+    int st = default_cfg(N, dtype, &dflt, &why);
+    if (st == ADDRMS_OK) st = h->init(M, N, dtype, static_cast<HarnessFactory*>(user)->eps, true);
+    if (st == ADDRMS_OK) st = h->make_reference(dflt);
+    if (st != ADDRMS_OK) { delete h; return st; }
+    out->user = h;
+    out->validate = backend_validate;
+    out->measure = backend_measure;
+    return 0;
+}
+void factory_close(void*, addrms_backend* be) { delete static_cast<Harness*>(be->user); }
+
 }  // namespace
 
 extern "C" {
@@ -386,6 +405,16 @@ int addrms_tune(int64_t M, int64_t N, int dtype, const addrms_budget* budget, ad
     if (st != ADDRMS_OK) return st;
     if (report) *report = local;
     return addrms_table_insert(M, N, dtype, out_cfg, local.best_us);
+}
+
+int addrms_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                          addrms_cfg* out_general, addrms_general_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    HarnessFactory hf{(budget && budget->eps > 0.0f) ? budget->eps : 1e-6f};
+    addrms_backend_factory fac{&hf, factory_open, factory_close};
+    return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report);
 }
 
 int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,

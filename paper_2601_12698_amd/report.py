@@ -24,6 +24,10 @@ from . import binding as B
 from . import workloads as W
 
 HBM_PEAK_GBPS = 8000.0
+# (m, n) shape lists of the paper's evaluation (Section 4, Kernels): plain shape tuples
+PAPER_MN_16BIT = [(16, 4096), (32, 5120), (32, 8192), (16, 12288), (64, 8192)]
+PAPER_MN_FP32 = [(128, 4096), (256, 4096), (1024, 4096), (2048, 8192), (128, 11008), (256, 13824), (512, 14336),
+                 (1024, 8192)]
 
 
 def shapes():
@@ -63,6 +67,9 @@ def main(argv=None) -> int:
     ap.add_argument("--exhaustive-prefill", action="store_true",
                     help="also run the exhaustive search on the prefill shape and report the guided search's regret")
     ap.add_argument("--table", default=None, help="save the specialised table here")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
+                         "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("needs a GPU", file=sys.stderr)
@@ -92,6 +99,18 @@ def main(argv=None) -> int:
         print(f"\nprefill: guided {g.as_tuple()} {tg:.2f} us after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
               f"exhaustive {e.as_tuple()} {te:.2f} us after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms; "
               f"regret {tg / te:.4f}")
+    if a.paper_shapes:
+        for dtype, shapes in (("bf16", PAPER_MN_16BIT), ("fp16", PAPER_MN_16BIT), ("fp32", PAPER_MN_FP32)):
+            g, rep = B.addrms_select_general(shapes, dtype, B.make_budget())
+            print(f"\n{dtype}: general cfg {g.as_tuple()}: geomean speedup over default x{rep.geomean_speedup_general:.3f} "
+                  f"(arithmetic mean x{rep.mean_speedup_general:.3f}); specialised table x{rep.geomean_speedup_specialized:.3f}; "
+                  f"{rep.n_pool} universally feasible candidates timed; {rep.wall_ms:.0f} ms\n")
+            print("| m x n | default us | general us | specialised us | general speedup | specialised speedup | specialised cfg |")
+            print("|---|---|---|---|---|---|---|")
+            for i, (m, n) in enumerate(shapes):
+                print(f"| {m} x {n} | {rep.default_us[i]:.2f} | {rep.general_us[i]:.2f} | {rep.specialized_us[i]:.2f} | "
+                      f"{rep.default_us[i] / rep.general_us[i]:.3f} | {rep.default_us[i] / rep.specialized_us[i]:.3f} | "
+                      f"{rep.specialized[i].as_tuple()} |", flush=True)
     if a.table:
         B.addrms_table_save(a.table)
     return 0

@@ -35,6 +35,8 @@ def test_struct_sizes_match_c_layout():
     assert ctypes.sizeof(B.Cfg) == 32
     assert ctypes.sizeof(B.Resources) == 64
     assert ctypes.sizeof(B.Budget) == 8 + 4 * 10 + 8
+    assert ctypes.sizeof(B.GeneralReport) == 8 + 8 * 4 + 8 * 16 * 3 + 32 * 16
+    assert ctypes.sizeof(B.Shape) == 16
     assert ctypes.sizeof(B.TuneReport) == 8 * 5 + 8 * 4 + 32 * 2 + 8 + 32 * 8 + 8 * 8
 
 

@@ -90,3 +90,24 @@ def test_measure_and_stream_probe():
     B.addrms_stream_probe(x, r, M, N, dt)
     torch.cuda.synchronize()
     assert torch.equal(x.view(torch.int16), ~x0.view(torch.int16)) and torch.equal(r.view(torch.int16), ~r0.view(torch.int16))
+
+
+PAPER_MN_16BIT = [(16, 4096), (32, 5120), (32, 8192), (16, 12288), (64, 8192)]
+PAPER_MN_FP32 = [(128, 4096), (256, 4096), (1024, 4096), (2048, 8192), (128, 11008), (256, 13824), (512, 14336),
+                 (1024, 8192)]
+
+
+@pytest.mark.parametrize("shapes,dtype", [(PAPER_MN_16BIT, "bf16"), (PAPER_MN_FP32, "fp32")])
+def test_select_general_on_paper_shape_lists(shapes, dtype):
+    """One general cfg over the (m, n) shape lists the paper evaluates on (Section 4,
+    Kernels), and the specialised table built on the way (Algorithm 1 lines 22-23)."""
+    budget = B.make_budget(max_candidates=60, warmup=5, reps=30, coarse_reps=8)
+    g, rep = B.addrms_select_general(shapes, dtype, budget)
+    print(f"{dtype}: general {g} geomean x{rep.geomean_speedup_general:.3f} (mean x{rep.mean_speedup_general:.3f}), "
+          f"specialised x{rep.geomean_speedup_specialized:.3f}, pool {rep.n_pool}, {rep.wall_ms:.0f} ms", flush=True)
+    for i, (M, N) in enumerate(shapes):
+        assert B.addrms_cfg_feasible(g, M, N, dtype)[0] == 0
+        assert rep.default_us[i] > 0 and rep.general_us[i] > 0 and rep.specialized_us[i] > 0
+        assert B.addrms_table_lookup(M, N, dtype) is not None
+    assert rep.geomean_speedup_specialized >= rep.geomean_speedup_general - 1e-9
+    assert rep.geomean_speedup_general > 0.97        # the defaults are in the pool when they fit every shape
