@@ -130,6 +130,13 @@ int64_t addrms_enumerate_feasible(int64_t M, int64_t N, int dtype,
 
 /* ---- search (Algorithm 1 lines 19-23: Search, BuildSpecialized) -------------- */
 enum { ADDRMS_SEARCH_GUIDED = 0, ADDRMS_SEARCH_EXHAUSTIVE = 1 };
+/* Hints for the guided search, derived from profiler counters of an earlier round
+ * (Algorithm 1 line 9, Suggest): they decide which neighbouring cfgs are tried first
+ * and add a sweep mode; they never remove a candidate. */
+enum { ADDRMS_HINT_LOWER_OCCUPANCY = 1,         /* memory system saturated: try fewer resident waves      */
+       ADDRMS_HINT_HIGHER_OCCUPANCY = 2,        /* latency-bound: try more waves / more loads in flight   */
+       ADDRMS_HINT_FEWER_LARGER_WORKGROUPS = 4, /* prefer whole rows per workgroup, persistent grids      */
+       ADDRMS_HINT_WIDER_VECTORS = 8 };         /* instruction-bound: prefer wider vector accesses        */
 
 typedef struct addrms_budget {
     double  max_wall_ms;     /* 0 = unlimited                                              */
@@ -142,7 +149,7 @@ typedef struct addrms_budget {
     int32_t coarse_reps;     /* 0 = 15                                                     */
     int32_t skip_validation; /* nonzero: do not gate candidates on correctness (tests only)*/
     float   eps;             /* eps used for the tuning launches; 0 = 1e-6                 */
-    int32_t reserved0;
+    int32_t hints;           /* ADDRMS_HINT_* bits; 0 = none                               */
     const char* log_path;    /* host; JSON-lines log of every candidate; NULL = none       */
 } addrms_budget;
 

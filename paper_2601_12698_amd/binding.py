@@ -26,6 +26,7 @@ FLAG_XCD_CONTIG = 1
 FLAG_NONTEMPORAL = 2
 FLAG_PERSISTENT = 4
 SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
+HINT_LOWER_OCCUPANCY, HINT_HIGHER_OCCUPANCY, HINT_FEWER_LARGER_WORKGROUPS, HINT_WIDER_VECTORS = 1, 2, 4, 8
 MAX_TOPK = 8
 
 OK = 0
@@ -85,7 +86,7 @@ class Budget(Structure):
     _fields_ = [("max_wall_ms", c_double), ("max_candidates", c_int32), ("strategy", c_int32),
                 ("top_k", c_int32), ("warmup", c_int32), ("reps", c_int32), ("coarse_warmup", c_int32),
                 ("coarse_reps", c_int32), ("skip_validation", c_int32), ("eps", c_float),
-                ("reserved0", c_int32), ("log_path", c_char_p)]
+                ("hints", c_int32), ("log_path", c_char_p)]
 
 
 class TuneReport(Structure):
@@ -270,11 +271,12 @@ def addrms_enumerate_feasible(M: int, N: int, dtype) -> Tuple[List[Cfg], int]:
 
 def make_budget(max_wall_ms: float = 0.0, max_candidates: int = 0, strategy: int = SEARCH_GUIDED, top_k: int = 0,
                 warmup: int = 0, reps: int = 0, coarse_warmup: int = 0, coarse_reps: int = 0,
-                skip_validation: bool = False, eps: float = 0.0, log_path: Optional[str] = None) -> Budget:
+                skip_validation: bool = False, eps: float = 0.0, log_path: Optional[str] = None,
+                hints: int = 0) -> Budget:
     b = Budget()
     b.max_wall_ms, b.max_candidates, b.strategy, b.top_k = max_wall_ms, max_candidates, strategy, top_k
     b.warmup, b.reps, b.coarse_warmup, b.coarse_reps = warmup, reps, coarse_warmup, coarse_reps
-    b.skip_validation, b.eps = int(skip_validation), eps
+    b.skip_validation, b.eps, b.hints = int(skip_validation), eps, hints
     b.log_path = log_path.encode() if log_path else None
     return b
 

@@ -133,22 +133,25 @@ struct Searcher {
     //   streaming   the same launch shape with the non-temporal policy
     //   persistent  non-temporal, persistent grid (XCD-contiguous when available), the
     //               largest workgroup and the deepest load batching the class admits
-    enum Mode { kPlain = 0, kStreaming = 1, kPersistent = 2 };
+    //   capped      (only with the lower-occupancy hint) streaming with about half the
+    //               resident waves
+    enum Mode { kPlain = 0, kStreaming = 1, kPersistent = 2, kCapped = 3 };
     std::vector<int> class_representatives(Mode mode) const
     {
         std::map<std::pair<int, int>, std::pair<double, int>> best;   // class -> (score, index)
         for (int i = 0; i < static_cast<int>(cands.size()); ++i) {
             const addrms_cfg& c = cands[i].cfg;
-            if (c.reduce != ADDRMS_REDUCE_WAVE || c.max_waves_per_simd != 0) continue;
+            if (c.reduce != ADDRMS_REDUCE_WAVE || (c.max_waves_per_simd != 0) != (mode == kCapped)) continue;
             const double threads = static_cast<double>(c.threads_per_row) * c.rows_per_wg;
             double score;
             if (mode == kPersistent) {
                 if (!(c.flags & ADDRMS_FLAG_PERSISTENT) || !(c.flags & ADDRMS_FLAG_NONTEMPORAL)) continue;
                 score = -threads - 0.1 * c.unroll - ((c.flags & ADDRMS_FLAG_XCD_CONTIG) ? 0.01 : 0.0);
             } else {
-                if (c.flags != (mode == kStreaming ? ADDRMS_FLAG_NONTEMPORAL : 0)) continue;
+                if (c.flags != (mode == kPlain ? 0 : ADDRMS_FLAG_NONTEMPORAL)) continue;
                 const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
                 score = fabs(log2(threads / 256.0)) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
+                if (mode == kCapped) score += 0.5 * fabs(static_cast<double>(c.max_waves_per_simd) - 4.0);
             }
             auto key = std::make_pair(-c.vec, c.threads_per_row);       // widest vector first
             auto it = best.find(key);
@@ -227,6 +230,14 @@ struct Searcher {
         const int64_t resident = static_cast<int64_t>(hw().compute_units) * std::max(1, from.res.wgs_per_cu);
         if (n_row_blocks(from.cfg, M) < resident && n_row_blocks(to.cfg, M) > n_row_blocks(from.cfg, M)) p += 2;
         if (to.cfg.vec > from.cfg.vec) p += 1;
+        // hints from the previous round's profiler counters
+        if ((b.hints & ADDRMS_HINT_LOWER_OCCUPANCY) && to.res.waves_per_simd < from.res.waves_per_simd) p += 3;
+        if ((b.hints & ADDRMS_HINT_HIGHER_OCCUPANCY) &&
+            (to.res.waves_per_simd > from.res.waves_per_simd || to.cfg.unroll > from.cfg.unroll)) p += 3;
+        if ((b.hints & ADDRMS_HINT_FEWER_LARGER_WORKGROUPS) &&
+            (n_row_blocks(to.cfg, M) < n_row_blocks(from.cfg, M) ||
+             ((to.cfg.flags & ~from.cfg.flags) & ADDRMS_FLAG_PERSISTENT))) p += 3;
+        if ((b.hints & ADDRMS_HINT_WIDER_VECTORS) && to.cfg.vec > from.cfg.vec) p += 3;
         return p;
     }
 
@@ -337,14 +348,17 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
                 if (best_plain == 0.0 || s.cands[i].us < best_plain) best_plain = s.cands[i].us;
             }
         }
-        for (Searcher::Mode mode : {Searcher::kStreaming, Searcher::kPersistent})
+        std::vector<Searcher::Mode> modes = {Searcher::kStreaming, Searcher::kPersistent};
+        if (b.hints & ADDRMS_HINT_LOWER_OCCUPANCY) modes.push_back(Searcher::kCapped);
+        for (Searcher::Mode mode : modes)
             for (int i : s.class_representatives(mode)) {
                 if (!s.budget_left()) break;
                 const addrms_cfg& c = s.cands[i].cfg;
                 auto it = plain_us.find({c.vec, c.threads_per_row});
                 if (it != plain_us.end() && it->second > 2.0 * best_plain) continue;
-                s.eval(i, mode == Searcher::kStreaming ? "sweep_streaming" : "sweep_persistent", b.coarse_warmup,
-                       b.coarse_reps);
+                s.eval(i, mode == Searcher::kStreaming ? "sweep_streaming"
+                          : mode == Searcher::kPersistent ? "sweep_persistent" : "sweep_capped",
+                       b.coarse_warmup, b.coarse_reps);
             }
         std::vector<int> seeds = s.ranked();
         // descend from the best three distinct (vec, threads_per_row, persistent) corners

@@ -1,0 +1,285 @@
+"""Profiling signals for the tuner (Algorithm 1 line 25, CollectSignals; line 9, Suggest).
+
+The paper's testing agent collects performance signals for the configurations a
+round produced and the planning agent turns them into suggestions for the next
+round.  Hardware counters on this platform are read by ``rocprofv3``, which wraps
+a whole process, so collection is out of process:
+
+* ``collect(cfgs, M, N, dtype)`` writes the configurations to a spec file and
+  runs ``rocprofv3 --pmc <counters> -- python3 -m paper_2601_12698_amd.signals
+  --child <spec>`` once per counter pass (one pass per run: the profiler does
+  not split counters over passes and a pass may hold only a few counters of
+  each hardware block).  The child launches every configuration a few times
+  through the C ABI; the parent reads the per-dispatch counter CSV back and
+  averages per configuration.
+* ``suggest(record)`` is the deterministic stand-in for the planner: it maps a
+  configuration's signals to search hints (``ADDRMS_HINT_*`` bits of the budget)
+  with a stated reason each.
+* ``tune_with_signals(M, N, dtype)`` is the two-round loop: search, collect
+  signals for the Top-K, derive hints, search again with the hints, keep the
+  better configuration; everything is appended to a JSON-lines log.  The
+  orchestrating process never touches the GPU itself: the searches and the
+  profiled launches all run in child processes it starts, so that no process
+  that holds GPU state ever has to start another program.
+
+No arithmetic of the operator happens here; kernels run in ``libaddrms.so``.
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import json
+import os
+import shutil
+import subprocess
+import sys
+import tempfile
+from typing import Dict, List, Optional, Sequence, Tuple
+
+from . import binding as B
+
+# One list per profiler run.  Derived metrics expand to several hardware counters, so they
+# travel alone; FETCH_SIZE uses three L2 counters and WRITE_SIZE two.
+DEFAULT_PASSES: Tuple[Tuple[str, ...], ...] = (
+    ("FETCH_SIZE",),
+    ("WRITE_SIZE",),
+    ("TCC_HIT_sum", "TCC_MISS_sum"),
+    ("TCC_EA0_WRREQ_STALL_sum", "TCC_EA0_RDREQ_DRAM_CREDIT_STALL_sum"),
+    ("MemUnitStalled",),
+    ("VALUBusy",),
+    ("MeanOccupancyPerCU",),
+)
+LAUNCHES_PER_CFG = 4          # the first launch of each configuration is discarded (cold code, cold TLB)
+
+# FETCH_SIZE and WRITE_SIZE units on this device, from the calibration kernel of known
+# traffic (65,536 KiB read registers as 32,779.0; 65,536 KiB written as 65,536.0).
+FETCH_UNIT_BYTES = 65536.0 * 1024.0 / 32779.0
+WRITE_UNIT_BYTES = 1024.0
+
+
+def _spec(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float) -> dict:
+    return {"M": M, "N": N, "dtype": dtype, "eps": eps, "launches": LAUNCHES_PER_CFG,
+            "cfgs": [c.as_dict() for c in cfgs]}
+
+
+def child_main(spec_path: str) -> int:
+    """Runs inside the profiler: launch every cfg of the spec LAUNCHES_PER_CFG times."""
+    import torch
+
+    from . import workloads as W
+    spec = json.load(open(spec_path))
+    M, N, dtype = spec["M"], spec["N"], spec["dtype"]
+    wl = W.Workload("signals", M, N, dtype, spec["eps"], 7)
+    nsets = 3
+    xs = [torch.randn(M, N, device="cuda").to(W.x_torch_dtype(dtype)) for _ in range(nsets)]
+    rs = [torch.randn(M, N, device="cuda").to(W.r_torch_dtype(dtype)) for _ in range(nsets)]
+    w = (torch.rand(N, device="cuda") + 0.5).to(W.x_torch_dtype(dtype))
+    torch.cuda.synchronize()
+    k = 0
+    for d in spec["cfgs"]:
+        cfg = B.make_cfg(**d)
+        for _ in range(spec["launches"]):
+            B.addrms_run(xs[k % nsets], rs[k % nsets], w, wl.eps, M, N, dtype, cfg)
+            k += 1
+        torch.cuda.synchronize()
+    return 0
+
+
+def _read_counter_csv(outdir: str) -> List[dict]:
+    rows = []
+    for root, _dirs, files in os.walk(outdir):
+        for f in files:
+            if f.endswith("counter_collection.csv"):
+                with open(os.path.join(root, f), newline="") as fh:
+                    rows.extend(csv.DictReader(fh))
+    rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+    return rows
+
+
+def collect(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float = 1e-6,
+            passes: Sequence[Sequence[str]] = DEFAULT_PASSES, workdir: Optional[str] = None,
+            timeout_s: int = 180) -> List[dict]:
+    """Counter values per configuration: ``[{cfg, counters: {name: mean}, derived: {...}}, ...]``."""
+    rocprof = shutil.which("rocprofv3")
+    if rocprof is None:
+        raise RuntimeError("rocprofv3 is not on PATH")
+    tmp = workdir or tempfile.mkdtemp(prefix="addrms_signals_")
+    os.makedirs(tmp, exist_ok=True)
+    spec_path = os.path.join(tmp, "spec.json")
+    with open(spec_path, "w") as f:
+        json.dump(_spec(cfgs, M, N, dtype, eps), f)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ)
+    env["PYTHONPATH"] = root + os.pathsep + env.get("PYTHONPATH", "")
+    env.setdefault("TMPDIR", "/tmp")
+    records = [{"cfg": c.as_dict(), "counters": {}} for c in cfgs]
+    for i, names in enumerate(passes):
+        outdir = os.path.join(tmp, f"pass{i}")
+        cmd = [rocprof, "--pmc", *names, "--output-format", "csv", "-d", outdir, "-o", "sig", "--",
+               sys.executable, "-m", "paper_2601_12698_amd.signals", "--child", spec_path]
+        r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
+                           timeout=timeout_s)
+        if r.returncode != 0:
+            raise RuntimeError(f"rocprofv3 pass {names} failed ({r.returncode}):\n{r.stdout[-2000:]}")
+        rows = [x for x in _read_counter_csv(outdir) if x["Kernel_Name"].startswith("addrms_k_")]
+        by_counter: Dict[str, List[float]] = {}
+        for x in rows:
+            by_counter.setdefault(x["Counter_Name"], []).append(float(x["Counter_Value"]))
+        for name, vals in by_counter.items():
+            if len(vals) != LAUNCHES_PER_CFG * len(cfgs):
+                raise RuntimeError(f"{name}: expected {LAUNCHES_PER_CFG * len(cfgs)} dispatches, saw {len(vals)}")
+            for j in range(len(cfgs)):
+                chunk = vals[j * LAUNCHES_PER_CFG + 1:(j + 1) * LAUNCHES_PER_CFG]
+                records[j]["counters"][name] = sum(chunk) / len(chunk)
+    from . import workloads as W
+    nbytes = W.algorithmic_bytes(M, N, dtype)     # plain formula; the orchestrator does not load the HIP library
+    for rec in records:
+        c = rec["counters"]
+        d = {}
+        if "FETCH_SIZE" in c and "WRITE_SIZE" in c:
+            d["hbm_read_bytes"] = c["FETCH_SIZE"] * FETCH_UNIT_BYTES
+            d["hbm_write_bytes"] = c["WRITE_SIZE"] * WRITE_UNIT_BYTES
+            d["traffic_over_algorithmic"] = (d["hbm_read_bytes"] + d["hbm_write_bytes"]) / nbytes
+        if "TCC_HIT_sum" in c and "TCC_MISS_sum" in c and c["TCC_HIT_sum"] + c["TCC_MISS_sum"] > 0:
+            d["l2_hit_rate"] = c["TCC_HIT_sum"] / (c["TCC_HIT_sum"] + c["TCC_MISS_sum"])
+        if "TCC_EA0_RDREQ_DRAM_CREDIT_STALL_sum" in c and c.get("TCC_MISS_sum", 0) > 0:
+            d["dram_credit_stall_per_l2_miss"] = c["TCC_EA0_RDREQ_DRAM_CREDIT_STALL_sum"] / c["TCC_MISS_sum"]
+        rec["derived"] = d
+    if workdir is None:
+        shutil.rmtree(tmp, ignore_errors=True)
+    return records
+
+
+HBM_PEAK_BYTES_PER_S = 8.0e12
+
+
+def suggest(record: dict, achieved_frac: Optional[float] = None) -> Tuple[int, List[str]]:
+    """Signals of one configuration (plus, if known, the fraction of the HBM roofline
+    its measured time corresponds to) -> (hint bits for the next search, reasons)."""
+    c, d = record.get("counters", {}), record.get("derived", {})
+    hints, why = 0, []
+    occ = c.get("MeanOccupancyPerCU")
+    valu = c.get("VALUBusy")
+    stall_per_miss = d.get("dram_credit_stall_per_l2_miss")
+    if d.get("traffic_over_algorithmic", 1.0) > 1.05:
+        hints |= B.HINT_FEWER_LARGER_WORKGROUPS
+        why.append(f"HBM traffic is {d['traffic_over_algorithmic']:.2f}x the algorithmic bytes: something is re-read; "
+                   "prefer shapes that keep a row in one workgroup's registers")
+    if valu is not None and valu > 70.0:
+        hints |= B.HINT_WIDER_VECTORS
+        why.append(f"VALU busy {valu:.0f}%: instruction-bound; wider vectors amortise address and control work")
+    saturated = (achieved_frac is not None and achieved_frac >= 0.6 and (valu is None or valu < 60.0)
+                 and (occ is None or occ >= 16.0) and (stall_per_miss is None or stall_per_miss > 0.005))
+    if saturated:
+        hints |= B.HINT_LOWER_OCCUPANCY
+        why.append(f"{100 * achieved_frac:.0f}% of the HBM roofline with VALU busy {valu if valu is not None else float('nan'):.0f}%, "
+                   f"{occ if occ is not None else float('nan'):.0f} waves per CU resident and "
+                   f"{stall_per_miss if stall_per_miss is not None else float('nan'):.3f} DRAM credit stalls per L2 miss: the memory "
+                   "system is saturated; fewer requests in flight may raise mixed read/write DRAM efficiency")
+    if achieved_frac is not None and achieved_frac < 0.4 and (valu is None or valu < 40.0):
+        hints |= B.HINT_HIGHER_OCCUPANCY
+        why.append(f"only {100 * achieved_frac:.0f}% of the HBM roofline and VALU busy "
+                   f"{valu if valu is not None else float('nan'):.0f}%: latency-bound; more waves or more loads in flight "
+                   "per wave should help")
+    return hints, why
+
+
+def _run_stage(args: List[str], timeout_s: int = 600) -> dict:
+    """Run one GPU stage of this module in a child process and return its JSON result."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ)
+    env["PYTHONPATH"] = root + os.pathsep + env.get("PYTHONPATH", "")
+    r = subprocess.run([sys.executable, "-m", "paper_2601_12698_amd.signals", *args], env=env,
+                       stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=timeout_s)
+    if r.returncode != 0:
+        raise RuntimeError(f"stage {args} failed ({r.returncode}):\n{r.stderr[-2000:]}")
+    return json.loads(r.stdout.strip().splitlines()[-1])
+
+
+def stage_tune(M: int, N: int, dtype: str, eps: float, hints: int, log_path: Optional[str], top_k: int) -> dict:
+    """(child process) One search; prints the winner and the Top-K as JSON."""
+    cfg, rep = B.addrms_tune(M, N, dtype, B.make_budget(eps=eps, log_path=log_path, hints=hints))
+    return {"cfg": cfg.as_dict(), "us": rep.best_us, "default_us": rep.default_us, "n_measured": rep.n_measured,
+            "wall_ms": rep.wall_ms,
+            "topk": [{"cfg": rep.topk[i].as_dict(), "us": rep.topk_us[i]} for i in range(min(top_k, rep.n_topk))]}
+
+
+def stage_table(M: int, N: int, dtype: str, cfg: dict, us: float, path: str) -> dict:
+    """(child process) Merge one entry into a table file."""
+    if os.path.exists(path):
+        B.addrms_table_load(path)
+    B.addrms_table_insert(M, N, dtype, B.make_cfg(**cfg), us)
+    B.addrms_table_save(path)
+    return {"entries": B.addrms_table_size()}
+
+
+def tune_with_signals(M: int, N: int, dtype: str, eps: float = 1e-6, log_path: Optional[str] = None,
+                      top_k: int = 3, table_path: Optional[str] = None) -> dict:
+    """Two rounds of Level 2 with counter feedback in between (runs GPU work in child processes)."""
+    def log(obj):
+        if log_path:
+            with open(log_path, "a") as f:
+                f.write(json.dumps(obj) + "\n")
+
+    base = ["--stage-tune", str(M), str(N), dtype, "--eps", repr(eps), "--top-k", str(top_k)]
+    if log_path:
+        base += ["--log", log_path]
+    r0 = _run_stage(base + ["--hints", "0"])
+    top = [B.make_cfg(**t["cfg"]) for t in r0["topk"]]
+    records = collect(top, M, N, dtype, eps)
+    for r in records:
+        log({"event": "signals", **r})
+    from . import workloads as W
+    frac = W.algorithmic_bytes(M, N, dtype) / (r0["us"] * 1e-6) / HBM_PEAK_BYTES_PER_S
+    hints, why = suggest(records[0], frac)
+    log({"event": "suggest", "achieved_frac": frac, "hints": hints, "reasons": why})
+    result = {"round0": r0, "signals": records, "hints": hints, "reasons": why, "best": r0["cfg"], "best_us": r0["us"]}
+    if hints:
+        r1 = _run_stage(base + ["--hints", str(hints)])
+        result["round1"] = r1
+        if r1["us"] < r0["us"]:
+            result["best"], result["best_us"] = r1["cfg"], r1["us"]
+    if table_path:
+        _run_stage(["--stage-table", str(M), str(N), dtype, "--cfg-json", json.dumps(result["best"]),
+                    "--us", repr(result["best_us"]), "--table", table_path])
+    log({"event": "rounds_end", "best": result["best"], "best_us": result["best_us"]})
+    return result
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--child", default=None, help="(internal) run the launches of a spec file")
+    ap.add_argument("--stage-tune", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
+                    help="(internal) run one search in this process and print its result as JSON")
+    ap.add_argument("--stage-table", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
+                    help="(internal) merge --cfg-json/--us into --table")
+    ap.add_argument("--cfg-json", default=None)
+    ap.add_argument("--us", type=float, default=0.0)
+    ap.add_argument("--shape", nargs=3, metavar=("M", "N", "DTYPE"), help="tune this shape with counter feedback")
+    ap.add_argument("--eps", type=float, default=1e-6)
+    ap.add_argument("--hints", type=int, default=0)
+    ap.add_argument("--top-k", type=int, default=3)
+    ap.add_argument("--log", default=None)
+    ap.add_argument("--table", default=None, help="merge the winner into this table file")
+    a = ap.parse_args(argv)
+    if a.child:
+        return child_main(a.child)
+    if a.stage_tune:
+        m, n, dt = a.stage_tune
+        print(json.dumps(stage_tune(int(m), int(n), dt, a.eps, a.hints, a.log, a.top_k)))
+        return 0
+    if a.stage_table:
+        m, n, dt = a.stage_table
+        print(json.dumps(stage_table(int(m), int(n), dt, json.loads(a.cfg_json), a.us, a.table)))
+        return 0
+    if a.shape:
+        res = tune_with_signals(int(a.shape[0]), int(a.shape[1]), a.shape[2], eps=a.eps, log_path=a.log,
+                                top_k=a.top_k, table_path=a.table)
+        print(json.dumps(res, indent=1))
+        return 0
+    ap.print_help()
+    return 2
+
+
+if __name__ == "__main__":
+    sys.exit(main())
