@@ -130,6 +130,12 @@ int64_t addrms_enumerate_feasible(int64_t M, int64_t N, int dtype,
 
 /* ---- search (Algorithm 1 lines 19-23: Search, BuildSpecialized) -------------- */
 enum { ADDRMS_SEARCH_GUIDED = 0, ADDRMS_SEARCH_EXHAUSTIVE = 1 };
+/* Strategy families of the template beyond its base form (Level 1 of Algorithm 1 adds
+ * them round by round; a search can be restricted to a subset). */
+enum { ADDRMS_FAMILY_STREAMING = 1,      /* non-temporal cache policy (ADDRMS_FLAG_NONTEMPORAL)              */
+       ADDRMS_FAMILY_OCCUPANCY_CAP = 2,  /* max_waves_per_simd != 0                                          */
+       ADDRMS_FAMILY_GRID_MAPPING = 4,   /* XCD-contiguous mapping and the persistent grid                   */
+       ADDRMS_FAMILY_BASE_ONLY = 8 };    /* none of the above: the base template only                        */
 /* Hints for the guided search, derived from profiler counters of an earlier round
  * (Algorithm 1 line 9, Suggest): they decide which neighbouring cfgs are tried first
  * and add a sweep mode; they never remove a candidate. */
@@ -151,6 +157,8 @@ typedef struct addrms_budget {
     float   eps;             /* eps used for the tuning launches; 0 = 1e-6                 */
     int32_t hints;           /* ADDRMS_HINT_* bits; 0 = none                               */
     const char* log_path;    /* host; JSON-lines log of every candidate; NULL = none       */
+    int32_t family_mask;     /* ADDRMS_FAMILY_* bits the search may use; 0 = all of them   */
+    int32_t reserved1;
 } addrms_budget;
 
 #define ADDRMS_MAX_TOPK 8
@@ -239,6 +247,37 @@ typedef struct addrms_backend_factory {
 int addrms_select_general_with_backend(const addrms_shape* shapes, int32_t n, int dtype,
                                        const addrms_budget* budget, const addrms_backend_factory* factory,
                                        addrms_cfg* out_general, addrms_general_report* report);
+
+/* ---- the outer loop (Algorithm 1 lines 6-32) with a fixed strategy list ----------
+ * Round 0 uses the base template; each later round adds one strategy family (streaming
+ * cache policy, occupancy cap, grid mapping) in that order -- the deterministic stand-in
+ * for the planning agent's suggestions.  Per round: Validate the new family on the first
+ * shape against the base default's output and roll it back if it fails (lines 13-14);
+ * search every shape within the families enabled so far (lines 19-21); SelectGeneral and
+ * BuildSpecialized (22-23); score = minus the geometric-mean speed-up of the specialised
+ * table over the per-shape defaults (line 27); keep the incumbent (28-30).  Every round is
+ * appended to budget->log_path as an "event":"round" line. */
+#define ADDRMS_MAX_ROUNDS 4
+typedef struct addrms_round_info {
+    int32_t families;          /* ADDRMS_FAMILY_* bits enabled in this round (0 = base only)  */
+    int32_t pass;              /* 1 if the family added in this round passed validation       */
+    double  score;             /* -geomean speed-up of the specialised table                  */
+    double  geomean_speedup_general;
+    addrms_cfg general;
+} addrms_round_info;
+typedef struct addrms_rounds_report {
+    int32_t n_rounds;
+    int32_t best_round;
+    double  wall_ms;
+    addrms_round_info rounds[ADDRMS_MAX_ROUNDS];
+    addrms_general_report best;   /* report of the incumbent round */
+} addrms_rounds_report;
+
+int addrms_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                       addrms_cfg* out_general, addrms_rounds_report* report);
+int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                                    const addrms_backend_factory* factory, addrms_cfg* out_general,
+                                    addrms_rounds_report* report);
 
 /* addrms_measure: mean time in microseconds of `cfg` (NULL = table/default, as
  * in addrms_run) on (M, N, dtype) over `reps` launches after `warmup`, on

@@ -26,6 +26,8 @@ FLAG_XCD_CONTIG = 1
 FLAG_NONTEMPORAL = 2
 FLAG_PERSISTENT = 4
 SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
+FAMILY_STREAMING, FAMILY_OCCUPANCY_CAP, FAMILY_GRID_MAPPING, FAMILY_BASE_ONLY = 1, 2, 4, 8
+MAX_ROUNDS = 4
 HINT_LOWER_OCCUPANCY, HINT_HIGHER_OCCUPANCY, HINT_FEWER_LARGER_WORKGROUPS, HINT_WIDER_VECTORS = 1, 2, 4, 8
 MAX_TOPK = 8
 
@@ -86,7 +88,8 @@ class Budget(Structure):
     _fields_ = [("max_wall_ms", c_double), ("max_candidates", c_int32), ("strategy", c_int32),
                 ("top_k", c_int32), ("warmup", c_int32), ("reps", c_int32), ("coarse_warmup", c_int32),
                 ("coarse_reps", c_int32), ("skip_validation", c_int32), ("eps", c_float),
-                ("hints", c_int32), ("log_path", c_char_p)]
+                ("hints", c_int32), ("log_path", c_char_p),
+                ("family_mask", c_int32), ("reserved1", c_int32)]
 
 
 class TuneReport(Structure):
@@ -135,6 +138,23 @@ class GeneralReport(Structure):
                     specialized=[self.specialized[i].as_dict() for i in range(n)])
 
 
+class RoundInfo(Structure):
+    _fields_ = [("families", c_int32), ("passed", c_int32), ("score", c_double),
+                ("geomean_speedup_general", c_double), ("general", Cfg)]
+
+
+class RoundsReport(Structure):
+    _fields_ = [("n_rounds", c_int32), ("best_round", c_int32), ("wall_ms", c_double),
+                ("rounds", RoundInfo * MAX_ROUNDS), ("best", GeneralReport)]
+
+    def as_dict(self) -> dict:
+        return dict(n_rounds=self.n_rounds, best_round=self.best_round, wall_ms=self.wall_ms,
+                    rounds=[dict(families=r.families, passed=bool(r.passed), score=r.score,
+                                 geomean_speedup_general=r.geomean_speedup_general, general=r.general.as_dict())
+                            for r in self.rounds[:self.n_rounds]],
+                    best=self.best.as_dict())
+
+
 OPEN_FN = CFUNCTYPE(c_int, c_void_p, c_int64, c_int64, c_int, POINTER(Backend))
 CLOSE_FN = CFUNCTYPE(None, c_void_p, POINTER(Backend))
 
@@ -156,6 +176,10 @@ SIGNATURES = {
                                       POINTER(GeneralReport)]),
     "addrms_select_general_with_backend": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget),
                                                    POINTER(BackendFactory), POINTER(Cfg), POINTER(GeneralReport)]),
+    "addrms_tune_rounds": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg),
+                                   POINTER(RoundsReport)]),
+    "addrms_tune_rounds_with_backend": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget),
+                                                POINTER(BackendFactory), POINTER(Cfg), POINTER(RoundsReport)]),
     "addrms_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_float, c_int, c_int, c_int, POINTER(c_double)]),
     "addrms_table_insert": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg), c_double]),
     "addrms_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
@@ -272,11 +296,11 @@ def addrms_enumerate_feasible(M: int, N: int, dtype) -> Tuple[List[Cfg], int]:
 def make_budget(max_wall_ms: float = 0.0, max_candidates: int = 0, strategy: int = SEARCH_GUIDED, top_k: int = 0,
                 warmup: int = 0, reps: int = 0, coarse_warmup: int = 0, coarse_reps: int = 0,
                 skip_validation: bool = False, eps: float = 0.0, log_path: Optional[str] = None,
-                hints: int = 0) -> Budget:
+                hints: int = 0, family_mask: int = 0) -> Budget:
     b = Budget()
     b.max_wall_ms, b.max_candidates, b.strategy, b.top_k = max_wall_ms, max_candidates, strategy, top_k
     b.warmup, b.reps, b.coarse_warmup, b.coarse_reps = warmup, reps, coarse_warmup, coarse_reps
-    b.skip_validation, b.eps, b.hints = int(skip_validation), eps, hints
+    b.skip_validation, b.eps, b.hints, b.family_mask = int(skip_validation), eps, hints, family_mask
     b.log_path = log_path.encode() if log_path else None
     return b
 
@@ -355,6 +379,48 @@ def addrms_select_general(shapes, dtype, budget: Optional[Budget] = None) -> Tup
     c, rep = Cfg(), GeneralReport()
     _check(load().addrms_select_general(_shape_array(shapes), len(shapes), _dtype_id(dtype),
                                         byref(budget) if budget is not None else None, byref(c), byref(rep)))
+    return c, rep
+
+
+def _python_factory(make_backend, keep):
+    def _open(_user, M, N, _dt, out):
+        try:
+            measure, validate = make_backend(M, N)
+        except Exception:
+            return 1
+        m, v = _wrap_measure(measure), _wrap_validate(validate)
+        keep.append((m, v))
+        out.contents.user = None
+        out.contents.measure = m
+        out.contents.validate = v
+        return 0
+
+    def _close(_user, _be):
+        return None
+
+    fac = BackendFactory()
+    fac.user = None
+    fac.open = OPEN_FN(_open)
+    fac.close = CLOSE_FN(_close)
+    keep.append((fac.open, fac.close))
+    return fac
+
+
+def addrms_tune_rounds(shapes, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, RoundsReport]:
+    c, rep = Cfg(), RoundsReport()
+    _check(load().addrms_tune_rounds(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                     byref(budget) if budget is not None else None, byref(c), byref(rep)))
+    return c, rep
+
+
+def addrms_tune_rounds_with_backend(shapes, dtype, budget: Optional[Budget], make_backend
+                                    ) -> Tuple[Cfg, RoundsReport]:
+    keep = []
+    fac = _python_factory(make_backend, keep)
+    c, rep = Cfg(), RoundsReport()
+    _check(load().addrms_tune_rounds_with_backend(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                                  byref(budget) if budget is not None else None, byref(fac),
+                                                  byref(c), byref(rep)))
     return c, rep
 
 

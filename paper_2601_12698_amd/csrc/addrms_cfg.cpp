@@ -159,6 +159,15 @@ static int lds_padding_for_wgs(int wgs)
     return g * hw().lds_granule;
 }
 
+bool cfg_in_families(const addrms_cfg& c, int mask)
+{
+    if (mask == 0) return true;
+    if ((c.flags & ADDRMS_FLAG_NONTEMPORAL) && !(mask & ADDRMS_FAMILY_STREAMING)) return false;
+    if (c.max_waves_per_simd != 0 && !(mask & ADDRMS_FAMILY_OCCUPANCY_CAP)) return false;
+    if ((c.flags & (ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_PERSISTENT)) && !(mask & ADDRMS_FAMILY_GRID_MAPPING)) return false;
+    return true;
+}
+
 int lds_bytes_for(const addrms_cfg& c)
 {
     const int need = reduction_lds_bytes(c);

@@ -5,6 +5,7 @@
 //
 // Host-only: measurement comes through a backend factory, one backend per shape.
 #include <math.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <algorithm>
@@ -164,7 +165,100 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
     return ADDRMS_OK;
 }
 
+// ---- the outer loop with a fixed strategy list ------------------------------------
+int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
+                    const addrms_backend_factory& factory, bool insert_in_table,
+                    addrms_cfg* out_general, addrms_rounds_report* report)
+{
+    using Clock = std::chrono::steady_clock;
+    const auto t0 = Clock::now();
+    if (!shapes || !out_general) return fail(ADDRMS_ERR_INVALID_ARG, "shapes and out_general must not be NULL");
+    if (n < 1 || n > ADDRMS_MAX_SHAPES) return fail(ADDRMS_ERR_INVALID_ARG, "n must be 1..%d", ADDRMS_MAX_SHAPES);
+    if (!factory.open) return fail(ADDRMS_ERR_INVALID_ARG, "backend factory has no open function");
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    addrms_budget b{};
+    if (budget) b = *budget;
+    static const int kOrder[ADDRMS_MAX_ROUNDS] = {0, ADDRMS_FAMILY_STREAMING, ADDRMS_FAMILY_OCCUPANCY_CAP,
+                                                  ADDRMS_FAMILY_GRID_MAPPING};
+    addrms_rounds_report rep{};
+    rep.best_round = -1;
+    double best_score = 0.0;
+    int enabled = 0;
+    for (int r = 0; r < ADDRMS_MAX_ROUNDS; ++r) {
+        addrms_round_info& info = rep.rounds[r];
+        info.pass = 1;
+        if (kOrder[r] != 0) {
+            // Validate the rewritten kernel (the family just added) on the first shape: the cheapest
+            // feasible cfg that uses it must reproduce the reference output; otherwise roll back.
+            std::vector<addrms_cfg> all;
+            enumerate(shapes[0].M, shapes[0].N, dtype, &all, nullptr, nullptr);
+            const addrms_cfg* probe = nullptr;
+            for (const addrms_cfg& c : all)
+                if (cfg_in_families(c, enabled | kOrder[r]) && !cfg_in_families(c, enabled ? enabled : ADDRMS_FAMILY_BASE_ONLY)) {
+                    probe = &c;
+                    break;
+                }
+            if (probe) {
+                OpenBackend ob(factory);
+                if (ob.start(shapes[0].M, shapes[0].N, dtype) != 0)
+                    return fail(ADDRMS_ERR_HIP, "could not open a measurement backend for validation");
+                if (ob.be.validate && ob.be.validate(ob.be.user, probe) != 0) info.pass = 0;
+            } else {
+                info.pass = 0;      // the family has no feasible member on this shape: nothing to add
+            }
+            if (info.pass) enabled |= kOrder[r];
+        }
+        info.families = enabled;
+        addrms_budget rb = b;
+        rb.family_mask = enabled ? enabled : ADDRMS_FAMILY_BASE_ONLY;
+        addrms_cfg general{};
+        addrms_general_report gr{};
+        int st = ADDRMS_OK;
+        if (r == 0 || info.pass) {
+            st = run_select_general(shapes, n, dtype, &rb, factory, false, &general, &gr);
+            if (st != ADDRMS_OK) return st;
+            info.general = general;
+            info.geomean_speedup_general = gr.geomean_speedup_general;
+            info.score = -gr.geomean_speedup_specialized;
+            if (rep.best_round < 0 || info.score < best_score) {
+                rep.best_round = r;
+                best_score = info.score;
+                rep.best = gr;
+                *out_general = general;
+            }
+        } else {            // rolled back: this round is the previous round again
+            info.general = rep.rounds[r - 1].general;
+            info.geomean_speedup_general = rep.rounds[r - 1].geomean_speedup_general;
+            info.score = rep.rounds[r - 1].score;
+        }
+        rep.n_rounds = r + 1;
+        if (b.log_path) {
+            if (FILE* f = fopen(b.log_path, "a")) {
+                fprintf(f, "{\"event\":\"round\",\"round\":%d,\"families\":%d,\"pass\":%s,\"general\":%s,"
+                           "\"geomean_speedup_general\":%.5f,\"score\":%.5f,\"incumbent\":%d}\n",
+                        r, info.families, info.pass ? "true" : "false", cfg_json(info.general).c_str(),
+                        info.geomean_speedup_general, info.score, rep.best_round);
+                fclose(f);
+            }
+        }
+    }
+    if (insert_in_table)
+        for (int i = 0; i < n; ++i)
+            addrms_table_insert(shapes[i].M, shapes[i].N, dtype, &rep.best.specialized[i], rep.best.specialized_us[i]);
+    rep.wall_ms = std::chrono::duration<double, std::milli>(Clock::now() - t0).count();
+    if (report) *report = rep;
+    return ADDRMS_OK;
+}
+
 }  // namespace addrms_host
+
+extern "C" int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int dtype,
+                                               const addrms_budget* budget, const addrms_backend_factory* factory,
+                                               addrms_cfg* out_general, addrms_rounds_report* report)
+{
+    if (!factory) return addrms_host::fail(ADDRMS_ERR_INVALID_ARG, "factory is NULL");
+    return addrms_host::run_tune_rounds(shapes, n, dtype, budget, *factory, false, out_general, report);
+}
 
 extern "C" int addrms_select_general_with_backend(const addrms_shape* shapes, int32_t n, int dtype,
                                                   const addrms_budget* budget, const addrms_backend_factory* factory,

@@ -96,6 +96,12 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
                        const addrms_backend_factory& factory, bool insert_in_table,
                        addrms_cfg* out_general, addrms_general_report* report);
 
+int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
+                    const addrms_backend_factory& factory, bool insert_in_table,
+                    addrms_cfg* out_general, addrms_rounds_report* report);
+// True if cfg only uses strategy families allowed by mask (0 = all).
+bool cfg_in_families(const addrms_cfg& c, int family_mask);
+
 // ---- error text ------------------------------------------------------------
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();

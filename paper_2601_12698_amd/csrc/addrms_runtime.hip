@@ -417,6 +417,16 @@ int addrms_select_general(const addrms_shape* shapes, int32_t n, int dtype, cons
     return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report);
 }
 
+int addrms_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                       addrms_cfg* out_general, addrms_rounds_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    HarnessFactory hf{(budget && budget->eps > 0.0f) ? budget->eps : 1e-6f};
+    addrms_backend_factory fac{&hf, factory_open, factory_close};
+    return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report);
+}
+
 int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,
                    int rotate, double* mean_us)
 {

@@ -295,6 +295,13 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     int64_t n_grid = 0;
     std::map<std::string, int64_t> pruned;   // which rule removed how many grid points
     enumerate(M, N, dtype, &feasible, &n_grid, &pruned);
+    if (b.family_mask != 0) {   // Level-1 rounds restrict the search to the strategy families enabled so far
+        std::vector<addrms_cfg> kept;
+        for (const addrms_cfg& c : feasible)
+            if (cfg_in_families(c, b.family_mask)) kept.push_back(c);
+        pruned["family_not_enabled"] += static_cast<int64_t>(feasible.size() - kept.size());
+        feasible.swap(kept);
+    }
     addrms_cfg dflt{};
     std::string why;
     const int dst = default_cfg(N, dtype, &dflt, &why);

@@ -111,3 +111,19 @@ def test_select_general_on_paper_shape_lists(shapes, dtype):
         assert B.addrms_table_lookup(M, N, dtype) is not None
     assert rep.geomean_speedup_specialized >= rep.geomean_speedup_general - 1e-9
     assert rep.geomean_speedup_general > 0.97        # the defaults are in the pool when they fit every shape
+
+
+def test_rounds_on_device(tmp_path):
+    """Level-1 rounds on the device: every family passes validation (all instances share
+    one arithmetic), the score never gets worse, streaming is the structural gain."""
+    log = str(tmp_path / "rounds.jsonl")
+    shapes = [(4096, 4096), (2048, 8192)]
+    g, rep = B.addrms_tune_rounds(shapes, "bf16", B.make_budget(log_path=log, warmup=5, reps=30))
+    print(json.dumps(rep.as_dict()["rounds"]), flush=True)
+    assert rep.n_rounds == 4 and all(rep.rounds[i].passed for i in range(4))
+    scores = [rep.rounds[i].score for i in range(4)]
+    assert scores[1] < scores[0] - 0.03            # the non-temporal policy is worth well over 3 %
+    assert min(scores) == scores[rep.best_round]
+    assert rep.rounds[0].general.flags == 0 and rep.rounds[0].general.max_waves_per_simd == 0
+    for M, N in shapes:
+        assert B.addrms_table_lookup(M, N, "bf16") is not None
