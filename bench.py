@@ -134,9 +134,14 @@ def cpu_baseline(W, wl, d, nbytes):
         spent += time.perf_counter() - t0
         passes += 1
     per = spent / passes
+    t0 = time.perf_counter()
+    oracle.addrms(xb, rb, wb, wl.eps, dt, nthreads=1)                         # one pass on one core
+    one = time.perf_counter() - t0
     return {"value": nbytes / per * 1e-9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"{passes} full passes over {wl.name} ({wl.M}x{wl.N}), rows split over {cores} threads",
-            "ms_per_step": per * 1e3, "tokens_per_s": wl.M / per}
+            "sample": f"{passes} full passes over {wl.name} ({wl.M}x{wl.N}), rows split over {cores} threads; "
+                      "plus one pass on a single thread",
+            "ms_per_step": per * 1e3, "tokens_per_s": wl.M / per,
+            "single_thread": {"value": nbytes / one * 1e-9, "unit": "GB/s", "cores": 1, "ms_per_step": one * 1e3}}
 
 
 def make_sets(torch, B, W, wl, d, dtype_id):

@@ -287,6 +287,27 @@ int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int d
 int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps,
                    int warmup, int reps, int rotate, double* mean_us);
 
+/* Timing statistics of one cfg: the batch mean of addrms_measure plus per-launch figures
+ * from an event pair around every launch (which include the launch floor that back-to-back
+ * launches hide).  out (host): mean_us = batch mean over `reps` launches, per_launch_mean_us,
+ * median_us and min_us from the per-launch events.  Same arguments as addrms_measure. */
+typedef struct addrms_time_stats {
+    double mean_us, per_launch_mean_us, median_us, min_us, max_us;
+    int32_t reps, buffer_sets;
+} addrms_time_stats;
+int addrms_measure_stats(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps,
+                         int warmup, int reps, int rotate, addrms_time_stats* out);
+
+/* r(h): the resource upper bounds of the target the deriver works from (Algorithm 1, Input),
+ * so that they can be checked against what the device reports. out: host. */
+typedef struct addrms_hw_limits {
+    int32_t compute_units, xcds, simds_per_cu, wave_size, max_waves_per_simd, regs_per_lane, reg_granule,
+            lds_bytes_per_cu, lds_granule, max_threads_per_wg, max_access_bytes, reserved;
+    double  hbm_bytes_per_s;
+    int64_t last_level_cache_bytes, l2_bytes_per_xcd;
+} addrms_hw_limits;
+int addrms_get_hw_limits(addrms_hw_limits* out);
+
 /* ---- specialised table D_spec: (dtype, N, M) -> cfg (Algorithm 1 line 23) ---- */
 int addrms_table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, double mean_us);
 /* Exact (dtype, N, M) entry if present, else the entry of the same (dtype, N)

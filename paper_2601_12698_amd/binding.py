@@ -138,6 +138,25 @@ class GeneralReport(Structure):
                     specialized=[self.specialized[i].as_dict() for i in range(n)])
 
 
+class TimeStats(Structure):
+    _fields_ = [("mean_us", c_double), ("per_launch_mean_us", c_double), ("median_us", c_double),
+                ("min_us", c_double), ("max_us", c_double), ("reps", c_int32), ("buffer_sets", c_int32)]
+
+    def as_dict(self) -> dict:
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class HwLimits(Structure):
+    _fields_ = [("compute_units", c_int32), ("xcds", c_int32), ("simds_per_cu", c_int32), ("wave_size", c_int32),
+                ("max_waves_per_simd", c_int32), ("regs_per_lane", c_int32), ("reg_granule", c_int32),
+                ("lds_bytes_per_cu", c_int32), ("lds_granule", c_int32), ("max_threads_per_wg", c_int32),
+                ("max_access_bytes", c_int32), ("reserved", c_int32), ("hbm_bytes_per_s", c_double),
+                ("last_level_cache_bytes", c_int64), ("l2_bytes_per_xcd", c_int64)]
+
+    def as_dict(self) -> dict:
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
 class RoundInfo(Structure):
     _fields_ = [("families", c_int32), ("passed", c_int32), ("score", c_double),
                 ("geomean_speedup_general", c_double), ("general", Cfg)]
@@ -181,6 +200,9 @@ SIGNATURES = {
     "addrms_tune_rounds_with_backend": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget),
                                                 POINTER(BackendFactory), POINTER(Cfg), POINTER(RoundsReport)]),
     "addrms_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_float, c_int, c_int, c_int, POINTER(c_double)]),
+    "addrms_measure_stats": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_float, c_int, c_int, c_int,
+                                     POINTER(TimeStats)]),
+    "addrms_get_hw_limits": (c_int, [POINTER(HwLimits)]),
     "addrms_table_insert": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg), c_double]),
     "addrms_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
     "addrms_table_size": (c_int64, []),
@@ -462,6 +484,20 @@ def addrms_measure(cfg: Optional[Cfg], M: int, N: int, dtype, eps: float = 1e-6,
     _check(load().addrms_measure(byref(cfg) if cfg is not None else None, M, N, _dtype_id(dtype), float(eps),
                                  warmup, reps, int(rotate), byref(us)))
     return float(us.value)
+
+
+def addrms_measure_stats(cfg: Optional[Cfg], M: int, N: int, dtype, eps: float = 1e-6, warmup: int = 20,
+                         reps: int = 100, rotate: bool = True) -> TimeStats:
+    out = TimeStats()
+    _check(load().addrms_measure_stats(byref(cfg) if cfg is not None else None, M, N, _dtype_id(dtype), float(eps),
+                                       warmup, reps, int(rotate), byref(out)))
+    return out
+
+
+def addrms_get_hw_limits() -> HwLimits:
+    out = HwLimits()
+    _check(load().addrms_get_hw_limits(byref(out)))
+    return out
 
 
 def addrms_table_insert(M: int, N: int, dtype, cfg: Cfg, mean_us: float = 0.0) -> None:

@@ -404,6 +404,21 @@ int64_t addrms_algorithmic_bytes(int64_t M, int64_t N, int dtype)
     return M * N * (2 * x_bytes(dtype) + 2 * r_bytes(dtype)) + N * x_bytes(dtype);
 }
 
+int addrms_get_hw_limits(addrms_hw_limits* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    const HwLimits& L = hw();
+    memset(out, 0, sizeof *out);
+    out->compute_units = L.compute_units; out->xcds = L.xcds; out->simds_per_cu = L.simds_per_cu;
+    out->wave_size = L.wave_size; out->max_waves_per_simd = L.max_waves_per_simd;
+    out->regs_per_lane = L.regs_per_lane; out->reg_granule = L.reg_granule;
+    out->lds_bytes_per_cu = L.lds_bytes_per_cu; out->lds_granule = L.lds_granule;
+    out->max_threads_per_wg = L.max_threads_per_wg; out->max_access_bytes = L.max_access_bytes;
+    out->hbm_bytes_per_s = L.hbm_bytes_per_s;
+    out->last_level_cache_bytes = L.last_level_cache_bytes; out->l2_bytes_per_xcd = L.l2_bytes_per_xcd;
+    return ADDRMS_OK;
+}
+
 int addrms_default_cfg(int64_t N, int dtype, addrms_cfg* out)
 {
     if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");

@@ -319,6 +319,47 @@ struct Harness {
         *mean_us = static_cast<double>(ms) * 1000.0 / reps;
         return ADDRMS_OK;
     }
+    // Per-launch timing: an event before and after every launch.
+    int measure_stats(const addrms_cfg& c, int warmup, int reps, addrms_time_stats* out)
+    {
+        const Feas f = check_cfg(c, M, N, dtype);
+        if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+        double batch = 0.0;
+        int st = measure(c, warmup, reps, &batch);
+        if (st != ADDRMS_OK) return st;
+        std::vector<hipEvent_t> ev(static_cast<size_t>(reps) + 1, nullptr);
+        auto destroy = [&] { for (hipEvent_t e : ev) if (e) (void)hipEventDestroy(e); };
+        for (hipEvent_t& e : ev)
+            if (hipEventCreate(&e) != hipSuccess) { destroy(); return fail(ADDRMS_ERR_HIP, "hipEventCreate failed"); }
+        int set = 0;
+        hipError_t err = hipEventRecord(ev[0], stream);
+        for (int i = 0; i < reps && err == hipSuccess; ++i) {
+            st = run_on(c, f, set);
+            if (st != ADDRMS_OK) { destroy(); return st; }
+            set = (set + 1) % nsets;
+            err = hipEventRecord(ev[i + 1], stream);
+        }
+        if (err == hipSuccess) err = hipEventSynchronize(ev[reps]);
+        std::vector<double> us(reps);
+        for (int i = 0; i < reps && err == hipSuccess; ++i) {
+            float ms = 0.0f;
+            err = hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+            us[i] = static_cast<double>(ms) * 1000.0;
+        }
+        destroy();
+        if (err != hipSuccess) return fail(ADDRMS_ERR_HIP, "per-launch timing failed: %s", hipGetErrorString(err));
+        std::sort(us.begin(), us.end());
+        double sum = 0.0;
+        for (double v : us) sum += v;
+        out->mean_us = batch;
+        out->per_launch_mean_us = sum / reps;
+        out->median_us = (reps % 2) ? us[reps / 2] : 0.5 * (us[reps / 2 - 1] + us[reps / 2]);
+        out->min_us = us.front();
+        out->max_us = us.back();
+        out->reps = reps;
+        out->buffer_sets = nsets;
+        return ADDRMS_OK;
+    }
 };
 
 int backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<Harness*>(user)->validate(*cfg); }
@@ -442,6 +483,25 @@ int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float
     st = h.init(M, N, dtype, eps, rotate != 0);
     if (st != ADDRMS_OK) return st;
     return h.measure(c, warmup, reps, mean_us);
+}
+
+int addrms_measure_stats(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,
+                         int rotate, addrms_time_stats* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M <= 0 || N <= 0 || reps <= 0 || reps > 100000 || warmup < 0)
+        return fail(ADDRMS_ERR_INVALID_ARG, "need M, N > 0, 0 < reps <= 100000 and warmup >= 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    addrms_cfg c{};
+    int st = resolve_cfg(cfg, M, N, dtype, &c);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    Harness h;
+    st = h.init(M, N, dtype, eps, rotate != 0);
+    if (st != ADDRMS_OK) return st;
+    memset(out, 0, sizeof *out);
+    return h.measure_stats(c, warmup, reps, out);
 }
 
 int addrms_device_resources(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, addrms_resources* out)

@@ -199,3 +199,35 @@ def test_runs_on_a_side_stream(oracle):
         B.addrms_run(case.x, case.r, case.w, wl.eps, wl.M, wl.N, wl.dtype, None, stream=s)
     s.synchronize()
     compare(W.to_bits(case.x), W.to_bits(case.r), y_ref, res_ref, "bf16", "side stream")
+
+
+def _run_raw(x, r, w, eps, dtype, cfg=None):
+    M, N = x.shape
+    xd, rd, wd = x.cuda(), r.cuda(), w.cuda()
+    B.addrms_run(xd, rd, wd, eps, M, N, dtype, cfg)
+    torch.cuda.synchronize()
+    return W.to_bits(xd), W.to_bits(rd)
+
+
+def test_exact_invariants_hold_on_the_device():
+    """Properties that hold at any size, checked on the device output itself: row
+    permutation, negation, power-of-two scaling (with eps scaled by 4^k)."""
+    wl = _wl(3000, 4096, "bf16", 70)
+    d = W.generate(wl)
+    x, r, w = d["x"], d["r"], d["w"]
+    eps = 2.0 ** -20
+    y0, r0 = _run_raw(x, r, w, eps, "bf16")
+    perm = torch.randperm(wl.M, generator=torch.Generator().manual_seed(1))
+    y1, r1 = _run_raw(x[perm].contiguous(), r[perm].contiguous(), w, eps, "bf16", B.make_cfg(8, 512, 2, flags=2))
+    assert np.array_equal(y1, y0[perm.numpy()]) and np.array_equal(r1, r0[perm.numpy()])
+    # negation flips every sign, except where x + r cancels exactly: a + (-a) is +0 either way
+    nz = (r0 & 0x7fff) != 0
+    assert (~nz).sum() < 0.01 * nz.size
+    y2, r2 = _run_raw(-x, -r, w, eps, "bf16")
+    assert np.array_equal((y2 ^ np.uint16(0x8000))[nz], y0[nz]) and np.array_equal((r2 ^ np.uint16(0x8000))[nz], r0[nz])
+    assert np.all(r2[~nz] == 0) and np.all(r0[~nz] == 0) and np.all((y2[~nz] & 0x7fff) == 0)
+    # scale by 2^k: y unchanged, residual scaled (zeros excluded: 0 * 2^k keeps its pattern)
+    k = 5
+    y3, r3 = _run_raw(x * 2.0 ** k, r * 2.0 ** k, w, eps * 4.0 ** k, "bf16")
+    assert np.array_equal(y3, y0)
+    assert np.array_equal(r3[nz], (r0 + np.uint16(k << 7))[nz])

@@ -127,3 +127,32 @@ def test_rounds_on_device(tmp_path):
     assert rep.rounds[0].general.flags == 0 and rep.rounds[0].general.max_waves_per_simd == 0
     for M, N in shapes:
         assert B.addrms_table_lookup(M, N, "bf16") is not None
+
+
+def test_hw_limits_match_the_device():
+    """The deriver's r(h) against what the runtime reports for the card."""
+    L = B.addrms_get_hw_limits()
+    p = torch.cuda.get_device_properties(0)
+    assert "gfx950" in p.gcnArchName
+    assert L.compute_units == p.multi_processor_count
+    assert L.wave_size == p.warp_size
+    assert L.max_threads_per_wg == getattr(p, "max_threads_per_block", 1024)
+    assert L.max_waves_per_simd * L.simds_per_cu * L.wave_size == p.max_threads_per_multi_processor
+    assert p.total_memory > 200 * (1 << 30)                       # 288 GB HBM3E part
+    assert L.lds_bytes_per_cu == 160 * 1024
+    l2 = getattr(p, "L2_cache_size", None)
+    if l2:
+        assert l2 == L.l2_bytes_per_xcd
+
+
+def test_measure_stats():
+    M, N, dt = 4096, 4096, "bf16"
+    d = B.addrms_default_cfg(N, dt)
+    s = B.addrms_measure_stats(d, M, N, dt, warmup=10, reps=60)
+    print(s.as_dict(), flush=True)
+    assert s.reps == 60 and s.buffer_sets >= 9
+    assert 0 < s.min_us <= s.median_us <= s.max_us
+    assert s.min_us <= s.per_launch_mean_us <= s.max_us
+    # an event pair around each launch can only add to what back-to-back launches cost on average
+    assert s.per_launch_mean_us >= 0.9 * s.mean_us
+    assert 10.0 < s.mean_us < 100.0
