@@ -19,6 +19,7 @@ VARIANTS = {"canonical": 0, "seq32": 1, "pair32": 2}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "addrms_oracle.c")
+_SRC2 = os.path.join(_HERE, "silumul_oracle.c")
 _LIB = os.path.join(_HERE, "libaddrms_oracle.so")
 _lock = threading.Lock()
 _lib = None
@@ -26,12 +27,12 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain -O2, no contraction, no fast-math)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2))
     if force or stale:
         tmp = _LIB + f".{os.getpid()}.tmp"
         subprocess.run(
             ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
-             "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"],
+             "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, "-lm"],
             check=True)
         os.replace(tmp, _LIB)
     return _LIB
@@ -57,6 +58,10 @@ def _load():
             lib.oracle_f32_to_bf16.restype = ctypes.c_uint16
             lib.oracle_f32_to_f16.argtypes = [ctypes.c_float]
             lib.oracle_f32_to_f16.restype = ctypes.c_uint16
+            lib.oracle_silumul.argtypes = [vp, i64, i64, ci, vp, ci]
+            lib.oracle_silumul.restype = ci
+            lib.oracle_silumul_f64.argtypes = [vp, i64, i64, ci, vp]
+            lib.oracle_silumul_f64.restype = ci
             for name in ("oracle_f32_to_bf16_array", "oracle_f32_to_f16_array",
                          "oracle_bf16_to_f32_array", "oracle_f16_to_f32_array"):
                 getattr(lib, name).argtypes = [vp, vp, i64]
@@ -116,6 +121,32 @@ def addrms_y64(x, r, w, eps: float, dtype: int) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"oracle_addrms_y64 failed with {rc}")
     return y64
+
+
+def silumul(x, dtype: int, nthreads: int = 1) -> np.ndarray:
+    """silu_and_mul oracle: x [M, 2d] (uint16 bit patterns or float32) -> out [M, d], same storage."""
+    M, two_d = x.shape
+    if two_d % 2:
+        raise ValueError("row length must be even")
+    d = two_d // 2
+    x = _check(x, _x_np(dtype), (M, two_d), "x")
+    out = np.empty((M, d), dtype=_x_np(dtype))
+    rc = _load().oracle_silumul(x.ctypes.data, M, d, dtype, out.ctypes.data, int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"oracle_silumul failed with {rc}")
+    return out
+
+
+def silumul_f64(x, dtype: int) -> np.ndarray:
+    """The unrounded fp64 values silu(gate) * up."""
+    M, two_d = x.shape
+    d = two_d // 2
+    x = _check(x, _x_np(dtype), (M, two_d), "x")
+    out = np.empty((M, d), dtype=np.float64)
+    rc = _load().oracle_silumul_f64(x.ctypes.data, M, d, dtype, out.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_silumul_f64 failed with {rc}")
+    return out
 
 
 def rstd_canonical(ss: float, N: int, eps: float) -> np.float32:
