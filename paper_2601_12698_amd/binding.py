@@ -213,6 +213,16 @@ SIGNATURES = {
     "addrms_rstd_probe": (c_int, [c_void_p, c_int64, c_int64, c_float, c_void_p, c_void_p]),
     "addrms_stream_probe": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p]),
     "addrms_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
+    "silumul_run": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, POINTER(Cfg), c_void_p]),
+    "silumul_default_cfg": (c_int, [c_int64, c_int, POINTER(Cfg)]),
+    "silumul_cfg_feasible": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_char_p, c_size_t, POINTER(Resources)]),
+    "silumul_enumerate_feasible": (c_int64, [c_int64, c_int64, c_int, POINTER(Cfg), c_int64, POINTER(c_int64)]),
+    "silumul_tune": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Cfg), POINTER(TuneReport)]),
+    "silumul_tune_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
+                                          POINTER(Cfg), POINTER(TuneReport)]),
+    "silumul_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_int, c_int, c_int, POINTER(c_double)]),
+    "silumul_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
+    "silumul_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
     "addrms_last_error": (c_char_p, []),
     "addrms_version": (c_char_p, []),
 }
@@ -542,3 +552,83 @@ def addrms_rstd_probe(ss, N: int, eps: float, out, stream=None) -> None:
 
 def addrms_stream_probe(x, residual, M: int, N: int, dtype, stream=None) -> None:
     _check(load().addrms_stream_probe(_ptr(x), _ptr(residual), M, N, _dtype_id(dtype), _stream_ptr(stream, x)))
+
+
+# ---- silu_and_mul (include/silumul.h) -------------------------------------------------
+
+def silumul_algorithmic_bytes(M: int, d: int, dtype) -> int:
+    return _check(load().silumul_algorithmic_bytes(M, d, _dtype_id(dtype)))
+
+
+def silumul_run(x, out, M: int, d: int, dtype, cfg: Optional[Cfg] = None, stream=None) -> None:
+    """out[i, j] = silu(x[i, j]) * x[i, d + j]; x is [M, 2d], out is [M, d], both on the device."""
+    for name, t in (("x", x), ("out", out)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous device tensor")
+    if x.numel() != 2 * M * d or out.numel() != M * d:
+        raise ValueError("tensor sizes do not match M and d")
+    _check(load().silumul_run(_ptr(x), _ptr(out), M, d, _dtype_id(dtype),
+                              byref(cfg) if cfg is not None else None, _stream_ptr(stream, x)))
+
+
+def silumul_default_cfg(d: int, dtype) -> Cfg:
+    c = Cfg()
+    _check(load().silumul_default_cfg(d, _dtype_id(dtype), byref(c)))
+    return c
+
+
+def silumul_cfg_feasible(cfg: Cfg, M: int, d: int, dtype) -> Tuple[int, str, Resources]:
+    buf = ctypes.create_string_buffer(512)
+    res = Resources()
+    st = load().silumul_cfg_feasible(byref(cfg), M, d, _dtype_id(dtype), buf, len(buf), byref(res))
+    return int(st), buf.value.decode("utf-8", "replace"), res
+
+
+def silumul_enumerate_feasible(M: int, d: int, dtype) -> Tuple[List[Cfg], int]:
+    lib = load()
+    grid = c_int64(0)
+    n = _check(lib.silumul_enumerate_feasible(M, d, _dtype_id(dtype), None, 0, byref(grid)))
+    arr = (Cfg * max(n, 1))()
+    _check(lib.silumul_enumerate_feasible(M, d, _dtype_id(dtype), arr, n, byref(grid)))
+    out = []
+    for i in range(n):
+        c = Cfg()
+        ctypes.memmove(byref(c), byref(arr[i]), ctypes.sizeof(Cfg))
+        out.append(c)
+    return out, int(grid.value)
+
+
+def silumul_tune(M: int, d: int, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, TuneReport]:
+    c, rep = Cfg(), TuneReport()
+    _check(load().silumul_tune(M, d, _dtype_id(dtype), byref(budget) if budget is not None else None,
+                               byref(c), byref(rep)))
+    return c, rep
+
+
+def silumul_tune_with_backend(M: int, d: int, dtype, budget: Optional[Budget], measure, validate=None
+                              ) -> Tuple[Cfg, TuneReport]:
+    be = Backend()
+    be.user = None
+    be.measure = _wrap_measure(measure)
+    be.validate = _wrap_validate(validate)
+    c, rep = Cfg(), TuneReport()
+    _check(load().silumul_tune_with_backend(M, d, _dtype_id(dtype), byref(budget) if budget is not None else None,
+                                            byref(be), byref(c), byref(rep)))
+    return c, rep
+
+
+def silumul_measure(cfg: Optional[Cfg], M: int, d: int, dtype, warmup: int = 20, reps: int = 100,
+                    rotate: bool = True) -> float:
+    us = c_double(0.0)
+    _check(load().silumul_measure(byref(cfg) if cfg is not None else None, M, d, _dtype_id(dtype), warmup, reps,
+                                  int(rotate), byref(us)))
+    return float(us.value)
+
+
+def silumul_table_lookup(M: int, d: int, dtype) -> Optional[Cfg]:
+    c = Cfg()
+    st = load().silumul_table_lookup(M, d, _dtype_id(dtype), byref(c))
+    if st == ERR_NO_RESULT:
+        return None
+    _check(st)
+    return c

@@ -76,7 +76,8 @@ def parse_remarks(text: str) -> dict:
 def _compile_kernel_unit(src: str, force: bool) -> str:
     obj = src[:-4] + ".o"
     rem = src[:-4] + ".remarks"
-    if not force and _newer(obj, src, os.path.join(CSRC, "addrms_kernel.h")) and os.path.exists(rem):
+    if (not force and os.path.exists(rem) and
+            _newer(obj, src, os.path.join(CSRC, "addrms_kernel.h"), os.path.join(CSRC, "silumul_kernel.h"))):
         return open(rem).read()
     r = _run(["hipcc", *DEVICE_FLAGS, *INCLUDES, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj])
     with open(rem, "w") as f:
@@ -92,22 +93,27 @@ def build(force: bool = False, jobs: int = 8, verbose: bool = False) -> str:
         sys.path.pop(0)
     os.makedirs(BUILD, exist_ok=True)
     gen_kernels.main(BUILD)
-    units = sorted(os.path.join(BUILD, f) for f in os.listdir(BUILD) if f.startswith("kern_") and f.endswith(".hip"))
+    wanted = {f"kern_{gen_kernels.OP_PREFIX[op]}_d{dt}_v{vec}.hip" for op, dt, vec, *_ in gen_kernels.instances()}
+    for f in os.listdir(BUILD):          # units of an older instance list must not be linked in
+        if f.startswith("kern_") and f.split(".")[0] + ".hip" not in wanted:
+            os.remove(os.path.join(BUILD, f))
+    units = sorted(os.path.join(BUILD, f) for f in wanted)
     with cf.ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
         remarks = list(ex.map(lambda s: _compile_kernel_unit(s, force), units))
     res = {}
     for text in remarks:
         res.update(parse_remarks(text))
     rows = []
-    for dt, vec, cpt, unr, nt, _maxt in gen_kernels.instances():
-        r = res.get(gen_kernels.name(dt, vec, cpt, unr, nt))
+    for op, dt, vec, cpt, unr, nt, _maxt in gen_kernels.instances():
+        r = res.get(gen_kernels.name(op, dt, vec, cpt, unr, nt))
         if r is None or any(k not in r for k in ("vgprs", "agprs", "sgprs", "scratch", "lds", "occupancy")):
-            raise RuntimeError(f"no resource report for {gen_kernels.name(dt, vec, cpt, unr, nt)}")
+            raise RuntimeError(f"no resource report for {gen_kernels.name(op, dt, vec, cpt, unr, nt)}")
         rows.append(f"    {{{r['vgprs']}, {r['agprs']}, {r['sgprs']}, {r['scratch']}, {r['lds']}, {r['occupancy']}}},")
     gen_kernels._write(os.path.join(BUILD, "gen_resources.inc"), "\n".join(rows) + "\n")
 
     objs = [u[:-4] + ".o" for u in units]
-    hdrs = [os.path.join(ROOT, "include", "addrms.h"), os.path.join(CSRC, "addrms_internal.h")]
+    hdrs = [os.path.join(ROOT, "include", "addrms.h"), os.path.join(ROOT, "include", "silumul.h"),
+            os.path.join(CSRC, "addrms_internal.h")]
     gen = [os.path.join(BUILD, f) for f in ("gen_instances.inc", "gen_resources.inc",
                                              "gen_dispatch_decl.inc", "gen_dispatch_rows.inc")]
     for name in ("addrms_cfg.cpp", "addrms_table.cpp", "addrms_search.cpp", "addrms_general.cpp"):
@@ -118,7 +124,8 @@ def build(force: bool = False, jobs: int = 8, verbose: bool = False) -> str:
         objs.append(obj)
     src = os.path.join(CSRC, "addrms_runtime.hip")
     obj = os.path.join(BUILD, "addrms_runtime.o")
-    if force or not _newer(obj, src, os.path.join(CSRC, "addrms_kernel.h"), *hdrs, *gen):
+    if force or not _newer(obj, src, os.path.join(CSRC, "addrms_kernel.h"), os.path.join(CSRC, "silumul_kernel.h"),
+                           *hdrs, *gen):
         _run(["hipcc", *DEVICE_FLAGS, *INCLUDES, "-c", src, "-o", obj])
     objs.append(obj)
     tmp = LIB + f".{os.getpid()}.tmp"

@@ -56,33 +56,45 @@ int n_instances() { return static_cast<int>(sizeof(kInstances) / sizeof(kInstanc
 const Instance& instance(int idx) { return kInstances[idx]; }
 const InstanceRes& instance_res(int idx) { return kInstanceRes[idx]; }
 
-static uint32_t inst_key(int dt, int vec, int cpt, int unr, int nt)
+const char* op_name(int op) { return op == OP_SILUMUL ? "silu_and_mul" : "add_rmsnorm"; }
+
+static uint32_t inst_key(int op, int dt, int vec, int cpt, int unr, int nt)
 {
-    return (static_cast<uint32_t>(dt) << 24) | (static_cast<uint32_t>(vec) << 16) |
+    return (static_cast<uint32_t>(op) << 28) | (static_cast<uint32_t>(dt) << 24) | (static_cast<uint32_t>(vec) << 16) |
            (static_cast<uint32_t>(cpt) << 8) | (static_cast<uint32_t>(unr) << 1) | static_cast<uint32_t>(nt);
 }
 
-int find_instance(int dt, int vec, int cpt, int unr, int nt)
+int find_instance(int op, int dt, int vec, int cpt, int unr, int nt)
 {
     static const std::unordered_map<uint32_t, int> index = [] {
         std::unordered_map<uint32_t, int> m;
         for (int i = 0; i < n_instances(); ++i)
-            m[inst_key(kInstances[i].dt, kInstances[i].vec, kInstances[i].cpt, kInstances[i].unr, kInstances[i].nt)] = i;
+            m[inst_key(kInstances[i].op, kInstances[i].dt, kInstances[i].vec, kInstances[i].cpt, kInstances[i].unr, kInstances[i].nt)] = i;
         return m;
     }();
-    auto it = index.find(inst_key(dt, vec, cpt, unr, nt));
+    auto it = index.find(inst_key(op, dt, vec, cpt, unr, nt));
     return it == index.end() ? -1 : it->second;
 }
 
-bool cpt_supported(int cpt)
+bool cpt_supported(int op, int cpt)
 {
     for (int i = 0; i < n_instances(); ++i)
-        if (kInstances[i].cpt == cpt) return true;
+        if (kInstances[i].op == op && kInstances[i].cpt == cpt) return true;
     return false;
 }
 
 // ---- formats -------------------------------------------------------------------
-bool dtype_valid(int dtype) { return dtype >= ADDRMS_BF16 && dtype <= ADDRMS_FP32; }
+bool dtype_valid(int dtype, int op)
+{
+    if (dtype < ADDRMS_BF16 || dtype > ADDRMS_FP32) return false;
+    return op == OP_ADDRMS || dtype != ADDRMS_FP16_RES32;     // only add+RMSNorm has a separate residual stream
+}
+
+int64_t algorithmic_bytes(int op, int64_t M, int64_t N, int dtype)
+{
+    if (op == OP_SILUMUL) return M * N * 3 * x_bytes(dtype);                   // read gate and up, write out
+    return M * N * (2 * x_bytes(dtype) + 2 * r_bytes(dtype)) + N * x_bytes(dtype);
+}
 int x_bytes(int dtype) { return dtype == ADDRMS_FP32 ? 4 : 2; }
 int r_bytes(int dtype) { return (dtype == ADDRMS_FP32 || dtype == ADDRMS_FP16_RES32) ? 4 : 2; }
 const char* dtype_name(int dtype)
@@ -133,8 +145,9 @@ std::string cfg_json(const addrms_cfg& c)
     return buf;
 }
 
-int reduction_lds_bytes(const addrms_cfg& c)
+int reduction_lds_bytes(const addrms_cfg& c, int op)
 {
+    if (op != OP_ADDRMS) return 0;          // no reduction, no LDS
     // a persistent workgroup alternates between two regions from one row block to the next
     const int regions = (c.flags & ADDRMS_FLAG_PERSISTENT) ? 2 : 1;
     if (c.reduce == ADDRMS_REDUCE_LDS) return regions * c.threads_per_row * c.rows_per_wg * 8;
@@ -168,9 +181,9 @@ bool cfg_in_families(const addrms_cfg& c, int mask)
     return true;
 }
 
-int lds_bytes_for(const addrms_cfg& c)
+int lds_bytes_for(const addrms_cfg& c, int op)
 {
-    const int need = reduction_lds_bytes(c);
+    const int need = reduction_lds_bytes(c, op);
     const int wgs = capped_wgs_per_cu(c);
     if (c.max_waves_per_simd <= 0) return need;
     if (wgs == 0) return 0;
@@ -201,13 +214,14 @@ static Feas infeasible(const char* rule, const char* fmt, ...)
     return f;
 }
 
-Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
+Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op)
 {
     const HwLimits& L = hw();
     Feas f;
-    if (!dtype_valid(dtype)) {
+    if (!dtype_valid(dtype, op)) {
         f.status = ADDRMS_ERR_UNSUPPORTED_DTYPE;
-        f.reason = "dtype is not one of bf16, fp16, fp16_res32, fp32";
+        f.reason = op == OP_ADDRMS ? "dtype is not one of bf16, fp16, fp16_res32, fp32"
+                                   : "dtype is not one of bf16, fp16, fp32";
         return f;
     }
     if (M < 0 || N <= 0) {
@@ -223,6 +237,8 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     if (!in_set(c.rows_per_wg, kRows, 5)) return infeasible("grid", "rows_per_wg=%d: must be 1, 2, 4, 8 or 16", c.rows_per_wg);
     if (c.reduce != ADDRMS_REDUCE_WAVE && c.reduce != ADDRMS_REDUCE_LDS)
         return infeasible("grid", "reduce=%d: must be wave (0) or lds (1)", c.reduce);
+    if (op != OP_ADDRMS && c.reduce != 0)
+        return infeasible("grid", "reduce=%d: %s has no reduction; the knob must stay 0", c.reduce, op_name(op));
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
     if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT)) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
     if (c.max_waves_per_simd < 0 || c.max_waves_per_simd >= L.max_waves_per_simd)
@@ -257,8 +273,9 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
                           "holds %d (more would spill or leave under %d waves per SIMD)",
                           (long long)N, c.threads_per_row, c.vec, (long long)(need * c.vec), kMaxElemsPerThread,
                           kMinWavesPerSimd);
-    if (!cpt_supported(static_cast<int>(need)))
-        return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (1-8, 10, 12, 14, 16 exist)", (long long)need);
+    if (!cpt_supported(op, static_cast<int>(need)))
+        return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (%s)", (long long)need,
+                          op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : "1-8 exist");
     f.res.chunks_per_thread = static_cast<int>(need);
     const double util = static_cast<double>(N) / static_cast<double>(per_pass * need);
     if (util <= 0.5)
@@ -276,7 +293,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
                           2 * L.xcds);
 
     // -- compiled instance and its resources
-    const int idx = find_instance(dtype, c.vec, static_cast<int>(need), c.unroll,
+    const int idx = find_instance(op, dtype, c.vec, static_cast<int>(need), c.unroll,
                                   (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0);
     if (idx < 0)
         return infeasible("no_instance", "no compiled instance for dtype=%s vec=%d chunks=%lld unroll=%d", dtype_name(dtype), c.vec,
@@ -287,7 +304,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
     addrms_resources& o = f.res;
     o.vgprs = r.vgprs; o.agprs = r.agprs; o.sgprs = r.sgprs; o.scratch_bytes = r.scratch;
     o.max_threads = in.maxt;
-    o.lds_bytes = reduction_lds_bytes(c) + r.lds_static;
+    o.lds_bytes = reduction_lds_bytes(c, op) + r.lds_static;
     o.waves_per_wg = threads / L.wave_size;
     if (r.scratch > 0)
         return infeasible("scratch", "instance spills %d bytes per lane to scratch memory", r.scratch);
@@ -335,7 +352,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype)
 }
 
 void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid,
-               std::map<std::string, int64_t>* pruned)
+               std::map<std::string, int64_t>* pruned, int op)
 {
     int64_t grid = 0;
     std::vector<int> tprs = {8, 16, 32};
@@ -351,16 +368,16 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
                                 addrms_cfg c{};
                                 c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;
                                 c.reduce = red; c.unroll = unr; c.flags = flags; c.max_waves_per_simd = cap;
-                                const Feas f = check_cfg(c, M, N, dtype);
+                                const Feas f = check_cfg(c, M, N, dtype, op);
                                 if (f.status == ADDRMS_OK) { if (out) out->push_back(c); }
                                 else if (pruned) ++(*pruned)[f.rule];
                             }
     if (n_grid) *n_grid = grid;
 }
 
-int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why)
+int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op)
 {
-    if (!dtype_valid(dtype)) { if (why) *why = "unsupported dtype"; return ADDRMS_ERR_UNSUPPORTED_DTYPE; }
+    if (!dtype_valid(dtype, op)) { if (why) *why = "unsupported dtype"; return ADDRMS_ERR_UNSUPPORTED_DTYPE; }
     if (N <= 0) { if (why) *why = "N must be > 0"; return ADDRMS_ERR_INVALID_ARG; }
     // Preference order: widest vector; 256 threads per row, then wider, then
     // narrower rows; one row per workgroup (more only to fill a wave).
@@ -375,7 +392,7 @@ int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why)
             c.reduce = ADDRMS_REDUCE_WAVE;
             const int64_t need = (N + static_cast<int64_t>(vec) * tpr - 1) / (static_cast<int64_t>(vec) * tpr);
             c.unroll = need >= 2 ? 2 : 1;
-            if (check_cfg(c, big_m, N, dtype).status == ADDRMS_OK) { *out = c; return ADDRMS_OK; }
+            if (check_cfg(c, big_m, N, dtype, op).status == ADDRMS_OK) { *out = c; return ADDRMS_OK; }
         }
     if (why) {
         char buf[160];
@@ -401,7 +418,7 @@ int64_t addrms_algorithmic_bytes(int64_t M, int64_t N, int dtype)
 {
     if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
     if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
-    return M * N * (2 * x_bytes(dtype) + 2 * r_bytes(dtype)) + N * x_bytes(dtype);
+    return algorithmic_bytes(OP_ADDRMS, M, N, dtype);
 }
 
 int addrms_get_hw_limits(addrms_hw_limits* out)

@@ -38,19 +38,25 @@ const HwLimits& hw();
 constexpr int kMinWavesPerSimd = 2;
 constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
 
+// ---- operators that go through the tuner ------------------------------------
+enum Op : int { OP_ADDRMS = 0, OP_SILUMUL = 1 };
+const char* op_name(int op);
+
 // ---- kernel instances ------------------------------------------------------
-struct Instance { int dt, vec, cpt, unr, nt, maxt; };
+struct Instance { int op, dt, vec, cpt, unr, nt, maxt; };
 struct InstanceRes { int vgprs, agprs, sgprs, scratch, lds_static, occupancy; };
 
 int n_instances();
 const Instance& instance(int idx);
 const InstanceRes& instance_res(int idx);
 // Index of the instance with exactly these knob values, or -1.
-int find_instance(int dt, int vec, int cpt, int unr, int nt);
-bool cpt_supported(int cpt);
+int find_instance(int op, int dt, int vec, int cpt, int unr, int nt);
+bool cpt_supported(int op, int cpt);
 
 // ---- storage formats -------------------------------------------------------
-bool dtype_valid(int dtype);
+bool dtype_valid(int dtype, int op = OP_ADDRMS);
+// Bytes the operator must move for (M rows, N outputs per row).
+int64_t algorithmic_bytes(int op, int64_t M, int64_t N, int dtype);
 int x_bytes(int dtype);
 int r_bytes(int dtype);
 const char* dtype_name(int dtype);
@@ -63,15 +69,15 @@ struct Feas {
     int inst = -1;              // instance index when one was selected
     addrms_resources res{};
 };
-Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype);
+Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op = OP_ADDRMS);
 // Walks the whole knob grid; `pruned` (optional) counts rejected points by rule tag.
 void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid,
-               std::map<std::string, int64_t>* pruned = nullptr);
-int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why);
+               std::map<std::string, int64_t>* pruned = nullptr, int op = OP_ADDRMS);
+int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op = OP_ADDRMS);
 // Dynamic LDS bytes of a launch: what the reduction needs, raised to the padding that
 // imposes cfg.max_waves_per_simd (0 if the cap cannot be imposed; check_cfg rejects that).
-int lds_bytes_for(const addrms_cfg& c);
-int reduction_lds_bytes(const addrms_cfg& c);
+int lds_bytes_for(const addrms_cfg& c, int op = OP_ADDRMS);
+int reduction_lds_bytes(const addrms_cfg& c, int op = OP_ADDRMS);
 // Workgroups per CU that cfg.max_waves_per_simd allows (0 = no cap requested).
 int capped_wgs_per_cu(const addrms_cfg& c);
 // Blocks of rows_per_wg rows; and the grid size: one workgroup per block, or for a
@@ -84,11 +90,12 @@ uint64_t cfg_key(const addrms_cfg& c);
 std::string cfg_json(const addrms_cfg& c);
 
 // ---- specialised table -----------------------------------------------------
-int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out);
+int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out, int op = OP_ADDRMS);
+int table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg& cfg, double mean_us, int op);
 
 // ---- search ----------------------------------------------------------------
 int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
-               const addrms_backend& be, addrms_cfg* out_cfg, addrms_tune_report* report);
+               const addrms_backend& be, addrms_cfg* out_cfg, addrms_tune_report* report, int op = OP_ADDRMS);
 
 // ---- general configuration ---------------------------------------------------
 // insert_in_table: store each shape's winner in the specialised table (device runs only).

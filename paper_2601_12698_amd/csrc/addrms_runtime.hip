@@ -11,12 +11,13 @@
 #include <vector>
 
 #include "addrms_internal.h"
-#include "addrms_kernel.h"
+#include "silumul.h"
+#include "silumul_kernel.h"
 
 // Declarations of every kernel instance and the table of their addresses, in
 // the order of the instance list the deriver uses.
 #include "gen_dispatch_decl.inc"
-struct DispatchEntry { int dt, vec, cpt, unr, nt; const void* fn; };
+struct DispatchEntry { int op, dt, vec, cpt, unr, nt; const void* fn; };
 static const DispatchEntry kDispatch[] = {
 #include "gen_dispatch_rows.inc"
 };
@@ -39,7 +40,7 @@ bool dispatch_consistent()
         for (int i = 0; i < n_instances(); ++i) {
             const Instance& in = instance(i);
             const DispatchEntry& d = kDispatch[i];
-            if (d.dt != in.dt || d.vec != in.vec || d.cpt != in.cpt || d.unr != in.unr || d.nt != in.nt) return false;
+            if (d.op != in.op || d.dt != in.dt || d.vec != in.vec || d.cpt != in.cpt || d.unr != in.unr || d.nt != in.nt) return false;
         }
         return true;
     }();
@@ -51,20 +52,12 @@ std::atomic<bool> g_big_lds_enabled[sizeof(kDispatch) / sizeof(kDispatch[0])];
 
 bool aligned(const void* p, int bytes) { return (reinterpret_cast<uintptr_t>(p) % static_cast<uintptr_t>(bytes)) == 0; }
 
-// Launch with every check already done.
-int launch(const Feas& f, const addrms_cfg& c, void* x, void* r, const void* w, float eps, int64_t M, int64_t N,
-           hipStream_t stream)
+// Launch of a kernel instance with every check already done.
+int launch_instance(const Feas& f, const addrms_cfg& c, int64_t M, int op, void** args, hipStream_t stream)
 {
-    double inv_n = 1.0 / static_cast<double>(N);
-    long long m = M;
-    int n = static_cast<int>(N);
-    unsigned flags = static_cast<unsigned>(c.flags);
-    int reduce = c.reduce;
-    unsigned nblocks = static_cast<unsigned>(n_row_blocks(c, M));
-    void* args[] = {&x, &r, &w, &eps, &inv_n, &m, &n, &flags, &reduce, &nblocks};
     const dim3 grid(static_cast<unsigned>(n_workgroups(c, M, f.res.wgs_per_cu)));
     const dim3 block(static_cast<unsigned>(c.threads_per_row), static_cast<unsigned>(c.rows_per_wg));
-    const int lds = lds_bytes_for(c);
+    const int lds = lds_bytes_for(c, op);
     if (lds > kDefaultDynamicLdsLimit) {
         // Occupancy padding beyond the default per-launch limit has to be enabled once per kernel.
         std::atomic<bool>& done = g_big_lds_enabled[f.inst];
@@ -78,12 +71,35 @@ int launch(const Feas& f, const addrms_cfg& c, void* x, void* r, const void* w, 
     return ADDRMS_OK;
 }
 
-int resolve_cfg(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, addrms_cfg* out)
+int launch(const Feas& f, const addrms_cfg& c, void* x, void* r, const void* w, float eps, int64_t M, int64_t N,
+           hipStream_t stream)
+{
+    double inv_n = 1.0 / static_cast<double>(N);
+    long long m = M;
+    int n = static_cast<int>(N);
+    unsigned flags = static_cast<unsigned>(c.flags);
+    int reduce = c.reduce;
+    unsigned nblocks = static_cast<unsigned>(n_row_blocks(c, M));
+    void* args[] = {&x, &r, &w, &eps, &inv_n, &m, &n, &flags, &reduce, &nblocks};
+    return launch_instance(f, c, M, OP_ADDRMS, args, stream);
+}
+
+int launch_silumul(const Feas& f, const addrms_cfg& c, const void* x, void* out, int64_t M, int64_t d, hipStream_t stream)
+{
+    long long m = M;
+    int dd = static_cast<int>(d);
+    unsigned flags = static_cast<unsigned>(c.flags);
+    unsigned nblocks = static_cast<unsigned>(n_row_blocks(c, M));
+    void* args[] = {&x, &out, &m, &dd, &flags, &nblocks};
+    return launch_instance(f, c, M, OP_SILUMUL, args, stream);
+}
+
+int resolve_cfg(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, addrms_cfg* out, int op = OP_ADDRMS)
 {
     if (cfg) { *out = *cfg; return ADDRMS_OK; }
-    if (table_lookup(M, N, dtype, out) == ADDRMS_OK) return ADDRMS_OK;
+    if (table_lookup(M, N, dtype, out, op) == ADDRMS_OK) return ADDRMS_OK;
     std::string why;
-    const int st = default_cfg(N, dtype, out, &why);
+    const int st = default_cfg(N, dtype, out, &why, op);
     return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
 }
 
@@ -370,6 +386,112 @@ int backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, dou
 
 std::mutex g_tune_mu;
 
+// ---- measurement harness of silu_and_mul: one pristine input, a reference output, and
+// rotating (input, output) pairs; the operator is out of place, so nothing is restored.
+struct SiluHarness {
+    int64_t M = 0, d = 0;
+    int dtype = 0;
+    int nsets = 0;
+    size_t inbytes = 0, outbytes = 0;
+    char* pool = nullptr;
+    char *ref = nullptr;
+    std::vector<char*> ins, outs;
+    unsigned* counts = nullptr;
+    hipStream_t stream = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+
+    static size_t pad(size_t b) { return (b + 65535) / 65536 * 65536 + 65536; }
+
+    int init(int64_t m, int64_t dd, int dt, bool rotate)
+    {
+        M = m; d = dd; dtype = dt;
+        inbytes = static_cast<size_t>(M) * 2 * d * x_bytes(dt);
+        outbytes = static_cast<size_t>(M) * d * x_bytes(dt);
+        const size_t set = pad(inbytes) + pad(outbytes);
+        const size_t want = 2 * (static_cast<size_t>(hw().last_level_cache_bytes) +
+                                 static_cast<size_t>(hw().l2_bytes_per_xcd) * hw().xcds);
+        nsets = rotate ? static_cast<int>(std::min<size_t>(32, std::max<size_t>(2, (want + set - 1) / set))) : 1;
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), set * nsets + pad(outbytes) + pad(256)));
+        char* p = pool;
+        auto take = [&](size_t b, size_t skew) { char* q = p + skew; p += pad(b); return q; };
+        ref = take(outbytes, 0);
+        counts = reinterpret_cast<unsigned*>(take(256, 0));
+        for (int i = 0; i < nsets; ++i) { ins.push_back(take(inbytes, 0)); outs.push_back(take(outbytes, 4096)); }
+        HIP_TRY(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
+        HIP_TRY(hipEventCreate(&ev0));
+        HIP_TRY(hipEventCreate(&ev1));
+        const int st = fill(ins[0], M * 2 * d, x_bytes(dt), dt == ADDRMS_BF16, 0x2468aceu, 0, 0, true, stream);
+        if (st != ADDRMS_OK) return st;
+        for (int i = 1; i < nsets; ++i)
+            HIP_TRY(hipMemcpyAsync(ins[i], ins[0], inbytes, hipMemcpyDeviceToDevice, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        return ADDRMS_OK;
+    }
+    ~SiluHarness()
+    {
+        if (ev0) (void)hipEventDestroy(ev0);
+        if (ev1) (void)hipEventDestroy(ev1);
+        if (stream) (void)hipStreamDestroy(stream);
+        if (pool) (void)hipFree(pool);
+    }
+    int make_reference(const addrms_cfg& c)
+    {
+        const Feas f = check_cfg(c, M, d, dtype, OP_SILUMUL);
+        if (f.status != ADDRMS_OK) return fail(f.status, "reference cfg infeasible: %s", f.reason.c_str());
+        const int st = launch_silumul(f, c, ins[0], ref, M, d, stream);
+        if (st != ADDRMS_OK) return st;
+        HIP_TRY(hipStreamSynchronize(stream));
+        return ADDRMS_OK;
+    }
+    int validate(const addrms_cfg& c)
+    {
+        const Feas f = check_cfg(c, M, d, dtype, OP_SILUMUL);
+        if (f.status != ADDRMS_OK) return f.status;
+        HIP_TRY(hipMemsetAsync(outs[0], 0xff, outbytes, stream));     // stale output must not pass for a result
+        int st = launch_silumul(f, c, ins[0], outs[0], M, d, stream);
+        if (st != ADDRMS_OK) return st;
+        const long long n = static_cast<long long>(M) * d;
+        const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
+        HIP_TRY(hipMemsetAsync(counts, 0, 16, stream));
+        // the residual slots of the comparison are fed the same buffer twice: only the output is graded
+        if (x_bytes(dtype) == 2)
+            hipLaunchKernelGGL((compare_kernel<2, 2>), grid, block, 0, stream, outs[0], ref, ref, ref, n, 1u, counts);
+        else
+            hipLaunchKernelGGL((compare_kernel<4, 4>), grid, block, 0, stream, outs[0], ref, ref, ref, n, 1u, counts);
+        HIP_TRY(hipGetLastError());
+        unsigned h[4] = {0, 0, 0, 0};
+        HIP_TRY(hipMemcpyAsync(h, counts, 16, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        if (h[1] != 0)
+            return fail(ADDRMS_ERR_INFEASIBLE_CFG, "candidate %s disagrees with the reference: %u outputs beyond 1 ulp "
+                        "(max distance %u)", cfg_json(c).c_str(), h[1], h[2]);
+        return ADDRMS_OK;
+    }
+    int measure(const addrms_cfg& c, int warmup, int reps, double* mean_us)
+    {
+        const Feas f = check_cfg(c, M, d, dtype, OP_SILUMUL);
+        if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+        int set = 0;
+        for (int i = 0; i < warmup + reps; ++i) {
+            if (i == warmup) HIP_TRY(hipEventRecord(ev0, stream));
+            const int st = launch_silumul(f, c, ins[set], outs[set], M, d, stream);
+            if (st != ADDRMS_OK) return st;
+            set = (set + 1) % nsets;
+        }
+        HIP_TRY(hipEventRecord(ev1, stream));
+        HIP_TRY(hipEventSynchronize(ev1));
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, ev0, ev1));
+        *mean_us = static_cast<double>(ms) * 1000.0 / reps;
+        return ADDRMS_OK;
+    }
+};
+int silu_backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<SiluHarness*>(user)->validate(*cfg); }
+int silu_backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
+{
+    return static_cast<SiluHarness*>(user)->measure(*cfg, warmup, reps, us);
+}
+
 // Backend factory over the device harness: one Harness per shape, reference output from
 // that shape's default cfg.
 struct HarnessFactory { float eps; };
@@ -556,6 +678,126 @@ int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype
                        static_cast<addrms::u32x4*>(x), static_cast<addrms::u32x4*>(residual), n, static_cast<int>(rb / xb));
     HIP_TRY(hipGetLastError());
     return ADDRMS_OK;
+}
+
+// ---- silu_and_mul ----------------------------------------------------------------------
+
+int silumul_run(const void* x, void* out, int64_t M, int64_t d, int dtype, const addrms_cfg* cfg, void* stream)
+{
+    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for silu_and_mul", dtype);
+    if (M < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and d > 0 (got M=%lld d=%lld)",
+                                     (long long)M, (long long)d);
+    if (M == 0) return ADDRMS_OK;
+    if (!x || !out) return fail(ADDRMS_ERR_INVALID_ARG, "x and out must not be NULL");
+    if (M > (1ll << 31) - 1) return fail(ADDRMS_ERR_INVALID_ARG, "M=%lld exceeds the 2^31-1 row limit", (long long)M);
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    addrms_cfg c{};
+    const int st = resolve_cfg(cfg, M, d, dtype, &c, OP_SILUMUL);
+    if (st != ADDRMS_OK) return st;
+    const Feas f = check_cfg(c, M, d, dtype, OP_SILUMUL);
+    if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+    const int al = c.vec * x_bytes(dtype);
+    if (!aligned(x, al) || !aligned(out, al))
+        return fail(ADDRMS_ERR_MISALIGNED, "x and out must be %d-byte aligned for vec=%d", al, c.vec);
+    return launch_silumul(f, c, x, out, M, d, static_cast<hipStream_t>(stream));
+}
+
+int silumul_default_cfg(int64_t d, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    std::string why;
+    const int st = default_cfg(d, dtype, out, &why, OP_SILUMUL);
+    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
+}
+
+int silumul_cfg_feasible(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, char* reason, size_t reason_len,
+                         addrms_resources* res)
+{
+    if (reason && reason_len) reason[0] = '\0';
+    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
+    const Feas f = check_cfg(*cfg, M, d, dtype, OP_SILUMUL);
+    if (res) *res = f.res;
+    if (f.status != ADDRMS_OK) {
+        if (reason && reason_len) snprintf(reason, reason_len, "%s", f.reason.c_str());
+        return fail(f.status, "%s", f.reason.c_str());
+    }
+    return ADDRMS_OK;
+}
+
+int64_t silumul_enumerate_feasible(int64_t M, int64_t d, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid)
+{
+    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and d > 0");
+    if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
+    std::vector<addrms_cfg> v;
+    enumerate(M, d, dtype, &v, n_grid, nullptr, OP_SILUMUL);
+    const int64_t n = static_cast<int64_t>(v.size());
+    for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
+    return n;
+}
+
+int silumul_tune_with_backend(int64_t M, int64_t d, int dtype, const addrms_budget* budget, const addrms_backend* backend,
+                              addrms_cfg* out_cfg, addrms_tune_report* report)
+{
+    if (!backend) return fail(ADDRMS_ERR_INVALID_ARG, "backend is NULL");
+    return run_search(M, d, dtype, budget, *backend, out_cfg, report, OP_SILUMUL);
+}
+
+int silumul_tune(int64_t M, int64_t d, int dtype, const addrms_budget* budget, addrms_cfg* out_cfg,
+                 addrms_tune_report* report)
+{
+    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
+    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M <= 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs M > 0 and d > 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_cfg dflt{};
+    std::string why;
+    int st = default_cfg(d, dtype, &dflt, &why, OP_SILUMUL);
+    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
+    SiluHarness h;
+    st = h.init(M, d, dtype, true);
+    if (st != ADDRMS_OK) return st;
+    st = h.make_reference(dflt);
+    if (st != ADDRMS_OK) return st;
+    addrms_backend be{&h, silu_backend_validate, silu_backend_measure};
+    addrms_tune_report local{};
+    st = run_search(M, d, dtype, budget, be, out_cfg, &local, OP_SILUMUL);
+    if (st != ADDRMS_OK) return st;
+    if (report) *report = local;
+    return table_insert(M, d, dtype, *out_cfg, local.best_us, OP_SILUMUL);
+}
+
+int silumul_measure(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, int warmup, int reps, int rotate,
+                    double* mean_us)
+{
+    if (!mean_us) return fail(ADDRMS_ERR_INVALID_ARG, "mean_us is NULL");
+    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M <= 0 || d <= 0 || reps <= 0 || warmup < 0) return fail(ADDRMS_ERR_INVALID_ARG, "need M, d, reps > 0 and warmup >= 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    addrms_cfg c{};
+    int st = resolve_cfg(cfg, M, d, dtype, &c, OP_SILUMUL);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    SiluHarness h;
+    st = h.init(M, d, dtype, rotate != 0);
+    if (st != ADDRMS_OK) return st;
+    return h.measure(c, warmup, reps, mean_us);
+}
+
+int silumul_table_lookup(int64_t M, int64_t d, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    const int st = table_lookup(M, d, dtype, out, OP_SILUMUL);
+    return st == ADDRMS_OK ? st : fail(st, "no silu_and_mul table entry usable for M=%lld d=%lld dtype=%d",
+                                       (long long)M, (long long)d, dtype);
+}
+
+int64_t silumul_algorithmic_bytes(int64_t M, int64_t d, int dtype)
+{
+    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and d > 0");
+    return algorithmic_bytes(OP_SILUMUL, M, d, dtype);
 }
 
 }  // extern "C"

@@ -277,11 +277,11 @@ void fill_defaults(addrms_budget* b)
 }  // namespace
 
 int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, const addrms_backend& be,
-               addrms_cfg* out_cfg, addrms_tune_report* report)
+               addrms_cfg* out_cfg, addrms_tune_report* report, int op)
 {
     if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
     if (!be.measure) return fail(ADDRMS_ERR_INVALID_ARG, "backend has no measure function");
-    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (!dtype_valid(dtype, op)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for %s", dtype, op_name(op));
     if (M <= 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs M > 0 and N > 0");
     addrms_budget b{};
     if (budget) b = *budget;
@@ -290,11 +290,11 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     fill_defaults(&b);
 
     Searcher s(M, N, dtype, b, be);
-    s.bytes = static_cast<double>(addrms_algorithmic_bytes(M, N, dtype));
+    s.bytes = static_cast<double>(algorithmic_bytes(op, M, N, dtype));
     std::vector<addrms_cfg> feasible;
     int64_t n_grid = 0;
     std::map<std::string, int64_t> pruned;   // which rule removed how many grid points
-    enumerate(M, N, dtype, &feasible, &n_grid, &pruned);
+    enumerate(M, N, dtype, &feasible, &n_grid, &pruned, op);
     if (b.family_mask != 0) {   // Level-1 rounds restrict the search to the strategy families enabled so far
         std::vector<addrms_cfg> kept;
         for (const addrms_cfg& c : feasible)
@@ -304,12 +304,12 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     }
     addrms_cfg dflt{};
     std::string why;
-    const int dst = default_cfg(N, dtype, &dflt, &why);
+    const int dst = default_cfg(N, dtype, &dflt, &why, op);
     if (dst != ADDRMS_OK || feasible.empty())
         return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty for M=%lld N=%lld %s: %s", (long long)M,
                     (long long)N, dtype_name(dtype), why.c_str());
     // The default is feasible for any M except that a wave-filling row count may exceed a tiny M; keep it anyway.
-    if (check_cfg(dflt, M, N, dtype).status != ADDRMS_OK) {
+    if (check_cfg(dflt, M, N, dtype, op).status != ADDRMS_OK) {
         bool found = false;
         for (const addrms_cfg& c : feasible)
             if (c.vec == dflt.vec && c.threads_per_row == dflt.threads_per_row) { dflt = c; found = true; break; }
@@ -319,7 +319,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     for (const addrms_cfg& c : feasible) {
         Cand cd;
         cd.cfg = c;
-        cd.res = check_cfg(c, M, N, dtype).res;
+        cd.res = check_cfg(c, M, N, dtype, op).res;
         s.index[cfg_key(c)] = static_cast<int>(s.cands.size());
         s.cands.push_back(cd);
     }
@@ -328,9 +328,10 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     if (b.log_path) {
         s.log = fopen(b.log_path, "a");
         if (!s.log) return fail(ADDRMS_ERR_IO, "cannot open log %s", b.log_path);
-        fprintf(s.log, "{\"event\":\"begin\",\"M\":%lld,\"N\":%lld,\"dtype\":\"%s\",\"strategy\":\"%s\",\"n_grid\":%lld,"
+        fprintf(s.log, "{\"event\":\"begin\",\"op\":\"%s\",\"M\":%lld,\"N\":%lld,\"dtype\":\"%s\",\"strategy\":\"%s\",\"n_grid\":%lld,"
                        "\"n_feasible\":%lld,\"default\":%s,\"pruned\":{",
-                (long long)M, (long long)N, dtype_name(dtype), b.strategy == ADDRMS_SEARCH_GUIDED ? "guided" : "exhaustive",
+                op_name(op), (long long)M, (long long)N, dtype_name(dtype),
+                b.strategy == ADDRMS_SEARCH_GUIDED ? "guided" : "exhaustive",
                 (long long)n_grid, (long long)feasible.size(), cfg_json(dflt).c_str());
         bool first = true;
         for (auto& kv : pruned) { fprintf(s.log, "%s\"%s\":%lld", first ? "" : ",", kv.first.c_str(), (long long)kv.second); first = false; }

@@ -14,7 +14,7 @@
 namespace addrms_host {
 
 struct Entry { addrms_cfg cfg; double us; };
-using Key = std::tuple<int, int64_t, int64_t>;   // dtype, N, M
+using Key = std::tuple<int, int, int64_t, int64_t>;   // operator, dtype, N, M
 
 static std::mutex g_mu;
 static std::map<Key, Entry>& table()
@@ -23,21 +23,30 @@ static std::map<Key, Entry>& table()
     return t;
 }
 
-int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out)
+int table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg& cfg, double mean_us, int op)
+{
+    const Feas f = check_cfg(cfg, M, N, dtype, op);
+    if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+    std::lock_guard<std::mutex> lock(g_mu);
+    table()[Key(op, dtype, N, M)] = Entry{cfg, mean_us};
+    return ADDRMS_OK;
+}
+
+int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out, int op)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     auto& t = table();
-    auto it = t.find(Key(dtype, N, M));
+    auto it = t.find(Key(op, dtype, N, M));
     if (it != t.end()) { *out = it->second.cfg; return ADDRMS_OK; }
     // Same (dtype, N): nearest M in ratio whose cfg is still feasible at this M.
     double best = 0.0;
     const Entry* pick = nullptr;
-    for (auto lo = t.lower_bound(Key(dtype, N, INT64_MIN)); lo != t.end(); ++lo) {
-        if (std::get<0>(lo->first) != dtype || std::get<1>(lo->first) != N) break;
-        const double d = fabs(log(static_cast<double>(std::max<int64_t>(std::get<2>(lo->first), 1)) /
+    for (auto lo = t.lower_bound(Key(op, dtype, N, INT64_MIN)); lo != t.end(); ++lo) {
+        if (std::get<0>(lo->first) != op || std::get<1>(lo->first) != dtype || std::get<2>(lo->first) != N) break;
+        const double d = fabs(log(static_cast<double>(std::max<int64_t>(std::get<3>(lo->first), 1)) /
                                   static_cast<double>(std::max<int64_t>(M, 1))));
         if (pick && d >= best) continue;
-        if (check_cfg(lo->second.cfg, M, N, dtype).status != ADDRMS_OK) continue;
+        if (check_cfg(lo->second.cfg, M, N, dtype, op).status != ADDRMS_OK) continue;
         best = d;
         pick = &lo->second;
     }
@@ -46,7 +55,7 @@ int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out)
     return ADDRMS_OK;
 }
 
-static const char kMagic[] = "addrms-table 2 gfx950";
+static const char kMagic[] = "addrms-table 3 gfx950";
 
 }  // namespace addrms_host
 
@@ -57,11 +66,7 @@ extern "C" {
 int addrms_table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, double mean_us)
 {
     if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
-    const Feas f = check_cfg(*cfg, M, N, dtype);
-    if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
-    std::lock_guard<std::mutex> lock(g_mu);
-    table()[Key(dtype, N, M)] = Entry{*cfg, mean_us};
-    return ADDRMS_OK;
+    return table_insert(M, N, dtype, *cfg, mean_us, OP_ADDRMS);
 }
 
 int addrms_table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out)
@@ -90,11 +95,11 @@ int addrms_table_save(const char* path)
     std::lock_guard<std::mutex> lock(g_mu);
     FILE* f = fopen(path, "w");
     if (!f) return fail(ADDRMS_ERR_IO, "cannot open %s for writing", path);
-    fprintf(f, "%s\n# dtype M N vec threads_per_row rows_per_wg reduce unroll flags max_waves_per_simd mean_us\n", kMagic);
+    fprintf(f, "%s\n# operator dtype M N vec threads_per_row rows_per_wg reduce unroll flags max_waves_per_simd mean_us\n", kMagic);
     for (const auto& kv : table()) {
         const addrms_cfg& c = kv.second.cfg;
-        fprintf(f, "%d %lld %lld %d %d %d %d %d %d %d %.6f\n", std::get<0>(kv.first),
-                (long long)std::get<2>(kv.first), (long long)std::get<1>(kv.first), c.vec, c.threads_per_row,
+        fprintf(f, "%d %d %lld %lld %d %d %d %d %d %d %d %.6f\n", std::get<0>(kv.first), std::get<1>(kv.first),
+                (long long)std::get<3>(kv.first), (long long)std::get<2>(kv.first), c.vec, c.threads_per_row,
                 c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd, kv.second.us);
     }
     const bool bad = ferror(f) != 0;
@@ -124,20 +129,20 @@ int addrms_table_load(const char* path)
             continue;
         }
         if (len == 0 || line[0] == '#') continue;
-        int dtype; long long M, N; addrms_cfg c{}; double us; int used = 0;
-        const int got = sscanf(line, "%d %lld %lld %d %d %d %d %d %d %d %lf %n", &dtype, &M, &N, &c.vec,
+        int op, dtype; long long M, N; addrms_cfg c{}; double us; int used = 0;
+        const int got = sscanf(line, "%d %d %lld %lld %d %d %d %d %d %d %d %lf %n", &op, &dtype, &M, &N, &c.vec,
                                &c.threads_per_row, &c.rows_per_wg, &c.reduce, &c.unroll, &c.flags,
                                &c.max_waves_per_simd, &us, &used);
-        if (got != 11 || static_cast<size_t>(used) != len) {
+        if (got != 12 || (op != OP_ADDRMS && op != OP_SILUMUL) || static_cast<size_t>(used) != len) {
             fclose(f);
             return fail(ADDRMS_ERR_IO, "%s:%d: malformed entry", path, lineno);
         }
-        const Feas fe = check_cfg(c, M, N, dtype);
+        const Feas fe = check_cfg(c, M, N, dtype, op);
         if (fe.status != ADDRMS_OK) {
             fclose(f);
             return fail(ADDRMS_ERR_IO, "%s:%d: entry is not feasible: %s", path, lineno, fe.reason.c_str());
         }
-        staged[Key(dtype, N, M)] = Entry{c, us};
+        staged[Key(op, dtype, N, M)] = Entry{c, us};
     }
     fclose(f);
     if (!have_magic) return fail(ADDRMS_ERR_IO, "%s: empty file", path);

@@ -1,9 +1,10 @@
 """Writes the instantiation list of the kernel template.
 
-The template in ``addrms_kernel.h`` has four compile-time knobs (VEC, CPT,
-UNR, NT) per storage format.  This script emits, into a build directory:
+The templates in ``addrms_kernel.h`` and ``silumul_kernel.h`` have four
+compile-time knobs (VEC, CPT, UNR, NT) per storage format.  This script emits,
+into a build directory:
 
-  kern_d<DT>_v<VEC>.hip   one translation unit per (format, vector width),
+  kern_<op>_d<DT>_v<VEC>.hip  one translation unit per (operator, format, vector width),
                           each kernel an ``extern "C"`` wrapper with a readable
                           name so the compiler's resource remarks can be
                           matched back to knob values;
@@ -29,49 +30,64 @@ MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 val
 BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
 
 
+OP_ADDRMS, OP_SILUMUL = 0, 1
+OP_PREFIX = {OP_ADDRMS: "addrms", OP_SILUMUL: "silumul"}
+SILU_DTS = (0, 1, 3)                    # silu_and_mul has no mixed-precision residual stream
+SILU_CPTS = (1, 2, 3, 4, 5, 6, 7, 8)
+
+
 def instances():
-    for dt in DTS:
-        for vec in VECS:
-            if vec * X_BYTES[dt] > 16:           # wider than one global access: never selectable
-                continue
-            for cpt in CPTS:
-                if vec * cpt > MAX_ELEMS:
+    """(op, dt, vec, cpt, unr, nt, maxt) of every compiled kernel, in table order."""
+    for op, dts, cpts in ((OP_ADDRMS, DTS, CPTS), (OP_SILUMUL, SILU_DTS, SILU_CPTS)):
+        for dt in dts:
+            for vec in VECS:
+                if vec * X_BYTES[dt] > 16:           # wider than one global access: never selectable
                     continue
-                for unr in UNRS:
-                    if unr > cpt:
+                for cpt in cpts:
+                    if vec * cpt > MAX_ELEMS:
                         continue
-                    maxt = 1024 if vec * cpt <= BIG_ELEMS else 256
-                    for nt in (0, 1):
-                        yield dt, vec, cpt, unr, nt, maxt
+                    for unr in UNRS:
+                        if unr > cpt:
+                            continue
+                        maxt = 1024 if vec * cpt <= BIG_ELEMS else 256
+                        for nt in (0, 1):
+                            yield op, dt, vec, cpt, unr, nt, maxt
 
 
-def name(dt, vec, cpt, unr, nt):
-    return f"addrms_k_d{dt}_v{vec}_c{cpt}_u{unr}_n{nt}"
+def name(op, dt, vec, cpt, unr, nt):
+    return f"{OP_PREFIX[op]}_k_d{dt}_v{vec}_c{cpt}_u{unr}_n{nt}"
 
 
-ARGS = ("void* x, void* r, const void* w, float eps, double inv_n, "
-        "long long M, int N, unsigned flags, int reduce, unsigned nblocks")
+ARGS = {
+    OP_ADDRMS: ("void* x, void* r, const void* w, float eps, double inv_n, "
+                "long long M, int N, unsigned flags, int reduce, unsigned nblocks"),
+    OP_SILUMUL: "const void* x, void* out, long long M, int d, unsigned flags, unsigned nblocks",
+}
+CALL = {
+    OP_ADDRMS: "addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}, {nt}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);",
+    OP_SILUMUL: "addrms::silumul_body<{dt}, {vec}, {cpt}, {unr}, {nt}>(x, out, M, d, flags, nblocks);",
+}
+HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h"}
 
 
 def main(outdir: str) -> None:
     os.makedirs(outdir, exist_ok=True)
     units = {}
-    for dt, vec, cpt, unr, nt, maxt in instances():
-        units.setdefault((dt, vec), []).append((cpt, unr, nt, maxt))
-    for (dt, vec), lst in units.items():
-        lines = ['#include "addrms_kernel.h"', ""]
+    for op, dt, vec, cpt, unr, nt, maxt in instances():
+        units.setdefault((op, dt, vec), []).append((cpt, unr, nt, maxt))
+    for (op, dt, vec), lst in units.items():
+        lines = [f'#include "{HEADER[op]}"', ""]
         for cpt, unr, nt, maxt in lst:
-            lines.append(
-                f'extern "C" __global__ __launch_bounds__({maxt}) void {name(dt, vec, cpt, unr, nt)}({ARGS})\n'
-                f"{{ addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}, {'true' if nt else 'false'}>"
-                f"(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks); }}")
-        _write(os.path.join(outdir, f"kern_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")
+            call = CALL[op].format(dt=dt, vec=vec, cpt=cpt, unr=unr, nt="true" if nt else "false")
+            lines.append(f'extern "C" __global__ __launch_bounds__({maxt}) void {name(op, dt, vec, cpt, unr, nt)}'
+                         f"({ARGS[op]})\n{{ {call} }}")
+        _write(os.path.join(outdir, f"kern_{OP_PREFIX[op]}_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")
     decl, table, inst = [], [], []
-    for dt, vec, cpt, unr, nt, maxt in instances():
-        n = name(dt, vec, cpt, unr, nt)
-        decl.append(f'extern "C" __global__ void {n}({ARGS});')
-        table.append(f"    {{{dt}, {vec}, {cpt}, {unr}, {nt}, reinterpret_cast<const void*>(&{n})}},")
-        inst.append(f"    {{{dt}, {vec}, {cpt}, {unr}, {nt}, {maxt}}},")
+    for op, dt, vec, cpt, unr, nt, maxt in instances():
+        n = name(op, dt, vec, cpt, unr, nt)
+        decl.append(f'extern "C" __global__ void {n}({ARGS[op]});')
+        table.append(f"    {{{op}, {dt}, {vec}, {cpt}, {unr}, {nt}, reinterpret_cast<const void*>(&{n})}},")
+        inst.append(f"    {{{op}, {dt}, {vec}, {cpt}, {unr}, {nt}, {maxt}}},")
     _write(os.path.join(outdir, "gen_dispatch_decl.inc"), "\n".join(decl) + "\n")
     _write(os.path.join(outdir, "gen_dispatch_rows.inc"), "\n".join(table) + "\n")
     _write(os.path.join(outdir, "gen_instances.inc"), "\n".join(inst) + "\n")

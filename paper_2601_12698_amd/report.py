@@ -67,6 +67,8 @@ def main(argv=None) -> int:
     ap.add_argument("--exhaustive-prefill", action="store_true",
                     help="also run the exhaustive search on the prefill shape and report the guided search's regret")
     ap.add_argument("--table", default=None, help="save the specialised table here")
+    ap.add_argument("--silumul", action="store_true",
+                    help="also tune silu_and_mul (the second kernel behind the same tuner) on three shapes")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
                          "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
@@ -99,6 +101,19 @@ def main(argv=None) -> int:
         print(f"\nprefill: guided {g.as_tuple()} {tg:.2f} us after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
               f"exhaustive {e.as_tuple()} {te:.2f} us after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms; "
               f"regret {tg / te:.4f}")
+    if a.silumul:
+        print("\nsilu_and_mul (out[i,j] = silu(x[i,j]) * x[i,d+j]), tuned vs default:\n")
+        print("| workload | M x d | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|")
+        for wl in (W.SILU_PREFILL, W.SILU_DECODE, W.SILU_FP16):
+            nbytes = B.silumul_algorithmic_bytes(wl.M, wl.d, wl.dtype)
+            t0 = time.perf_counter()
+            cfg, rep = B.silumul_tune(wl.M, wl.d, wl.dtype, B.make_budget())
+            wall = (time.perf_counter() - t0) * 1e3
+            gbps = nbytes / rep.best_us * 1e-3
+            print(f"| {wl.name} | {wl.M} x {wl.d} | {rep.default_us:.2f} | {rep.best_us:.2f} | "
+                  f"{rep.default_us / rep.best_us:.3f} | {gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | {cfg.as_tuple()} | "
+                  f"{rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
     if a.paper_shapes:
         for dtype, shapes in (("bf16", PAPER_MN_16BIT), ("fp16", PAPER_MN_16BIT), ("fp32", PAPER_MN_FP32)):
             g, rep = B.addrms_select_general(shapes, dtype, B.make_budget())

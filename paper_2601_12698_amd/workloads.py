@@ -121,3 +121,34 @@ def to_bits(t: torch.Tensor) -> np.ndarray:
     if t.dtype == torch.float32:
         return t.numpy()
     raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+# ---- silu_and_mul -----------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class GatedWorkload:
+    """Input of the gated activation: x [M, 2d] ~ N(0, x_std), gate half first then up half.
+    d stands in for the feed-forward width of an LLM layer (11008, 13824, 14336, 28672)."""
+    name: str
+    M: int
+    d: int
+    dtype: str
+    seed: int
+    x_std: float = 1.5
+
+
+SILU_PREFILL = GatedWorkload("silu_prefill_4096x11008_bf16", 4096, 11008, "bf16", 11)
+SILU_DECODE = GatedWorkload("silu_decode_64x14336_bf16", 64, 14336, "bf16", 12)
+SILU_FP16 = GatedWorkload("silu_2048x13824_fp16", 2048, 13824, "fp16", 13)
+
+
+def silumul_algorithmic_bytes(M: int, d: int, dtype: str) -> int:
+    """Both halves of x read once, out written once."""
+    return 3 * M * d * x_bytes(dtype)
+
+
+def generate_gated(wl: GatedWorkload) -> torch.Tensor:
+    g = torch.Generator(device="cpu")
+    g.manual_seed(wl.seed)
+    x = torch.randn((wl.M, 2 * wl.d), generator=g, dtype=torch.float32) * wl.x_std
+    return x.to(x_torch_dtype(wl.dtype)).contiguous()

@@ -10,16 +10,18 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "addrms.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(addrms_[a-z_0-9]+)\s*\(", text))
+    names = set()
+    for header in ("addrms.h", "silumul.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b((?:addrms|silumul)_[a-z_0-9]+)\s*\(", text))
     return names
 
 
 def test_header_symbols_are_exported():
     lib = ctypes.CDLL(B.LIB_PATH)
     names = _declared()
-    assert len(names) >= 18
+    assert len(names) >= 30 and any(n.startswith('silumul_') for n in names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in addrms.h but not exported"
 

@@ -1,0 +1,116 @@
+"""silu_and_mul on the device against its oracle (needs an MI355X).
+
+Bar: the oracle rounds the real value once; the kernel computes in fp32 with the hardware
+exponential and reciprocal, a few fp32 ulps from the real value.  So: 16-bit outputs within
+1 unit in the last place, and all but a small fraction identical (a difference needs the
+real value within ~2^-20 relative of a rounding boundary whose cell is 2^-8 or 2^-11 wide);
+fp32 outputs within 2^-18 relative of the fp64 value."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_12698_amd import binding as B
+from paper_2601_12698_amd import workloads as W
+from ulp import ulp_distance
+
+pytestmark = pytest.mark.gpu
+DT = {"bf16": 0, "fp16": 1, "fp32": 3}
+
+
+def _check(oracle, wl, cfgs, ref=None, real=None):
+    x = W.generate_gated(wl)
+    xb = W.to_bits(x)
+    if ref is None:
+        ref = oracle.silumul(xb, DT[wl.dtype], nthreads=16)
+    xd = x.cuda()
+    out = torch.empty((wl.M, wl.d), dtype=x.dtype, device="cuda")
+    worst = 0.0
+    for c in cfgs:
+        out.fill_(float("nan"))
+        B.silumul_run(xd, out, wl.M, wl.d, wl.dtype, c)
+        torch.cuda.synchronize()
+        got = W.to_bits(out)
+        if wl.dtype == "fp32":
+            if real is None:
+                real = oracle.silumul_f64(xb, DT[wl.dtype])
+            err = np.abs(got.astype(np.float64) - real)
+            assert np.all(err <= 2.0 ** -18 * np.abs(real) + 1e-37), (wl.name, c, float(err.max()))
+        else:
+            dist = ulp_distance(got, ref)
+            frac = float((dist > 0).mean())
+            worst = max(worst, frac)
+            assert dist.max() <= 1, (wl.name, c, int(dist.max()))
+            assert frac < 2e-3, (wl.name, c, frac)
+    return worst
+
+
+SMALL = [("bf16", 37, 1024, 1), ("bf16", 5, 11008, 2), ("fp16", 19, 1000, 3), ("fp16", 130, 512, 4),
+         ("fp32", 13, 1536, 5), ("bf16", 70, 3584, 6)]
+
+
+@pytest.mark.parametrize("dtype,M,d,seed", SMALL)
+def test_every_feasible_cfg_small_shapes(oracle, dtype, M, d, seed):
+    wl = W.GatedWorkload(f"s_{M}x{d}_{dtype}", M, d, dtype, seed, x_std=2.0)
+    cfgs, grid = B.silumul_enumerate_feasible(M, d, dtype)
+    assert len(cfgs) > 50
+    cfgs = [c for i, c in enumerate(cfgs) if c.max_waves_per_simd == 0 or i % 3 == 0]
+    worst = _check(oracle, wl, cfgs)
+    print(f"{wl.name}: {len(cfgs)} cfgs, worst differing fraction {worst:.2e}", flush=True)
+
+
+def test_all_cfgs_agree_bit_for_bit():
+    """Every instance performs the same fp32 arithmetic, so outputs are identical across cfgs."""
+    wl = W.GatedWorkload("same", 257, 4096, "bf16", 8)
+    x = W.generate_gated(wl).cuda()
+    out = torch.empty((wl.M, wl.d), dtype=x.dtype, device="cuda")
+    cfgs, _ = B.silumul_enumerate_feasible(wl.M, wl.d, wl.dtype)
+    first = None
+    for c in cfgs[::25]:
+        B.silumul_run(x, out, wl.M, wl.d, wl.dtype, c)
+        torch.cuda.synchronize()
+        bits = W.to_bits(out)
+        first = bits if first is None else first
+        assert np.array_equal(bits, first), str(c)
+
+
+@pytest.mark.parametrize("wl", [W.SILU_PREFILL, W.SILU_DECODE, W.SILU_FP16], ids=lambda w: w.name)
+def test_full_size_default_and_tuned(oracle, wl):
+    B.addrms_table_clear()
+    tuned, rep = B.silumul_tune(wl.M, wl.d, wl.dtype, B.make_budget(max_candidates=60, warmup=5, reps=30))
+    assert rep.n_failed == 0
+    nbytes = B.silumul_algorithmic_bytes(wl.M, wl.d, wl.dtype)
+    print(f"{wl.name}: default {rep.default_us:.2f} us, tuned {tuned} {rep.best_us:.2f} us = "
+          f"{nbytes / rep.best_us * 1e-3:.0f} GB/s", flush=True)
+    assert B.silumul_table_lookup(wl.M, wl.d, wl.dtype).as_tuple() == tuned.as_tuple()
+    _check(oracle, wl, [None, tuned, B.silumul_default_cfg(wl.d, wl.dtype)])
+    B.addrms_table_clear()
+
+
+def test_edge_values_and_errors(oracle):
+    d = 256
+    x = torch.zeros((6, 2 * d), dtype=torch.bfloat16)
+    x[0, :d] = 0.0; x[0, d:] = 3.0                      # gate 0 -> 0
+    x[1, :d] = 5.0; x[1, d:] = 0.0                      # up 0 -> 0
+    x[2, :d] = 60.0; x[2, d:] = -1.5                    # saturated gate passes up through: -90
+    x[3, :d] = -60.0; x[3, d:] = 2.0                    # large negative gate: essentially 0
+    x[4, :d] = torch.linspace(-20, 20, d); x[4, d:] = 1.0
+    x[5, :d] = torch.linspace(-3, 3, d); x[5, d:] = torch.linspace(3, -3, d)
+    xb = W.to_bits(x)
+    ref = oracle.silumul(xb, 0)
+    xd = x.cuda()
+    out = torch.empty((6, d), dtype=torch.bfloat16, device="cuda")
+    B.silumul_run(xd, out, 6, d, "bf16")
+    torch.cuda.synchronize()
+    got = W.to_bits(out)
+    assert ulp_distance(got[:3], ref[:3]).max() == 0
+    assert np.all(out[2].float().cpu().numpy() == -90.0)
+    assert float(out[3].float().abs().max()) < 1e-20
+    assert ulp_distance(got[4:], ref[4:]).max() <= 1
+    lib = B.load()
+    ok = B.make_cfg(8, 32, 2)
+    assert lib.silumul_run(xd.data_ptr() + 2, out.data_ptr(), 6, d, B.BF16, ok, None) == B.ERR_MISALIGNED
+    assert lib.silumul_run(xd.data_ptr(), None, 6, d, B.BF16, ok, None) == B.ERR_INVALID_ARG
+    assert lib.silumul_run(xd.data_ptr(), out.data_ptr(), 6, d, B.FP16_RES32, ok, None) == B.ERR_UNSUPPORTED_DTYPE
+    assert lib.silumul_run(xd.data_ptr(), out.data_ptr(), 0, d, B.BF16, ok, None) == B.OK
+    bad = B.make_cfg(8, 32, 2, reduce=1)
+    assert lib.silumul_run(xd.data_ptr(), out.data_ptr(), 6, d, B.BF16, bad, None) == B.ERR_INFEASIBLE_CFG

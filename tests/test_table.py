@@ -55,12 +55,13 @@ def test_save_load_round_trip(tmp_path):
 
 @pytest.mark.parametrize("content", [
     "",                                                     # empty
-    "not a table\n0 1 8192 8 1024 1 0 1 0 0 3.0\n",         # wrong magic
-    "addrms-table 1 gfx950\n0 1 8192 8 1024 1 0 1 0 3.0\n",  # older format version
-    "addrms-table 2 gfx950\n0 1 8192 8 1024 1 0 1 0\n",      # truncated entry
-    "addrms-table 2 gfx950\n0 1 8192 8 1024 1 0 1 0 0 3.0 junk\n",
-    "addrms-table 2 gfx950\n0 4096 4096 8 1024 1 0 1 0 0 3.0\n",   # parses, but cfg infeasible for that shape
-    "addrms-table 2 gfx950\n7 1 8192 8 1024 1 0 1 0 0 3.0\n",      # bad dtype
+    "not a table\n0 0 1 8192 8 1024 1 0 1 0 0 3.0\n",         # wrong magic
+    "addrms-table 2 gfx950\n0 1 8192 8 1024 1 0 1 0 0 3.0\n",  # older format version
+    "addrms-table 3 gfx950\n0 0 1 8192 8 1024 1 0 1 0\n",      # truncated entry
+    "addrms-table 3 gfx950\n0 0 1 8192 8 1024 1 0 1 0 0 3.0 junk\n",
+    "addrms-table 3 gfx950\n0 0 4096 4096 8 1024 1 0 1 0 0 3.0\n",   # parses, but cfg infeasible for that shape
+    "addrms-table 3 gfx950\n0 7 1 8192 8 1024 1 0 1 0 0 3.0\n",      # bad dtype
+    "addrms-table 3 gfx950\n5 0 1 8192 8 1024 1 0 1 0 0 3.0\n",      # unknown operator
 ])
 def test_corrupt_file_leaves_table_unchanged(tmp_path, content):
     keep = B.make_cfg(8, 1024, 1)
