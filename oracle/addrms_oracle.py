@@ -20,6 +20,7 @@ VARIANTS = {"canonical": 0, "seq32": 1, "pair32": 2}
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "addrms_oracle.c")
 _SRC2 = os.path.join(_HERE, "silumul_oracle.c")
+_SRC3 = os.path.join(_HERE, "mergestates_oracle.c")
 _LIB = os.path.join(_HERE, "libaddrms_oracle.so")
 _lock = threading.Lock()
 _lib = None
@@ -27,12 +28,12 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain -O2, no contraction, no fast-math)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2))
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2), os.path.getmtime(_SRC3))
     if force or stale:
         tmp = _LIB + f".{os.getpid()}.tmp"
         subprocess.run(
             ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
-             "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, "-lm"],
+             "-fPIC", "-shared", "-o", tmp, _SRC, _SRC2, _SRC3, "-lm"],
             check=True)
         os.replace(tmp, _LIB)
     return _LIB
@@ -58,6 +59,8 @@ def _load():
             lib.oracle_f32_to_bf16.restype = ctypes.c_uint16
             lib.oracle_f32_to_f16.argtypes = [ctypes.c_float]
             lib.oracle_f32_to_f16.restype = ctypes.c_uint16
+            lib.oracle_mergestates.argtypes = [vp, vp, vp, vp, i64, i64, ci, vp, vp, vp]
+            lib.oracle_mergestates.restype = ci
             lib.oracle_silumul.argtypes = [vp, i64, i64, ci, vp, ci]
             lib.oracle_silumul.restype = ci
             lib.oracle_silumul_f64.argtypes = [vp, i64, i64, ci, vp]
@@ -147,6 +150,24 @@ def silumul_f64(x, dtype: int) -> np.ndarray:
     if rc != 0:
         raise RuntimeError(f"oracle_silumul_f64 failed with {rc}")
     return out
+
+
+def mergestates(va, sa, vb, sb, dtype: int, want_f64: bool = False):
+    """merge_attn_states oracle.  va, vb: [rows, d] uint16 bit patterns; sa, sb: [rows] float32.
+    Returns (v_out bits, s_out fp32) and, if asked, the unrounded fp64 v_out as a third item."""
+    rows, d = va.shape
+    va = _check(va, np.uint16, (rows, d), "va")
+    vb = _check(vb, np.uint16, (rows, d), "vb")
+    sa = _check(sa, np.float32, (rows,), "sa")
+    sb = _check(sb, np.float32, (rows,), "sb")
+    vout = np.empty((rows, d), dtype=np.uint16)
+    sout = np.empty((rows,), dtype=np.float32)
+    v64 = np.empty((rows, d), dtype=np.float64) if want_f64 else None
+    rc = _load().oracle_mergestates(va.ctypes.data, sa.ctypes.data, vb.ctypes.data, sb.ctypes.data, rows, d, dtype,
+                                    vout.ctypes.data, sout.ctypes.data, v64.ctypes.data if want_f64 else None)
+    if rc != 0:
+        raise RuntimeError(f"oracle_mergestates failed with {rc}")
+    return (vout, sout, v64) if want_f64 else (vout, sout)
 
 
 def rstd_canonical(ss: float, N: int, eps: float) -> np.float32:
