@@ -223,6 +223,17 @@ SIGNATURES = {
     "silumul_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_int, c_int, c_int, POINTER(c_double)]),
     "silumul_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
     "silumul_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
+    "mergestates_run": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int,
+                                POINTER(Cfg), c_void_p]),
+    "mergestates_default_cfg": (c_int, [c_int64, c_int, POINTER(Cfg)]),
+    "mergestates_cfg_feasible": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_char_p, c_size_t, POINTER(Resources)]),
+    "mergestates_enumerate_feasible": (c_int64, [c_int64, c_int64, c_int, POINTER(Cfg), c_int64, POINTER(c_int64)]),
+    "mergestates_tune": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Cfg), POINTER(TuneReport)]),
+    "mergestates_tune_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
+                                              POINTER(Cfg), POINTER(TuneReport)]),
+    "mergestates_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_int, c_int, c_int, POINTER(c_double)]),
+    "mergestates_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
+    "mergestates_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
     "addrms_last_error": (c_char_p, []),
     "addrms_version": (c_char_p, []),
 }
@@ -628,6 +639,93 @@ def silumul_measure(cfg: Optional[Cfg], M: int, d: int, dtype, warmup: int = 20,
 def silumul_table_lookup(M: int, d: int, dtype) -> Optional[Cfg]:
     c = Cfg()
     st = load().silumul_table_lookup(M, d, _dtype_id(dtype), byref(c))
+    if st == ERR_NO_RESULT:
+        return None
+    _check(st)
+    return c
+
+
+# ---- merge_attn_states (include/mergestates.h) ----------------------------------------
+
+def _enumerate(fn_name: str, M: int, N: int, dtype) -> Tuple[List[Cfg], int]:
+    fn = getattr(load(), fn_name)
+    grid = c_int64(0)
+    n = _check(fn(M, N, _dtype_id(dtype), None, 0, byref(grid)))
+    arr = (Cfg * max(n, 1))()
+    _check(fn(M, N, _dtype_id(dtype), arr, n, byref(grid)))
+    out = []
+    for i in range(n):
+        c = Cfg()
+        ctypes.memmove(byref(c), byref(arr[i]), ctypes.sizeof(Cfg))
+        out.append(c)
+    return out, int(grid.value)
+
+
+def mergestates_algorithmic_bytes(rows: int, d: int, dtype) -> int:
+    return _check(load().mergestates_algorithmic_bytes(rows, d, _dtype_id(dtype)))
+
+
+def mergestates_run(v_a, s_a, v_b, s_b, v_out, s_out, rows: int, d: int, dtype, cfg: Optional[Cfg] = None,
+                    stream=None) -> None:
+    """Merge two partial attention states; v tensors [rows, d], scores fp32 [rows], all on the device."""
+    for name, t, n in (("v_a", v_a, rows * d), ("v_b", v_b, rows * d), ("v_out", v_out, rows * d),
+                       ("s_a", s_a, rows), ("s_b", s_b, rows), ("s_out", s_out, rows)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous device tensor")
+        if t.numel() != n:
+            raise ValueError(f"{name} has {t.numel()} elements, expected {n}")
+    _check(load().mergestates_run(_ptr(v_a), _ptr(s_a), _ptr(v_b), _ptr(s_b), _ptr(v_out), _ptr(s_out), rows, d,
+                                  _dtype_id(dtype), byref(cfg) if cfg is not None else None, _stream_ptr(stream, v_a)))
+
+
+def mergestates_default_cfg(d: int, dtype) -> Cfg:
+    c = Cfg()
+    _check(load().mergestates_default_cfg(d, _dtype_id(dtype), byref(c)))
+    return c
+
+
+def mergestates_cfg_feasible(cfg: Cfg, rows: int, d: int, dtype) -> Tuple[int, str, Resources]:
+    buf = ctypes.create_string_buffer(512)
+    res = Resources()
+    st = load().mergestates_cfg_feasible(byref(cfg), rows, d, _dtype_id(dtype), buf, len(buf), byref(res))
+    return int(st), buf.value.decode("utf-8", "replace"), res
+
+
+def mergestates_enumerate_feasible(rows: int, d: int, dtype) -> Tuple[List[Cfg], int]:
+    return _enumerate("mergestates_enumerate_feasible", rows, d, dtype)
+
+
+def mergestates_tune(rows: int, d: int, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, TuneReport]:
+    c, rep = Cfg(), TuneReport()
+    _check(load().mergestates_tune(rows, d, _dtype_id(dtype), byref(budget) if budget is not None else None,
+                                   byref(c), byref(rep)))
+    return c, rep
+
+
+def mergestates_tune_with_backend(rows: int, d: int, dtype, budget: Optional[Budget], measure, validate=None
+                                  ) -> Tuple[Cfg, TuneReport]:
+    be = Backend()
+    be.user = None
+    be.measure = _wrap_measure(measure)
+    be.validate = _wrap_validate(validate)
+    c, rep = Cfg(), TuneReport()
+    _check(load().mergestates_tune_with_backend(rows, d, _dtype_id(dtype),
+                                                byref(budget) if budget is not None else None, byref(be),
+                                                byref(c), byref(rep)))
+    return c, rep
+
+
+def mergestates_measure(cfg: Optional[Cfg], rows: int, d: int, dtype, warmup: int = 20, reps: int = 100,
+                        rotate: bool = True) -> float:
+    us = c_double(0.0)
+    _check(load().mergestates_measure(byref(cfg) if cfg is not None else None, rows, d, _dtype_id(dtype), warmup, reps,
+                                      int(rotate), byref(us)))
+    return float(us.value)
+
+
+def mergestates_table_lookup(rows: int, d: int, dtype) -> Optional[Cfg]:
+    c = Cfg()
+    st = load().mergestates_table_lookup(rows, d, _dtype_id(dtype), byref(c))
     if st == ERR_NO_RESULT:
         return None
     _check(st)

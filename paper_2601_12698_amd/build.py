@@ -77,7 +77,8 @@ def _compile_kernel_unit(src: str, force: bool) -> str:
     obj = src[:-4] + ".o"
     rem = src[:-4] + ".remarks"
     if (not force and os.path.exists(rem) and
-            _newer(obj, src, os.path.join(CSRC, "addrms_kernel.h"), os.path.join(CSRC, "silumul_kernel.h"))):
+            _newer(obj, src, os.path.join(CSRC, "addrms_kernel.h"), os.path.join(CSRC, "silumul_kernel.h"),
+                   os.path.join(CSRC, "mergestates_kernel.h"))):
         return open(rem).read()
     r = _run(["hipcc", *DEVICE_FLAGS, *INCLUDES, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj])
     with open(rem, "w") as f:
@@ -112,7 +113,7 @@ def build(force: bool = False, jobs: int = 8, verbose: bool = False) -> str:
     gen_kernels._write(os.path.join(BUILD, "gen_resources.inc"), "\n".join(rows) + "\n")
 
     objs = [u[:-4] + ".o" for u in units]
-    hdrs = [os.path.join(ROOT, "include", "addrms.h"), os.path.join(ROOT, "include", "silumul.h"),
+    hdrs = [os.path.join(ROOT, "include", "addrms.h"), os.path.join(ROOT, "include", "silumul.h"), os.path.join(ROOT, "include", "mergestates.h"),
             os.path.join(CSRC, "addrms_internal.h")]
     gen = [os.path.join(BUILD, f) for f in ("gen_instances.inc", "gen_resources.inc",
                                              "gen_dispatch_decl.inc", "gen_dispatch_rows.inc")]
@@ -125,7 +126,7 @@ def build(force: bool = False, jobs: int = 8, verbose: bool = False) -> str:
     src = os.path.join(CSRC, "addrms_runtime.hip")
     obj = os.path.join(BUILD, "addrms_runtime.o")
     if force or not _newer(obj, src, os.path.join(CSRC, "addrms_kernel.h"), os.path.join(CSRC, "silumul_kernel.h"),
-                           *hdrs, *gen):
+                           os.path.join(CSRC, "mergestates_kernel.h"), *hdrs, *gen):
         _run(["hipcc", *DEVICE_FLAGS, *INCLUDES, "-c", src, "-o", obj])
     objs.append(obj)
     tmp = LIB + f".{os.getpid()}.tmp"

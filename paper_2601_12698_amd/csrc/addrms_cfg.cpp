@@ -56,7 +56,10 @@ int n_instances() { return static_cast<int>(sizeof(kInstances) / sizeof(kInstanc
 const Instance& instance(int idx) { return kInstances[idx]; }
 const InstanceRes& instance_res(int idx) { return kInstanceRes[idx]; }
 
-const char* op_name(int op) { return op == OP_SILUMUL ? "silu_and_mul" : "add_rmsnorm"; }
+const char* op_name(int op)
+{
+    return op == OP_SILUMUL ? "silu_and_mul" : op == OP_MERGE ? "merge_attn_states" : "add_rmsnorm";
+}
 
 static uint32_t inst_key(int op, int dt, int vec, int cpt, int unr, int nt)
 {
@@ -87,12 +90,14 @@ bool cpt_supported(int op, int cpt)
 bool dtype_valid(int dtype, int op)
 {
     if (dtype < ADDRMS_BF16 || dtype > ADDRMS_FP32) return false;
+    if (op == OP_MERGE) return dtype == ADDRMS_BF16 || dtype == ADDRMS_FP16;   // 16-bit partial outputs
     return op == OP_ADDRMS || dtype != ADDRMS_FP16_RES32;     // only add+RMSNorm has a separate residual stream
 }
 
 int64_t algorithmic_bytes(int op, int64_t M, int64_t N, int dtype)
 {
     if (op == OP_SILUMUL) return M * N * 3 * x_bytes(dtype);                   // read gate and up, write out
+    if (op == OP_MERGE) return M * (N * 3 * x_bytes(dtype) + 12);              // two parts in, one out, three fp32 scores
     return M * N * (2 * x_bytes(dtype) + 2 * r_bytes(dtype)) + N * x_bytes(dtype);
 }
 int x_bytes(int dtype) { return dtype == ADDRMS_FP32 ? 4 : 2; }
@@ -221,7 +226,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op)
     if (!dtype_valid(dtype, op)) {
         f.status = ADDRMS_ERR_UNSUPPORTED_DTYPE;
         f.reason = op == OP_ADDRMS ? "dtype is not one of bf16, fp16, fp16_res32, fp32"
-                                   : "dtype is not one of bf16, fp16, fp32";
+                   : op == OP_MERGE ? "dtype is not one of bf16, fp16" : "dtype is not one of bf16, fp16, fp32";
         return f;
     }
     if (M < 0 || N <= 0) {
@@ -275,7 +280,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op)
                           kMinWavesPerSimd);
     if (!cpt_supported(op, static_cast<int>(need)))
         return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (%s)", (long long)need,
-                          op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : "1-8 exist");
+                          op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : op == OP_MERGE ? "1-4 exist" : "1-8 exist");
     f.res.chunks_per_thread = static_cast<int>(need);
     const double util = static_cast<double>(N) / static_cast<double>(per_pass * need);
     if (util <= 0.5)

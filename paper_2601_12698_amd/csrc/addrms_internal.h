@@ -39,7 +39,8 @@ constexpr int kMinWavesPerSimd = 2;
 constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
 
 // ---- operators that go through the tuner ------------------------------------
-enum Op : int { OP_ADDRMS = 0, OP_SILUMUL = 1 };
+enum Op : int { OP_ADDRMS = 0, OP_SILUMUL = 1, OP_MERGE = 2 };
+constexpr int kNumOps = 3;
 const char* op_name(int op);
 
 // ---- kernel instances ------------------------------------------------------

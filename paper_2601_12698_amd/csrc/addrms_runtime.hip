@@ -11,6 +11,8 @@
 #include <vector>
 
 #include "addrms_internal.h"
+#include "mergestates.h"
+#include "mergestates_kernel.h"
 #include "silumul.h"
 #include "silumul_kernel.h"
 
@@ -92,6 +94,17 @@ int launch_silumul(const Feas& f, const addrms_cfg& c, const void* x, void* out,
     unsigned nblocks = static_cast<unsigned>(n_row_blocks(c, M));
     void* args[] = {&x, &out, &m, &dd, &flags, &nblocks};
     return launch_instance(f, c, M, OP_SILUMUL, args, stream);
+}
+
+int launch_mergestates(const Feas& f, const addrms_cfg& c, const void* va, const float* sa, const void* vb,
+                       const float* sb, void* vo, float* so, int64_t rows, int64_t d, hipStream_t stream)
+{
+    long long m = rows;
+    int dd = static_cast<int>(d);
+    unsigned flags = static_cast<unsigned>(c.flags);
+    unsigned nblocks = static_cast<unsigned>(n_row_blocks(c, rows));
+    void* args[] = {&va, &sa, &vb, &sb, &vo, &so, &m, &dd, &flags, &nblocks};
+    return launch_instance(f, c, rows, OP_MERGE, args, stream);
 }
 
 int resolve_cfg(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, addrms_cfg* out, int op = OP_ADDRMS)
@@ -486,6 +499,134 @@ struct SiluHarness {
         return ADDRMS_OK;
     }
 };
+// ---- measurement harness of merge_attn_states: rotating (v_a, v_b, s_a, s_b, v_out, s_out)
+// sets plus a reference output; out of place, nothing to restore.
+struct MergeHarness {
+    int64_t rows = 0, d = 0;
+    int dtype = 0;
+    int nsets = 0;
+    size_t vbytes = 0, sbytes = 0;
+    char* pool = nullptr;
+    char* vref = nullptr;
+    float* sref = nullptr;
+    struct Set { char *va, *vb, *vo; float *sa, *sb, *so; };
+    std::vector<Set> sets;
+    unsigned* counts = nullptr;
+    hipStream_t stream = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+
+    static size_t pad(size_t b) { return (b + 65535) / 65536 * 65536 + 65536; }
+
+    int init(int64_t r, int64_t dd, int dt, bool rotate)
+    {
+        rows = r; d = dd; dtype = dt;
+        vbytes = static_cast<size_t>(rows) * d * x_bytes(dt);
+        sbytes = static_cast<size_t>(rows) * 4;
+        const size_t set = 3 * pad(vbytes) + 3 * pad(sbytes);
+        const size_t want = 2 * (static_cast<size_t>(hw().last_level_cache_bytes) +
+                                 static_cast<size_t>(hw().l2_bytes_per_xcd) * hw().xcds);
+        nsets = rotate ? static_cast<int>(std::min<size_t>(32, std::max<size_t>(2, (want + set - 1) / set))) : 1;
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), set * nsets + pad(vbytes) + pad(sbytes) + pad(256)));
+        char* p = pool;
+        auto take = [&](size_t b, size_t skew) { char* q = p + skew; p += pad(b); return q; };
+        vref = take(vbytes, 0);
+        sref = reinterpret_cast<float*>(take(sbytes, 0));
+        counts = reinterpret_cast<unsigned*>(take(256, 0));
+        for (int i = 0; i < nsets; ++i) {
+            Set s;
+            s.va = take(vbytes, 0); s.vb = take(vbytes, 4096); s.vo = take(vbytes, 8192);
+            s.sa = reinterpret_cast<float*>(take(sbytes, 0)); s.sb = reinterpret_cast<float*>(take(sbytes, 0));
+            s.so = reinterpret_cast<float*>(take(sbytes, 0));
+            sets.push_back(s);
+        }
+        HIP_TRY(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
+        HIP_TRY(hipEventCreate(&ev0));
+        HIP_TRY(hipEventCreate(&ev1));
+        const bool bf = dt == ADDRMS_BF16;
+        int st = fill(sets[0].va, rows * d, x_bytes(dt), bf, 0x1357911u, 0, 0, true, stream);
+        if (st == ADDRMS_OK) st = fill(sets[0].vb, rows * d, x_bytes(dt), bf, 0x2468acfu, 0, 0, true, stream);
+        if (st == ADDRMS_OK) st = fill(sets[0].sa, rows, 4, false, 0x0badcafu, -4.0f, 4.0f, false, stream);
+        if (st == ADDRMS_OK) st = fill(sets[0].sb, rows, 4, false, 0x0defaceu, -4.0f, 4.0f, false, stream);
+        if (st != ADDRMS_OK) return st;
+        for (int i = 1; i < nsets; ++i) {
+            HIP_TRY(hipMemcpyAsync(sets[i].va, sets[0].va, vbytes, hipMemcpyDeviceToDevice, stream));
+            HIP_TRY(hipMemcpyAsync(sets[i].vb, sets[0].vb, vbytes, hipMemcpyDeviceToDevice, stream));
+            HIP_TRY(hipMemcpyAsync(sets[i].sa, sets[0].sa, sbytes, hipMemcpyDeviceToDevice, stream));
+            HIP_TRY(hipMemcpyAsync(sets[i].sb, sets[0].sb, sbytes, hipMemcpyDeviceToDevice, stream));
+        }
+        HIP_TRY(hipStreamSynchronize(stream));
+        return ADDRMS_OK;
+    }
+    ~MergeHarness()
+    {
+        if (ev0) (void)hipEventDestroy(ev0);
+        if (ev1) (void)hipEventDestroy(ev1);
+        if (stream) (void)hipStreamDestroy(stream);
+        if (pool) (void)hipFree(pool);
+    }
+    int run_set(const Feas& f, const addrms_cfg& c, const Set& s, char* vo, float* so)
+    {
+        return launch_mergestates(f, c, s.va, s.sa, s.vb, s.sb, vo, so, rows, d, stream);
+    }
+    int make_reference(const addrms_cfg& c)
+    {
+        const Feas f = check_cfg(c, rows, d, dtype, OP_MERGE);
+        if (f.status != ADDRMS_OK) return fail(f.status, "reference cfg infeasible: %s", f.reason.c_str());
+        const int st = run_set(f, c, sets[0], vref, sref);
+        if (st != ADDRMS_OK) return st;
+        HIP_TRY(hipStreamSynchronize(stream));
+        return ADDRMS_OK;
+    }
+    int validate(const addrms_cfg& c)
+    {
+        const Feas f = check_cfg(c, rows, d, dtype, OP_MERGE);
+        if (f.status != ADDRMS_OK) return f.status;
+        HIP_TRY(hipMemsetAsync(sets[0].vo, 0xff, vbytes, stream));
+        HIP_TRY(hipMemsetAsync(sets[0].so, 0xff, sbytes, stream));
+        const int st = run_set(f, c, sets[0], sets[0].vo, sets[0].so);
+        if (st != ADDRMS_OK) return st;
+        HIP_TRY(hipMemsetAsync(counts, 0, 16, stream));
+        const long long n = static_cast<long long>(rows) * d;
+        const dim3 block(256);
+        // merged outputs within 1 ulp of the reference; merged scores bit-identical
+        hipLaunchKernelGGL((compare_kernel<2, 2>), dim3(static_cast<unsigned>((n + 255) / 256)), block, 0, stream,
+                           sets[0].vo, vref, vref, vref, n, 1u, counts);
+        hipLaunchKernelGGL((compare_kernel<4, 4>), dim3(static_cast<unsigned>((rows + 255) / 256)), block, 0, stream,
+                           sets[0].so, sref, sref, sref, static_cast<long long>(rows), 0u, counts);
+        HIP_TRY(hipGetLastError());
+        unsigned h[4] = {0, 0, 0, 0};
+        HIP_TRY(hipMemcpyAsync(h, counts, 16, hipMemcpyDeviceToHost, stream));
+        HIP_TRY(hipStreamSynchronize(stream));
+        if (h[1] != 0)
+            return fail(ADDRMS_ERR_INFEASIBLE_CFG, "candidate %s disagrees with the reference on %u values (max "
+                        "distance %u)", cfg_json(c).c_str(), h[1], h[2]);
+        return ADDRMS_OK;
+    }
+    int measure(const addrms_cfg& c, int warmup, int reps, double* mean_us)
+    {
+        const Feas f = check_cfg(c, rows, d, dtype, OP_MERGE);
+        if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+        int set = 0;
+        for (int i = 0; i < warmup + reps; ++i) {
+            if (i == warmup) HIP_TRY(hipEventRecord(ev0, stream));
+            const int st = run_set(f, c, sets[set], sets[set].vo, sets[set].so);
+            if (st != ADDRMS_OK) return st;
+            set = (set + 1) % nsets;
+        }
+        HIP_TRY(hipEventRecord(ev1, stream));
+        HIP_TRY(hipEventSynchronize(ev1));
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, ev0, ev1));
+        *mean_us = static_cast<double>(ms) * 1000.0 / reps;
+        return ADDRMS_OK;
+    }
+};
+int merge_backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<MergeHarness*>(user)->validate(*cfg); }
+int merge_backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
+{
+    return static_cast<MergeHarness*>(user)->measure(*cfg, warmup, reps, us);
+}
+
 int silu_backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<SiluHarness*>(user)->validate(*cfg); }
 int silu_backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
 {
@@ -798,6 +939,127 @@ int64_t silumul_algorithmic_bytes(int64_t M, int64_t d, int dtype)
     if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
     if (M < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and d > 0");
     return algorithmic_bytes(OP_SILUMUL, M, d, dtype);
+}
+
+// ---- merge_attn_states -----------------------------------------------------------------
+
+int mergestates_run(const void* v_a, const float* s_a, const void* v_b, const float* s_b, void* v_out, float* s_out,
+                    int64_t rows, int64_t d, int dtype, const addrms_cfg* cfg, void* stream)
+{
+    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for merge_attn_states", dtype);
+    if (rows < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "rows must be >= 0 and d > 0 (got rows=%lld d=%lld)",
+                                        (long long)rows, (long long)d);
+    if (rows == 0) return ADDRMS_OK;
+    if (!v_a || !s_a || !v_b || !s_b || !v_out || !s_out) return fail(ADDRMS_ERR_INVALID_ARG, "no pointer may be NULL");
+    if (rows > (1ll << 31) - 1) return fail(ADDRMS_ERR_INVALID_ARG, "rows=%lld exceeds the 2^31-1 limit", (long long)rows);
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    addrms_cfg c{};
+    const int st = resolve_cfg(cfg, rows, d, dtype, &c, OP_MERGE);
+    if (st != ADDRMS_OK) return st;
+    const Feas f = check_cfg(c, rows, d, dtype, OP_MERGE);
+    if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
+    const int al = c.vec * x_bytes(dtype);
+    if (!aligned(v_a, al) || !aligned(v_b, al) || !aligned(v_out, al) || !aligned(s_a, 4) || !aligned(s_b, 4) || !aligned(s_out, 4))
+        return fail(ADDRMS_ERR_MISALIGNED, "v_a, v_b and v_out must be %d-byte aligned for vec=%d, scores 4-byte aligned", al, c.vec);
+    return launch_mergestates(f, c, v_a, s_a, v_b, s_b, v_out, s_out, rows, d, static_cast<hipStream_t>(stream));
+}
+
+int mergestates_default_cfg(int64_t d, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    std::string why;
+    const int st = default_cfg(d, dtype, out, &why, OP_MERGE);
+    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
+}
+
+int mergestates_cfg_feasible(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, char* reason, size_t reason_len,
+                             addrms_resources* res)
+{
+    if (reason && reason_len) reason[0] = '\0';
+    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
+    const Feas f = check_cfg(*cfg, rows, d, dtype, OP_MERGE);
+    if (res) *res = f.res;
+    if (f.status != ADDRMS_OK) {
+        if (reason && reason_len) snprintf(reason, reason_len, "%s", f.reason.c_str());
+        return fail(f.status, "%s", f.reason.c_str());
+    }
+    return ADDRMS_OK;
+}
+
+int64_t mergestates_enumerate_feasible(int64_t rows, int64_t d, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid)
+{
+    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (rows < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "rows must be >= 0 and d > 0");
+    if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
+    std::vector<addrms_cfg> v;
+    enumerate(rows, d, dtype, &v, n_grid, nullptr, OP_MERGE);
+    const int64_t n = static_cast<int64_t>(v.size());
+    for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
+    return n;
+}
+
+int mergestates_tune_with_backend(int64_t rows, int64_t d, int dtype, const addrms_budget* budget,
+                                  const addrms_backend* backend, addrms_cfg* out_cfg, addrms_tune_report* report)
+{
+    if (!backend) return fail(ADDRMS_ERR_INVALID_ARG, "backend is NULL");
+    return run_search(rows, d, dtype, budget, *backend, out_cfg, report, OP_MERGE);
+}
+
+int mergestates_tune(int64_t rows, int64_t d, int dtype, const addrms_budget* budget, addrms_cfg* out_cfg,
+                     addrms_tune_report* report)
+{
+    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
+    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (rows <= 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs rows > 0 and d > 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_cfg dflt{};
+    std::string why;
+    int st = default_cfg(d, dtype, &dflt, &why, OP_MERGE);
+    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
+    MergeHarness h;
+    st = h.init(rows, d, dtype, true);
+    if (st != ADDRMS_OK) return st;
+    st = h.make_reference(dflt);
+    if (st != ADDRMS_OK) return st;
+    addrms_backend be{&h, merge_backend_validate, merge_backend_measure};
+    addrms_tune_report local{};
+    st = run_search(rows, d, dtype, budget, be, out_cfg, &local, OP_MERGE);
+    if (st != ADDRMS_OK) return st;
+    if (report) *report = local;
+    return table_insert(rows, d, dtype, *out_cfg, local.best_us, OP_MERGE);
+}
+
+int mergestates_measure(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, int warmup, int reps, int rotate,
+                        double* mean_us)
+{
+    if (!mean_us) return fail(ADDRMS_ERR_INVALID_ARG, "mean_us is NULL");
+    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (rows <= 0 || d <= 0 || reps <= 0 || warmup < 0) return fail(ADDRMS_ERR_INVALID_ARG, "need rows, d, reps > 0 and warmup >= 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    addrms_cfg c{};
+    int st = resolve_cfg(cfg, rows, d, dtype, &c, OP_MERGE);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    MergeHarness h;
+    st = h.init(rows, d, dtype, rotate != 0);
+    if (st != ADDRMS_OK) return st;
+    return h.measure(c, warmup, reps, mean_us);
+}
+
+int mergestates_table_lookup(int64_t rows, int64_t d, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    const int st = table_lookup(rows, d, dtype, out, OP_MERGE);
+    return st == ADDRMS_OK ? st : fail(st, "no merge_attn_states table entry usable for rows=%lld d=%lld dtype=%d",
+                                       (long long)rows, (long long)d, dtype);
+}
+
+int64_t mergestates_algorithmic_bytes(int64_t rows, int64_t d, int dtype)
+{
+    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (rows < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "rows must be >= 0 and d > 0");
+    return algorithmic_bytes(OP_MERGE, rows, d, dtype);
 }
 
 }  // extern "C"

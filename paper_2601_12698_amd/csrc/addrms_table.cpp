@@ -133,7 +133,7 @@ int addrms_table_load(const char* path)
         const int got = sscanf(line, "%d %d %lld %lld %d %d %d %d %d %d %d %lf %n", &op, &dtype, &M, &N, &c.vec,
                                &c.threads_per_row, &c.rows_per_wg, &c.reduce, &c.unroll, &c.flags,
                                &c.max_waves_per_simd, &us, &used);
-        if (got != 12 || (op != OP_ADDRMS && op != OP_SILUMUL) || static_cast<size_t>(used) != len) {
+        if (got != 12 || op < 0 || op >= kNumOps || static_cast<size_t>(used) != len) {
             fclose(f);
             return fail(ADDRMS_ERR_IO, "%s:%d: malformed entry", path, lineno);
         }

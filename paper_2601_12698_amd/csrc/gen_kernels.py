@@ -30,15 +30,18 @@ MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 val
 BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
 
 
-OP_ADDRMS, OP_SILUMUL = 0, 1
-OP_PREFIX = {OP_ADDRMS: "addrms", OP_SILUMUL: "silumul"}
+OP_ADDRMS, OP_SILUMUL, OP_MERGE = 0, 1, 2
+OP_PREFIX = {OP_ADDRMS: "addrms", OP_SILUMUL: "silumul", OP_MERGE: "mergestates"}
+MERGE_DTS = (0, 1)                      # merge_attn_states: 16-bit partial outputs, fp32 scores
+MERGE_CPTS = (1, 2, 3, 4)               # head sizes are small: a row is a few chunks at most
 SILU_DTS = (0, 1, 3)                    # silu_and_mul has no mixed-precision residual stream
 SILU_CPTS = (1, 2, 3, 4, 5, 6, 7, 8)
 
 
 def instances():
     """(op, dt, vec, cpt, unr, nt, maxt) of every compiled kernel, in table order."""
-    for op, dts, cpts in ((OP_ADDRMS, DTS, CPTS), (OP_SILUMUL, SILU_DTS, SILU_CPTS)):
+    for op, dts, cpts in ((OP_ADDRMS, DTS, CPTS), (OP_SILUMUL, SILU_DTS, SILU_CPTS),
+                          (OP_MERGE, MERGE_DTS, MERGE_CPTS)):
         for dt in dts:
             for vec in VECS:
                 if vec * X_BYTES[dt] > 16:           # wider than one global access: never selectable
@@ -62,12 +65,16 @@ ARGS = {
     OP_ADDRMS: ("void* x, void* r, const void* w, float eps, double inv_n, "
                 "long long M, int N, unsigned flags, int reduce, unsigned nblocks"),
     OP_SILUMUL: "const void* x, void* out, long long M, int d, unsigned flags, unsigned nblocks",
+    OP_MERGE: ("const void* va, const float* sa, const void* vb, const float* sb, void* vo, float* so, "
+               "long long rows, int d, unsigned flags, unsigned nblocks"),
 }
 CALL = {
     OP_ADDRMS: "addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}, {nt}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);",
     OP_SILUMUL: "addrms::silumul_body<{dt}, {vec}, {cpt}, {unr}, {nt}>(x, out, M, d, flags, nblocks);",
+    OP_MERGE: ("addrms::mergestates_body<{dt}, {vec}, {cpt}, {unr}, {nt}>"
+               "(va, sa, vb, sb, vo, so, rows, d, flags, nblocks);"),
 }
-HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h"}
+HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h", OP_MERGE: "mergestates_kernel.h"}
 
 
 def main(outdir: str) -> None:

@@ -69,6 +69,8 @@ def main(argv=None) -> int:
     ap.add_argument("--table", default=None, help="save the specialised table here")
     ap.add_argument("--silumul", action="store_true",
                     help="also tune silu_and_mul (the second kernel behind the same tuner) on three shapes")
+    ap.add_argument("--mergestates", action="store_true",
+                    help="also tune merge_attn_states (third kernel) on the (n, h, d) shapes of the paper's evaluation")
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
                          "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
@@ -114,6 +116,20 @@ def main(argv=None) -> int:
             print(f"| {wl.name} | {wl.M} x {wl.d} | {rep.default_us:.2f} | {rep.best_us:.2f} | "
                   f"{rep.default_us / rep.best_us:.3f} | {gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | {cfg.as_tuple()} | "
                   f"{rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
+    if a.mergestates:
+        print("\nmerge_attn_states (log-sum-exp merge of two partial attention states), tuned vs default:\n")
+        print("| n x h x d | dtype | default us | tuned us | speedup | tuned GB/s | tuned cfg | feasible | timed | search ms |")
+        print("|---|---|---|---|---|---|---|---|---|---|")
+        for dtype in ("bf16", "fp16"):
+            for n, h, d in W.MERGE_SHAPES:
+                rows = n * h
+                nbytes = B.mergestates_algorithmic_bytes(rows, d, dtype)
+                t0 = time.perf_counter()
+                cfg, rep = B.mergestates_tune(rows, d, dtype, B.make_budget())
+                wall = (time.perf_counter() - t0) * 1e3
+                print(f"| {n} x {h} x {d} | {dtype} | {rep.default_us:.2f} | {rep.best_us:.2f} | "
+                      f"{rep.default_us / rep.best_us:.3f} | {nbytes / rep.best_us * 1e-3:.0f} | {cfg.as_tuple()} | "
+                      f"{rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
     if a.paper_shapes:
         for dtype, shapes in (("bf16", PAPER_MN_16BIT), ("fp16", PAPER_MN_16BIT), ("fp32", PAPER_MN_FP32)):
             g, rep = B.addrms_select_general(shapes, dtype, B.make_budget())

@@ -152,3 +152,44 @@ def generate_gated(wl: GatedWorkload) -> torch.Tensor:
     g.manual_seed(wl.seed)
     x = torch.randn((wl.M, 2 * wl.d), generator=g, dtype=torch.float32) * wl.x_std
     return x.to(x_torch_dtype(wl.dtype)).contiguous()
+
+
+# ---- merge_attn_states --------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class MergeWorkload:
+    """Two partial attention states to merge: v_a, v_b [n*h, d] ~ N(0, 1) in storage dtype and
+    their log-sum-exp scores s_a, s_b [n*h] ~ N(0, s_std) in fp32.  (n, h, d) stands for
+    tokens x heads x head size; the tuples below are of the kind the paper lists for its
+    3-D shaped kernel (Section 4, Kernels)."""
+    name: str
+    n: int
+    h: int
+    d: int
+    dtype: str
+    seed: int
+    s_std: float = 3.0
+
+    @property
+    def rows(self) -> int:
+        return self.n * self.h
+
+
+MERGE_SHAPES = ((512, 32, 256), (512, 40, 128), (768, 32, 256), (768, 40, 128), (512, 64, 128))
+MERGE_MAIN = MergeWorkload("merge_512x32x256_bf16", 512, 32, 256, "bf16", 21)
+
+
+def merge_algorithmic_bytes(rows: int, d: int, dtype: str) -> int:
+    return rows * (3 * d * x_bytes(dtype) + 12)
+
+
+def generate_merge(wl: MergeWorkload) -> Dict[str, torch.Tensor]:
+    g = torch.Generator(device="cpu")
+    g.manual_seed(wl.seed)
+    shape = (wl.rows, wl.d)
+    va = torch.randn(shape, generator=g, dtype=torch.float32)
+    vb = torch.randn(shape, generator=g, dtype=torch.float32)
+    sa = torch.randn((wl.rows,), generator=g, dtype=torch.float32) * wl.s_std
+    sb = torch.randn((wl.rows,), generator=g, dtype=torch.float32) * wl.s_std
+    dt = x_torch_dtype(wl.dtype)
+    return {"va": va.to(dt).contiguous(), "vb": vb.to(dt).contiguous(), "sa": sa.contiguous(), "sb": sb.contiguous()}

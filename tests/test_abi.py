@@ -11,10 +11,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared():
     names = set()
-    for header in ("addrms.h", "silumul.h"):
+    for header in ("addrms.h", "silumul.h", "mergestates.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b((?:addrms|silumul)_[a-z_0-9]+)\s*\(", text))
+        names |= set(re.findall(r"\b((?:addrms|silumul|mergestates)_[a-z_0-9]+)\s*\(", text))
     return names
 
 

@@ -1,0 +1,99 @@
+"""merge_attn_states on the device against its oracle (needs an MI355X).
+
+Bar: v_out within 1 unit in the last place of its 16-bit format, all but a small fraction
+identical (the kernel is a few fp32 ulps from the real value the oracle rounds) -- except
+where the two weighted terms cancel: the sum of two fp32 terms of opposite sign carries an
+absolute error of a few 2^-24 of the larger term whatever the size of the result, so there
+the bound is absolute, 2^-20 * max(|v_a|, |v_b|) (the weights are at most 1);
+s_out within 4 fp32 ulps plus 2e-7 absolute (hardware log2 on a value in [1, 2])."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_12698_amd import binding as B
+from paper_2601_12698_amd import workloads as W
+from ulp import ulp_distance
+
+pytestmark = pytest.mark.gpu
+DT = {"bf16": 0, "fp16": 1}
+
+
+def _run(d, wl, cfg):
+    va, vb, sa, sb = (d[k].cuda() for k in ("va", "vb", "sa", "sb"))
+    vo = torch.full_like(va, float("nan"))
+    so = torch.full_like(sa, float("nan"))
+    B.mergestates_run(va, sa, vb, sb, vo, so, wl.rows, wl.d, wl.dtype, cfg)
+    torch.cuda.synchronize()
+    return W.to_bits(vo), so.cpu().numpy()
+
+
+def _check(oracle, wl, cfgs):
+    d = W.generate_merge(wl)
+    vref, sref = oracle.mergestates(W.to_bits(d["va"]), d["sa"].numpy(), W.to_bits(d["vb"]), d["sb"].numpy(), DT[wl.dtype])
+    worst = 0.0
+    for c in cfgs:
+        v, s = _run(d, wl, c)
+        dist = ulp_distance(v, vref)
+        if dist.max() > 1:
+            idx = np.nonzero(dist > 1)
+            dec = oracle.bf16_to_f32_array if wl.dtype == "bf16" else oracle.f16_to_f32_array
+            err = np.abs(dec(v[idx]).astype(np.float64) - dec(vref[idx]).astype(np.float64))
+            scale = np.maximum(np.abs(d["va"].float().numpy()[idx]), np.abs(d["vb"].float().numpy()[idx]))
+            assert np.all(err <= 2.0 ** -20 * scale), (wl.name, c, int(dist.max()), float((err / scale).max()))
+            assert idx[0].size < 1e-5 * dist.size + 2, (wl.name, c, idx[0].size)
+        frac = float((dist > 0).mean())
+        assert frac < 2e-3, (wl.name, c, frac)
+        worst = max(worst, frac)
+        sd = ulp_distance(s, sref)
+        assert np.all((sd <= 4) | (np.abs(s.astype(np.float64) - sref) <= 2e-7)), (wl.name, c, int(sd.max()))
+    return worst
+
+
+@pytest.mark.parametrize("dtype,n,h,d,seed", [("bf16", 37, 3, 256, 1), ("fp16", 19, 5, 128, 2), ("bf16", 7, 9, 64, 3),
+                                              ("fp16", 130, 1, 96, 4), ("bf16", 3, 2, 1024, 5)])
+def test_every_feasible_cfg_small_shapes(oracle, dtype, n, h, d, seed):
+    wl = W.MergeWorkload(f"m_{n}x{h}x{d}_{dtype}", n, h, d, dtype, seed)
+    cfgs, _ = B.mergestates_enumerate_feasible(wl.rows, d, dtype)
+    assert len(cfgs) > 20
+    cfgs = [c for i, c in enumerate(cfgs) if c.max_waves_per_simd == 0 or i % 3 == 0]
+    worst = _check(oracle, wl, cfgs)
+    print(f"{wl.name}: {len(cfgs)} cfgs, worst differing fraction {worst:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("shape", W.MERGE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_paper_shapes_default_and_tuned(oracle, shape, dtype):
+    n, h, d = shape
+    wl = W.MergeWorkload(f"merge_{n}x{h}x{d}_{dtype}", n, h, d, dtype, 30 + n + h + d)
+    B.addrms_table_clear()
+    tuned, rep = B.mergestates_tune(wl.rows, d, dtype, B.make_budget(max_candidates=50, warmup=5, reps=30))
+    assert rep.n_failed == 0
+    nbytes = B.mergestates_algorithmic_bytes(wl.rows, d, dtype)
+    print(f"{wl.name}: default {rep.default_us:.2f} us, tuned {tuned} {rep.best_us:.2f} us = "
+          f"{nbytes / rep.best_us * 1e-3:.0f} GB/s", flush=True)
+    _check(oracle, wl, [None, tuned, B.mergestates_default_cfg(d, dtype)])
+    B.addrms_table_clear()
+
+
+def test_special_scores_and_errors(oracle):
+    wl = W.MergeWorkload("edge", 8, 1, 128, "bf16", 40)
+    d = W.generate_merge(wl)
+    d["sa"] = torch.tensor([0.0, 5.0, -5.0, 90.0, -90.0, 1e3, 3.25, 3.25])
+    d["sb"] = torch.tensor([0.0, -5.0, 5.0, -90.0, 90.0, -1e3, 3.25, 3.2500002])
+    vref, sref = oracle.mergestates(W.to_bits(d["va"]), d["sa"].numpy(), W.to_bits(d["vb"]), d["sb"].numpy(), 0)
+    v, s = _run(d, wl, None)
+    assert ulp_distance(v, vref).max() <= 1
+    assert np.array_equal(v[3], W.to_bits(d["va"])[3]) and np.array_equal(v[4], W.to_bits(d["vb"])[4])   # dominant part
+    assert np.array_equal(v[5], W.to_bits(d["va"])[5]) and s[5] == 1e3
+    assert np.allclose(s, sref, rtol=0, atol=4e-7 * np.maximum(1.0, np.abs(sref)))
+    lib = B.load()
+    va, vb, sa, sb = (d[k].cuda() for k in ("va", "vb", "sa", "sb"))
+    vo, so = torch.empty_like(va), torch.empty_like(sa)
+    ok = B.make_cfg(8, 16, 4)
+    args = (va.data_ptr(), sa.data_ptr(), vb.data_ptr(), sb.data_ptr(), vo.data_ptr(), so.data_ptr())
+    assert lib.mergestates_run(*args, 8, 128, B.BF16, ok, None) == B.OK
+    assert lib.mergestates_run(args[0] + 2, *args[1:], 8, 128, B.BF16, ok, None) == B.ERR_MISALIGNED
+    assert lib.mergestates_run(None, *args[1:], 8, 128, B.BF16, ok, None) == B.ERR_INVALID_ARG
+    assert lib.mergestates_run(*args, 8, 128, B.FP32, ok, None) == B.ERR_UNSUPPORTED_DTYPE
+    assert lib.mergestates_run(*args, 0, 128, B.BF16, ok, None) == B.OK
+    torch.cuda.synchronize()
