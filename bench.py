@@ -33,7 +33,7 @@ SKEW_BYTES = 4096               # residual base is skewed against x by one 4 KiB
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) on this workload,
 # scaled by the same counters on the library's calibration kernel of known size (summary under profiles/).
-MEASURED_TRAFFIC_BYTES = 134308600
+MEASURED_TRAFFIC_BYTES = 134361400
 
 
 def parse_args():
@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune-log", default=None, help="write the search's JSON-lines log here")
     ap.add_argument("--exhaustive", action="store_true", help="tune by exhaustive search instead of guided")
+    ap.add_argument("--cfg", default=None,
+                    help="skip the search and time this configuration: vec,threads_per_row,rows_per_wg,reduce,unroll,"
+                         "flags,max_waves_per_simd (used for profiler runs, whose overhead would mislead the search)")
     ap.add_argument("--probe", action="store_true",
                     help="time the library's copy-like calibration kernel (same traffic, no arithmetic) over the "
                          "same buffers instead of the operator; used to calibrate profiler byte counters")
@@ -198,7 +201,15 @@ def main():
     budget = B.make_budget(strategy=B.SEARCH_EXHAUSTIVE if a.exhaustive else B.SEARCH_GUIDED, eps=wl.eps,
                            log_path=a.tune_log)
     t0 = time.perf_counter()
-    tuned, rep = B.addrms_tune(wl.M, wl.N, wl.dtype, budget)
+    if a.cfg:
+        tuned = B.make_cfg(*[int(v) for v in a.cfg.split(",")])
+        st, why, _ = B.addrms_cfg_feasible(tuned, wl.M, wl.N, wl.dtype)
+        if st != 0:
+            print(f"--cfg is not feasible: {why}", file=sys.stderr)
+            sys.exit(2)
+        rep = B.TuneReport()
+    else:
+        tuned, rep = B.addrms_tune(wl.M, wl.N, wl.dtype, budget)
     tune_wall = time.perf_counter() - t0
     default = B.addrms_default_cfg(wl.N, wl.dtype)
 
@@ -234,7 +245,7 @@ def main():
                         "kernel_us": round(ev_d / a.steps * 1e3, 3),
                         "pct_of_peak": round(100.0 * nbytes / (wall_d / a.steps) * 1e-9 / HBM_PEAK_GBPS, 2)},
         "tuned_over_default": round(wall_d / wall_t, 4),
-        "tune": {"strategy": "exhaustive" if a.exhaustive else "guided", "wall_ms": round(tune_wall * 1e3, 1),
+        "tune": {"strategy": "given" if a.cfg else "exhaustive" if a.exhaustive else "guided", "wall_ms": round(tune_wall * 1e3, 1),
                  "n_grid": rep.n_grid, "n_feasible": rep.n_feasible, "n_measured": rep.n_measured,
                  "n_failed": rep.n_failed, "best_found_at": rep.best_found_at,
                  "time_to_best_ms": round(rep.time_to_best_ms, 2), "best_us": round(rep.best_us, 3),
