@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused residual-add + RMSNorm hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--op addrms|silumul|mergestates]
 
 Workload: the prefill shape M=4096, N=4096, bf16 storage (seed 1), the
 configuration the headline metric is quoted on.  One step = one in-place launch
@@ -12,6 +12,11 @@ than from the 256 MB last-level cache.
 Before the timed region the library's guided search tunes the launch
 configuration (its cost is reported, not timed as steps).  The same protocol
 is then run with the untuned default configuration.  One JSON line is printed.
+
+--op silumul / --op mergestates time the two further operators that sit behind
+the same tuner (gated activation 4096 x 11008 bf16; merge of two partial
+attention states, 768 x 32 x 256 bf16) with the same protocol and print the
+same kind of line; the default, and the headline figure, is the fused add+RMSNorm.
 """
 from __future__ import annotations
 
@@ -47,6 +52,8 @@ def parse_args():
     ap.add_argument("--cfg", default=None,
                     help="skip the search and time this configuration: vec,threads_per_row,rows_per_wg,reduce,unroll,"
                          "flags,max_waves_per_simd (used for profiler runs, whose overhead would mislead the search)")
+    ap.add_argument("--op", default="addrms", choices=("addrms", "silumul", "mergestates"),
+                    help="operator to time (default: the fused add+RMSNorm hot path)")
     ap.add_argument("--probe", action="store_true",
                     help="time the library's copy-like calibration kernel (same traffic, no arithmetic) over the "
                          "same buffers instead of the operator; used to calibrate profiler byte counters")
@@ -173,6 +180,131 @@ def run_probe(a, torch, lib, B, W, wl, d, dtype_id):
                       "config": {"workload": wl.name, "rotating_buffer_sets": nsets}}))
 
 
+def timed_loop(torch, launch, nsets, warmup, steps, stream):
+    """`launch(i)` enqueues one step on buffer set i.  Returns (wall s, event ms) for `steps` launches."""
+    k = 0
+    for _ in range(warmup):
+        launch(k % nsets); k += 1
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        launch(k % nsets); k += 1
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0, e0.elapsed_time(e1)
+
+
+def bounded_cpu_passes(fn, t_budget=12.0):
+    fn()
+    passes, spent = 0, 0.0
+    while spent < t_budget and passes < 5000:
+        t0 = time.perf_counter()
+        fn()
+        spent += time.perf_counter() - t0
+        passes += 1
+    return spent / passes, passes
+
+
+def run_other_op(a, torch, lib, B, W):
+    """silu_and_mul or merge_attn_states: tune, then default and tuned cfg timed over rotated buffers."""
+    stream = torch.cuda.current_stream()
+    sp = int(stream.cuda_stream)
+    budget = B.make_budget(strategy=B.SEARCH_EXHAUSTIVE if a.exhaustive else B.SEARCH_GUIDED, log_path=a.tune_log)
+    if a.op == "silumul":
+        wl = W.SILU_PREFILL
+        rows, width, units = wl.M, wl.d, wl.M
+        nbytes = B.silumul_algorithmic_bytes(wl.M, wl.d, wl.dtype)
+        tune, feasible, default_of, run = B.silumul_tune, B.silumul_cfg_feasible, B.silumul_default_cfg, lib.silumul_run
+        x0 = W.generate_gated(wl)
+        nsets = max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // nbytes))
+        xs = [x0.cuda() for _ in range(nsets)]
+        outs = [torch.empty((wl.M, wl.d), dtype=x0.dtype, device="cuda") for _ in range(nsets)]
+        dt = B.DTYPE_IDS[wl.dtype]
+        argv = [(x.data_ptr(), o.data_ptr(), wl.M, wl.d, dt) for x, o in zip(xs, outs)]
+        metric = "silu_and_mul achieved HBM GB/s (% of peak), tuned vs default cfg"
+    else:
+        n, h, d = max(W.MERGE_SHAPES, key=lambda t: t[0] * t[1] * t[2])
+        wl = W.MergeWorkload(f"merge_{n}x{h}x{d}_bf16", n, h, d, "bf16", 21)
+        rows, width, units = wl.rows, wl.d, wl.n
+        nbytes = B.mergestates_algorithmic_bytes(wl.rows, wl.d, wl.dtype)
+        tune, feasible, default_of, run = (B.mergestates_tune, B.mergestates_cfg_feasible, B.mergestates_default_cfg,
+                                           lib.mergestates_run)
+        t0 = W.generate_merge(wl)
+        nsets = max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // nbytes))
+        sets = [{k: v.cuda() for k, v in t0.items()} for _ in range(nsets)]
+        for s_ in sets:
+            s_["vo"] = torch.empty_like(s_["va"])
+            s_["so"] = torch.empty_like(s_["sa"])
+        dt = B.DTYPE_IDS[wl.dtype]
+        argv = [(s_["va"].data_ptr(), s_["sa"].data_ptr(), s_["vb"].data_ptr(), s_["sb"].data_ptr(),
+                 s_["vo"].data_ptr(), s_["so"].data_ptr(), wl.rows, wl.d, dt) for s_ in sets]
+        metric = "merge_attn_states achieved HBM GB/s (% of peak), tuned vs default cfg"
+
+    t_start = time.perf_counter()
+    if a.cfg:
+        tuned = B.make_cfg(*[int(v) for v in a.cfg.split(",")])
+        st, why, _ = feasible(tuned, rows, width, wl.dtype)
+        if st != 0:
+            print(f"--cfg is not feasible: {why}", file=sys.stderr)
+            sys.exit(2)
+        rep = B.TuneReport()
+    else:
+        tuned, rep = tune(rows, width, wl.dtype, budget)
+    tune_wall = time.perf_counter() - t_start
+    default = default_of(width, wl.dtype)
+
+    def launcher(cfg):
+        ref = ctypes.byref(cfg)
+        def launch(i):
+            if run(*argv[i], ref, sp) != 0:
+                raise RuntimeError(B.addrms_last_error())
+        return launch
+
+    wall_d, ev_d = timed_loop(torch, launcher(default), nsets, a.warmup, a.steps, stream)
+    wall_t, ev_t = timed_loop(torch, launcher(tuned), nsets, a.warmup, a.steps, stream)
+    value = nbytes / (wall_t / a.steps) * 1e-9
+    kernel_us = ev_t / a.steps * 1e3
+    achieved = nbytes / (kernel_us * 1e-6) * 1e-9
+    out = {
+        "metric": metric, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(wall_t / a.steps * 1e3, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "rows": rows, "width": width, "storage": wl.dtype, "seed": wl.seed,
+                   "cfg": tuned.as_dict(), "rotating_buffer_sets": nsets, "algorithmic_bytes_per_step": nbytes},
+        "pct_of_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "tokens_per_s": round(units / (wall_t / a.steps), 1),
+        "default_cfg": {"cfg": default.as_dict(), "value": round(nbytes / (wall_d / a.steps) * 1e-9, 1),
+                        "ms_per_step": round(wall_d / a.steps * 1e3, 6), "kernel_us": round(ev_d / a.steps * 1e3, 3)},
+        "tuned_over_default": round(wall_d / wall_t, 4),
+        "tune": {"strategy": "given" if a.cfg else "exhaustive" if a.exhaustive else "guided",
+                 "wall_ms": round(tune_wall * 1e3, 1), "n_grid": rep.n_grid, "n_feasible": rep.n_feasible,
+                 "n_measured": rep.n_measured, "n_failed": rep.n_failed, "best_us": round(rep.best_us, 3),
+                 "default_us": round(rep.default_us, 3)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "kernel_us": round(kernel_us, 3),
+                     "algorithmic_bytes": nbytes},
+    }
+    if not a.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+        if a.op == "silumul":
+            xb = W.to_bits(x0)
+            per, passes = bounded_cpu_passes(lambda: oracle.silumul(xb, dt, nthreads=cores))
+            sample = f"{passes} full passes over {wl.name}, rows split over {cores} threads"
+        else:
+            cores = 1                                   # this oracle is a plain serial loop
+            bits = {k: (W.to_bits(v) if k in ("va", "vb") else v.numpy()) for k, v in t0.items()}
+            per, passes = bounded_cpu_passes(lambda: oracle.mergestates(bits["va"], bits["sa"], bits["vb"], bits["sb"], dt))
+            sample = f"{passes} full passes over {wl.name} on one thread"
+        out["cpu_baseline"] = {"value": nbytes / per * 1e-9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+                               "sample": sample, "ms_per_step": per * 1e3}
+    print(json.dumps(out))
+
+
 def main():
     a = parse_args()
     if a.gpus != 1:
@@ -188,6 +320,12 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     lib = B.load()
+    if a.op != "addrms":
+        if a.probe:
+            print("--probe applies to --op addrms only", file=sys.stderr)
+            sys.exit(2)
+        run_other_op(a, torch, lib, B, W)
+        return
     wl = W.PREFILL
     dtype_id = B.DTYPE_IDS[wl.dtype]
     nbytes = B.addrms_algorithmic_bytes(wl.M, wl.N, wl.dtype)

@@ -79,7 +79,10 @@ typedef struct addrms_cfg {
  *   residual device, [M, N] row-major, residual dtype.            in: r, out: round(x+r)
  *   weight   device, [N], x dtype, read only
  *   eps      added to the mean of squares
- *   M, N     rows, row length.  M == 0 is a successful no-op; N <= 0 is INVALID_ARG
+ *   M, N     rows, row length.  M == 0 is a successful no-op; N <= 0 is INVALID_ARG;
+ *            a row is held in registers between its two passes, so N is bounded
+ *            (1024 threads x 32 cached values, at most 16 accesses per thread):
+ *            even N up to 32768, odd N up to 16384; beyond that UNSUPPORTED_SHAPE
  *   dtype    addrms_dtype
  *   cfg      host; NULL = look (M, N, dtype) up in the specialised table
  *            (nearest tuned M for the same N and dtype), else the default cfg

@@ -161,3 +161,20 @@ def test_default_cfg():
     assert d.as_tuple() == (8, 256, 1, 0, 2, 0, 0)
     assert B.load().addrms_default_cfg(1 << 20, B.BF16, B.Cfg()) == B.ERR_UNSUPPORTED_SHAPE
     assert "row cache" in B.addrms_last_error()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16", "fp16_res32", "fp32"])
+def test_row_length_bound_of_the_register_cache(dtype):
+    """1024 threads x 32 cached values, at most 16 accesses per thread: even N up to
+    32768 and odd N up to 16384 have a configuration; one past either bound has none."""
+    for N in (32768, 32766, 32764, 16383, 16381):
+        c = B.addrms_default_cfg(N, dtype)
+        assert N % c.vec == 0 and c.threads_per_row * c.vec * 16 >= N
+        st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
+        assert st == 0, why
+        assert res.chunks_per_thread * c.vec <= 64 and res.scratch_bytes == 0
+    for N in (32767, 32770, 16385, 65536):
+        with pytest.raises(B.AddrmsError) as e:
+            B.addrms_default_cfg(N, dtype)
+        assert e.value.status == B.ERR_UNSUPPORTED_SHAPE
+        assert B.addrms_enumerate_feasible(4, N, dtype)[0] == []      # the feasible region is empty, not an error

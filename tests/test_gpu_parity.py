@@ -91,6 +91,35 @@ def test_narrow_and_odd_widths(oracle, N):
             assert compare(y, res, y_ref, res_ref, dtype, f"N={N} {c}")["n_diff"] == 0
 
 
+@pytest.mark.parametrize("dtype,M,N", [("bf16", 3, 32768), ("fp32", 2, 32768), ("fp16", 3, 32766),
+                                       ("bf16", 2, 16383), ("fp16_res32", 5, 28672)])
+def test_widest_rows_the_template_covers(oracle, dtype, M, N):
+    """The register row cache bounds N: even N up to 32768, odd N up to 16384.  Every
+    feasible cfg at the bound is checked (there are few), the default included."""
+    wl = _wl(M, N, dtype, 900 + N % 97)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
+    assert cfgs
+    print(f"{wl.name}: {len(cfgs)} feasible", flush=True)
+    for c in [None] + cfgs[:: max(1, len(cfgs) // 60)]:
+        y, res = case.run(c)
+        assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 32767), ("bf16", 32776), ("fp32", 16385), ("fp16", 65536)])
+def test_rows_beyond_the_template_are_refused_before_launch(dtype, N):
+    xb, rb = W.x_bytes(dtype), W.r_bytes(dtype)
+    x = torch.full((2 * N * xb,), 0x3C, dtype=torch.uint8, device="cuda")
+    r = torch.full((2 * N * rb,), 0x3C, dtype=torch.uint8, device="cuda")
+    w = torch.zeros(N * xb, dtype=torch.uint8, device="cuda")
+    st = B.load().addrms_run(x.data_ptr(), r.data_ptr(), w.data_ptr(), 1e-6, 2, N, B._dtype_id(dtype), None, None)
+    assert st == B.ERR_UNSUPPORTED_SHAPE, B.addrms_last_error()
+    torch.cuda.synchronize()
+    assert bool((x == 0x3C).all()) and bool((r == 0x3C).all())
+
+
 def test_degenerate_rows(oracle):
     """Zero rows, signed zeros, rounding ties, subnormal sums, large magnitudes."""
     N = 1024
