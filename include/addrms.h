@@ -282,6 +282,51 @@ int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int d
                                     const addrms_backend_factory* factory, addrms_cfg* out_general,
                                     addrms_rounds_report* report);
 
+/* ---- audit of the feasible region's efficiency rules (Section 3.3) ----------------
+ * The deriver prunes two kinds of configurations: invalid ones (a launch the hardware
+ * or the compiled instance cannot take) and ones it calls obviously inefficient (at
+ * most half the lanes of a row carrying data; fewer than two resident waves per SIMD;
+ * an instance that spills registers).  The second kind is a judgement, and this call
+ * puts it to the test: it enumerates the grid with those three rules switched off,
+ * passes both the retained configurations and the ones each rule would have pruned
+ * through the correctness gate and the screening protocol (budget.coarse_warmup /
+ * coarse_reps, default 3 + 15 launches), and reports per rule how the pruned ones
+ * compare.  A rule is sound on this shape if none of what it prunes is faster than
+ * the best retained configuration (n_beating_best == 0, up to timing noise).
+ * budget.max_candidates caps the configurations measured PER CLASS (evenly strided
+ * sample; 0 = all); budget.max_wall_ms stops early (truncated = 1).  Nothing is added
+ * to the table, and addrms_run still refuses the pruned configurations.  Blocking;
+ * allocates and frees device memory. */
+#define ADDRMS_AUDIT_RULES 3
+typedef struct addrms_audit_rule {
+    char    rule[24];          /* "lane_utilisation", "occupancy_floor", "scratch"                     */
+    int64_t n_pruned;          /* grid points this rule alone keeps out of the feasible region         */
+    int32_t n_measured;        /* of those, validated and timed                                        */
+    int32_t n_failed;          /* of those, failed the gate or the launch                              */
+    int32_t n_in_top_decile;   /* timed pruned cfgs faster than the retained region's fastest decile   */
+    int32_t n_beating_best;    /* timed pruned cfgs faster than the best retained cfg                  */
+    double  best_us;           /* fastest pruned cfg (0 if none was timed)                             */
+    double  median_us;
+    addrms_cfg best;
+} addrms_audit_rule;
+typedef struct addrms_audit_report {
+    int64_t n_retained;            /* size of the feasible region with every rule on                   */
+    int32_t n_retained_measured;
+    int32_t n_retained_failed;
+    double  retained_best_us;
+    double  retained_decile_us;    /* 10th percentile of the retained cfgs' times                      */
+    double  retained_median_us;
+    double  wall_ms;
+    int32_t truncated;
+    int32_t reserved;
+    addrms_cfg retained_best;
+    addrms_audit_rule rules[ADDRMS_AUDIT_RULES];
+} addrms_audit_report;
+int addrms_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget, addrms_audit_report* report);
+/* The same with validation and timing supplied by the caller (host-only; CPU tests). */
+int addrms_audit_rules_with_backend(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
+                                    const addrms_backend* backend, addrms_audit_report* report);
+
 /* addrms_measure: mean time in microseconds of `cfg` (NULL = table/default, as
  * in addrms_run) on (M, N, dtype) over `reps` launches after `warmup`, on
  * library-allocated synthetic buffers.  rotate != 0 cycles through enough

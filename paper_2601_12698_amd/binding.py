@@ -174,6 +174,34 @@ class RoundsReport(Structure):
                     best=self.best.as_dict())
 
 
+AUDIT_RULES = 3
+
+
+class AuditRule(Structure):
+    _fields_ = [("rule", ctypes.c_char * 24), ("n_pruned", c_int64), ("n_measured", c_int32), ("n_failed", c_int32),
+                ("n_in_top_decile", c_int32), ("n_beating_best", c_int32), ("best_us", c_double),
+                ("median_us", c_double), ("best", Cfg)]
+
+    def as_dict(self) -> dict:
+        return dict(rule=self.rule.decode(), n_pruned=self.n_pruned, n_measured=self.n_measured, n_failed=self.n_failed,
+                    n_in_top_decile=self.n_in_top_decile, n_beating_best=self.n_beating_best, best_us=self.best_us,
+                    median_us=self.median_us, best=self.best.as_dict())
+
+
+class AuditReport(Structure):
+    _fields_ = [("n_retained", c_int64), ("n_retained_measured", c_int32), ("n_retained_failed", c_int32),
+                ("retained_best_us", c_double), ("retained_decile_us", c_double), ("retained_median_us", c_double),
+                ("wall_ms", c_double), ("truncated", c_int32), ("reserved", c_int32), ("retained_best", Cfg),
+                ("rules", AuditRule * AUDIT_RULES)]
+
+    def as_dict(self) -> dict:
+        return dict(n_retained=self.n_retained, n_retained_measured=self.n_retained_measured,
+                    n_retained_failed=self.n_retained_failed, retained_best_us=self.retained_best_us,
+                    retained_decile_us=self.retained_decile_us, retained_median_us=self.retained_median_us,
+                    wall_ms=self.wall_ms, truncated=bool(self.truncated), retained_best=self.retained_best.as_dict(),
+                    rules=[r.as_dict() for r in self.rules])
+
+
 OPEN_FN = CFUNCTYPE(c_int, c_void_p, c_int64, c_int64, c_int, POINTER(Backend))
 CLOSE_FN = CFUNCTYPE(None, c_void_p, POINTER(Backend))
 
@@ -199,6 +227,9 @@ SIGNATURES = {
                                    POINTER(RoundsReport)]),
     "addrms_tune_rounds_with_backend": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget),
                                                 POINTER(BackendFactory), POINTER(Cfg), POINTER(RoundsReport)]),
+    "addrms_audit_rules": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(AuditReport)]),
+    "addrms_audit_rules_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
+                                                POINTER(AuditReport)]),
     "addrms_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_float, c_int, c_int, c_int, POINTER(c_double)]),
     "addrms_measure_stats": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_float, c_int, c_int, c_int,
                                      POINTER(TimeStats)]),
@@ -447,6 +478,25 @@ def _python_factory(make_backend, keep):
     fac.close = CLOSE_FN(_close)
     keep.append((fac.open, fac.close))
     return fac
+
+
+def addrms_audit_rules(M: int, N: int, dtype, budget: Optional[Budget] = None) -> AuditReport:
+    """Times what the deriver's efficiency rules prune beside what they retain."""
+    rep = AuditReport()
+    _check(load().addrms_audit_rules(M, N, _dtype_id(dtype), byref(budget) if budget is not None else None, byref(rep)))
+    return rep
+
+
+def addrms_audit_rules_with_backend(M: int, N: int, dtype, budget: Optional[Budget], measure, validate=None
+                                    ) -> AuditReport:
+    be = Backend()
+    be.user = None
+    be.measure = _wrap_measure(measure)
+    be.validate = _wrap_validate(validate)
+    rep = AuditReport()
+    _check(load().addrms_audit_rules_with_backend(M, N, _dtype_id(dtype), byref(budget) if budget is not None else None,
+                                                  byref(be), byref(rep)))
+    return rep
 
 
 def addrms_tune_rounds(shapes, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, RoundsReport]:

@@ -117,7 +117,7 @@ def build(force: bool = False, jobs: int = 8, verbose: bool = False) -> str:
             os.path.join(CSRC, "addrms_internal.h")]
     gen = [os.path.join(BUILD, f) for f in ("gen_instances.inc", "gen_resources.inc",
                                              "gen_dispatch_decl.inc", "gen_dispatch_rows.inc")]
-    for name in ("addrms_cfg.cpp", "addrms_table.cpp", "addrms_search.cpp", "addrms_general.cpp"):
+    for name in ("addrms_cfg.cpp", "addrms_table.cpp", "addrms_search.cpp", "addrms_general.cpp", "addrms_audit.cpp"):
         src = os.path.join(CSRC, name)
         obj = os.path.join(BUILD, name + ".o")
         if force or not _newer(obj, src, *hdrs, *gen):

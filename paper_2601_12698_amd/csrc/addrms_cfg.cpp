@@ -219,7 +219,7 @@ static Feas infeasible(const char* rule, const char* fmt, ...)
     return f;
 }
 
-Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op)
+Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int relax)
 {
     const HwLimits& L = hw();
     Feas f;
@@ -283,7 +283,9 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op)
                           op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : op == OP_MERGE ? "1-4 exist" : "1-8 exist");
     f.res.chunks_per_thread = static_cast<int>(need);
     const double util = static_cast<double>(N) / static_cast<double>(per_pass * need);
-    if (util <= 0.5)
+    if (util <= 0.5 && (relax & RELAX_LANE_UTILISATION)) {
+        if (!f.soft_rule[0]) f.soft_rule = "lane_utilisation";
+    } else if (util <= 0.5)
         return infeasible("lane_utilisation", "only %.0f%% of the %lld lane slots of a row would carry data (obviously inefficient: a "
                           "narrower row does the same work)", util * 100.0, (long long)(per_pass * need));
     if (c.unroll > need)
@@ -311,7 +313,9 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op)
     o.max_threads = in.maxt;
     o.lds_bytes = reduction_lds_bytes(c, op) + r.lds_static;
     o.waves_per_wg = threads / L.wave_size;
-    if (r.scratch > 0)
+    if (r.scratch > 0 && (relax & RELAX_SCRATCH)) {
+        if (!f.soft_rule[0]) f.soft_rule = "scratch";
+    } else if (r.scratch > 0)
         return infeasible("scratch", "instance spills %d bytes per lane to scratch memory", r.scratch);
     if (threads > in.maxt)
         return infeasible("wg_bound", "instance holds %d values per thread and was compiled for workgroups of at most %d threads; "
@@ -350,14 +354,16 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op)
     if ((c.flags & ADDRMS_FLAG_PERSISTENT) && n_row_blocks(c, M) <= static_cast<int64_t>(L.compute_units) * wgs)
         return infeasible("persistent_identity", "all %lld row blocks are resident at once (%d CUs x %d workgroups): a "
                           "persistent grid is the ordinary grid", (long long)n_row_blocks(c, M), L.compute_units, wgs);
-    if (o.waves_per_simd < kMinWavesPerSimd)
+    if (o.waves_per_simd < kMinWavesPerSimd && (relax & RELAX_OCCUPANCY_FLOOR)) {
+        if (!f.soft_rule[0]) f.soft_rule = "occupancy_floor";
+    } else if (o.waves_per_simd < kMinWavesPerSimd)
         return infeasible("occupancy", "only %d wave per SIMD would be resident (%d registers per lane, %d-wave workgroups): too "
                           "few loads in flight to cover HBM latency", o.waves_per_simd, regs, o.waves_per_wg);
     return f;
 }
 
 void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid,
-               std::map<std::string, int64_t>* pruned, int op)
+               std::map<std::string, int64_t>* pruned, int op, int relax)
 {
     int64_t grid = 0;
     std::vector<int> tprs = {8, 16, 32};
@@ -373,7 +379,7 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
                                 addrms_cfg c{};
                                 c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;
                                 c.reduce = red; c.unroll = unr; c.flags = flags; c.max_waves_per_simd = cap;
-                                const Feas f = check_cfg(c, M, N, dtype, op);
+                                const Feas f = check_cfg(c, M, N, dtype, op, relax);
                                 if (f.status == ADDRMS_OK) { if (out) out->push_back(c); }
                                 else if (pruned) ++(*pruned)[f.rule];
                             }

@@ -63,17 +63,23 @@ int r_bytes(int dtype);
 const char* dtype_name(int dtype);
 
 // ---- feasibility -----------------------------------------------------------
+// Efficiency rules that an audit may switch off to measure what they prune.  Rules that
+// keep a launch valid (sizes, alignment, instance limits, LDS, at least one workgroup per
+// CU) and rules that only remove duplicates of another cfg can never be switched off.
+enum Relax : int { RELAX_LANE_UTILISATION = 1, RELAX_OCCUPANCY_FLOOR = 2, RELAX_SCRATCH = 4, RELAX_ALL = 7 };
+
 struct Feas {
     int status = ADDRMS_OK;
     const char* rule = "";      // short tag of the rule that rejected the cfg
+    const char* soft_rule = ""; // first efficiency rule that a relaxed check let the cfg past
     std::string reason;
     int inst = -1;              // instance index when one was selected
     addrms_resources res{};
 };
-Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op = OP_ADDRMS);
+Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op = OP_ADDRMS, int relax = 0);
 // Walks the whole knob grid; `pruned` (optional) counts rejected points by rule tag.
 void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, int64_t* n_grid,
-               std::map<std::string, int64_t>* pruned = nullptr, int op = OP_ADDRMS);
+               std::map<std::string, int64_t>* pruned = nullptr, int op = OP_ADDRMS, int relax = 0);
 int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op = OP_ADDRMS);
 // Dynamic LDS bytes of a launch: what the reduction needs, raised to the padding that
 // imposes cfg.max_waves_per_simd (0 if the cap cannot be imposed; check_cfg rejects that).
@@ -107,6 +113,9 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
 int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
                     const addrms_backend_factory& factory, bool insert_in_table,
                     addrms_cfg* out_general, addrms_rounds_report* report);
+// Measures what the efficiency rules of the deriver prune (see addrms_audit_rules).
+int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget, const addrms_backend& be,
+                    addrms_audit_report* report);
 // True if cfg only uses strategy families allowed by mask (0 = all).
 bool cfg_in_families(const addrms_cfg& c, int family_mask);
 

@@ -231,6 +231,7 @@ struct Harness {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     bool have_ref = false;
     addrms_cfg ref_cfg{};
+    int relax = 0;   // efficiency rules switched off (audit only)
 
     // Buffers start on 64 KiB boundaries; each residual buffer is then skewed by
     // one 4 KiB interleave unit so that the x and residual accesses of a lane,
@@ -300,7 +301,7 @@ struct Harness {
     // 0 if cfg reproduces the reference output on the pristine inputs.
     int validate(const addrms_cfg& c)
     {
-        const Feas f = check_cfg(c, M, N, dtype);
+        const Feas f = check_cfg(c, M, N, dtype, OP_ADDRMS, relax);
         if (f.status != ADDRMS_OK) return f.status;
         HIP_TRY(hipMemcpyAsync(xs[0], x0, xbytes, hipMemcpyDeviceToDevice, stream));
         HIP_TRY(hipMemcpyAsync(rs[0], r0, rbytes, hipMemcpyDeviceToDevice, stream));
@@ -327,7 +328,7 @@ struct Harness {
 
     int measure(const addrms_cfg& c, int warmup, int reps, double* mean_us)
     {
-        const Feas f = check_cfg(c, M, N, dtype);
+        const Feas f = check_cfg(c, M, N, dtype, OP_ADDRMS, relax);
         if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
         int set = 0;
         for (int i = 0; i < warmup; ++i) {
@@ -729,6 +730,33 @@ int addrms_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const a
     HarnessFactory hf{(budget && budget->eps > 0.0f) ? budget->eps : 1e-6f};
     addrms_backend_factory fac{&hf, factory_open, factory_close};
     return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report);
+}
+
+int addrms_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget, addrms_audit_report* report)
+{
+    if (!report) return fail(ADDRMS_ERR_INVALID_ARG, "report is NULL");
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M <= 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "the audit needs M > 0 and N > 0");
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_cfg dflt{};
+    std::string why;
+    int st = default_cfg(N, dtype, &dflt, &why);
+    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
+    Harness h;
+    st = h.init(M, N, dtype, (budget && budget->eps > 0.0f) ? budget->eps : 1e-6f, true);
+    if (st != ADDRMS_OK) return st;
+    if (check_cfg(dflt, M, N, dtype).status != ADDRMS_OK) {
+        std::vector<addrms_cfg> v;
+        enumerate(M, N, dtype, &v, nullptr, nullptr);
+        if (v.empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
+        dflt = v.front();
+    }
+    st = h.make_reference(dflt);     // the reference comes from a configuration every rule retains
+    if (st != ADDRMS_OK) return st;
+    h.relax = RELAX_ALL;
+    addrms_backend be{&h, backend_validate, backend_measure};
+    return run_audit_rules(M, N, dtype, budget, be, report);
 }
 
 int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,

@@ -74,6 +74,8 @@ def main(argv=None) -> int:
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
                          "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
+    ap.add_argument("--audit", action="store_true",
+                    help="time what the deriver's efficiency rules prune beside what they retain (three shapes)")
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("needs a GPU", file=sys.stderr)
@@ -142,6 +144,19 @@ def main(argv=None) -> int:
                 print(f"| {m} x {n} | {rep.default_us[i]:.2f} | {rep.general_us[i]:.2f} | {rep.specialized_us[i]:.2f} | "
                       f"{rep.default_us[i] / rep.general_us[i]:.3f} | {rep.default_us[i] / rep.specialized_us[i]:.3f} | "
                       f"{rep.specialized[i].as_tuple()} |", flush=True)
+    if a.audit:
+        print("\nAudit of the efficiency rules (every cfg gated and timed, 3 + 15 launches):\n")
+        print("| M x N | dtype | retained | best us | decile us | median us | rule | pruned | failed gate | best us | "
+              "median us | in top decile | beating best | s |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+        for M, N, dtype in ((2048, 1000, "fp16_res32"), (4096, 4096, "bf16"), (1024, 11008, "fp32")):
+            rep = B.addrms_audit_rules(M, N, dtype, B.make_budget())
+            for r in rep.rules:
+                if r.n_pruned:
+                    print(f"| {M} x {N} | {dtype} | {rep.n_retained} | {rep.retained_best_us:.2f} | "
+                          f"{rep.retained_decile_us:.2f} | {rep.retained_median_us:.2f} | {r.rule.decode()} | {r.n_pruned} | "
+                          f"{r.n_failed} | {r.best_us:.2f} | {r.median_us:.2f} | {r.n_in_top_decile} | {r.n_beating_best} | "
+                          f"{rep.wall_ms / 1e3:.1f} |", flush=True)
     if a.table:
         B.addrms_table_save(a.table)
     return 0
