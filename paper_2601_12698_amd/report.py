@@ -62,6 +62,40 @@ def probe_us(wl, reps=50) -> float:
     return e0.elapsed_time(e1) * 1e3 / reps
 
 
+def graph_vs_eager_us(wl, cfg, chain=64, laps=20, nsets=8):
+    """Per-launch time of `chain` back-to-back launches (rotating over `nsets` buffer pairs):
+    issued one by one from the host, and replayed from a captured HIP graph."""
+    dev = torch.device("cuda")
+    d = W.generate(wl)
+    w = d["w"].to(dev)
+    xs = [d["x"].to(dev) for _ in range(nsets)]
+    rs = [d["r"].to(dev) for _ in range(nsets)]
+
+    def issue():
+        for i in range(chain):
+            B.addrms_run(xs[i % nsets], rs[i % nsets], w, wl.eps, wl.M, wl.N, wl.dtype, cfg)
+
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(laps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (laps * chain)
+
+    eager = timed(issue)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        issue()
+    torch.cuda.synchronize()
+    return eager, timed(g.replay)
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--exhaustive-prefill", action="store_true",
@@ -74,6 +108,8 @@ def main(argv=None) -> int:
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
                          "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
+    ap.add_argument("--graph-decode", action="store_true",
+                    help="decode shapes: per-launch time of a chain of launches issued eagerly vs replayed from a HIP graph")
     ap.add_argument("--audit", action="store_true",
                     help="time what the deriver's efficiency rules prune beside what they retain (three shapes)")
     a = ap.parse_args(argv)
@@ -133,17 +169,26 @@ def main(argv=None) -> int:
                       f"{rep.default_us / rep.best_us:.3f} | {nbytes / rep.best_us * 1e-3:.0f} | {cfg.as_tuple()} | "
                       f"{rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
     if a.paper_shapes:
-        for dtype, shapes in (("bf16", PAPER_MN_16BIT), ("fp16", PAPER_MN_16BIT), ("fp32", PAPER_MN_FP32)):
-            g, rep = B.addrms_select_general(shapes, dtype, B.make_budget())
+        for dtype, shape_list in (("bf16", PAPER_MN_16BIT), ("fp16", PAPER_MN_16BIT), ("fp32", PAPER_MN_FP32)):
+            g, rep = B.addrms_select_general(shape_list, dtype, B.make_budget())
             print(f"\n{dtype}: general cfg {g.as_tuple()}: geomean speedup over default x{rep.geomean_speedup_general:.3f} "
                   f"(arithmetic mean x{rep.mean_speedup_general:.3f}); specialised table x{rep.geomean_speedup_specialized:.3f}; "
                   f"{rep.n_pool} universally feasible candidates timed; {rep.wall_ms:.0f} ms\n")
             print("| m x n | default us | general us | specialised us | general speedup | specialised speedup | specialised cfg |")
             print("|---|---|---|---|---|---|---|")
-            for i, (m, n) in enumerate(shapes):
+            for i, (m, n) in enumerate(shape_list):
                 print(f"| {m} x {n} | {rep.default_us[i]:.2f} | {rep.general_us[i]:.2f} | {rep.specialized_us[i]:.2f} | "
                       f"{rep.default_us[i] / rep.general_us[i]:.3f} | {rep.default_us[i] / rep.specialized_us[i]:.3f} | "
                       f"{rep.specialized[i].as_tuple()} |", flush=True)
+    if a.graph_decode:
+        print("\nDecode shapes, chain of 64 launches, tuned cfg: microseconds per launch issued eagerly vs from a HIP graph:\n")
+        print("| M x N | cfg | eager us | graph us |")
+        print("|---|---|---|---|")
+        for m in W.DECODE_M:
+            wl = W.DECODE.with_rows(m)
+            cfg = B.addrms_table_lookup(wl.M, wl.N, wl.dtype) or B.addrms_default_cfg(wl.N, wl.dtype)
+            eager, graph = graph_vs_eager_us(wl, cfg)
+            print(f"| {wl.M} x {wl.N} | {cfg.as_tuple()} | {eager:.2f} | {graph:.2f} |", flush=True)
     if a.audit:
         print("\nAudit of the efficiency rules (every cfg gated and timed, 3 + 15 launches):\n")
         print("| M x N | dtype | retained | best us | decile us | median us | rule | pruned | failed gate | best us | "
