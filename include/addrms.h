@@ -378,7 +378,10 @@ int addrms_rstd_probe(const double* ss, int64_t n, int64_t N, float eps, float* 
 
 /* Calibration kernel with the operator's traffic and none of its arithmetic:
  * reads [M,N] of x and of residual and writes both back (bitwise complemented),
- * 16 bytes per lane.  Same argument meaning as addrms_run. */
+ * 16 bytes per lane, streaming cache policy, three 256-thread workgroups per CU
+ * (the fastest plain copy-like kernel found on MI355X; its rate is the practical
+ * ceiling the operator is compared with, and its known byte counts calibrate the
+ * profiler's HBM counters).  Same argument meaning as addrms_run. */
 int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype, void* stream);
 
 /* What the HIP runtime on the current device reports for the kernel instance and

@@ -127,18 +127,24 @@ __global__ void rstd_probe_kernel(const double* ss, long long n, double inv_n, f
 // Reads two streams and writes both back complemented: the operator's traffic
 // pattern (one read and one write of every byte, both streams touched by the
 // same lane) with no arithmetic to speak of.
-__global__ __launch_bounds__(256) void stream_probe_kernel(addrms::u32x4* a, addrms::u32x4* b, long long n, int b_per_a)
+// It uses the best settings a sweep of plain copy-like kernels found on this device:
+// streaming (non-temporal) policy on loads and stores, and at most three 256-thread
+// workgroups per CU (imposed by the dynamic LDS allocation; fewer requests in flight
+// suit mixed read/write traffic better than full occupancy).
+constexpr int kProbeLdsBytes = 160 * 1024 / 3 / 1280 * 1280;   // 53,760: three workgroups per CU
+template <int B_PER_A>   // 16-byte pieces of b per piece of a: 1, or 2 when the residual is fp32 beside 16-bit x
+__global__ __launch_bounds__(256) void stream_probe_kernel(addrms::u32x4* a, addrms::u32x4* b, long long n)
 {
     const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    addrms::u32x4 va = a[i];
-    if (b_per_a == 1) {
-        addrms::u32x4 vb = b[i];
-        a[i] = ~va; b[i] = ~vb;
-    } else {
-        addrms::u32x4 vb0 = b[2 * i], vb1 = b[2 * i + 1];
-        a[i] = ~va; b[2 * i] = ~vb0; b[2 * i + 1] = ~vb1;
-    }
+    // every load is issued before the first value is used
+    const addrms::u32x4 va = __builtin_nontemporal_load(a + i);
+    addrms::u32x4 vb[B_PER_A];
+#pragma unroll
+    for (int k = 0; k < B_PER_A; ++k) vb[k] = __builtin_nontemporal_load(b + B_PER_A * i + k);
+    __builtin_nontemporal_store(~va, a + i);
+#pragma unroll
+    for (int k = 0; k < B_PER_A; ++k) __builtin_nontemporal_store(~vb[k], b + B_PER_A * i + k);
 }
 
 // Synthetic activations for the tuner's own buffers: a counter-based hash mapped
@@ -843,8 +849,14 @@ int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype
                     "and both bases 16-byte aligned");
     const long long n = xb / 16;
     const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
-    hipLaunchKernelGGL(stream_probe_kernel, grid, block, 0, static_cast<hipStream_t>(stream),
-                       static_cast<addrms::u32x4*>(x), static_cast<addrms::u32x4*>(residual), n, static_cast<int>(rb / xb));
+    addrms::u32x4* xa = static_cast<addrms::u32x4*>(x);
+    addrms::u32x4* ra = static_cast<addrms::u32x4*>(residual);
+    if (rb == xb)
+        hipLaunchKernelGGL(stream_probe_kernel<1>, grid, block, kProbeLdsBytes, static_cast<hipStream_t>(stream), xa, ra, n);
+    else if (rb == 2 * xb)
+        hipLaunchKernelGGL(stream_probe_kernel<2>, grid, block, kProbeLdsBytes, static_cast<hipStream_t>(stream), xa, ra, n);
+    else
+        return fail(ADDRMS_ERR_INVALID_ARG, "unexpected residual/x size ratio");
     HIP_TRY(hipGetLastError());
     return ADDRMS_OK;
 }

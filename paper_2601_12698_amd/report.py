@@ -41,15 +41,24 @@ def shapes():
 
 
 def probe_us(wl, reps=50) -> float:
-    """Mean time of the calibration kernel over rotated buffers (0 if the shape
-    does not meet its 16-byte granularity)."""
+    """Mean time of the calibration kernel over rotated buffers (0 if the shape does not meet
+    its 16-byte granularity).  Buffers are carved from one pool the way the tuner's harness and
+    bench.py lay theirs out: 64 KiB-aligned, the residual skewed by 4 KiB against x."""
     xb, rb = W.x_bytes(wl.dtype), W.r_bytes(wl.dtype)
     if (wl.M * wl.N * xb) % 16:
         return 0.0
-    set_bytes = wl.M * wl.N * (xb + rb)
-    nsets = int(max(2, min(32, -(-2 * (288 << 20) // set_bytes))))
-    xs = [torch.zeros(wl.M * wl.N * xb, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
-    rs = [torch.zeros(wl.M * wl.N * rb, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    nx, nr = wl.M * wl.N * xb, wl.M * wl.N * rb
+    align, skew = 1 << 16, 4096
+
+    def up(v):
+        return (v + align - 1) // align * align
+
+    stride = up(nx) + up(nr) + 2 * align
+    nsets = int(max(2, min(32, -(-2 * (288 << 20) // (nx + nr)))))
+    pool = torch.zeros(stride * nsets + align, dtype=torch.uint8, device="cuda")
+    base = (-pool.data_ptr()) % align
+    xs = [pool[base + i * stride: base + i * stride + nx] for i in range(nsets)]
+    rs = [pool[base + i * stride + up(nx) + skew: base + i * stride + up(nx) + skew + nr] for i in range(nsets)]
     for i in range(10):
         B.addrms_stream_probe(xs[i % nsets], rs[i % nsets], wl.M, wl.N, wl.dtype)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
