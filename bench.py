@@ -36,9 +36,24 @@ LLC_BYTES = 256 << 20           # Infinity Cache
 L2_TOTAL_BYTES = 8 * (4 << 20)
 SKEW_BYTES = 4096               # residual base is skewed against x by one 4 KiB interleave unit
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) on this workload,
-# scaled by the same counters on the library's calibration kernel of known size (summary under profiles/).
-MEASURED_TRAFFIC_BYTES = 134361400
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) on the named workload,
+# scaled by the same counters on the library's calibration kernel of known size (summaries under profiles/).
+MEASURED_TRAFFIC_BYTES = {"prefill_4096x4096_bf16": 134361400,
+                          "large_prefill_32768x7168_bf16_outliers": 1879214200,
+                          "odd_width_8192xN_fp16_res32[N=1000]": 99665000}
+
+
+def pick_workload(W, name):
+    if name == "prefill":
+        return W.PREFILL
+    if name == "large_prefill":
+        return W.LARGE_PREFILL
+    if name.startswith("odd_width_") and int(name[10:]) in W.ODD_WIDTH_N:
+        return W.ODD_WIDTH.with_cols(int(name[10:]))
+    if name.startswith("decode_") and int(name[7:]) in W.DECODE_M:
+        return W.DECODE.with_rows(int(name[7:]))
+    print(f"unknown workload {name}", file=sys.stderr)
+    sys.exit(2)
 
 
 def parse_args():
@@ -52,6 +67,10 @@ def parse_args():
     ap.add_argument("--cfg", default=None,
                     help="skip the search and time this configuration: vec,threads_per_row,rows_per_wg,reduce,unroll,"
                          "flags,max_waves_per_simd (used for profiler runs, whose overhead would mislead the search)")
+    ap.add_argument("--workload", default="prefill",
+                    help="addrms workload: prefill (default; the configuration the headline metric is quoted on), "
+                         "large_prefill, odd_width_5120, odd_width_2880, odd_width_1000 or decode_<M>; the others "
+                         "serve profiling and the report, not the headline")
     ap.add_argument("--op", default="addrms", choices=("addrms", "silumul", "mergestates"),
                     help="operator to time (default: the fused add+RMSNorm hot path)")
     ap.add_argument("--probe", action="store_true",
@@ -157,7 +176,7 @@ def cpu_baseline(W, wl, d, nbytes):
 def make_sets(torch, B, W, wl, d, dtype_id):
     """Resident inputs, rotated so that each step misses the last-level cache."""
     set_bytes = wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
-    nsets = max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // set_bytes))
+    nsets = min(256, max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // set_bytes)))
     pool, xs, rs = carve_sets(torch, wl, W, nsets)
     w = d["w"].cuda()
     x0, r0 = d["x"].cuda(), d["r"].cuda()
@@ -326,7 +345,7 @@ def main():
             sys.exit(2)
         run_other_op(a, torch, lib, B, W)
         return
-    wl = W.PREFILL
+    wl = pick_workload(W, a.workload)
     dtype_id = B.DTYPE_IDS[wl.dtype]
     nbytes = B.addrms_algorithmic_bytes(wl.M, wl.N, wl.dtype)
     d = W.generate(wl)
@@ -389,7 +408,7 @@ def main():
                  "time_to_best_ms": round(rep.time_to_best_ms, 2), "best_us": round(rep.best_us, 3),
                  "default_us": round(rep.default_us, 3)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "kernel_us": round(kernel_us, 3), "algorithmic_bytes": nbytes},
     }
     if not a.no_cpu_baseline:
