@@ -260,3 +260,45 @@ def test_exact_invariants_hold_on_the_device():
     y3, r3 = _run_raw(x * 2.0 ** k, r * 2.0 ** k, w, eps * 4.0 ** k, "bf16")
     assert np.array_equal(y3, y0)
     assert np.array_equal(r3[nz], (r0 + np.uint16(k << 7))[nz])
+
+
+def test_run_is_reentrant_across_host_threads(oracle):
+    """Four host threads, each with its own stream, shape, storage format and cfg, call
+    addrms_run (and the error path) concurrently; every result must match the oracle."""
+    import threading
+
+    jobs = [(_wl(257, 4096, "bf16", 81), None), (_wl(64, 8192, "fp16", 82), B.make_cfg(8, 512, 2, flags=2)),
+            (_wl(500, 1000, "fp16_res32", 83), B.make_cfg(4, 128, 2, unroll=2)), (_wl(33, 5120, "fp32", 84), None)]
+    prepared = []
+    for wl, cfg in jobs:
+        d = W.generate(wl)
+        prepared.append((wl, cfg, DeviceCase(d, wl), oracle_outputs(oracle, d, wl), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(wl, cfg, case, stream):
+        try:
+            lib = B.load()
+            for _ in range(50):
+                with torch.cuda.stream(stream):
+                    case.x.copy_(case.x0, non_blocking=True)
+                    case.r.copy_(case.r0, non_blocking=True)
+                    B.addrms_run(case.x, case.r, case.w, wl.eps, wl.M, wl.N, wl.dtype, cfg, stream=stream)
+                # an argument error on this thread must not disturb the others (thread-local message)
+                st = lib.addrms_run(None, None, None, 1e-6, 1, wl.N, B.DTYPE_IDS[wl.dtype], None, None)
+                if st != B.ERR_INVALID_ARG or "NULL" not in B.addrms_last_error():
+                    errors.append(f"{wl.name}: error path returned {st}: {B.addrms_last_error()}")
+            stream.synchronize()
+        except Exception as e:                      # noqa: BLE001 - reported below
+            errors.append(f"{wl.name}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(wl, cfg, case, s)) for wl, cfg, case, _, s in prepared]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for wl, cfg, case, (y_ref, res_ref), _ in prepared:
+        st = compare(W.to_bits(case.x), W.to_bits(case.r), y_ref, res_ref, wl.dtype, f"threaded {wl.name}")
+        assert st["n_diff"] == 0
