@@ -89,7 +89,11 @@ typedef struct addrms_cfg {
  *   stream   a hipStream_t passed as void*; NULL = the default stream
  * Never synchronises, never allocates device memory.  Arguments are checked
  * before anything is launched (Section 3.3: invalid launches are pruned, not
- * attempted).  x, residual and weight must not overlap.  Re-entrant.
+ * attempted).  x, residual and weight must not overlap.  Re-entrant: host threads
+ * may call it concurrently on their own streams.  It can be recorded into a HIP
+ * graph (stream capture); the first launch of a cfg whose occupancy cap pads the
+ * LDS allocation beyond 64 KiB raises that kernel's dynamic-LDS limit once per
+ * process, so issue one such launch eagerly before capturing.
  */
 int addrms_run(void* x, void* residual, const void* weight, float eps,
                int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, void* stream);
