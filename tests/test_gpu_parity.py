@@ -302,3 +302,31 @@ def test_run_is_reentrant_across_host_threads(oracle):
     for wl, cfg, case, (y_ref, res_ref), _ in prepared:
         st = compare(W.to_bits(case.x), W.to_bits(case.r), y_ref, res_ref, wl.dtype, f"threaded {wl.name}")
         assert st["n_diff"] == 0
+
+
+def test_random_shapes_and_cfgs(oracle):
+    """Seeded random sweep: row lengths of every parity class (odd, 2, 4, 8 mod 16, ...), row counts that
+    leave ragged last workgroups, all four storage formats; per shape the default and six random feasible cfgs."""
+    rng = np.random.default_rng(20260112)
+    n_cases = 0
+    for k in range(48):
+        dtype = W.DTYPES[k % 4]
+        N = int(rng.choice([rng.integers(8, 200), rng.integers(200, 3000), 8 * rng.integers(64, 1200),
+                            rng.integers(3000, 12000)]))
+        M = int(rng.integers(1, 70))
+        try:
+            B.addrms_default_cfg(N, dtype)
+        except B.AddrmsError:
+            continue
+        cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
+        assert cfgs, (M, N, dtype)
+        wl = _wl(M, N, dtype, 1000 + k, x_std=float(rng.choice([0.01, 1.0, 30.0])), r_std=float(rng.choice([0.5, 2.0])))
+        d = W.generate(wl)
+        case = DeviceCase(d, wl)
+        y_ref, res_ref = oracle_outputs(oracle, d, wl)
+        picks = [None] + [cfgs[int(i)] for i in rng.integers(0, len(cfgs), 6)]
+        for c in picks:
+            y, res = case.run(c)
+            assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0
+            n_cases += 1
+    assert n_cases > 250
