@@ -57,8 +57,11 @@ enum { ADDRMS_REDUCE_WAVE = 0,   /* wave64 cross-lane butterfly, one LDS hop acr
        ADDRMS_REDUCE_LDS = 1 };  /* LDS-staged tree reduction                             */
 enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguous row range       */
        ADDRMS_FLAG_NONTEMPORAL = 2,   /* streaming cache policy on x/residual loads and stores    */
-       ADDRMS_FLAG_PERSISTENT = 4 };  /* grid = resident workgroups only; each walks several row
+       ADDRMS_FLAG_PERSISTENT = 4,    /* grid = resident workgroups only; each walks several row
                                          blocks and prefetches the next block before reducing   */
+       ADDRMS_FLAG_TWO_PASS = 8 };    /* rows too long for the register row cache: read the row
+                                         twice (sum of squares, then outputs); feasible only
+                                         where no single-pass configuration covers N            */
 
 typedef struct addrms_cfg {
     int32_t vec;              /* elements per thread per vector access: 1, 2, 4, 8        */
@@ -80,9 +83,11 @@ typedef struct addrms_cfg {
  *   weight   device, [N], x dtype, read only
  *   eps      added to the mean of squares
  *   M, N     rows, row length.  M == 0 is a successful no-op; N <= 0 is INVALID_ARG;
- *            a row is held in registers between its two passes, so N is bounded
- *            (1024 threads x 32 cached values, at most 16 accesses per thread):
- *            even N up to 32768, odd N up to 16384; beyond that UNSUPPORTED_SHAPE
+ *            a row is held in registers between the reduction and the scaling
+ *            (1024 threads x 32 cached values, at most 16 accesses per thread:
+ *            even N up to 32768, odd N up to 16384); longer rows, up to 2^28
+ *            elements, run in the two-pass form (ADDRMS_FLAG_TWO_PASS), which the
+ *            default configuration selects by itself; beyond that UNSUPPORTED_SHAPE
  *   dtype    addrms_dtype
  *   cfg      host; NULL = look (M, N, dtype) up in the specialised table
  *            (nearest tuned M for the same N and dtype), else the default cfg
@@ -290,8 +295,9 @@ int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int d
  * The deriver prunes two kinds of configurations: invalid ones (a launch the hardware
  * or the compiled instance cannot take) and ones it calls obviously inefficient (at
  * most half the lanes of a row carrying data; fewer than two resident waves per SIMD;
- * an instance that spills registers).  The second kind is a judgement, and this call
- * puts it to the test: it enumerates the grid with those three rules switched off,
+ * an instance that spills registers; the two-pass form where a single pass would do).
+ * The second kind is a judgement, and this call puts it to the test: it enumerates
+ * the grid with those four rules switched off,
  * passes both the retained configurations and the ones each rule would have pruned
  * through the correctness gate and the screening protocol (budget.coarse_warmup /
  * coarse_reps, default 3 + 15 launches), and reports per rule how the pruned ones
@@ -301,9 +307,9 @@ int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int d
  * sample; 0 = all); budget.max_wall_ms stops early (truncated = 1).  Nothing is added
  * to the table, and addrms_run still refuses the pruned configurations.  Blocking;
  * allocates and frees device memory. */
-#define ADDRMS_AUDIT_RULES 3
+#define ADDRMS_AUDIT_RULES 4
 typedef struct addrms_audit_rule {
-    char    rule[24];          /* "lane_utilisation", "occupancy_floor", "scratch"                     */
+    char    rule[24];          /* "lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless" */
     int64_t n_pruned;          /* grid points this rule alone keeps out of the feasible region         */
     int32_t n_measured;        /* of those, validated and timed                                        */
     int32_t n_failed;          /* of those, failed the gate or the launch                              */

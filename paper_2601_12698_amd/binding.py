@@ -25,6 +25,7 @@ REDUCE_WAVE, REDUCE_LDS = 0, 1
 FLAG_XCD_CONTIG = 1
 FLAG_NONTEMPORAL = 2
 FLAG_PERSISTENT = 4
+FLAG_TWO_PASS = 8
 SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
 FAMILY_STREAMING, FAMILY_OCCUPANCY_CAP, FAMILY_GRID_MAPPING, FAMILY_BASE_ONLY = 1, 2, 4, 8
 MAX_ROUNDS = 4
@@ -174,7 +175,7 @@ class RoundsReport(Structure):
                     best=self.best.as_dict())
 
 
-AUDIT_RULES = 3
+AUDIT_RULES = 4
 
 
 class AuditRule(Structure):

@@ -219,6 +219,21 @@ static Feas infeasible(const char* rule, const char* fmt, ...)
     return f;
 }
 
+// True if the single-pass form has a default configuration for rows of N elements, i.e. if
+// some launch shape holds such a row in its register cache and passes every rule.
+static bool single_pass_default(int64_t N, int dtype, int op, addrms_cfg* out);
+static bool single_pass_covers(int64_t N, int dtype, int op)
+{
+    static thread_local int64_t last_n = -1;
+    static thread_local int last_dt = -1, last_op = -1;
+    static thread_local bool last = false;
+    if (N == last_n && dtype == last_dt && op == last_op) return last;
+    addrms_cfg unused{};
+    const bool found = single_pass_default(N, dtype, op, &unused);
+    last_n = N; last_dt = dtype; last_op = op; last = found;
+    return found;
+}
+
 Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int relax)
 {
     const HwLimits& L = hw();
@@ -245,7 +260,13 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     if (op != OP_ADDRMS && c.reduce != 0)
         return infeasible("grid", "reduce=%d: %s has no reduction; the knob must stay 0", c.reduce, op_name(op));
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
-    if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT)) return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
+    if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT | ADDRMS_FLAG_TWO_PASS))
+        return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
+    const bool two_pass = (c.flags & ADDRMS_FLAG_TWO_PASS) != 0;
+    if (two_pass && op != OP_ADDRMS)
+        return infeasible("grid", "flags=0x%x: only add+RMSNorm has a two-pass form", c.flags);
+    if (two_pass && (c.flags & ADDRMS_FLAG_PERSISTENT))
+        return infeasible("grid", "flags=0x%x: the two-pass form has no persistent grid", c.flags);
     if (c.max_waves_per_simd < 0 || c.max_waves_per_simd >= L.max_waves_per_simd)
         return infeasible("grid", "max_waves_per_simd=%d: must be 0 (no cap) or 1..%d", c.max_waves_per_simd,
                           L.max_waves_per_simd - 1);
@@ -270,15 +291,25 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
         return infeasible("whole_waves", "workgroup of %d threads is not a whole number of %d-lane waves: the cross-lane reduction "
                           "needs full waves", threads, L.wave_size);
 
-    // -- register row cache: the row slice of a thread must fit in registers
+    // -- register row cache: the row slice of a thread must fit in registers (single-pass form)
     const int64_t per_pass = static_cast<int64_t>(c.vec) * c.threads_per_row;
     const int64_t need = (N + per_pass - 1) / per_pass;
-    if (need * c.vec > kMaxElemsPerThread)
+    if (two_pass) {
+        if (N * c.rows_per_wg > kMaxTwoPassElemsPerWg)
+            return infeasible("row_too_long", "N=%lld x rows_per_wg=%d exceeds the %lld elements a workgroup addresses with "
+                              "32-bit offsets", (long long)N, c.rows_per_wg, (long long)kMaxTwoPassElemsPerWg);
+        if (single_pass_covers(N, dtype, op)) {
+            if (!(relax & RELAX_TWO_PASS_NEEDLESS))
+                return infeasible("two_pass_needless", "N=%lld fits the register row cache of a single-pass configuration: "
+                                  "reading every row twice is obviously inefficient", (long long)N);
+            if (!f.soft_rule[0]) f.soft_rule = "two_pass_needless";
+        }
+    } else if (need * c.vec > kMaxElemsPerThread)
         return infeasible("row_cache", "N=%lld over %d threads at vec=%d needs %lld values per thread in registers; the row cache "
                           "holds %d (more would spill or leave under %d waves per SIMD)",
                           (long long)N, c.threads_per_row, c.vec, (long long)(need * c.vec), kMaxElemsPerThread,
                           kMinWavesPerSimd);
-    if (!cpt_supported(op, static_cast<int>(need)))
+    if (!two_pass && !cpt_supported(op, static_cast<int>(need)))
         return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (%s)", (long long)need,
                           op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : op == OP_MERGE ? "1-4 exist" : "1-8 exist");
     f.res.chunks_per_thread = static_cast<int>(need);
@@ -300,7 +331,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                           2 * L.xcds);
 
     // -- compiled instance and its resources
-    const int idx = find_instance(op, dtype, c.vec, static_cast<int>(need), c.unroll,
+    const int idx = find_instance(op, dtype, c.vec, two_pass ? 0 : static_cast<int>(need), c.unroll,
                                   (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0);
     if (idx < 0)
         return infeasible("no_instance", "no compiled instance for dtype=%s vec=%d chunks=%lld unroll=%d", dtype_name(dtype), c.vec,
@@ -373,7 +404,7 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
             for (int rows : kRows)
                 for (int red = 0; red < 2; ++red)
                     for (int unr : kUnrolls)
-                        for (int flags = 0; flags < 8; ++flags)
+                        for (int flags = 0; flags < 16; ++flags)
                             for (int cap = 0; cap < hw().max_waves_per_simd; ++cap) {
                                 ++grid;
                                 addrms_cfg c{};
@@ -386,10 +417,8 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
     if (n_grid) *n_grid = grid;
 }
 
-int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op)
+static bool single_pass_default(int64_t N, int dtype, int op, addrms_cfg* out)
 {
-    if (!dtype_valid(dtype, op)) { if (why) *why = "unsupported dtype"; return ADDRMS_ERR_UNSUPPORTED_DTYPE; }
-    if (N <= 0) { if (why) *why = "N must be > 0"; return ADDRMS_ERR_INVALID_ARG; }
     // Preference order: widest vector; 256 threads per row, then wider, then
     // narrower rows; one row per workgroup (more only to fill a wave).
     static const int tprs[] = {256, 512, 1024, 384, 768, 128, 192, 320, 448, 576, 640, 704, 832, 896, 960,
@@ -403,6 +432,22 @@ int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op)
             c.reduce = ADDRMS_REDUCE_WAVE;
             const int64_t need = (N + static_cast<int64_t>(vec) * tpr - 1) / (static_cast<int64_t>(vec) * tpr);
             c.unroll = need >= 2 ? 2 : 1;
+            if (check_cfg(c, big_m, N, dtype, op).status == ADDRMS_OK) { *out = c; return true; }
+        }
+    return false;
+}
+
+int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op)
+{
+    if (!dtype_valid(dtype, op)) { if (why) *why = "unsupported dtype"; return ADDRMS_ERR_UNSUPPORTED_DTYPE; }
+    if (N <= 0) { if (why) *why = "N must be > 0"; return ADDRMS_ERR_INVALID_ARG; }
+    const int64_t big_m = 1 << 20;
+    if (single_pass_default(N, dtype, op, out)) return ADDRMS_OK;
+    if (op == OP_ADDRMS)   // rows beyond the register cache: the two-pass form, widest vector, largest workgroup
+        for (int vec : kVecs) {
+            addrms_cfg c{};
+            c.vec = vec; c.threads_per_row = hw().max_threads_per_wg; c.rows_per_wg = 1;
+            c.reduce = ADDRMS_REDUCE_WAVE; c.unroll = 2; c.flags = ADDRMS_FLAG_TWO_PASS;
             if (check_cfg(c, big_m, N, dtype, op).status == ADDRMS_OK) { *out = c; return ADDRMS_OK; }
         }
     if (why) {

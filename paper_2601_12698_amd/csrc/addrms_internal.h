@@ -37,6 +37,7 @@ const HwLimits& hw();
 // Floors below which a launch shape is pruned as obviously inefficient.
 constexpr int kMinWavesPerSimd = 2;
 constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
+constexpr int64_t kMaxTwoPassElemsPerWg = 1ll << 28;   // two-pass form: rows_per_wg * N elements, 32-bit byte offsets
 
 // ---- operators that go through the tuner ------------------------------------
 enum Op : int { OP_ADDRMS = 0, OP_SILUMUL = 1, OP_MERGE = 2 };
@@ -66,7 +67,8 @@ const char* dtype_name(int dtype);
 // Efficiency rules that an audit may switch off to measure what they prune.  Rules that
 // keep a launch valid (sizes, alignment, instance limits, LDS, at least one workgroup per
 // CU) and rules that only remove duplicates of another cfg can never be switched off.
-enum Relax : int { RELAX_LANE_UTILISATION = 1, RELAX_OCCUPANCY_FLOOR = 2, RELAX_SCRATCH = 4, RELAX_ALL = 7 };
+enum Relax : int { RELAX_LANE_UTILISATION = 1, RELAX_OCCUPANCY_FLOOR = 2, RELAX_SCRATCH = 4, RELAX_TWO_PASS_NEEDLESS = 8,
+                   RELAX_ALL = 15 };
 
 struct Feas {
     int status = ADDRMS_OK;

@@ -35,7 +35,7 @@ namespace addrms {
 
 enum : int { DT_BF16 = 0, DT_FP16 = 1, DT_FP16_RES32 = 2, DT_FP32 = 3 };
 enum : int { RED_WAVE = 0, RED_LDS = 1 };
-enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u, FLAG_PERSISTENT = 4u };
+enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u, FLAG_PERSISTENT = 4u, FLAG_TWO_PASS = 8u };
 
 template <int DT> struct dt_traits;
 template <> struct dt_traits<DT_BF16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = true;  };
@@ -412,6 +412,106 @@ __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restr
         ra = rn;
         blk = next;
         parity ^= 1u;
+    }
+}
+
+// Two-pass form for rows that do not fit the register row cache.  Pass 1 reads the
+// row and accumulates the sum of squares; pass 2 reads it again, recomputes the same
+// fp32 sums, and writes both outputs.  Nothing is written before the whole row has
+// been summed, and every element is re-read and written by the lane that summed it,
+// so the in-place update is safe.  Pass 1 loads with the default cache policy so that
+// the second read of a row can be served from the L2 it was just pulled through;
+// NT selects the streaming policy for the pass-2 loads (last use) and the stores.
+// UNR chunks per stream are in flight per loop iteration.  The loop count is uniform
+// over the workgroup; lanes past the end of the row are predicated off (N is a
+// multiple of VEC, so a chunk is either wholly inside the row or wholly outside).
+template <int DT, int VEC, int UNR, bool NT>
+__device__ __forceinline__ void addrms_twopass_body(void* __restrict__ xp, void* __restrict__ rp,
+                                                    const void* __restrict__ wp, float eps, double inv_n,
+                                                    int64_t M, int32_t N, uint32_t flags, int32_t reduce,
+                                                    uint32_t nblocks)
+{
+    using T = dt_traits<DT>;
+    constexpr int XB = T::XB, RB = T::RB;
+    constexpr bool BF = T::BF;
+    extern __shared__ double lds[];
+    (void)nblocks;
+
+    const uint32_t tpr = blockDim.x, rpw = blockDim.y;
+    const uint32_t lane = threadIdx.x, ry = threadIdx.y;
+    uint32_t blk = blockIdx.x;
+    if (flags & FLAG_XCD_CONTIG) blk = xcd_contiguous(blk, gridDim.x);
+
+    const RowAddr ra = row_addr<XB, RB>(xp, rp, blk, rpw, ry, M, N);
+    const char* wbase = static_cast<const char*>(wp);
+    const uint32_t n = static_cast<uint32_t>(N);
+    const uint32_t stride = tpr * VEC;
+    const uint32_t span = stride * UNR;                        // elements of a row covered per iteration
+    const uint32_t iters = (n + span - 1u) / span;
+    const uint32_t col_first = lane * VEC;
+
+    double acc = 0.0;
+    for (uint32_t it = 0; it < iters; ++it) {
+        raw_t<XB * VEC> xv[UNR];
+        raw_t<RB * VEC> rv[UNR];
+        const uint32_t col0 = col_first + it * span;
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + static_cast<uint32_t>(u) * stride;
+            if (col < n) {
+                ld_raw<XB * VEC, false>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), xv[u]);
+                ld_raw<RB * VEC, false>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), rv[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + static_cast<uint32_t>(u) * stride;
+            if (ra.row_ok && col < n) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float h = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                    const double hd = static_cast<double>(h);
+                    acc = __builtin_fma(hd, hd, acc);
+                }
+            }
+        }
+    }
+
+    const double ss = row_sum(acc, reduce, tpr, lane, ry, lds);
+    const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
+
+    for (uint32_t it = 0; it < iters; ++it) {
+        raw_t<XB * VEC> xv[UNR], wv[UNR];
+        raw_t<RB * VEC> rv[UNR];
+        const uint32_t col0 = col_first + it * span;
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + static_cast<uint32_t>(u) * stride;
+            if (col < n) {
+                ld_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), xv[u]);
+                ld_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), rv[u]);
+                ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(col * XB), wv[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + static_cast<uint32_t>(u) * stride;
+            if (ra.row_ok && col < n) {
+                float h[VEC], y[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    h[e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                    const float t = h[e] * rstd;
+                    y[e] = t * get_elem<XB, BF>(wv[u], e);
+                }
+                raw_t<RB * VEC> rout;
+                pack_vec<RB, BF, VEC>(h, rout);
+                st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), rout);
+                raw_t<XB * VEC> yout;
+                pack_vec<XB, BF, VEC>(y, yout);
+                st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), yout);
+            }
+        }
     }
 }
 

@@ -148,7 +148,8 @@ struct Searcher {
                 if (!(c.flags & ADDRMS_FLAG_PERSISTENT) || !(c.flags & ADDRMS_FLAG_NONTEMPORAL)) continue;
                 score = -threads - 0.1 * c.unroll - ((c.flags & ADDRMS_FLAG_XCD_CONTIG) ? 0.01 : 0.0);
             } else {
-                if (c.flags != (mode == kPlain ? 0 : ADDRMS_FLAG_NONTEMPORAL)) continue;
+                // (the two-pass bit is the same for every feasible cfg of a shape: ignore it here)
+                if ((c.flags & ~ADDRMS_FLAG_TWO_PASS) != (mode == kPlain ? 0 : ADDRMS_FLAG_NONTEMPORAL)) continue;
                 const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
                 score = fabs(log2(threads / 256.0)) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
                 if (mode == kCapped) score += 0.5 * fabs(static_cast<double>(c.max_waves_per_simd) - 4.0);

@@ -1,7 +1,9 @@
 """Writes the instantiation list of the kernel template.
 
 The templates in ``addrms_kernel.h`` and ``silumul_kernel.h`` have four
-compile-time knobs (VEC, CPT, UNR, NT) per storage format.  This script emits,
+compile-time knobs (VEC, CPT, UNR, NT) per storage format.  CPT = 0 names the
+two-pass form of add+RMSNorm, which loops over the row instead of caching it
+(rows beyond the register row cache).  This script emits,
 into a build directory:
 
   kern_<op>_d<DT>_v<VEC>.hip  one translation unit per (operator, format, vector width),
@@ -55,6 +57,10 @@ def instances():
                         maxt = 1024 if vec * cpt <= BIG_ELEMS else 256
                         for nt in (0, 1):
                             yield op, dt, vec, cpt, unr, nt, maxt
+                if op == OP_ADDRMS:                  # two-pass form: no row cache, any row length
+                    for unr in UNRS:
+                        for nt in (0, 1):
+                            yield op, dt, vec, 0, unr, nt, 1024
 
 
 def name(op, dt, vec, cpt, unr, nt):
@@ -74,6 +80,7 @@ CALL = {
     OP_MERGE: ("addrms::mergestates_body<{dt}, {vec}, {cpt}, {unr}, {nt}>"
                "(va, sa, vb, sb, vo, so, rows, d, flags, nblocks);"),
 }
+TWO_PASS_CALL = "addrms::addrms_twopass_body<{dt}, {vec}, {unr}, {nt}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);"
 HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h", OP_MERGE: "mergestates_kernel.h"}
 
 
@@ -85,7 +92,8 @@ def main(outdir: str) -> None:
     for (op, dt, vec), lst in units.items():
         lines = [f'#include "{HEADER[op]}"', ""]
         for cpt, unr, nt, maxt in lst:
-            call = CALL[op].format(dt=dt, vec=vec, cpt=cpt, unr=unr, nt="true" if nt else "false")
+            fmt = TWO_PASS_CALL if (op == OP_ADDRMS and cpt == 0) else CALL[op]
+            call = fmt.format(dt=dt, vec=vec, cpt=cpt, unr=unr, nt="true" if nt else "false")
             lines.append(f'extern "C" __global__ __launch_bounds__({maxt}) void {name(op, dt, vec, cpt, unr, nt)}'
                          f"({ARGS[op]})\n{{ {call} }}")
         _write(os.path.join(outdir, f"kern_{OP_PREFIX[op]}_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")

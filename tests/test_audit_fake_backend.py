@@ -21,13 +21,14 @@ def _util(c):
 
 
 def _honest_cost(c, _w, _r):
-    """Idle lanes cost time; nothing pruned can win."""
-    return 10.0 / _util(c) + 0.01 * c.rows_per_wg + (0.5 if c.reduce else 0.0)
+    """Idle lanes cost time and so does reading a row twice; nothing pruned can win."""
+    t = 10.0 / _util(c) + 0.01 * c.rows_per_wg + (0.5 if c.reduce else 0.0)
+    return t * (1.5 if c.flags & B.FLAG_TWO_PASS else 1.0)
 
 
 def test_struct_sizes():
     assert ctypes.sizeof(B.AuditRule) == 96
-    assert ctypes.sizeof(B.AuditReport) == 88 + 3 * 96
+    assert ctypes.sizeof(B.AuditReport) == 88 + B.AUDIT_RULES * 96 and B.AUDIT_RULES == 4
 
 
 def test_classes_partition_the_relaxed_grid():
@@ -36,7 +37,7 @@ def test_classes_partition_the_relaxed_grid():
     strict, _ = B.addrms_enumerate_feasible(M, N, DT)
     assert rep.n_retained == len(strict) == rep.n_retained_measured
     names = [r.rule.decode() for r in rep.rules]
-    assert names == ["lane_utilisation", "occupancy_floor", "scratch"]
+    assert names == ["lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless"]
     lane = rep.rules[0]
     assert lane.n_pruned > 0 and lane.n_measured == lane.n_pruned
     assert len(seen) == len(set(seen)) == rep.n_retained + sum(r.n_measured for r in rep.rules)
@@ -44,7 +45,8 @@ def test_classes_partition_the_relaxed_grid():
     strict_set = {c.as_tuple() for c in strict}
     extra = [t for t in seen if t not in strict_set]
     assert len(extra) == sum(r.n_pruned for r in rep.rules)
-    words = {"lane_utilisation": "lane slots", "occupancy_floor": "wave per SIMD", "scratch": "spills"}
+    words = {"lane_utilisation": "lane slots", "occupancy_floor": "wave per SIMD", "scratch": "spills",
+             "two_pass_needless": "reading every row twice"}
     n_lane = 0
     for t in extra[::17]:
         st, why, _ = B.addrms_cfg_feasible(B.make_cfg(*t), M, N, DT)
@@ -107,7 +109,7 @@ def test_budget_caps_each_class_and_wall_time_truncates():
         time.sleep(0.002)
         return _honest_cost(c, w, r)
 
-    rep = B.addrms_audit_rules_with_backend(M, N, DT, B.make_budget(max_wall_ms=60.0), slow)
+    rep = B.addrms_audit_rules_with_backend(M, N, DT, B.make_budget(max_wall_ms=400.0), slow)
     assert rep.truncated and rep.n_retained_measured < rep.n_retained
 
 
@@ -117,5 +119,5 @@ def test_bad_arguments():
     with pytest.raises(B.AddrmsError):
         B.addrms_audit_rules_with_backend(M, N, 9, None, _honest_cost)
     with pytest.raises(B.AddrmsError) as e:
-        B.addrms_audit_rules_with_backend(4, 32776, "bf16", None, _honest_cost)
+        B.addrms_audit_rules_with_backend(4, (1 << 28) + 8, "bf16", None, _honest_cost)
     assert e.value.status == B.ERR_UNSUPPORTED_SHAPE

@@ -67,7 +67,8 @@ def test_bad_shape_and_dtype_codes():
                                        (8192, 1000, "fp16_res32"), (8192, 2880, "fp16_res32"), (128, 11008, "fp32")])
 def test_enumeration_is_exactly_the_feasible_subset(M, N, dtype):
     cfgs, grid = B.addrms_enumerate_feasible(M, N, dtype)
-    assert grid == 4 * 19 * 5 * 2 * 4 * 8 * 8
+    assert grid == 4 * 19 * 5 * 2 * 4 * 16 * 8          # vec, threads/row, rows/wg, reduce, unroll, 4 flag bits, cap
+    assert not any(c.flags & B.FLAG_TWO_PASS for c in cfgs)   # these rows fit the register cache
     assert 0 < len(cfgs) < grid
     seen = set()
     for c in cfgs:
@@ -119,8 +120,12 @@ def test_occupancy_model_matches_compiler_report():
             # an instance that spills is pruned by the deriver whenever a cfg selects it
             dt, vec, cpt, unr, nt = (int(g) for g in m.groups())
             dtype = ["bf16", "fp16", "fp16_res32", "fp32"][dt]
-            c = B.make_cfg(vec, 64, 1, unroll=unr, flags=B.FLAG_NONTEMPORAL if nt else 0)
-            st, why, _ = feas(c, 4096, vec * 64 * cpt, dtype)
+            if cpt == 0:       # two-pass instance: selected by the flag, for a row beyond the register cache
+                c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_TWO_PASS | (B.FLAG_NONTEMPORAL if nt else 0))
+                st, why, _ = feas(c, 4096, vec * 1024 * 40, dtype)
+            else:
+                c = B.make_cfg(vec, 64, 1, unroll=unr, flags=B.FLAG_NONTEMPORAL if nt else 0)
+                st, why, _ = feas(c, 4096, vec * 64 * cpt, dtype)
             assert st == B.ERR_INFEASIBLE_CFG and "spills" in why, (name, why)
             spilled += 1
     assert checked >= 1000 and spilled < 0.02 * checked
@@ -159,21 +164,41 @@ def test_default_cfg():
         assert d.reduce == B.REDUCE_WAVE and d.flags == 0 and d.max_waves_per_simd == 0
     d = B.addrms_default_cfg(4096, "bf16")
     assert d.as_tuple() == (8, 256, 1, 0, 2, 0, 0)
-    assert B.load().addrms_default_cfg(1 << 20, B.BF16, B.Cfg()) == B.ERR_UNSUPPORTED_SHAPE
+    assert B.load().addrms_default_cfg(1 << 30, B.BF16, B.Cfg()) == B.ERR_UNSUPPORTED_SHAPE
     assert "row cache" in B.addrms_last_error()
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16", "fp16_res32", "fp32"])
 def test_row_length_bound_of_the_register_cache(dtype):
-    """1024 threads x 32 cached values, at most 16 accesses per thread: even N up to
-    32768 and odd N up to 16384 have a configuration; one past either bound has none."""
+    """1024 threads x 32 cached values, at most 16 accesses per thread: even N up to 32768 and
+    odd N up to 16384 run in the single-pass form; one past either bound, and up to 2^28
+    elements, only the two-pass form is feasible; beyond that nothing is."""
     for N in (32768, 32766, 32764, 16383, 16381):
         c = B.addrms_default_cfg(N, dtype)
+        assert not c.flags & B.FLAG_TWO_PASS
         assert N % c.vec == 0 and c.threads_per_row * c.vec * 16 >= N
         st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
         assert st == 0, why
         assert res.chunks_per_thread * c.vec <= 64 and res.scratch_bytes == 0
-    for N in (32767, 32770, 16385, 65536):
+        two = B.make_cfg(c.vec, 1024, 1, unroll=2, flags=B.FLAG_TWO_PASS)
+        st, why, _ = B.addrms_cfg_feasible(two, 4, N, dtype)
+        assert st == B.ERR_INFEASIBLE_CFG and "reading every row twice" in why
+    for N in (32767, 32770, 16385, 65536, 1 << 20, 1 << 28):
+        c = B.addrms_default_cfg(N, dtype)
+        assert c.flags == B.FLAG_TWO_PASS and N % c.vec == 0 and c.threads_per_row == 1024 and c.rows_per_wg == 1
+        st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
+        assert st == 0, why
+        assert res.chunks_per_thread == -(-N // (c.vec * 1024)) and res.scratch_bytes == 0
+    for N in (65536, 100001):
+        cfgs, _ = B.addrms_enumerate_feasible(4, N, dtype)
+        assert cfgs and all(c.flags & B.FLAG_TWO_PASS and not c.flags & B.FLAG_PERSISTENT for c in cfgs)
+        one = B.make_cfg(cfgs[0].vec, 1024, 1)
+        st, why, _ = B.addrms_cfg_feasible(one, 4, N, dtype)
+        assert st == B.ERR_INFEASIBLE_CFG and ("row cache" in why or "compiled for workgroups" in why), why
+    # a workgroup addresses rows_per_wg * N elements with 32-bit byte offsets
+    st, why, _ = B.addrms_cfg_feasible(B.make_cfg(1, 64, 2, flags=B.FLAG_TWO_PASS), 4, (1 << 28) - 1, dtype)
+    assert st == B.ERR_INFEASIBLE_CFG and "32-bit offsets" in why
+    for N in ((1 << 28) + 8, 1 << 30):
         with pytest.raises(B.AddrmsError) as e:
             B.addrms_default_cfg(N, dtype)
         assert e.value.status == B.ERR_UNSUPPORTED_SHAPE

@@ -108,16 +108,36 @@ def test_widest_rows_the_template_covers(oracle, dtype, M, N):
         assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0
 
 
-@pytest.mark.parametrize("dtype,N", [("bf16", 32767), ("bf16", 32776), ("fp32", 16385), ("fp16", 65536)])
-def test_rows_beyond_the_template_are_refused_before_launch(dtype, N):
-    xb, rb = W.x_bytes(dtype), W.r_bytes(dtype)
-    x = torch.full((2 * N * xb,), 0x3C, dtype=torch.uint8, device="cuda")
-    r = torch.full((2 * N * rb,), 0x3C, dtype=torch.uint8, device="cuda")
-    w = torch.zeros(N * xb, dtype=torch.uint8, device="cuda")
-    st = B.load().addrms_run(x.data_ptr(), r.data_ptr(), w.data_ptr(), 1e-6, 2, N, B._dtype_id(dtype), None, None)
+def test_rows_beyond_the_template_are_refused_before_launch():
+    """Rows longer than 2^28 elements have no configuration: the call fails before anything is launched."""
+    N, dtype = (1 << 28) + 8, "bf16"
+    x = torch.full((N * 2,), 0x3C, dtype=torch.uint8, device="cuda")
+    r = torch.full((N * 2,), 0x3C, dtype=torch.uint8, device="cuda")
+    w = torch.zeros(N * 2, dtype=torch.uint8, device="cuda")
+    st = B.load().addrms_run(x.data_ptr(), r.data_ptr(), w.data_ptr(), 1e-6, 1, N, B._dtype_id(dtype), None, None)
     assert st == B.ERR_UNSUPPORTED_SHAPE, B.addrms_last_error()
     torch.cuda.synchronize()
     assert bool((x == 0x3C).all()) and bool((r == 0x3C).all())
+
+
+@pytest.mark.parametrize("dtype,M,N", [("bf16", 5, 32770), ("bf16", 3, 65536), ("fp16", 4, 40001), ("fp16_res32", 3, 49152),
+                                       ("fp32", 2, 100000), ("bf16", 37, 36864), ("fp32", 1, 1 << 20)])
+def test_two_pass_form_for_rows_beyond_the_register_cache(oracle, dtype, M, N):
+    """Rows that no single-pass configuration holds run in the two-pass form (read, sum, read again,
+    write).  Same arithmetic, same bar: bit-identical to the oracle over a spread of its configurations."""
+    wl = _wl(M, N, dtype, 1200 + N % 89)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    dflt = B.addrms_default_cfg(N, dtype)
+    assert dflt.flags & B.FLAG_TWO_PASS
+    cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
+    assert cfgs and all(c.flags & B.FLAG_TWO_PASS for c in cfgs)
+    print(f"{wl.name}: {len(cfgs)} feasible, default {dflt.as_tuple()}", flush=True)
+    picks = [None] + cfgs[:: max(1, len(cfgs) // 80)]
+    for c in picks:
+        y, res = case.run(c)
+        assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0
 
 
 def test_degenerate_rows(oracle):

@@ -69,11 +69,23 @@ def test_tune_small_budget_and_errors():
     c, rep = B.addrms_tune(16, 4096, "bf16", B.make_budget(max_candidates=6, warmup=2, reps=10))
     assert rep.n_measured <= 6 and B.addrms_cfg_feasible(c, 16, 4096, "bf16")[0] == 0
     with pytest.raises(B.AddrmsError) as e:
-        B.addrms_tune(16, 1 << 20, "bf16")
+        B.addrms_tune(16, 1 << 30, "bf16")
     assert e.value.status == B.ERR_UNSUPPORTED_SHAPE
     with pytest.raises(B.AddrmsError) as e:
         B.addrms_tune(0, 4096, "bf16")
     assert e.value.status == B.ERR_INVALID_ARG
+
+
+def test_tune_rows_beyond_the_register_cache():
+    """The search runs unchanged over the two-pass family: every candidate passes the gate, the winner
+    carries the two-pass flag, is not slower than the default and is what a cfg-less run resolves to."""
+    M, N, dt = 256, 40960, "bf16"
+    c, rep = B.addrms_tune(M, N, dt, B.make_budget(warmup=5, reps=30))
+    assert c.flags & B.FLAG_TWO_PASS and rep.n_failed == 0 and 20 < rep.n_measured < 0.1 * rep.n_feasible
+    assert rep.default_cfg.flags == B.FLAG_TWO_PASS and rep.best_us <= rep.default_us * 1.02
+    assert B.addrms_table_lookup(M, N, dt).as_tuple() == c.as_tuple()
+    nbytes = B.addrms_algorithmic_bytes(M, N, dt)
+    print(f"two-pass {M}x{N}: {c} {rep.best_us:.2f} us = {nbytes / rep.best_us * 1e-3:.0f} GB/s; default {rep.default_us:.2f} us", flush=True)
 
 
 def test_measure_and_stream_probe():

@@ -163,7 +163,7 @@ def test_argument_errors():
         B.addrms_tune_with_backend(M, N, 9, None, rec.measure)
     assert e.value.status == B.ERR_UNSUPPORTED_DTYPE
     with pytest.raises(B.AddrmsError) as e:
-        B.addrms_tune_with_backend(M, 1 << 20, DT, None, rec.measure)
+        B.addrms_tune_with_backend(M, 1 << 30, DT, None, rec.measure)
     assert e.value.status == B.ERR_UNSUPPORTED_SHAPE
     with pytest.raises(B.AddrmsError) as e:
         B.addrms_tune_with_backend(M, N, DT, B.make_budget(strategy=5), rec.measure)
