@@ -117,6 +117,8 @@ def main(argv=None) -> int:
     ap.add_argument("--paper-shapes", action="store_true",
                     help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
                          "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
+    ap.add_argument("--long-rows", action="store_true",
+                    help="also tune rows beyond the register row cache, which run in the two-pass form")
     ap.add_argument("--graph-decode", action="store_true",
                     help="decode shapes: per-launch time of a chain of launches issued eagerly vs replayed from a HIP graph")
     ap.add_argument("--audit", action="store_true",
@@ -189,6 +191,20 @@ def main(argv=None) -> int:
                 print(f"| {m} x {n} | {rep.default_us[i]:.2f} | {rep.general_us[i]:.2f} | {rep.specialized_us[i]:.2f} | "
                       f"{rep.default_us[i] / rep.general_us[i]:.3f} | {rep.default_us[i] / rep.specialized_us[i]:.3f} | "
                       f"{rep.specialized[i].as_tuple()} |", flush=True)
+    if a.long_rows:
+        print("\nRows beyond the register row cache (two-pass form: the row is read twice), tuned vs default:\n")
+        print("| M x N | dtype | default us | tuned us | speedup | tuned GB/s (algorithmic) | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|")
+        for M, N, dtype in ((4096, 40960, "bf16"), (2048, 65536, "bf16"), (1024, 131072, "bf16"),
+                            (2048, 49152, "fp16_res32"), (512, 262144, "fp32")):
+            nbytes = B.addrms_algorithmic_bytes(M, N, dtype)
+            t0 = time.perf_counter()
+            cfg, rep = B.addrms_tune(M, N, dtype, B.make_budget())
+            wall = (time.perf_counter() - t0) * 1e3
+            gbps = nbytes / rep.best_us * 1e-3
+            print(f"| {M} x {N} | {dtype} | {rep.default_us:.1f} | {rep.best_us:.1f} | {rep.default_us / rep.best_us:.3f} | "
+                  f"{gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | {cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | "
+                  f"{wall:.0f} |", flush=True)
     if a.graph_decode:
         print("\nDecode shapes, chain of 64 launches, tuned cfg: microseconds per launch issued eagerly vs from a HIP graph:\n")
         print("| M x N | cfg | eager us | graph us |")
