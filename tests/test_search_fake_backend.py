@@ -168,3 +168,22 @@ def test_argument_errors():
     with pytest.raises(B.AddrmsError) as e:
         B.addrms_tune_with_backend(M, N, DT, B.make_budget(strategy=5), rec.measure)
     assert e.value.status == B.ERR_INVALID_ARG
+
+
+def test_search_over_the_two_pass_family():
+    """Rows beyond the register cache: the region holds two-pass cfgs only and both strategies work on it."""
+    m, n = 512, 65536
+
+    def cost2(c):
+        assert c.flags & B.FLAG_TWO_PASS and not c.flags & B.FLAG_PERSISTENT
+        return cost(c) * 3.0
+
+    cfgs, _ = B.addrms_enumerate_feasible(m, n, DT)
+    best = min(cfgs, key=cost2)
+    rec = Recorder(cost2)
+    e, erep = B.addrms_tune_with_backend(m, n, DT, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE), rec.measure, rec.validate)
+    assert e.as_tuple() == best.as_tuple() and erep.n_measured == len(cfgs) == erep.n_feasible
+    rec = Recorder(cost2)
+    g, grep = B.addrms_tune_with_backend(m, n, DT, B.make_budget(), rec.measure, rec.validate)
+    assert cost2(g) <= 1.03 * cost2(best) and grep.n_measured < 0.05 * len(cfgs)
+    assert grep.default_cfg.flags == B.FLAG_TWO_PASS and grep.default_cfg.threads_per_row == 1024

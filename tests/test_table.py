@@ -83,3 +83,21 @@ def test_missing_file_and_unwritable_path(tmp_path):
     with pytest.raises(B.AddrmsError) as e:
         B.addrms_table_save(str(tmp_path / "no_such_dir" / "t.txt"))
     assert e.value.status == B.ERR_IO
+
+
+def test_two_pass_entries_round_trip_and_resolve_long_rows(tmp_path):
+    """A table entry for a row beyond the register cache carries the two-pass flag through save/load, and the
+    nearest-M fallback hands it to other row counts of the same N."""
+    c = B.make_cfg(8, 768, 1, reduce=B.REDUCE_LDS, unroll=4, flags=B.FLAG_TWO_PASS | B.FLAG_NONTEMPORAL)
+    B.addrms_table_insert(4096, 40960, "bf16", c, 261.7)
+    with pytest.raises(B.AddrmsError):                       # a single-pass cfg cannot hold such a row
+        B.addrms_table_insert(4096, 40960, "bf16", B.make_cfg(8, 1024, 1), 1.0)
+    with pytest.raises(B.AddrmsError):                       # and the two-pass form is refused where one pass does
+        B.addrms_table_insert(4096, 4096, "bf16", B.make_cfg(8, 256, 1, unroll=2, flags=B.FLAG_TWO_PASS), 1.0)
+    path = str(tmp_path / "t.txt")
+    B.addrms_table_save(path)
+    B.addrms_table_clear()
+    B.addrms_table_load(path)
+    assert B.addrms_table_lookup(4096, 40960, "bf16").as_tuple() == c.as_tuple()
+    assert B.addrms_table_lookup(100, 40960, "bf16").as_tuple() == c.as_tuple()
+    assert B.addrms_table_lookup(100, 40968, "bf16") is None
