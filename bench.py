@@ -43,6 +43,17 @@ MEASURED_TRAFFIC_BYTES = {"prefill_4096x4096_bf16": 134361400,
                           "odd_width_8192xN_fp16_res32[N=1000]": 99665000}
 
 
+def device_info(torch):
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "arch": getattr(p, "gcnArchName", ""), "compute_units": p.multi_processor_count,
+            "memory_gib": round(p.total_memory / 2 ** 30, 1)}
+    for key in ("clock_rate", "memory_clock_rate", "memory_bus_width", "L2_cache_size"):
+        v = getattr(p, key, None)
+        if v:
+            info[key] = v
+    return info
+
+
 def pick_workload(W, name):
     if name == "prefill":
         return W.PREFILL
@@ -306,6 +317,7 @@ def run_other_op(a, torch, lib, B, W):
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "kernel_us": round(kernel_us, 3),
                      "algorithmic_bytes": nbytes},
     }
+    out["device"] = device_info(torch)
     if not a.no_cpu_baseline:
         import oracle
         oracle.build()
@@ -411,6 +423,7 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "kernel_us": round(kernel_us, 3), "algorithmic_bytes": nbytes},
     }
+    out["device"] = device_info(torch)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W, wl, d, nbytes)
     print(json.dumps(out))
