@@ -480,7 +480,10 @@ __device__ __forceinline__ void addrms_twopass_body(void* __restrict__ xp, void*
     const double ss = row_sum(acc, reduce, tpr, lane, ry, lds);
     const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
 
-    for (uint32_t it = 0; it < iters; ++it) {
+    // Pass 2 walks the row backwards: its end was read last in pass 1 and is the part most
+    // likely to be still in the L2.
+    for (uint32_t k = 0; k < iters; ++k) {
+        const uint32_t it = iters - 1u - k;
         raw_t<XB * VEC> xv[UNR], wv[UNR];
         raw_t<RB * VEC> rv[UNR];
         const uint32_t col0 = col_first + it * span;
