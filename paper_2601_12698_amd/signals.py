@@ -161,7 +161,11 @@ def suggest(record: dict, achieved_frac: Optional[float] = None) -> Tuple[int, L
     occ = c.get("MeanOccupancyPerCU")
     valu = c.get("VALUBusy")
     stall_per_miss = d.get("dram_credit_stall_per_l2_miss")
-    if d.get("traffic_over_algorithmic", 1.0) > 1.05:
+    two_pass = bool(int(record.get("cfg", {}).get("flags", 0)) & B.FLAG_TWO_PASS)
+    if d.get("traffic_over_algorithmic", 1.0) > 1.05 and two_pass:
+        why.append(f"HBM traffic is {d['traffic_over_algorithmic']:.2f}x the algorithmic bytes, as expected of the two-pass "
+                   "form (rows beyond the register cache are read twice): no hint")
+    elif d.get("traffic_over_algorithmic", 1.0) > 1.05:
         hints |= B.HINT_FEWER_LARGER_WORKGROUPS
         why.append(f"HBM traffic is {d['traffic_over_algorithmic']:.2f}x the algorithmic bytes: something is re-read; "
                    "prefer shapes that keep a row in one workgroup's registers")

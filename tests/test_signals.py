@@ -70,3 +70,15 @@ def test_hints_reach_the_search():
         ph1 = {json.loads(l).get("phase") for l in open(p1)}
     assert "sweep_capped" not in ph0 and "sweep_capped" in ph1
     assert 0 < g.max_waves_per_simd <= 4
+
+
+def test_two_pass_re_reads_are_not_taken_for_waste():
+    rec = {"cfg": {"vec": 8, "threads_per_row": 1024, "rows_per_wg": 1, "reduce": 0, "unroll": 2, "flags": 10,
+                   "max_waves_per_simd": 0},
+           "counters": {"VALUBusy": 22.0, "MeanOccupancyPerCU": 12.0},
+           "derived": {"traffic_over_algorithmic": 1.45}}
+    hints, why = S.suggest(rec, achieved_frac=0.6)
+    assert hints == 0 and any("two-pass" in w for w in why)
+    rec["cfg"]["flags"] = 2
+    hints, why = S.suggest(rec, achieved_frac=0.6)
+    assert hints & B.HINT_FEWER_LARGER_WORKGROUPS
