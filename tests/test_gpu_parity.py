@@ -350,3 +350,38 @@ def test_random_shapes_and_cfgs(oracle):
             assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0
             n_cases += 1
     assert n_cases > 250
+
+
+@pytest.mark.parametrize("dtype,N,off", [("bf16", 1001, 1), ("bf16", 1002, 2), ("fp16", 2052, 4), ("fp16_res32", 1004, 4),
+                                         ("fp32", 1001, 1), ("fp32", 1002, 2)])
+def test_bases_aligned_only_to_the_vector(oracle, dtype, N, off):
+    """Tensors that start `off` elements into an allocation: the base is aligned to the widest vector that
+    divides N (which is what the cfg needs) and to nothing more."""
+    M = 9
+    wl = _wl(M, N, dtype, 1300 + N)
+    d = W.generate(wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    dev = torch.device("cuda:0")
+
+    def shifted(t):
+        big = torch.zeros(t.numel() + 64, dtype=t.dtype, device=dev)
+        view = big[off:off + t.numel()]
+        view.copy_(t.reshape(-1).to(dev))
+        return big, view
+
+    keep_x, x = shifted(d["x"])
+    keep_r, r = shifted(d["r"])
+    keep_w, w = shifted(d["w"])
+    vec = B.addrms_default_cfg(N, dtype).vec
+    assert x.data_ptr() % (vec * W.x_bytes(dtype)) == 0 and x.data_ptr() % (2 * vec * W.x_bytes(dtype)) != 0
+    cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
+    for c in [None] + [c for c in cfgs if c.vec <= vec][::23]:
+        x.copy_(d["x"].reshape(-1).to(dev))
+        r.copy_(d["r"].reshape(-1).to(dev))
+        B.addrms_run(x, r, w, wl.eps, M, N, dtype, c)
+        torch.cuda.synchronize()
+        got_y, got_r = W.to_bits(x.view(M, N)), W.to_bits(r.view(M, N))
+        assert compare(got_y, got_r, y_ref, res_ref, dtype, f"{wl.name} off={off} {c}")["n_diff"] == 0
+    # nothing outside the views was touched
+    assert float(keep_x[:off].abs().sum()) == 0 and float(keep_x[off + M * N:].abs().sum()) == 0
+    assert float(keep_r[:off].abs().sum()) == 0 and float(keep_r[off + M * N:].abs().sum()) == 0
