@@ -38,6 +38,16 @@ int mergestates_tune(int64_t rows, int64_t d, int dtype, const addrms_budget* bu
                      addrms_cfg* out_cfg, addrms_tune_report* report);
 int mergestates_tune_with_backend(int64_t rows, int64_t d, int dtype, const addrms_budget* budget,
                                   const addrms_backend* backend, addrms_cfg* out_cfg, addrms_tune_report* report);
+
+/* One general configuration over a set of shapes and the specialised table built on the way
+ * (Algorithm 1 lines 22-23), as addrms_select_general does for add+RMSNorm: per-shape search,
+ * pool of Top-K / defaults / universally feasible neighbours, every pool member timed on
+ * every shape, arg-max of the geometric-mean speed-up over the per-shape defaults.
+ * shapes: host, addrms_shape with M = rows (tokens x heads), N = d (head size).
+ * Blocking; allocates and frees device memory. */
+int mergestates_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                               addrms_cfg* out_general, addrms_general_report* report);
+
 int mergestates_measure(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, int warmup, int reps,
                         int rotate, double* mean_us);
 int mergestates_table_lookup(int64_t rows, int64_t d, int dtype, addrms_cfg* out);

@@ -41,6 +41,15 @@ int silumul_tune(int64_t M, int64_t d, int dtype, const addrms_budget* budget,
 int silumul_tune_with_backend(int64_t M, int64_t d, int dtype, const addrms_budget* budget,
                               const addrms_backend* backend, addrms_cfg* out_cfg, addrms_tune_report* report);
 
+/* One general configuration over a set of shapes and the specialised table built on the way
+ * (Algorithm 1 lines 22-23), as addrms_select_general does for add+RMSNorm: per-shape search,
+ * pool of Top-K / defaults / universally feasible neighbours, every pool member timed on
+ * every shape, arg-max of the geometric-mean speed-up over the per-shape defaults.
+ * shapes: host, addrms_shape with M rows, N = d outputs per row.
+ * Blocking; allocates and frees device memory. */
+int silumul_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                           addrms_cfg* out_general, addrms_general_report* report);
+
 /* Mean time in microseconds over `reps` launches after `warmup`, on library-allocated
  * synthetic buffers rotated past the last-level cache (rotate != 0). */
 int silumul_measure(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, int warmup, int reps, int rotate,

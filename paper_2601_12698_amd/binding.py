@@ -252,6 +252,7 @@ SIGNATURES = {
     "silumul_tune": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Cfg), POINTER(TuneReport)]),
     "silumul_tune_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
                                           POINTER(Cfg), POINTER(TuneReport)]),
+    "silumul_select_general": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg), POINTER(GeneralReport)]),
     "silumul_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_int, c_int, c_int, POINTER(c_double)]),
     "silumul_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
     "silumul_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
@@ -263,6 +264,8 @@ SIGNATURES = {
     "mergestates_tune": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Cfg), POINTER(TuneReport)]),
     "mergestates_tune_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
                                               POINTER(Cfg), POINTER(TuneReport)]),
+    "mergestates_select_general": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg),
+                                           POINTER(GeneralReport)]),
     "mergestates_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_int, c_int, c_int, POINTER(c_double)]),
     "mergestates_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
     "mergestates_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
@@ -679,6 +682,14 @@ def silumul_tune_with_backend(M: int, d: int, dtype, budget: Optional[Budget], m
     return c, rep
 
 
+def silumul_select_general(shapes, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, GeneralReport]:
+    """shapes: sequence of (M, d)."""
+    c, rep = Cfg(), GeneralReport()
+    _check(load().silumul_select_general(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                         byref(budget) if budget is not None else None, byref(c), byref(rep)))
+    return c, rep
+
+
 def silumul_measure(cfg: Optional[Cfg], M: int, d: int, dtype, warmup: int = 20, reps: int = 100,
                     rotate: bool = True) -> float:
     us = c_double(0.0)
@@ -763,6 +774,14 @@ def mergestates_tune_with_backend(rows: int, d: int, dtype, budget: Optional[Bud
     _check(load().mergestates_tune_with_backend(rows, d, _dtype_id(dtype),
                                                 byref(budget) if budget is not None else None, byref(be),
                                                 byref(c), byref(rep)))
+    return c, rep
+
+
+def mergestates_select_general(shapes, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, GeneralReport]:
+    """shapes: sequence of (rows, d)."""
+    c, rep = Cfg(), GeneralReport()
+    _check(load().mergestates_select_general(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                             byref(budget) if budget is not None else None, byref(c), byref(rep)))
     return c, rep
 
 

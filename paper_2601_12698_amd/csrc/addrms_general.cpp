@@ -26,10 +26,10 @@ double knob_distance(const addrms_cfg& a, const addrms_cfg& b)
            0.25 * abs(a.max_waves_per_simd - b.max_waves_per_simd);
 }
 
-bool feasible_everywhere(const addrms_cfg& c, const addrms_shape* shapes, int n, int dtype)
+bool feasible_everywhere(const addrms_cfg& c, const addrms_shape* shapes, int n, int dtype, int op)
 {
     for (int i = 0; i < n; ++i)
-        if (check_cfg(c, shapes[i].M, shapes[i].N, dtype).status != ADDRMS_OK) return false;
+        if (check_cfg(c, shapes[i].M, shapes[i].N, dtype, op).status != ADDRMS_OK) return false;
     return true;
 }
 
@@ -51,14 +51,14 @@ struct OpenBackend {
 
 int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
                        const addrms_backend_factory& factory, bool insert_in_table,
-                       addrms_cfg* out_general, addrms_general_report* report)
+                       addrms_cfg* out_general, addrms_general_report* report, int op)
 {
     using Clock = std::chrono::steady_clock;
     const auto t0 = Clock::now();
     if (!shapes || !out_general) return fail(ADDRMS_ERR_INVALID_ARG, "shapes and out_general must not be NULL");
     if (n < 1 || n > ADDRMS_MAX_SHAPES) return fail(ADDRMS_ERR_INVALID_ARG, "n must be 1..%d", ADDRMS_MAX_SHAPES);
     if (!factory.open) return fail(ADDRMS_ERR_INVALID_ARG, "backend factory has no open function");
-    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (!dtype_valid(dtype, op)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for %s", dtype, op_name(op));
     for (int i = 0; i < n; ++i)
         if (shapes[i].M <= 0 || shapes[i].N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "shape %d needs M > 0 and N > 0", i);
     addrms_budget b{};
@@ -79,13 +79,13 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
                         (long long)shapes[i].M, (long long)shapes[i].N);
         addrms_cfg best{};
         addrms_tune_report tr{};
-        const int st = run_search(shapes[i].M, shapes[i].N, dtype, budget, ob.be, &best, &tr);
+        const int st = run_search(shapes[i].M, shapes[i].N, dtype, budget, ob.be, &best, &tr, op);
         if (st != ADDRMS_OK) return st;
         rep.specialized[i] = best;
         rep.specialized_us[i] = tr.best_us;
         rep.default_us[i] = tr.default_us;
         defaults[i] = tr.default_cfg;
-        if (insert_in_table) addrms_table_insert(shapes[i].M, shapes[i].N, dtype, &best, tr.best_us);
+        if (insert_in_table) table_insert(shapes[i].M, shapes[i].N, dtype, best, tr.best_us, op);
         for (int k = 0; k < tr.n_topk; ++k) add(tr.topk[k]);
         add(tr.default_cfg);
     }
@@ -93,15 +93,15 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
     // ---- candidates that are one theta for every shape
     std::vector<addrms_cfg> cands;
     for (const addrms_cfg& c : pool)
-        if (feasible_everywhere(c, shapes, n, dtype)) cands.push_back(c);
+        if (feasible_everywhere(c, shapes, n, dtype, op)) cands.push_back(c);
     {
         // widen: the universally feasible cfgs nearest (in knob steps) to each shape's winner, so that a
         // compromise lying between the specialised winners is in the pool even if no winner fits every shape
         std::vector<addrms_cfg> all;
-        enumerate(shapes[0].M, shapes[0].N, dtype, &all, nullptr, nullptr);
+        enumerate(shapes[0].M, shapes[0].N, dtype, &all, nullptr, nullptr, op);
         std::vector<addrms_cfg> common;
         for (const addrms_cfg& c : all)
-            if (feasible_everywhere(c, shapes, n, dtype)) common.push_back(c);
+            if (feasible_everywhere(c, shapes, n, dtype, op)) common.push_back(c);
         if (common.empty() && cands.empty())
             return fail(ADDRMS_ERR_NO_RESULT, "no configuration is feasible on all %d shapes", n);
         std::unordered_set<uint64_t> have;

@@ -110,7 +110,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
 // insert_in_table: store each shape's winner in the specialised table (device runs only).
 int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
                        const addrms_backend_factory& factory, bool insert_in_table,
-                       addrms_cfg* out_general, addrms_general_report* report);
+                       addrms_cfg* out_general, addrms_general_report* report, int op = OP_ADDRMS);
 
 int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
                     const addrms_backend_factory& factory, bool insert_in_table,

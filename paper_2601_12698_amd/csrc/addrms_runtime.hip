@@ -659,6 +659,32 @@ int factory_open(void* user, int64_t M, int64_t N, int dtype, addrms_backend* ou
 }
 void factory_close(void*, addrms_backend* be) { delete static_cast<Harness*>(be->user); }
 
+// The same for the two further operators (no eps, so no state).
+template <class H, int OP, int (*VALIDATE)(void*, const addrms_cfg*), int (*MEASURE)(void*, const addrms_cfg*, int, int, double*)>
+int op_factory_open(void*, int64_t M, int64_t N, int dtype, addrms_backend* out)
+{
+    auto* h = new H();
+    addrms_cfg dflt{};
+    std::string why;
+    int st = default_cfg(N, dtype, &dflt, &why, OP);
+    if (st == ADDRMS_OK) st = h->init(M, N, dtype, true);
+    if (st == ADDRMS_OK) st = h->make_reference(dflt);
+    if (st != ADDRMS_OK) { delete h; return st; }
+    out->user = h;
+    out->validate = VALIDATE;
+    out->measure = MEASURE;
+    return 0;
+}
+template <class H>
+void op_factory_close(void*, addrms_backend* be) { delete static_cast<H*>(be->user); }
+
+int check_shapes(const addrms_shape* shapes, int32_t n)
+{
+    if (!shapes) return fail(ADDRMS_ERR_INVALID_ARG, "shapes is NULL");
+    if (n < 1 || n > ADDRMS_MAX_SHAPES) return fail(ADDRMS_ERR_INVALID_ARG, "n must be 1..%d", ADDRMS_MAX_SHAPES);
+    return ADDRMS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -949,6 +975,18 @@ int silumul_tune(int64_t M, int64_t d, int dtype, const addrms_budget* budget, a
     return table_insert(M, d, dtype, *out_cfg, local.best_us, OP_SILUMUL);
 }
 
+int silumul_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                           addrms_cfg* out_general, addrms_general_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    const int st = check_shapes(shapes, n);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_backend_factory fac{nullptr, op_factory_open<SiluHarness, OP_SILUMUL, silu_backend_validate, silu_backend_measure>,
+                               op_factory_close<SiluHarness>};
+    return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report, OP_SILUMUL);
+}
+
 int silumul_measure(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, int warmup, int reps, int rotate,
                     double* mean_us)
 {
@@ -1068,6 +1106,18 @@ int mergestates_tune(int64_t rows, int64_t d, int dtype, const addrms_budget* bu
     if (st != ADDRMS_OK) return st;
     if (report) *report = local;
     return table_insert(rows, d, dtype, *out_cfg, local.best_us, OP_MERGE);
+}
+
+int mergestates_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                               addrms_cfg* out_general, addrms_general_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    const int st = check_shapes(shapes, n);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_backend_factory fac{nullptr, op_factory_open<MergeHarness, OP_MERGE, merge_backend_validate, merge_backend_measure>,
+                               op_factory_close<MergeHarness>};
+    return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report, OP_MERGE);
 }
 
 int mergestates_measure(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, int warmup, int reps, int rotate,

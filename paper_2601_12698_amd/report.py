@@ -227,6 +227,27 @@ def main(argv=None) -> int:
                           f"{rep.retained_decile_us:.2f} | {rep.retained_median_us:.2f} | {r.rule.decode()} | {r.n_pruned} | "
                           f"{r.n_failed} | {r.best_us:.2f} | {r.median_us:.2f} | {r.n_in_top_decile} | {r.n_beating_best} | "
                           f"{rep.wall_ms / 1e3:.1f} |", flush=True)
+    if a.paper_shapes:
+        def general_table(title, select, shapes, dtype, label):
+            g, rep = select(shapes, dtype, B.make_budget())
+            print(f"\n{title} {dtype}: general cfg {g.as_tuple()}: geomean speedup over default x{rep.geomean_speedup_general:.3f}; "
+                  f"specialised table x{rep.geomean_speedup_specialized:.3f}; {rep.n_pool} universally feasible candidates "
+                  f"timed; {rep.wall_ms:.0f} ms\n")
+            print(f"| {label} | default us | general us | specialised us | general speedup | specialised speedup | specialised cfg |")
+            print("|---|---|---|---|---|---|---|")
+            for i, sh in enumerate(shapes):
+                print(f"| {sh[0]} x {sh[1]} | {rep.default_us[i]:.2f} | {rep.general_us[i]:.2f} | {rep.specialized_us[i]:.2f} | "
+                      f"{rep.default_us[i] / rep.general_us[i]:.3f} | {rep.default_us[i] / rep.specialized_us[i]:.3f} | "
+                      f"{rep.specialized[i].as_tuple()} |", flush=True)
+
+        merge_shapes = [(n * h, d) for n, h, d in W.MERGE_SHAPES]
+        for dtype in ("bf16", "fp16"):
+            general_table("merge_attn_states on the (n, h, d) shapes of Section 4 (rows = n*h),", B.mergestates_select_general,
+                          merge_shapes, dtype, "rows x d")
+        general_table("silu_and_mul on the fp32 (m, n) shapes of Section 4 (d = n),", B.silumul_select_general,
+                      PAPER_MN_FP32, "fp32", "m x d")
+        general_table("silu_and_mul on the 16-bit (m, n) shapes of Section 4 (d = n),", B.silumul_select_general,
+                      PAPER_MN_16BIT, "bf16", "m x d")
     if a.table:
         B.addrms_table_save(a.table)
     return 0

@@ -97,3 +97,19 @@ def test_special_scores_and_errors(oracle):
     assert lib.mergestates_run(*args, 8, 128, B.FP32, ok, None) == B.ERR_UNSUPPORTED_DTYPE
     assert lib.mergestates_run(*args, 0, 128, B.BF16, ok, None) == B.OK
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp16"])
+def test_select_general_on_paper_shapes(dtype):
+    """One general cfg over the five (n, h, d) shapes of the paper's evaluation (Section 4, Kernels) and the
+    specialised table built on the way (Algorithm 1 lines 22-23)."""
+    shapes = [(n * h, d) for n, h, d in W.MERGE_SHAPES]
+    g, rep = B.mergestates_select_general(shapes, dtype, B.make_budget(max_candidates=60, warmup=5, reps=30, coarse_reps=8))
+    print(f"merge {dtype}: general {g} geomean x{rep.geomean_speedup_general:.3f}, specialised "
+          f"x{rep.geomean_speedup_specialized:.3f}, pool {rep.n_pool}, {rep.wall_ms:.0f} ms", flush=True)
+    for i, (rows, d) in enumerate(shapes):
+        assert B.mergestates_cfg_feasible(g, rows, d, dtype)[0] == 0
+        assert rep.default_us[i] > 0 and rep.general_us[i] > 0 and rep.specialized_us[i] > 0
+        assert B.mergestates_table_lookup(rows, d, dtype) is not None
+    assert rep.geomean_speedup_specialized >= rep.geomean_speedup_general - 1e-9
+    assert rep.geomean_speedup_general > 0.97

@@ -114,3 +114,17 @@ def test_edge_values_and_errors(oracle):
     assert lib.silumul_run(xd.data_ptr(), out.data_ptr(), 0, d, B.BF16, ok, None) == B.OK
     bad = B.make_cfg(8, 32, 2, reduce=1)
     assert lib.silumul_run(xd.data_ptr(), out.data_ptr(), 6, d, B.BF16, bad, None) == B.ERR_INFEASIBLE_CFG
+
+
+def test_select_general_over_several_widths():
+    """One general cfg for the gated activation over feed-forward widths of several model sizes."""
+    shapes = [(256, 11008), (1024, 11008), (256, 13824), (512, 14336), (2048, 8192)]
+    g, rep = B.silumul_select_general(shapes, "bf16", B.make_budget(max_candidates=60, warmup=5, reps=30, coarse_reps=8))
+    print(f"silumul: general {g} geomean x{rep.geomean_speedup_general:.3f}, specialised "
+          f"x{rep.geomean_speedup_specialized:.3f}, pool {rep.n_pool}, {rep.wall_ms:.0f} ms", flush=True)
+    for i, (M, d) in enumerate(shapes):
+        assert B.silumul_cfg_feasible(g, M, d, "bf16")[0] == 0
+        assert rep.default_us[i] > 0 and rep.general_us[i] > 0 and rep.specialized_us[i] > 0
+        assert B.silumul_table_lookup(M, d, "bf16") is not None
+    assert rep.geomean_speedup_specialized >= rep.geomean_speedup_general - 1e-9
+    assert rep.geomean_speedup_general > 0.97
