@@ -67,3 +67,45 @@ def test_fp32_shapes(oracle, m, n):
     wl = W.Workload(f"fp32_{m}x{n}", m, n, "fp32", 1e-6, 100 + m + n)
     out, _ = _check(oracle, wl, tune=False)
     assert all(s["n_diff"] == 0 for s in out.values())
+
+
+ALL_CFG_WORKLOADS = [W.SMOKE, W.PREFILL, W.DECODE.with_rows(1), W.DECODE.with_rows(64), W.DECODE.with_rows(256),
+                     W.LARGE_PREFILL, W.ODD_WIDTH.with_cols(5120), W.ODD_WIDTH.with_cols(2880), W.ODD_WIDTH.with_cols(1000)]
+
+
+@pytest.mark.parametrize("wl", ALL_CFG_WORKLOADS, ids=lambda w: w.name)
+def test_every_feasible_cfg_matches_the_oracle_at_benchmark_size(oracle, wl):
+    """Not only the default and the tuned cfg: every member of the feasible region, at the full benchmark
+    size, against the oracle's own output (uploaded once, compared on the device).  The bar is the same;
+    since all instances share one arithmetic and the sum of squares is order-free, bit equality is expected
+    and is what is asserted, with the ulp comparison as the fallback report if it ever fails."""
+    import torch
+    d = W.generate(wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    dev = torch.device("cuda:0")
+    x0, r0, w = d["x"].to(dev), d["r"].to(dev), d["w"].to(dev)
+    as_int = lambda t: t.view(torch.int16 if t.element_size() == 2 else torch.int32)
+    y_ref_d = torch.from_numpy(y_ref.view(np.int16 if y_ref.itemsize == 2 else np.int32)).to(dev)
+    r_ref_d = torch.from_numpy(res_ref.view(np.int16 if res_ref.itemsize == 2 else np.int32)).to(dev)
+    x, r = torch.empty_like(x0), torch.empty_like(r0)
+    cfgs, _ = B.addrms_enumerate_feasible(wl.M, wl.N, wl.dtype)
+    stride = 3 if wl.M * wl.N > (1 << 27) else 1          # the 1.9 GB shape: every third cfg keeps the test short
+    picked = cfgs[::stride]
+    print(f"{wl.name}: {len(picked)} of {len(cfgs)} feasible cfgs", flush=True)
+    bad = []
+    for c in picked:
+        x.copy_(x0)
+        r.copy_(r0)
+        B.addrms_run(x, r, w, wl.eps, wl.M, wl.N, wl.dtype, c)
+        if not (torch.equal(as_int(r), r_ref_d) and torch.equal(as_int(x), y_ref_d)):
+            bad.append(c)
+            if len(bad) >= 3:
+                break
+    for c in bad:                                          # report through the ulp bar which cfg differs and by how much
+        x.copy_(x0)
+        r.copy_(r0)
+        B.addrms_run(x, r, w, wl.eps, wl.M, wl.N, wl.dtype, c)
+        torch.cuda.synchronize()
+        st = compare(W.to_bits(x), W.to_bits(r), y_ref, res_ref, wl.dtype, f"{wl.name} {c}")
+        print(f"{wl.name} {c}: {st}", flush=True)
+    assert not bad, [c.as_tuple() for c in bad]
