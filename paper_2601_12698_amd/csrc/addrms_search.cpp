@@ -37,6 +37,7 @@ namespace addrms_host {
 namespace {
 
 using Clock = std::chrono::steady_clock;
+constexpr double kShortKernelUs = 10.0;
 
 struct Cand {
     addrms_cfg cfg{};
@@ -108,6 +109,12 @@ struct Searcher {
             ++n_failed;
             log_eval(phase, c, false, -1.0, warmup, reps);
             return false;
+        }
+        // Launch-bound shapes (a few microseconds per launch) time noisily with a short protocol
+        // and cost next to nothing to time longer: repeat with eight times the repetitions.
+        if (us < kShortKernelUs && reps <= b.coarse_reps) {
+            double again = 0.0;
+            if (be.measure(be.user, &c.cfg, warmup, reps * 8, &again) == 0 && again > 0.0) us = again;
         }
         ++n_measured;
         c.us = us;
