@@ -385,3 +385,17 @@ def test_bases_aligned_only_to_the_vector(oracle, dtype, N, off):
     # nothing outside the views was touched
     assert float(keep_x[:off].abs().sum()) == 0 and float(keep_x[off + M * N:].abs().sum()) == 0
     assert float(keep_r[:off].abs().sum()) == 0 and float(keep_r[off + M * N:].abs().sum()) == 0
+
+
+@pytest.mark.parametrize("dtype,M,N", [("bf16", 1_000_003, 40), ("fp16_res32", 300_001, 24), ("fp32", 500_009, 12)])
+def test_a_million_short_rows(oracle, dtype, M, N):
+    """Rows shorter than a wave, a prime number of them: sub-wave row shapes, many row blocks, ragged last block."""
+    wl = _wl(M, N, dtype, 1400 + N)
+    d = W.generate(wl)
+    case = DeviceCase(d, wl)
+    y_ref, res_ref = oracle_outputs(oracle, d, wl)
+    cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
+    assert cfgs
+    for c in [None] + cfgs[:: max(1, len(cfgs) // 12)]:
+        y, res = case.run(c)
+        assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0
