@@ -48,6 +48,13 @@ int mergestates_tune_with_backend(int64_t rows, int64_t d, int dtype, const addr
 int mergestates_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
                                addrms_cfg* out_general, addrms_general_report* report);
 
+/* The outer loop of Algorithm 1 with a fixed list of strategy families (base template, then the
+ * streaming cache policy, the occupancy cap, the grid mapping), as addrms_tune_rounds: each round
+ * validates the family it adds, searches every shape within the families enabled so far, selects
+ * the general cfg and the specialised table, and scores the round. */
+int mergestates_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                            addrms_cfg* out_general, addrms_rounds_report* report);
+
 int mergestates_measure(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, int warmup, int reps,
                         int rotate, double* mean_us);
 int mergestates_table_lookup(int64_t rows, int64_t d, int dtype, addrms_cfg* out);

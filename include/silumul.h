@@ -50,6 +50,13 @@ int silumul_tune_with_backend(int64_t M, int64_t d, int dtype, const addrms_budg
 int silumul_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
                            addrms_cfg* out_general, addrms_general_report* report);
 
+/* The outer loop of Algorithm 1 with a fixed list of strategy families (base template, then the
+ * streaming cache policy, the occupancy cap, the grid mapping), as addrms_tune_rounds: each round
+ * validates the family it adds, searches every shape within the families enabled so far, selects
+ * the general cfg and the specialised table, and scores the round. */
+int silumul_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                        addrms_cfg* out_general, addrms_rounds_report* report);
+
 /* Mean time in microseconds over `reps` launches after `warmup`, on library-allocated
  * synthetic buffers rotated past the last-level cache (rotate != 0). */
 int silumul_measure(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, int warmup, int reps, int rotate,

@@ -253,6 +253,7 @@ SIGNATURES = {
     "silumul_tune_with_backend": (c_int, [c_int64, c_int64, c_int, POINTER(Budget), POINTER(Backend),
                                           POINTER(Cfg), POINTER(TuneReport)]),
     "silumul_select_general": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg), POINTER(GeneralReport)]),
+    "silumul_tune_rounds": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg), POINTER(RoundsReport)]),
     "silumul_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_int, c_int, c_int, POINTER(c_double)]),
     "silumul_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
     "silumul_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
@@ -266,6 +267,8 @@ SIGNATURES = {
                                               POINTER(Cfg), POINTER(TuneReport)]),
     "mergestates_select_general": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg),
                                            POINTER(GeneralReport)]),
+    "mergestates_tune_rounds": (c_int, [POINTER(Shape), c_int32, c_int, POINTER(Budget), POINTER(Cfg),
+                                        POINTER(RoundsReport)]),
     "mergestates_measure": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, c_int, c_int, c_int, POINTER(c_double)]),
     "mergestates_table_lookup": (c_int, [c_int64, c_int64, c_int, POINTER(Cfg)]),
     "mergestates_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
@@ -690,6 +693,13 @@ def silumul_select_general(shapes, dtype, budget: Optional[Budget] = None) -> Tu
     return c, rep
 
 
+def silumul_tune_rounds(shapes, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, RoundsReport]:
+    c, rep = Cfg(), RoundsReport()
+    _check(load().silumul_tune_rounds(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                      byref(budget) if budget is not None else None, byref(c), byref(rep)))
+    return c, rep
+
+
 def silumul_measure(cfg: Optional[Cfg], M: int, d: int, dtype, warmup: int = 20, reps: int = 100,
                     rotate: bool = True) -> float:
     us = c_double(0.0)
@@ -782,6 +792,13 @@ def mergestates_select_general(shapes, dtype, budget: Optional[Budget] = None) -
     c, rep = Cfg(), GeneralReport()
     _check(load().mergestates_select_general(_shape_array(shapes), len(shapes), _dtype_id(dtype),
                                              byref(budget) if budget is not None else None, byref(c), byref(rep)))
+    return c, rep
+
+
+def mergestates_tune_rounds(shapes, dtype, budget: Optional[Budget] = None) -> Tuple[Cfg, RoundsReport]:
+    c, rep = Cfg(), RoundsReport()
+    _check(load().mergestates_tune_rounds(_shape_array(shapes), len(shapes), _dtype_id(dtype),
+                                          byref(budget) if budget is not None else None, byref(c), byref(rep)))
     return c, rep
 
 

@@ -168,14 +168,14 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
 // ---- the outer loop with a fixed strategy list ------------------------------------
 int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
                     const addrms_backend_factory& factory, bool insert_in_table,
-                    addrms_cfg* out_general, addrms_rounds_report* report)
+                    addrms_cfg* out_general, addrms_rounds_report* report, int op)
 {
     using Clock = std::chrono::steady_clock;
     const auto t0 = Clock::now();
     if (!shapes || !out_general) return fail(ADDRMS_ERR_INVALID_ARG, "shapes and out_general must not be NULL");
     if (n < 1 || n > ADDRMS_MAX_SHAPES) return fail(ADDRMS_ERR_INVALID_ARG, "n must be 1..%d", ADDRMS_MAX_SHAPES);
     if (!factory.open) return fail(ADDRMS_ERR_INVALID_ARG, "backend factory has no open function");
-    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (!dtype_valid(dtype, op)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for %s", dtype, op_name(op));
     addrms_budget b{};
     if (budget) b = *budget;
     static const int kOrder[ADDRMS_MAX_ROUNDS] = {0, ADDRMS_FAMILY_STREAMING, ADDRMS_FAMILY_OCCUPANCY_CAP,
@@ -191,7 +191,7 @@ int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_b
             // Validate the rewritten kernel (the family just added) on the first shape: the cheapest
             // feasible cfg that uses it must reproduce the reference output; otherwise roll back.
             std::vector<addrms_cfg> all;
-            enumerate(shapes[0].M, shapes[0].N, dtype, &all, nullptr, nullptr);
+            enumerate(shapes[0].M, shapes[0].N, dtype, &all, nullptr, nullptr, op);
             const addrms_cfg* probe = nullptr;
             for (const addrms_cfg& c : all)
                 if (cfg_in_families(c, enabled | kOrder[r]) && !cfg_in_families(c, enabled ? enabled : ADDRMS_FAMILY_BASE_ONLY)) {
@@ -215,7 +215,7 @@ int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_b
         addrms_general_report gr{};
         int st = ADDRMS_OK;
         if (r == 0 || info.pass) {
-            st = run_select_general(shapes, n, dtype, &rb, factory, false, &general, &gr);
+            st = run_select_general(shapes, n, dtype, &rb, factory, false, &general, &gr, op);
             if (st != ADDRMS_OK) return st;
             info.general = general;
             info.geomean_speedup_general = gr.geomean_speedup_general;
@@ -244,7 +244,7 @@ int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_b
     }
     if (insert_in_table)
         for (int i = 0; i < n; ++i)
-            addrms_table_insert(shapes[i].M, shapes[i].N, dtype, &rep.best.specialized[i], rep.best.specialized_us[i]);
+            table_insert(shapes[i].M, shapes[i].N, dtype, rep.best.specialized[i], rep.best.specialized_us[i], op);
     rep.wall_ms = std::chrono::duration<double, std::milli>(Clock::now() - t0).count();
     if (report) *report = rep;
     return ADDRMS_OK;

@@ -114,7 +114,7 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
 
 int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_budget* budget,
                     const addrms_backend_factory& factory, bool insert_in_table,
-                    addrms_cfg* out_general, addrms_rounds_report* report);
+                    addrms_cfg* out_general, addrms_rounds_report* report, int op = OP_ADDRMS);
 // Measures what the efficiency rules of the deriver prune (see addrms_audit_rules).
 int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget, const addrms_backend& be,
                     addrms_audit_report* report);

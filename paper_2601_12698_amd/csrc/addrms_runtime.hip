@@ -987,6 +987,18 @@ int silumul_select_general(const addrms_shape* shapes, int32_t n, int dtype, con
     return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report, OP_SILUMUL);
 }
 
+int silumul_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                        addrms_cfg* out_general, addrms_rounds_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    const int st = check_shapes(shapes, n);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_backend_factory fac{nullptr, op_factory_open<SiluHarness, OP_SILUMUL, silu_backend_validate, silu_backend_measure>,
+                               op_factory_close<SiluHarness>};
+    return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report, OP_SILUMUL);
+}
+
 int silumul_measure(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, int warmup, int reps, int rotate,
                     double* mean_us)
 {
@@ -1118,6 +1130,18 @@ int mergestates_select_general(const addrms_shape* shapes, int32_t n, int dtype,
     addrms_backend_factory fac{nullptr, op_factory_open<MergeHarness, OP_MERGE, merge_backend_validate, merge_backend_measure>,
                                op_factory_close<MergeHarness>};
     return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report, OP_MERGE);
+}
+
+int mergestates_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                            addrms_cfg* out_general, addrms_rounds_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    const int st = check_shapes(shapes, n);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_backend_factory fac{nullptr, op_factory_open<MergeHarness, OP_MERGE, merge_backend_validate, merge_backend_measure>,
+                               op_factory_close<MergeHarness>};
+    return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report, OP_MERGE);
 }
 
 int mergestates_measure(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, int warmup, int reps, int rotate,

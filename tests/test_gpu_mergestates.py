@@ -113,3 +113,16 @@ def test_select_general_on_paper_shapes(dtype):
         assert B.mergestates_table_lookup(rows, d, dtype) is not None
     assert rep.geomean_speedup_specialized >= rep.geomean_speedup_general - 1e-9
     assert rep.geomean_speedup_general > 0.97
+
+
+def test_rounds_on_device():
+    """The outer loop over strategy families for the merge kernel on two of the paper's shapes."""
+    shapes = [(768 * 32, 256), (512 * 64, 128)]
+    g, rep = B.mergestates_tune_rounds(shapes, "bf16", B.make_budget(warmup=5, reps=30))
+    scores = [rep.rounds[i].score for i in range(rep.n_rounds)]
+    print("merge rounds", scores, g, flush=True)
+    assert rep.n_rounds == 4 and all(rep.rounds[i].passed for i in range(4))
+    assert min(scores) == scores[rep.best_round] and scores[rep.best_round] < scores[0] - 0.03
+    assert rep.rounds[0].general.flags == 0 and rep.rounds[0].general.max_waves_per_simd == 0
+    for rows, d in shapes:
+        assert B.mergestates_table_lookup(rows, d, "bf16") is not None

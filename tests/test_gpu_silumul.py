@@ -128,3 +128,17 @@ def test_select_general_over_several_widths():
         assert B.silumul_table_lookup(M, d, "bf16") is not None
     assert rep.geomean_speedup_specialized >= rep.geomean_speedup_general - 1e-9
     assert rep.geomean_speedup_general > 0.97
+
+
+def test_rounds_on_device():
+    """The outer loop over strategy families for the gated activation: every family validates, the score
+    never gets worse than the base round's, the streaming policy is the structural gain."""
+    shapes = [(4096, 11008), (2048, 13824)]
+    g, rep = B.silumul_tune_rounds(shapes, "bf16", B.make_budget(warmup=5, reps=30))
+    scores = [rep.rounds[i].score for i in range(rep.n_rounds)]
+    print("silumul rounds", scores, g, flush=True)
+    assert rep.n_rounds == 4 and all(rep.rounds[i].passed for i in range(4))
+    assert scores[1] < scores[0] - 0.03 and min(scores) == scores[rep.best_round]
+    assert rep.rounds[0].general.flags == 0 and rep.rounds[0].general.max_waves_per_simd == 0
+    for M, d in shapes:
+        assert B.silumul_table_lookup(M, d, "bf16") is not None
