@@ -59,9 +59,12 @@ enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguou
        ADDRMS_FLAG_NONTEMPORAL = 2,   /* streaming cache policy on x/residual loads and stores    */
        ADDRMS_FLAG_PERSISTENT = 4,    /* grid = resident workgroups only; each walks several row
                                          blocks and prefetches the next block before reducing   */
-       ADDRMS_FLAG_TWO_PASS = 8 };    /* rows too long for the register row cache: read the row
+       ADDRMS_FLAG_TWO_PASS = 8,      /* rows too long for the register row cache: read the row
                                          twice (sum of squares, then outputs); feasible only
                                          where no single-pass configuration covers N            */
+       ADDRMS_FLAG_LDS_CACHE = 16 };  /* rows somewhat too long for the registers: still one pass,
+                                         the row cache continues in the workgroup's LDS (up to
+                                         160 KB per CU, so about 73 K elements per row)          */
 
 typedef struct addrms_cfg {
     int32_t vec;              /* elements per thread per vector access: 1, 2, 4, 8        */
@@ -85,9 +88,10 @@ typedef struct addrms_cfg {
  *   M, N     rows, row length.  M == 0 is a successful no-op; N <= 0 is INVALID_ARG;
  *            a row is held in registers between the reduction and the scaling
  *            (1024 threads x 32 cached values, at most 16 accesses per thread:
- *            even N up to 32768, odd N up to 16384); longer rows, up to 2^28
- *            elements, run in the two-pass form (ADDRMS_FLAG_TWO_PASS), which the
- *            default configuration selects by itself; beyond that UNSUPPORTED_SHAPE
+ *            even N up to 32768, odd N up to 16384); longer rows continue the
+ *            cache in LDS (ADDRMS_FLAG_LDS_CACHE) while it fits and otherwise, up to
+ *            2^28 elements, run in the two-pass form (ADDRMS_FLAG_TWO_PASS); the default
+ *            configuration selects these by itself; beyond that UNSUPPORTED_SHAPE
  *   dtype    addrms_dtype
  *   cfg      host; NULL = look (M, N, dtype) up in the specialised table
  *            (nearest tuned M for the same N and dtype), else the default cfg
@@ -295,21 +299,23 @@ int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int d
  * The deriver prunes two kinds of configurations: invalid ones (a launch the hardware
  * or the compiled instance cannot take) and ones it calls obviously inefficient (at
  * most half the lanes of a row carrying data; fewer than two resident waves per SIMD;
- * an instance that spills registers; the two-pass form where a single pass would do).
- * The second kind is a judgement, and this call puts it to the test: it enumerates
- * the grid with those four rules switched off,
+ * an instance that spills registers; the two-pass form or the LDS-extended cache where
+ * the registers of a single pass would do).  The second kind is a judgement, and this
+ * call puts it to the test: it enumerates the grid with those five rules switched off,
  * passes both the retained configurations and the ones each rule would have pruned
  * through the correctness gate and the screening protocol (budget.coarse_warmup /
  * coarse_reps, default 3 + 15 launches), and reports per rule how the pruned ones
  * compare.  A rule is sound on this shape if none of what it prunes is faster than
  * the best retained configuration (n_beating_best == 0, up to timing noise).
- * budget.max_candidates caps the configurations measured PER CLASS (evenly strided
- * sample; 0 = all); budget.max_wall_ms stops early (truncated = 1).  Nothing is added
+ * budget.max_candidates caps the configurations measured per PRUNED class (evenly
+ * strided sample; 0 = all; the retained region is always measured in full, since its
+ * best member is the yardstick); budget.max_wall_ms stops early (truncated = 1).  Nothing is added
  * to the table, and addrms_run still refuses the pruned configurations.  Blocking;
  * allocates and frees device memory. */
-#define ADDRMS_AUDIT_RULES 4
+#define ADDRMS_AUDIT_RULES 5
 typedef struct addrms_audit_rule {
-    char    rule[24];          /* "lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless" */
+    char    rule[24];          /* "lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless",
+                                  "lds_cache_needless"                                                 */
     int64_t n_pruned;          /* grid points this rule alone keeps out of the feasible region         */
     int32_t n_measured;        /* of those, validated and timed                                        */
     int32_t n_failed;          /* of those, failed the gate or the launch                              */

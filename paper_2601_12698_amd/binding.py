@@ -26,6 +26,7 @@ FLAG_XCD_CONTIG = 1
 FLAG_NONTEMPORAL = 2
 FLAG_PERSISTENT = 4
 FLAG_TWO_PASS = 8
+FLAG_LDS_CACHE = 16
 SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
 FAMILY_STREAMING, FAMILY_OCCUPANCY_CAP, FAMILY_GRID_MAPPING, FAMILY_BASE_ONLY = 1, 2, 4, 8
 MAX_ROUNDS = 4
@@ -175,7 +176,7 @@ class RoundsReport(Structure):
                     best=self.best.as_dict())
 
 
-AUDIT_RULES = 4
+AUDIT_RULES = 5
 
 
 class AuditRule(Structure):

@@ -31,12 +31,13 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
     if (budget && (budget->reserved1 != 0)) return fail(ADDRMS_ERR_INVALID_ARG, "budget.reserved1 must be 0");
     const int warm = budget && budget->coarse_warmup > 0 ? budget->coarse_warmup : 3;
     const int reps = budget && budget->coarse_reps > 0 ? budget->coarse_reps : 15;
-    const int per_class = budget && budget->max_candidates > 0 ? budget->max_candidates : 0;   // 0 = all
+    const int per_class = budget && budget->max_candidates > 0 ? budget->max_candidates : 0;   // pruned classes; 0 = all
     const double wall_cap = budget ? budget->max_wall_ms : 0.0;
     const bool gate = !(budget && budget->skip_validation) && be.validate;
 
     memset(report, 0, sizeof *report);
-    static const char* kRules[ADDRMS_AUDIT_RULES] = {"lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless"};
+    static const char* kRules[ADDRMS_AUDIT_RULES] = {"lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless",
+                                                      "lds_cache_needless"};
     for (int r = 0; r < ADDRMS_AUDIT_RULES; ++r) snprintf(report->rules[r].rule, sizeof report->rules[r].rule, "%s", kRules[r]);
 
     // class 0 = retained by every rule; class 1 + r = let through only because rule r was switched off
@@ -54,9 +55,9 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
     if (cls[0].empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
 
     bool out_of_time = false;
-    auto run_class = [&](const std::vector<addrms_cfg>& v, std::vector<double>* times, addrms_cfg* best_cfg,
+    auto run_class = [&](const std::vector<addrms_cfg>& v, bool sample, std::vector<double>* times, addrms_cfg* best_cfg,
                          int32_t* n_failed) {
-        const size_t stride = per_class > 0 ? std::max<size_t>(1, (v.size() + per_class - 1) / per_class) : 1;
+        const size_t stride = (sample && per_class > 0) ? std::max<size_t>(1, (v.size() + per_class - 1) / per_class) : 1;
         double best = 0.0;
         for (size_t i = 0; i < v.size(); i += stride) {
             if (wall_cap > 0.0 && elapsed_ms() >= wall_cap) { out_of_time = true; break; }
@@ -71,7 +72,7 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
 
     std::vector<double> t_ret;
     int32_t failed_ret = 0;
-    report->retained_best_us = run_class(cls[0], &t_ret, &report->retained_best, &failed_ret);
+    report->retained_best_us = run_class(cls[0], false, &t_ret, &report->retained_best, &failed_ret);
     report->n_retained_measured = static_cast<int32_t>(t_ret.size());
     report->n_retained_failed = failed_ret;
     if (t_ret.empty()) return fail(ADDRMS_ERR_NO_RESULT, "no retained configuration could be measured");
@@ -83,7 +84,7 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
         addrms_audit_rule& o = report->rules[r];
         o.n_pruned = static_cast<int64_t>(cls[1 + r].size());
         std::vector<double> t;
-        o.best_us = run_class(cls[1 + r], &t, &o.best, &o.n_failed);
+        o.best_us = run_class(cls[1 + r], true, &t, &o.best, &o.n_failed);
         o.n_measured = static_cast<int32_t>(t.size());
         for (double us : t) {
             if (us < report->retained_decile_us) ++o.n_in_top_decile;

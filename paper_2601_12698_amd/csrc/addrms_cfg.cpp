@@ -135,10 +135,10 @@ bool cfg_equal(const addrms_cfg& a, const addrms_cfg& b)
 }
 uint64_t cfg_key(const addrms_cfg& c)
 {
-    return (static_cast<uint64_t>(c.vec) << 40) | (static_cast<uint64_t>(c.threads_per_row) << 24) |
-           (static_cast<uint64_t>(c.rows_per_wg) << 16) | (static_cast<uint64_t>(c.reduce) << 12) |
-           (static_cast<uint64_t>(c.unroll) << 8) | (static_cast<uint64_t>(c.max_waves_per_simd & 0xf) << 4) |
-           static_cast<uint64_t>(c.flags & 0xf);
+    return (static_cast<uint64_t>(c.vec) << 40) | (static_cast<uint64_t>(c.threads_per_row) << 28) |
+           (static_cast<uint64_t>(c.rows_per_wg) << 20) | (static_cast<uint64_t>(c.reduce) << 16) |
+           (static_cast<uint64_t>(c.unroll) << 12) | (static_cast<uint64_t>(c.max_waves_per_simd & 0xf) << 8) |
+           static_cast<uint64_t>(c.flags & 0xff);
 }
 std::string cfg_json(const addrms_cfg& c)
 {
@@ -260,13 +260,17 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     if (op != OP_ADDRMS && c.reduce != 0)
         return infeasible("grid", "reduce=%d: %s has no reduction; the knob must stay 0", c.reduce, op_name(op));
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
-    if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT | ADDRMS_FLAG_TWO_PASS))
+    if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT | ADDRMS_FLAG_TWO_PASS |
+                    ADDRMS_FLAG_LDS_CACHE))
         return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
     const bool two_pass = (c.flags & ADDRMS_FLAG_TWO_PASS) != 0;
-    if (two_pass && op != OP_ADDRMS)
-        return infeasible("grid", "flags=0x%x: only add+RMSNorm has a two-pass form", c.flags);
-    if (two_pass && (c.flags & ADDRMS_FLAG_PERSISTENT))
-        return infeasible("grid", "flags=0x%x: the two-pass form has no persistent grid", c.flags);
+    const bool lds_cache = (c.flags & ADDRMS_FLAG_LDS_CACHE) != 0;
+    if ((two_pass || lds_cache) && op != OP_ADDRMS)
+        return infeasible("grid", "flags=0x%x: only add+RMSNorm has forms for long rows", c.flags);
+    if (two_pass && lds_cache)
+        return infeasible("grid", "flags=0x%x: the two-pass form and the LDS-extended cache exclude each other", c.flags);
+    if ((two_pass || lds_cache) && (c.flags & ADDRMS_FLAG_PERSISTENT))
+        return infeasible("grid", "flags=0x%x: the long-row forms have no persistent grid", c.flags);
     if (c.max_waves_per_simd < 0 || c.max_waves_per_simd >= L.max_waves_per_simd)
         return infeasible("grid", "max_waves_per_simd=%d: must be 0 (no cap) or 1..%d", c.max_waves_per_simd,
                           L.max_waves_per_simd - 1);
@@ -294,6 +298,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     // -- register row cache: the row slice of a thread must fit in registers (single-pass form)
     const int64_t per_pass = static_cast<int64_t>(c.vec) * c.threads_per_row;
     const int64_t need = (N + per_pass - 1) / per_pass;
+    int64_t lds_cache_bytes = 0;
     if (two_pass) {
         if (N * c.rows_per_wg > kMaxTwoPassElemsPerWg)
             return infeasible("row_too_long", "N=%lld x rows_per_wg=%d exceeds the %lld elements a workgroup addresses with "
@@ -304,12 +309,29 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                                   "reading every row twice is obviously inefficient", (long long)N);
             if (!f.soft_rule[0]) f.soft_rule = "two_pass_needless";
         }
+    } else if (lds_cache) {
+        const int64_t reg_chunks = kLdsCacheRegElems / c.vec;
+        // (a chunk count that fits the registers but has no plain instance - 17 to 32 one-element chunks, say -
+        // runs here with nothing parked: the register part of this form clamps its unused chunks)
+        if (need <= reg_chunks && cpt_supported(op, static_cast<int>(need)))
+            return infeasible("lds_cache_needless", "N=%lld over %d threads at vec=%d is %lld chunks per thread: they fit the "
+                              "registers, there is nothing to park in LDS", (long long)N, c.threads_per_row, c.vec, (long long)need);
+        lds_cache_bytes = static_cast<int64_t>(c.rows_per_wg) * std::max<int64_t>(0, need - reg_chunks) * per_pass * 4;
+        if (lds_cache_bytes + reduction_lds_bytes(c, op) > L.lds_bytes_per_cu)
+            return infeasible("lds_cache_too_big", "parking %lld chunks per thread takes %lld bytes of LDS per workgroup; a CU has %d",
+                              (long long)std::max<int64_t>(0, need - reg_chunks), (long long)lds_cache_bytes, L.lds_bytes_per_cu);
+        if (single_pass_covers(N, dtype, op)) {
+            if (!(relax & RELAX_LDS_CACHE_NEEDLESS))
+                return infeasible("lds_cache_needless", "N=%lld fits the register row cache of a single-pass configuration: "
+                                  "a detour through LDS is obviously inefficient", (long long)N);
+            if (!f.soft_rule[0]) f.soft_rule = "lds_cache_needless";
+        }
     } else if (need * c.vec > kMaxElemsPerThread)
         return infeasible("row_cache", "N=%lld over %d threads at vec=%d needs %lld values per thread in registers; the row cache "
                           "holds %d (more would spill or leave under %d waves per SIMD)",
                           (long long)N, c.threads_per_row, c.vec, (long long)(need * c.vec), kMaxElemsPerThread,
                           kMinWavesPerSimd);
-    if (!two_pass && !cpt_supported(op, static_cast<int>(need)))
+    if (!two_pass && !lds_cache && !cpt_supported(op, static_cast<int>(need)))
         return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (%s)", (long long)need,
                           op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : op == OP_MERGE ? "1-4 exist" : "1-8 exist");
     f.res.chunks_per_thread = static_cast<int>(need);
@@ -331,8 +353,8 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                           2 * L.xcds);
 
     // -- compiled instance and its resources
-    const int idx = find_instance(op, dtype, c.vec, two_pass ? 0 : static_cast<int>(need), c.unroll,
-                                  (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0);
+    const int cpt_code = two_pass ? 0 : lds_cache ? kLdsCacheCptBase + kLdsCacheRegElems / c.vec : static_cast<int>(need);
+    const int idx = find_instance(op, dtype, c.vec, cpt_code, c.unroll, (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0);
     if (idx < 0)
         return infeasible("no_instance", "no compiled instance for dtype=%s vec=%d chunks=%lld unroll=%d", dtype_name(dtype), c.vec,
                           (long long)need, c.unroll);
@@ -342,7 +364,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     addrms_resources& o = f.res;
     o.vgprs = r.vgprs; o.agprs = r.agprs; o.sgprs = r.sgprs; o.scratch_bytes = r.scratch;
     o.max_threads = in.maxt;
-    o.lds_bytes = reduction_lds_bytes(c, op) + r.lds_static;
+    o.lds_bytes = reduction_lds_bytes(c, op) + static_cast<int>(lds_cache_bytes) + r.lds_static;
     o.waves_per_wg = threads / L.wave_size;
     if (r.scratch > 0 && (relax & RELAX_SCRATCH)) {
         if (!f.soft_rule[0]) f.soft_rule = "scratch";
@@ -390,6 +412,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     } else if (o.waves_per_simd < kMinWavesPerSimd)
         return infeasible("occupancy", "only %d wave per SIMD would be resident (%d registers per lane, %d-wave workgroups): too "
                           "few loads in flight to cover HBM latency", o.waves_per_simd, regs, o.waves_per_wg);
+    f.dyn_lds = o.lds_bytes - r.lds_static;
     return f;
 }
 
@@ -404,7 +427,7 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
             for (int rows : kRows)
                 for (int red = 0; red < 2; ++red)
                     for (int unr : kUnrolls)
-                        for (int flags = 0; flags < 16; ++flags)
+                        for (int flags = 0; flags < 32; ++flags)
                             for (int cap = 0; cap < hw().max_waves_per_simd; ++cap) {
                                 ++grid;
                                 addrms_cfg c{};
@@ -443,7 +466,14 @@ int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op)
     if (N <= 0) { if (why) *why = "N must be > 0"; return ADDRMS_ERR_INVALID_ARG; }
     const int64_t big_m = 1 << 20;
     if (single_pass_default(N, dtype, op, out)) return ADDRMS_OK;
-    if (op == OP_ADDRMS)   // rows beyond the register cache: the two-pass form, widest vector, largest workgroup
+    if (op == OP_ADDRMS)   // rows somewhat beyond the register cache: one pass, the cache continued in LDS
+        for (int vec : kVecs) {
+            addrms_cfg c{};
+            c.vec = vec; c.threads_per_row = hw().max_threads_per_wg; c.rows_per_wg = 1;
+            c.reduce = ADDRMS_REDUCE_WAVE; c.unroll = 2; c.flags = ADDRMS_FLAG_LDS_CACHE;
+            if (check_cfg(c, big_m, N, dtype, op).status == ADDRMS_OK) { *out = c; return ADDRMS_OK; }
+        }
+    if (op == OP_ADDRMS)   // longer still: the two-pass form, widest vector, largest workgroup
         for (int vec : kVecs) {
             addrms_cfg c{};
             c.vec = vec; c.threads_per_row = hw().max_threads_per_wg; c.rows_per_wg = 1;

@@ -37,6 +37,8 @@ const HwLimits& hw();
 // Floors below which a launch shape is pruned as obviously inefficient.
 constexpr int kMinWavesPerSimd = 2;
 constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
+constexpr int kLdsCacheRegElems = 32;     // LDS-extended form: values per thread kept in registers (1024-thread bound)
+constexpr int kLdsCacheCptBase = 100;    // its instances carry cpt = 100 + register-held chunks
 constexpr int64_t kMaxTwoPassElemsPerWg = 1ll << 28;   // two-pass form: rows_per_wg * N elements, 32-bit byte offsets
 
 // ---- operators that go through the tuner ------------------------------------
@@ -68,7 +70,7 @@ const char* dtype_name(int dtype);
 // keep a launch valid (sizes, alignment, instance limits, LDS, at least one workgroup per
 // CU) and rules that only remove duplicates of another cfg can never be switched off.
 enum Relax : int { RELAX_LANE_UTILISATION = 1, RELAX_OCCUPANCY_FLOOR = 2, RELAX_SCRATCH = 4, RELAX_TWO_PASS_NEEDLESS = 8,
-                   RELAX_ALL = 15 };
+                   RELAX_LDS_CACHE_NEEDLESS = 16, RELAX_ALL = 31 };
 
 struct Feas {
     int status = ADDRMS_OK;
@@ -76,6 +78,7 @@ struct Feas {
     const char* soft_rule = ""; // first efficiency rule that a relaxed check let the cfg past
     std::string reason;
     int inst = -1;              // instance index when one was selected
+    int dyn_lds = 0;            // dynamic LDS bytes of the launch (reduction scratch, row cache, occupancy padding)
     addrms_resources res{};
 };
 Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op = OP_ADDRMS, int relax = 0);

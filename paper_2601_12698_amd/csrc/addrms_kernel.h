@@ -35,7 +35,8 @@ namespace addrms {
 
 enum : int { DT_BF16 = 0, DT_FP16 = 1, DT_FP16_RES32 = 2, DT_FP32 = 3 };
 enum : int { RED_WAVE = 0, RED_LDS = 1 };
-enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u, FLAG_PERSISTENT = 4u, FLAG_TWO_PASS = 8u };
+enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u, FLAG_PERSISTENT = 4u, FLAG_TWO_PASS = 8u,
+                  FLAG_LDS_CACHE = 16u };
 
 template <int DT> struct dt_traits;
 template <> struct dt_traits<DT_BF16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = true;  };
@@ -513,6 +514,168 @@ __device__ __forceinline__ void addrms_twopass_body(void* __restrict__ xp, void*
                 raw_t<XB * VEC> yout;
                 pack_vec<XB, BF, VEC>(y, yout);
                 st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), yout);
+            }
+        }
+    }
+}
+
+// Single pass with the row cache extended into LDS, for rows somewhat beyond what the
+// registers hold.  The first CPT chunks of a thread stay in registers exactly as in
+// addrms_body; the fp32 sums of its further chunks are parked in the thread's own slots
+// of the workgroup's LDS allocation (after the reduction scratch) and read back by the
+// same thread once rstd is known.  No other thread touches those slots, so the only
+// barrier is the reduction's.  Every byte of x and residual is still read once and
+// written once.  lds_cache_off: byte offset of the cache region in the dynamic LDS.
+template <int DT, int VEC, int CPT, int UNR, bool NT>
+__device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void* __restrict__ rp,
+                                                     const void* __restrict__ wp, float eps, double inv_n,
+                                                     int64_t M, int32_t N, uint32_t flags, int32_t reduce,
+                                                     uint32_t nblocks)
+{
+    using T = dt_traits<DT>;
+    constexpr int XB = T::XB, RB = T::RB;
+    constexpr bool BF = T::BF;
+    extern __shared__ double lds[];
+    (void)nblocks;
+
+    const uint32_t tpr = blockDim.x, rpw = blockDim.y;
+    const uint32_t lane = threadIdx.x, ry = threadIdx.y;
+    uint32_t blk = blockIdx.x;
+    if (flags & FLAG_XCD_CONTIG) blk = xcd_contiguous(blk, gridDim.x);
+
+    const RowAddr ra = row_addr<XB, RB>(xp, rp, blk, rpw, ry, M, N);
+    const char* wbase = static_cast<const char*>(wp);
+    const uint32_t n = static_cast<uint32_t>(N);
+    const uint32_t stride = tpr * VEC;
+    const uint32_t nlast = n - VEC;
+    const uint32_t col0 = lane * VEC;
+    const uint32_t reg_span = stride * CPT;                               // elements of a row held in registers
+    const uint32_t extra = n > reg_span ? (n - reg_span + stride - 1u) / stride : 0u;   // chunks per thread parked in LDS
+    // reduction scratch first (doubles), then the cache: [row][chunk][lane][VEC] floats
+    const uint32_t red_doubles = (reduce == RED_WAVE) ? (tpr > 64u ? rpw * 16u : 0u) : rpw * tpr;
+    float* cache = reinterpret_cast<float*>(lds + red_doubles) + (static_cast<size_t>(ry) * extra * tpr + lane) * VEC;
+    const uint32_t cache_step = tpr * VEC;                                // floats between a thread's consecutive chunks
+
+    float h[CPT][VEC];
+    double acc = 0.0;
+    // ---- register part
+#pragma unroll
+    for (int g = 0; g < CPT; g += UNR) {
+        raw_t<XB * VEC> xv[UNR];
+        raw_t<RB * VEC> rv[UNR];
+        load_group<XB, RB, VEC, CPT, UNR, NT>(ra.xbase, ra.rbase, ra.rowoff, col0, stride, nlast, g, xv, rv);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (g + u < CPT) {
+                const int c = g + u;
+                const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    h[c][e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                if (ra.row_ok && col <= nlast) {
+                    raw_t<RB * VEC> out;
+                    pack_vec<RB, BF, VEC>(h[c], out);
+                    st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), out);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const double hd = static_cast<double>(h[c][e]);
+                        acc = __builtin_fma(hd, hd, acc);
+                    }
+                }
+            }
+        }
+        if (g + UNR < CPT) __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- LDS part: uniform trip count, UNR chunks in flight
+    for (uint32_t e0 = 0; e0 < extra; e0 += UNR) {
+        raw_t<XB * VEC> xv[UNR];
+        raw_t<RB * VEC> rv[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (e0 + u < extra) {
+                const uint32_t col = col0 + (CPT + e0 + u) * stride;
+                const uint32_t colc = col < nlast ? col : nlast;
+                ld_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + colc) * XB), xv[u]);
+                ld_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + colc) * RB), rv[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (e0 + u < extra) {
+                const uint32_t col = col0 + (CPT + e0 + u) * stride;
+                float hx[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    hx[e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                if (ra.row_ok && col <= nlast) {
+                    raw_t<RB * VEC> out;
+                    pack_vec<RB, BF, VEC>(hx, out);
+                    st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), out);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const double hd = static_cast<double>(hx[e]);
+                        acc = __builtin_fma(hd, hd, acc);
+                    }
+                }
+                float* slot = cache + static_cast<size_t>(e0 + u) * cache_step;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) slot[e] = hx[e];
+            }
+        }
+    }
+
+    raw_t<XB * VEC> wv[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+        const uint32_t colc = col < nlast ? col : nlast;
+        ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(colc * XB), wv[c]);
+    }
+
+    const double ss = row_sum(acc, reduce, tpr, lane, ry, lds);
+    const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
+
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+        float y[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float t = h[c][e] * rstd;
+            y[e] = t * get_elem<XB, BF>(wv[c], e);
+        }
+        if (ra.row_ok && col <= nlast) {
+            raw_t<XB * VEC> out;
+            pack_vec<XB, BF, VEC>(y, out);
+            st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), out);
+        }
+    }
+    for (uint32_t e0 = 0; e0 < extra; e0 += UNR) {
+        raw_t<XB * VEC> wx[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (e0 + u < extra) {
+                const uint32_t col = col0 + (CPT + e0 + u) * stride;
+                const uint32_t colc = col < nlast ? col : nlast;
+                ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(colc * XB), wx[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (e0 + u < extra) {
+                const uint32_t col = col0 + (CPT + e0 + u) * stride;
+                const float* slot = cache + static_cast<size_t>(e0 + u) * cache_step;
+                float y[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float t = slot[e] * rstd;
+                    y[e] = t * get_elem<XB, BF>(wx[u], e);
+                }
+                if (ra.row_ok && col <= nlast) {
+                    raw_t<XB * VEC> out;
+                    pack_vec<XB, BF, VEC>(y, out);
+                    st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), out);
+                }
             }
         }
     }

@@ -59,7 +59,8 @@ int launch_instance(const Feas& f, const addrms_cfg& c, int64_t M, int op, void*
 {
     const dim3 grid(static_cast<unsigned>(n_workgroups(c, M, f.res.wgs_per_cu)));
     const dim3 block(static_cast<unsigned>(c.threads_per_row), static_cast<unsigned>(c.rows_per_wg));
-    const int lds = lds_bytes_for(c, op);
+    const int lds = f.dyn_lds;
+    (void)op;
     if (lds > kDefaultDynamicLdsLimit) {
         // Occupancy padding beyond the default per-launch limit has to be enabled once per kernel.
         std::atomic<bool>& done = g_big_lds_enabled[f.inst];
@@ -839,11 +840,11 @@ int addrms_device_resources(const addrms_cfg* cfg, int64_t M, int64_t N, int dty
     const int threads = cfg->threads_per_row * cfg->rows_per_wg;
     int wgs = 0;
     HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs, kDispatch[f.inst].fn, threads,
-                                                         static_cast<size_t>(lds_bytes_for(*cfg))));
+                                                         static_cast<size_t>(f.dyn_lds)));
     out->chunks_per_thread = f.res.chunks_per_thread;
     out->vgprs = attr.numRegs;
     out->scratch_bytes = static_cast<int32_t>(attr.localSizeBytes);
-    out->lds_bytes = static_cast<int32_t>(attr.sharedSizeBytes) + lds_bytes_for(*cfg);
+    out->lds_bytes = static_cast<int32_t>(attr.sharedSizeBytes) + f.dyn_lds;
     out->max_threads = attr.maxThreadsPerBlock;
     out->waves_per_wg = threads / hw().wave_size;
     out->wgs_per_cu = wgs;

@@ -38,6 +38,7 @@ namespace {
 
 using Clock = std::chrono::steady_clock;
 constexpr double kShortKernelUs = 10.0;
+constexpr int kFormBits = ADDRMS_FLAG_TWO_PASS | ADDRMS_FLAG_LDS_CACHE;
 
 struct Cand {
     addrms_cfg cfg{};
@@ -155,13 +156,14 @@ struct Searcher {
                 if (!(c.flags & ADDRMS_FLAG_PERSISTENT) || !(c.flags & ADDRMS_FLAG_NONTEMPORAL)) continue;
                 score = -threads - 0.1 * c.unroll - ((c.flags & ADDRMS_FLAG_XCD_CONTIG) ? 0.01 : 0.0);
             } else {
-                // (the two-pass bit is the same for every feasible cfg of a shape: ignore it here)
-                if ((c.flags & ~ADDRMS_FLAG_TWO_PASS) != (mode == kPlain ? 0 : ADDRMS_FLAG_NONTEMPORAL)) continue;
+                // (the long-row form is part of the class, not of the mode)
+                if ((c.flags & ~kFormBits) != (mode == kPlain ? 0 : ADDRMS_FLAG_NONTEMPORAL)) continue;
                 const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
                 score = fabs(log2(threads / 256.0)) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
                 if (mode == kCapped) score += 0.5 * fabs(static_cast<double>(c.max_waves_per_simd) - 4.0);
             }
-            auto key = std::make_pair(-c.vec, c.threads_per_row);       // widest vector first
+            // widest vector first; the long-row forms (two-pass, LDS-extended cache) are classes of their own
+            auto key = std::make_pair(-c.vec - 16 * (c.flags & kFormBits), c.threads_per_row);
             auto it = best.find(key);
             if (it == best.end() || score < it->second.first) best[key] = {score, i};
         }
@@ -184,6 +186,7 @@ struct Searcher {
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_XCD_CONTIG; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_NONTEMPORAL; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_PERSISTENT; push(n); }
+        if (c.flags & kFormBits) { addrms_cfg n = c; n.flags ^= kFormBits; push(n); }   // the other long-row form
         // occupancy cap: one step tighter, one step looser (0 = uncapped sits above the natural occupancy)
         {
             const int natural = cands[i].res.waves_per_simd;
@@ -360,7 +363,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
             if (!s.budget_left()) break;
             if (s.eval(i, "sweep", b.coarse_warmup, b.coarse_reps)) {
                 const addrms_cfg& c = s.cands[i].cfg;
-                plain_us[{c.vec, c.threads_per_row}] = s.cands[i].us;
+                plain_us[{c.vec + 16 * (c.flags & kFormBits), c.threads_per_row}] = s.cands[i].us;
                 if (best_plain == 0.0 || s.cands[i].us < best_plain) best_plain = s.cands[i].us;
             }
         }
@@ -370,7 +373,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
             for (int i : s.class_representatives(mode)) {
                 if (!s.budget_left()) break;
                 const addrms_cfg& c = s.cands[i].cfg;
-                auto it = plain_us.find({c.vec, c.threads_per_row});
+                auto it = plain_us.find({c.vec + 16 * (c.flags & kFormBits), c.threads_per_row});
                 if (it != plain_us.end() && it->second > 2.0 * best_plain) continue;
                 s.eval(i, mode == Searcher::kStreaming ? "sweep_streaming"
                           : mode == Searcher::kPersistent ? "sweep_persistent" : "sweep_capped",
@@ -384,7 +387,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
             for (int j : starts)
                 dup = dup || (s.cands[j].cfg.vec == s.cands[i].cfg.vec &&
                               s.cands[j].cfg.threads_per_row == s.cands[i].cfg.threads_per_row &&
-                              ((s.cands[j].cfg.flags ^ s.cands[i].cfg.flags) & ADDRMS_FLAG_PERSISTENT) == 0);
+                              ((s.cands[j].cfg.flags ^ s.cands[i].cfg.flags) & (ADDRMS_FLAG_PERSISTENT | kFormBits)) == 0);
             if (!dup) starts.push_back(i);
             if (starts.size() == 3) break;
         }

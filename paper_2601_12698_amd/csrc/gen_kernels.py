@@ -3,7 +3,8 @@
 The templates in ``addrms_kernel.h`` and ``silumul_kernel.h`` have four
 compile-time knobs (VEC, CPT, UNR, NT) per storage format.  CPT = 0 names the
 two-pass form of add+RMSNorm, which loops over the row instead of caching it
-(rows beyond the register row cache).  This script emits,
+(rows beyond the register row cache), and CPT = 100 + k the single-pass form
+whose cache continues in LDS after k register-held chunks.  This script emits,
 into a build directory:
 
   kern_<op>_d<DT>_v<VEC>.hip  one translation unit per (operator, format, vector width),
@@ -30,6 +31,7 @@ UNRS = (1, 2, 4, 8)
 X_BYTES = {0: 2, 1: 2, 2: 2, 3: 4}      # bytes per x element of each format
 MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 values per thread
 BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
+LDS_CACHE_BASE = 100                    # cpt code of the LDS-extended form: 100 + register-held chunks
 
 
 OP_ADDRMS, OP_SILUMUL, OP_MERGE = 0, 1, 2
@@ -61,6 +63,12 @@ def instances():
                     for unr in UNRS:
                         for nt in (0, 1):
                             yield op, dt, vec, 0, unr, nt, 1024
+                    reg_cpt = BIG_ELEMS // vec       # LDS-extended cache: registers filled to the 1024-thread bound
+                    for unr in UNRS:
+                        if unr > reg_cpt:
+                            continue
+                        for nt in (0, 1):
+                            yield op, dt, vec, LDS_CACHE_BASE + reg_cpt, unr, nt, 1024
 
 
 def name(op, dt, vec, cpt, unr, nt):
@@ -81,6 +89,8 @@ CALL = {
                "(va, sa, vb, sb, vo, so, rows, d, flags, nblocks);"),
 }
 TWO_PASS_CALL = "addrms::addrms_twopass_body<{dt}, {vec}, {unr}, {nt}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);"
+LDS_CACHE_CALL = ("addrms::addrms_ldscache_body<{dt}, {vec}, {cpt}, {unr}, {nt}>"
+                  "(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);")
 HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h", OP_MERGE: "mergestates_kernel.h"}
 
 
@@ -92,8 +102,12 @@ def main(outdir: str) -> None:
     for (op, dt, vec), lst in units.items():
         lines = [f'#include "{HEADER[op]}"', ""]
         for cpt, unr, nt, maxt in lst:
-            fmt = TWO_PASS_CALL if (op == OP_ADDRMS and cpt == 0) else CALL[op]
-            call = fmt.format(dt=dt, vec=vec, cpt=cpt, unr=unr, nt="true" if nt else "false")
+            fmt = CALL[op]
+            if op == OP_ADDRMS and cpt == 0:
+                fmt = TWO_PASS_CALL
+            elif op == OP_ADDRMS and cpt >= LDS_CACHE_BASE:
+                fmt = LDS_CACHE_CALL
+            call = fmt.format(dt=dt, vec=vec, cpt=cpt % LDS_CACHE_BASE, unr=unr, nt="true" if nt else "false")
             lines.append(f'extern "C" __global__ __launch_bounds__({maxt}) void {name(op, dt, vec, cpt, unr, nt)}'
                          f"({ARGS[op]})\n{{ {call} }}")
         _write(os.path.join(outdir, f"kern_{OP_PREFIX[op]}_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")

@@ -118,7 +118,7 @@ def main(argv=None) -> int:
                     help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
                          "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
     ap.add_argument("--long-rows", action="store_true",
-                    help="also tune rows beyond the register row cache, which run in the two-pass form")
+                    help="also tune rows beyond the register row cache (LDS-extended cache or two-pass form)")
     ap.add_argument("--graph-decode", action="store_true",
                     help="decode shapes: per-launch time of a chain of launches issued eagerly vs replayed from a HIP graph")
     ap.add_argument("--audit", action="store_true",
@@ -192,7 +192,7 @@ def main(argv=None) -> int:
                       f"{rep.default_us[i] / rep.general_us[i]:.3f} | {rep.default_us[i] / rep.specialized_us[i]:.3f} | "
                       f"{rep.specialized[i].as_tuple()} |", flush=True)
     if a.long_rows:
-        print("\nRows beyond the register row cache (two-pass form: the row is read twice), tuned vs default:\n")
+        print("\nRows beyond the register row cache (flags 16: cache continued in LDS, one pass; flags 8: two passes), tuned vs default:\n")
         print("| M x N | dtype | default us | tuned us | speedup | tuned GB/s (algorithmic) | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
         print("|---|---|---|---|---|---|---|---|---|---|---|")
         for M, N, dtype in ((4096, 40960, "bf16"), (2048, 65536, "bf16"), (1024, 131072, "bf16"),

@@ -28,7 +28,7 @@ KNOWN_INFEASIBLE = [
     (B.make_cfg(8, 256, 3), 4096, 4096, "bf16", "rows_per_wg"),
     (B.make_cfg(8, 256, 1, reduce=2), 4096, 4096, "bf16", "reduce"),
     (B.make_cfg(8, 256, 1, unroll=3), 4096, 4096, "bf16", "unroll"),
-    (B.make_cfg(8, 256, 1, flags=16), 4096, 4096, "bf16", "flags"),
+    (B.make_cfg(8, 256, 1, flags=32), 4096, 4096, "bf16", "flags"),
     (B.make_cfg(8, 256, 1, unroll=2, flags=4), 1024, 4096, "bf16", "persistent grid is the ordinary grid"),
     (B.make_cfg(8, 256, 1), 4096, 4100, "bf16", "does not divide"),
     (B.make_cfg(8, 256, 1), 4096, 4096, "fp32", "wider than"),
@@ -67,8 +67,8 @@ def test_bad_shape_and_dtype_codes():
                                        (8192, 1000, "fp16_res32"), (8192, 2880, "fp16_res32"), (128, 11008, "fp32")])
 def test_enumeration_is_exactly_the_feasible_subset(M, N, dtype):
     cfgs, grid = B.addrms_enumerate_feasible(M, N, dtype)
-    assert grid == 4 * 19 * 5 * 2 * 4 * 16 * 8          # vec, threads/row, rows/wg, reduce, unroll, 4 flag bits, cap
-    assert not any(c.flags & B.FLAG_TWO_PASS for c in cfgs)   # these rows fit the register cache
+    assert grid == 4 * 19 * 5 * 2 * 4 * 32 * 8          # vec, threads/row, rows/wg, reduce, unroll, 5 flag bits, cap
+    assert not any(c.flags & (B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE) for c in cfgs)   # these rows fit the register cache
     assert 0 < len(cfgs) < grid
     seen = set()
     for c in cfgs:
@@ -123,6 +123,9 @@ def test_occupancy_model_matches_compiler_report():
             if cpt == 0:       # two-pass instance: selected by the flag, for a row beyond the register cache
                 c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_TWO_PASS | (B.FLAG_NONTEMPORAL if nt else 0))
                 st, why, _ = feas(c, 4096, vec * 1024 * 40, dtype)
+            elif cpt >= 100:   # LDS-extended instance: registers full (cpt - 100 chunks), one more chunk parked in LDS
+                c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_LDS_CACHE | (B.FLAG_NONTEMPORAL if nt else 0))
+                st, why, _ = feas(c, 4096, vec * 1024 * (cpt - 100 + 1), dtype)
             else:
                 c = B.make_cfg(vec, 64, 1, unroll=unr, flags=B.FLAG_NONTEMPORAL if nt else 0)
                 st, why, _ = feas(c, 4096, vec * 64 * cpt, dtype)
@@ -170,12 +173,13 @@ def test_default_cfg():
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp16", "fp16_res32", "fp32"])
 def test_row_length_bound_of_the_register_cache(dtype):
-    """1024 threads x 32 cached values, at most 16 accesses per thread: even N up to 32768 and
-    odd N up to 16384 run in the single-pass form; one past either bound, and up to 2^28
-    elements, only the two-pass form is feasible; beyond that nothing is."""
+    """1024 threads x 32 cached values, at most 16 accesses per thread: even N up to 32768 and odd N up to
+    16384 run in the plain single-pass form; beyond that the row cache continues in LDS while 160 KB hold
+    the rest, then the two-pass form takes over up to 2^28 elements; beyond that nothing is feasible."""
+    long_forms = B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE
     for N in (32768, 32766, 32764, 16383, 16381):
         c = B.addrms_default_cfg(N, dtype)
-        assert not c.flags & B.FLAG_TWO_PASS
+        assert not c.flags & long_forms
         assert N % c.vec == 0 and c.threads_per_row * c.vec * 16 >= N
         st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
         assert st == 0, why
@@ -183,18 +187,39 @@ def test_row_length_bound_of_the_register_cache(dtype):
         two = B.make_cfg(c.vec, 1024, 1, unroll=2, flags=B.FLAG_TWO_PASS)
         st, why, _ = B.addrms_cfg_feasible(two, 4, N, dtype)
         assert st == B.ERR_INFEASIBLE_CFG and "reading every row twice" in why
-    for N in (32767, 32770, 16385, 65536, 1 << 20, 1 << 28):
+        st, why, _ = B.addrms_cfg_feasible(B.make_cfg(c.vec, 256, 1, unroll=2, flags=B.FLAG_LDS_CACHE), 4, N, dtype)
+        assert st == B.ERR_INFEASIBLE_CFG and ("detour through LDS" in why or "nothing to park" in why), why
+    for N in (16385, 24577, 32767):                 # odd rows past 16 one-element chunks: still all in registers
         c = B.addrms_default_cfg(N, dtype)
+        assert c.flags == B.FLAG_LDS_CACHE and c.vec == 1 and c.threads_per_row == 1024
+        st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
+        assert st == 0 and 17 <= res.chunks_per_thread <= 32 and res.lds_bytes <= 128, why
+    for N in (32770, 40960, 65536):
+        c = B.addrms_default_cfg(N, dtype)          # somewhat beyond the registers: one pass, the rest parked in LDS
+        assert c.flags == B.FLAG_LDS_CACHE and N % c.vec == 0 and c.threads_per_row == 1024 and c.rows_per_wg == 1
+        st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
+        assert st == 0, why
+        parked = res.chunks_per_thread - 32 // c.vec
+        assert parked >= 1 and res.lds_bytes >= parked * 1024 * c.vec * 4 and res.lds_bytes <= 160 * 1024
+        assert res.scratch_bytes == 0
+    for N in (32767 * 4 + 1, 1 << 20, 1 << 28):
+        c = B.addrms_default_cfg(N, dtype)          # too long for LDS as well: read the row twice
         assert c.flags == B.FLAG_TWO_PASS and N % c.vec == 0 and c.threads_per_row == 1024 and c.rows_per_wg == 1
         st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
         assert st == 0, why
         assert res.chunks_per_thread == -(-N // (c.vec * 1024)) and res.scratch_bytes == 0
+        st, why, _ = B.addrms_cfg_feasible(B.make_cfg(c.vec, 1024, 1, unroll=2, flags=B.FLAG_LDS_CACHE), 4, N, dtype)
+        assert st == B.ERR_INFEASIBLE_CFG and "bytes of LDS" in why, why
     for N in (65536, 100001):
         cfgs, _ = B.addrms_enumerate_feasible(4, N, dtype)
-        assert cfgs and all(c.flags & B.FLAG_TWO_PASS and not c.flags & B.FLAG_PERSISTENT for c in cfgs)
+        assert cfgs and all(c.flags & long_forms and not c.flags & B.FLAG_PERSISTENT for c in cfgs)
+        assert any(c.flags & B.FLAG_TWO_PASS for c in cfgs)
         one = B.make_cfg(cfgs[0].vec, 1024, 1)
         st, why, _ = B.addrms_cfg_feasible(one, 4, N, dtype)
         assert st == B.ERR_INFEASIBLE_CFG and ("row cache" in why or "compiled for workgroups" in why), why
+    st, why, _ = B.addrms_cfg_feasible(B.make_cfg(8 if dtype != "fp32" else 4, 1024, 1, flags=B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE),
+                                       4, 65536, dtype)
+    assert st == B.ERR_INFEASIBLE_CFG and "exclude each other" in why
     # a workgroup addresses rows_per_wg * N elements with 32-bit byte offsets
     st, why, _ = B.addrms_cfg_feasible(B.make_cfg(1, 64, 2, flags=B.FLAG_TWO_PASS), 4, (1 << 28) - 1, dtype)
     assert st == B.ERR_INFEASIBLE_CFG and "32-bit offsets" in why

@@ -121,20 +121,27 @@ def test_rows_beyond_the_template_are_refused_before_launch():
 
 
 @pytest.mark.parametrize("dtype,M,N", [("bf16", 5, 32770), ("bf16", 3, 65536), ("fp16", 4, 40001), ("fp16_res32", 3, 49152),
-                                       ("fp32", 2, 100000), ("bf16", 37, 36864), ("fp32", 1, 1 << 20)])
-def test_two_pass_form_for_rows_beyond_the_register_cache(oracle, dtype, M, N):
-    """Rows that no single-pass configuration holds run in the two-pass form (read, sum, read again,
-    write).  Same arithmetic, same bar: bit-identical to the oracle over a spread of its configurations."""
+                                       ("fp32", 2, 100000), ("bf16", 37, 36864), ("fp32", 1, 1 << 20), ("bf16", 7, 20001),
+                                       ("fp32", 6, 32767), ("bf16", 3, 73720)])
+def test_long_row_forms_beyond_the_register_cache(oracle, dtype, M, N):
+    """Rows that no plain single-pass configuration holds run with the row cache continued in LDS (one pass)
+    while 160 KB suffice, and in the two-pass form (read, sum, read again, write) beyond.  Same arithmetic,
+    same bar: bit-identical to the oracle over a spread of the configurations of each form."""
+    long_forms = B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE
     wl = _wl(M, N, dtype, 1200 + N % 89)
     d = W.generate(wl)
     case = DeviceCase(d, wl)
     y_ref, res_ref = oracle_outputs(oracle, d, wl)
     dflt = B.addrms_default_cfg(N, dtype)
-    assert dflt.flags & B.FLAG_TWO_PASS
+    assert dflt.flags & long_forms
     cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
-    assert cfgs and all(c.flags & B.FLAG_TWO_PASS for c in cfgs)
-    print(f"{wl.name}: {len(cfgs)} feasible, default {dflt.as_tuple()}", flush=True)
-    picks = [None] + cfgs[:: max(1, len(cfgs) // 80)]
+    assert cfgs and all(c.flags & long_forms for c in cfgs)
+    by_form = {f: [c for c in cfgs if c.flags & f] for f in (B.FLAG_TWO_PASS, B.FLAG_LDS_CACHE)}
+    print(f"{wl.name}: two-pass {len(by_form[B.FLAG_TWO_PASS])}, lds-cache {len(by_form[B.FLAG_LDS_CACHE])} feasible, "
+          f"default {dflt.as_tuple()}", flush=True)
+    picks = [None]
+    for lst in by_form.values():
+        picks += lst[:: max(1, len(lst) // 50)]
     for c in picks:
         y, res = case.run(c)
         assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0

@@ -20,7 +20,7 @@ def clean_table():
 
 
 @pytest.mark.parametrize("M,N,dtype", [(4096, 4096, "bf16"), (8192, 1000, "fp16_res32"), (512, 14336, "fp32"),
-                                       (64, 8192, "bf16")])
+                                       (64, 8192, "bf16"), (64, 49152, "bf16")])
 def test_deriver_model_matches_device(M, N, dtype):
     """Registers, LDS, workgroup bound and resident workgroups per CU predicted by
     the host-side deriver equal what the HIP runtime reports for the loaded kernels."""
@@ -77,15 +77,17 @@ def test_tune_small_budget_and_errors():
 
 
 def test_tune_rows_beyond_the_register_cache():
-    """The search runs unchanged over the two-pass family: every candidate passes the gate, the winner
-    carries the two-pass flag, is not slower than the default and is what a cfg-less run resolves to."""
-    M, N, dt = 256, 40960, "bf16"
-    c, rep = B.addrms_tune(M, N, dt, B.make_budget(warmup=5, reps=30))
-    assert c.flags & B.FLAG_TWO_PASS and rep.n_failed == 0 and 20 < rep.n_measured < 0.1 * rep.n_feasible
-    assert rep.default_cfg.flags == B.FLAG_TWO_PASS and rep.best_us <= rep.default_us * 1.02
-    assert B.addrms_table_lookup(M, N, dt).as_tuple() == c.as_tuple()
-    nbytes = B.addrms_algorithmic_bytes(M, N, dt)
-    print(f"two-pass {M}x{N}: {c} {rep.best_us:.2f} us = {nbytes / rep.best_us * 1e-3:.0f} GB/s; default {rep.default_us:.2f} us", flush=True)
+    """The search runs unchanged over the long-row forms: every candidate passes the gate, the winner is one of
+    them, is not slower than the default and is what a cfg-less run resolves to."""
+    long_forms = B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE
+    for M, N, dt in ((256, 40960, "bf16"), (128, 131072, "bf16")):
+        c, rep = B.addrms_tune(M, N, dt, B.make_budget(warmup=5, reps=30))
+        assert c.flags & long_forms and rep.n_failed == 0 and 20 < rep.n_measured < 0.1 * rep.n_feasible
+        assert rep.default_cfg.flags & long_forms and rep.best_us <= rep.default_us * 1.02
+        assert B.addrms_table_lookup(M, N, dt).as_tuple() == c.as_tuple()
+        nbytes = B.addrms_algorithmic_bytes(M, N, dt)
+        print(f"long rows {M}x{N}: {c} {rep.best_us:.2f} us = {nbytes / rep.best_us * 1e-3:.0f} GB/s; default "
+              f"{rep.default_cfg} {rep.default_us:.2f} us", flush=True)
 
 
 def test_measure_and_stream_probe():

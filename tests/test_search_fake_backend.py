@@ -170,20 +170,27 @@ def test_argument_errors():
     assert e.value.status == B.ERR_INVALID_ARG
 
 
-def test_search_over_the_two_pass_family():
-    """Rows beyond the register cache: the region holds two-pass cfgs only and both strategies work on it."""
+def test_search_over_the_long_row_forms():
+    """Rows beyond the register cache: the region holds the two long-row forms only (cache continued in LDS,
+    or two passes) and both strategies work across them."""
     m, n = 512, 65536
+    long_forms = B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE
 
     def cost2(c):
-        assert c.flags & B.FLAG_TWO_PASS and not c.flags & B.FLAG_PERSISTENT
-        return cost(c) * 3.0
+        assert c.flags & long_forms and not c.flags & B.FLAG_PERSISTENT
+        return cost(c) * (3.0 if c.flags & B.FLAG_TWO_PASS else 1.5)
 
     cfgs, _ = B.addrms_enumerate_feasible(m, n, DT)
+    assert {c.flags & long_forms for c in cfgs} == {B.FLAG_TWO_PASS, B.FLAG_LDS_CACHE}
     best = min(cfgs, key=cost2)
+    assert best.flags & B.FLAG_LDS_CACHE
     rec = Recorder(cost2)
     e, erep = B.addrms_tune_with_backend(m, n, DT, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE), rec.measure, rec.validate)
     assert e.as_tuple() == best.as_tuple() and erep.n_measured == len(cfgs) == erep.n_feasible
     rec = Recorder(cost2)
     g, grep = B.addrms_tune_with_backend(m, n, DT, B.make_budget(), rec.measure, rec.validate)
     assert cost2(g) <= 1.03 * cost2(best) and grep.n_measured < 0.05 * len(cfgs)
-    assert grep.default_cfg.flags == B.FLAG_TWO_PASS and grep.default_cfg.threads_per_row == 1024
+    assert grep.default_cfg.flags == B.FLAG_LDS_CACHE and grep.default_cfg.threads_per_row == 1024
+    # where only two passes fit, the search still works
+    g2, grep2 = B.addrms_tune_with_backend(m, 1 << 20, DT, B.make_budget(), rec.measure, rec.validate)
+    assert g2.flags & B.FLAG_TWO_PASS and grep2.default_cfg.flags == B.FLAG_TWO_PASS
