@@ -392,6 +392,27 @@ int addrms_table_load(const char* path);
  * out: device, fp32[n].  Asynchronous on stream. */
 int addrms_rstd_probe(const double* ss, int64_t n, int64_t N, float eps, float* out, void* stream);
 
+/* The correctness gate of the tuner (Algorithm 1 line 13, Validate; Section 3.1: d(S~(x), S(x)) <= eps over a
+ * finite test set) applied to caller buffers: compares n elements of an output pair (y, residual) with a
+ * reference pair.  residual must agree bit for bit; y may differ by at most `tol` units in the last place of
+ * its storage format, +0 and -0 counting as equal.
+ *   y, y_ref               device, n elements of the x dtype of `dtype`
+ *   residual, residual_ref device, n elements of the residual dtype of `dtype`
+ *   n                      0 .. 2^32-1 (the counters are 32 bits wide; more is INVALID_ARG)
+ *   counts_out             device, 16-byte aligned; receives the verdict
+ *   stream                 a hipStream_t passed as void*; NULL = the default stream
+ * Blocking: allocates a buffer of per-workgroup partial counts (16 bytes per 4096 elements, at most 64 KiB),
+ * runs the two kernels of the gate on `stream`, waits for them and frees the buffer.  The counts are exact and
+ * cost the same whether nothing or everything disagrees (no atomics). */
+typedef struct addrms_gate_counts {
+    uint32_t residual_mismatches;  /* residual elements whose bits differ                          */
+    uint32_t y_beyond_tol;         /* y elements further than tol units in the last place          */
+    uint32_t y_max_distance;       /* largest y distance seen, in units in the last place          */
+    uint32_t reserved;             /* written as 0                                                 */
+} addrms_gate_counts;
+int addrms_gate_probe(const void* y, const void* y_ref, const void* residual, const void* residual_ref, int64_t n,
+                      int dtype, uint32_t tol, addrms_gate_counts* counts_out, void* stream);
+
 /* Calibration kernel with the operator's traffic and none of its arithmetic:
  * reads [M,N] of x and of residual and writes both back (bitwise complemented),
  * 16 bytes per lane, streaming cache policy, three 256-thread workgroups per CU

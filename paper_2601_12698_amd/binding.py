@@ -245,6 +245,8 @@ SIGNATURES = {
     "addrms_device_resources": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, POINTER(Resources)]),
     "addrms_rstd_probe": (c_int, [c_void_p, c_int64, c_int64, c_float, c_void_p, c_void_p]),
     "addrms_stream_probe": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p]),
+    "addrms_gate_probe": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int, ctypes.c_uint32, c_void_p,
+                                  c_void_p]),
     "addrms_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
     "silumul_run": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, POINTER(Cfg), c_void_p]),
     "silumul_default_cfg": (c_int, [c_int64, c_int, POINTER(Cfg)]),
@@ -318,6 +320,28 @@ def _ptr(t) -> int:
     return int(t.data_ptr())
 
 
+_X_ELEM = {BF16: "bfloat16", FP16: "float16", FP16_RES32: "float16", FP32: "float32"}
+_R_ELEM = {BF16: "bfloat16", FP16: "float16", FP16_RES32: "float32", FP32: "float32"}
+
+
+def _expect_elem(name: str, t, want: str) -> None:
+    """The C ABI sees only pointers, so a tensor whose element type is narrower than the
+    storage format named by ``dtype`` would be read and written past its end: refuse it here."""
+    got = str(t.dtype).replace("torch.", "")
+    if got != want:
+        raise ValueError(f"{name} is {got} but dtype asks for {want}")
+
+
+def _expect_device_tensor(name: str, t, numel: int, elem: str) -> None:
+    _expect_elem(name, t, elem)
+    if t.numel() != numel:
+        raise ValueError(f"{name} has {t.numel()} elements, expected {numel}")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
 # ---- entry points --------------------------------------------------------------
 
 def addrms_version() -> str:
@@ -335,13 +359,12 @@ def addrms_algorithmic_bytes(M: int, N: int, dtype) -> int:
 def addrms_run(x, residual, weight, eps: float, M: int, N: int, dtype, cfg: Optional[Cfg] = None,
                stream=None) -> None:
     """In place: residual <- round(x + residual), x <- rmsnorm(x + residual) * weight."""
-    for name, t in (("x", x), ("residual", residual), ("weight", weight)):
-        if not t.is_cuda:
-            raise ValueError(f"{name} must be a device tensor")
-        if not t.is_contiguous():
-            raise ValueError(f"{name} must be contiguous")
-    if x.numel() != M * N or residual.numel() != M * N or weight.numel() != N:
-        raise ValueError("tensor sizes do not match M and N")
+    dt = _dtype_id(dtype)
+    if dt not in _X_ELEM:
+        raise ValueError(f"unknown dtype {dtype!r}")
+    _expect_device_tensor("x", x, M * N, _X_ELEM[dt])
+    _expect_device_tensor("residual", residual, M * N, _R_ELEM[dt])
+    _expect_device_tensor("weight", weight, N, _X_ELEM[dt])
     _check(load().addrms_run(_ptr(x), _ptr(residual), _ptr(weight), float(eps), M, N, _dtype_id(dtype),
                              byref(cfg) if cfg is not None else None, _stream_ptr(stream, x)))
 
@@ -616,11 +639,44 @@ def addrms_device_resources(cfg: Cfg, M: int, N: int, dtype) -> Resources:
 
 def addrms_rstd_probe(ss, N: int, eps: float, out, stream=None) -> None:
     """ss: device fp64 [n]; out: device fp32 [n]."""
+    _expect_device_tensor("ss", ss, ss.numel(), "float64")
+    _expect_device_tensor("out", out, ss.numel(), "float32")
     _check(load().addrms_rstd_probe(_ptr(ss), ss.numel(), N, float(eps), _ptr(out), _stream_ptr(stream, ss)))
 
 
 def addrms_stream_probe(x, residual, M: int, N: int, dtype, stream=None) -> None:
+    dt = _dtype_id(dtype)
+    if dt not in _X_ELEM:
+        raise ValueError(f"unknown dtype {dtype!r}")
+    _expect_device_tensor("x", x, M * N, _X_ELEM[dt])
+    _expect_device_tensor("residual", residual, M * N, _R_ELEM[dt])
     _check(load().addrms_stream_probe(_ptr(x), _ptr(residual), M, N, _dtype_id(dtype), _stream_ptr(stream, x)))
+
+
+class GateCounts(Structure):
+    _fields_ = [("residual_mismatches", ctypes.c_uint32), ("y_beyond_tol", ctypes.c_uint32),
+                ("y_max_distance", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+def _gate_args(y, y_ref, residual, residual_ref, dtype, counts_out):
+    dt = _dtype_id(dtype)
+    if dt not in _X_ELEM:
+        raise ValueError(f"unknown dtype {dtype!r}")
+    n = y.numel()
+    _expect_device_tensor("y", y, n, _X_ELEM[dt])
+    _expect_device_tensor("y_ref", y_ref, n, _X_ELEM[dt])
+    _expect_device_tensor("residual", residual, n, _R_ELEM[dt])
+    _expect_device_tensor("residual_ref", residual_ref, n, _R_ELEM[dt])
+    if not counts_out.is_cuda or counts_out.numel() * counts_out.element_size() < 16:
+        raise ValueError("counts_out must be a device tensor of at least 16 bytes")
+    return n, dt
+
+
+def addrms_gate_probe(y, y_ref, residual, residual_ref, dtype, tol: int, counts_out, stream=None) -> None:
+    """counts_out: device tensor of four 32-bit counters (residual mismatches, y beyond tol, max y distance, 0)."""
+    n, dt = _gate_args(y, y_ref, residual, residual_ref, dtype, counts_out)
+    _check(load().addrms_gate_probe(_ptr(y), _ptr(y_ref), _ptr(residual), _ptr(residual_ref), n, dt, int(tol),
+                                    _ptr(counts_out), _stream_ptr(stream, y)))
 
 
 # ---- silu_and_mul (include/silumul.h) -------------------------------------------------
@@ -631,11 +687,11 @@ def silumul_algorithmic_bytes(M: int, d: int, dtype) -> int:
 
 def silumul_run(x, out, M: int, d: int, dtype, cfg: Optional[Cfg] = None, stream=None) -> None:
     """out[i, j] = silu(x[i, j]) * x[i, d + j]; x is [M, 2d], out is [M, d], both on the device."""
-    for name, t in (("x", x), ("out", out)):
-        if not t.is_cuda or not t.is_contiguous():
-            raise ValueError(f"{name} must be a contiguous device tensor")
-    if x.numel() != 2 * M * d or out.numel() != M * d:
-        raise ValueError("tensor sizes do not match M and d")
+    dt = _dtype_id(dtype)
+    if dt not in _X_ELEM:
+        raise ValueError(f"unknown dtype {dtype!r}")
+    _expect_device_tensor("x", x, 2 * M * d, _X_ELEM[dt])
+    _expect_device_tensor("out", out, M * d, _X_ELEM[dt])
     _check(load().silumul_run(_ptr(x), _ptr(out), M, d, _dtype_id(dtype),
                               byref(cfg) if cfg is not None else None, _stream_ptr(stream, x)))
 
@@ -741,12 +797,13 @@ def mergestates_algorithmic_bytes(rows: int, d: int, dtype) -> int:
 def mergestates_run(v_a, s_a, v_b, s_b, v_out, s_out, rows: int, d: int, dtype, cfg: Optional[Cfg] = None,
                     stream=None) -> None:
     """Merge two partial attention states; v tensors [rows, d], scores fp32 [rows], all on the device."""
-    for name, t, n in (("v_a", v_a, rows * d), ("v_b", v_b, rows * d), ("v_out", v_out, rows * d),
-                       ("s_a", s_a, rows), ("s_b", s_b, rows), ("s_out", s_out, rows)):
-        if not t.is_cuda or not t.is_contiguous():
-            raise ValueError(f"{name} must be a contiguous device tensor")
-        if t.numel() != n:
-            raise ValueError(f"{name} has {t.numel()} elements, expected {n}")
+    dt = _dtype_id(dtype)
+    if dt not in _X_ELEM:
+        raise ValueError(f"unknown dtype {dtype!r}")
+    for name, t in (("v_a", v_a), ("v_b", v_b), ("v_out", v_out)):
+        _expect_device_tensor(name, t, rows * d, _X_ELEM[dt])
+    for name, t in (("s_a", s_a), ("s_b", s_b), ("s_out", s_out)):
+        _expect_device_tensor(name, t, rows, "float32")
     _check(load().mergestates_run(_ptr(v_a), _ptr(s_a), _ptr(v_b), _ptr(s_b), _ptr(v_out), _ptr(s_out), rows, d,
                                   _dtype_id(dtype), byref(cfg) if cfg is not None else None, _stream_ptr(stream, v_a)))
 

@@ -26,6 +26,8 @@ static const DispatchEntry kDispatch[] = {
 
 using namespace addrms_host;
 
+constexpr int kGateScratchSlots = 4096;   // most partial-count slots one gate launch uses
+
 namespace {
 
 #define HIP_TRY(expr)                                                                              \
@@ -175,8 +177,19 @@ __global__ void fill_kernel(void* p, long long n, uint32_t seed, float lo, float
 }
 
 // Correctness gate d(S~(x), S(x)) <= eps (Section 3.1): residual must match bit
-// for bit; y may differ by at most `tol` units in the last place of its format.
-// counts[0] = residual mismatches, counts[1] = y elements beyond tol, counts[2] = max y distance.
+// for bit; y may differ by at most `tol` units in the last place of its format
+// (+0 and -0 are the same value).  Counted in two stages so that the cost and the
+// result do not depend on how many elements disagree: every workgroup of
+// gate_partial_kernel walks a grid-stride slice and writes its three counts to its
+// own slot of `partial`; gate_finish_kernel folds the slots into `out`:
+//   out[0] = residual elements that differ, out[1] = y elements beyond tol,
+//   out[2] = largest y distance seen, out[3] = 0.
+// Every slot that is read was written by the same call, so the buffer needs no clearing.
+constexpr int kGateBlock = 256;
+constexpr int kGateMaxGrid = kGateScratchSlots;          // slots of 4 counters each
+constexpr size_t kGateScratchBytes = static_cast<size_t>(kGateMaxGrid) * 4 * sizeof(unsigned);
+constexpr long long kGateMaxElems = 0xffffffffll;        // the counters are 32 bits wide
+
 template <int ES>
 __device__ __forceinline__ long long ordered_bits(const void* p, long long i)
 {
@@ -191,22 +204,90 @@ __device__ __forceinline__ long long ordered_bits(const void* p, long long i)
     }
 }
 template <int XB, int RB>
-__global__ void compare_kernel(const void* y, const void* y_ref, const void* r, const void* r_ref, long long n,
-                               unsigned tol, unsigned* counts)
+__global__ __launch_bounds__(kGateBlock) void gate_partial_kernel(const void* y, const void* y_ref, const void* r,
+                                                                   const void* r_ref, long long n, unsigned tol,
+                                                                   unsigned* partial)
 {
-    const long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    bool rbad;
-    if constexpr (RB == 4) rbad = static_cast<const uint32_t*>(r)[i] != static_cast<const uint32_t*>(r_ref)[i];
-    else rbad = static_cast<const uint16_t*>(r)[i] != static_cast<const uint16_t*>(r_ref)[i];
-    if (rbad) atomicAdd(&counts[0], 1u);
-    long long d = ordered_bits<XB>(y, i) - ordered_bits<XB>(y_ref, i);
-    if (d < 0) d = -d;
-    if (d > 0) {
+    __shared__ unsigned red[3][kGateBlock];
+    unsigned rbad = 0, ybad = 0, ymax = 0;
+    const long long step = static_cast<long long>(gridDim.x) * kGateBlock;
+    for (long long i = static_cast<long long>(blockIdx.x) * kGateBlock + threadIdx.x; i < n; i += step) {
+        if constexpr (RB == 4) rbad += static_cast<const uint32_t*>(r)[i] != static_cast<const uint32_t*>(r_ref)[i];
+        else rbad += static_cast<const uint16_t*>(r)[i] != static_cast<const uint16_t*>(r_ref)[i];
+        long long d = ordered_bits<XB>(y, i) - ordered_bits<XB>(y_ref, i);
+        if (d < 0) d = -d;
         const unsigned du = d > 0xffffffffll ? 0xffffffffu : static_cast<unsigned>(d);
-        if (du > tol) atomicAdd(&counts[1], 1u);
-        atomicMax(&counts[2], du);
+        ybad += du > tol;
+        ymax = du > ymax ? du : ymax;
     }
+    red[0][threadIdx.x] = rbad; red[1][threadIdx.x] = ybad; red[2][threadIdx.x] = ymax;
+    __syncthreads();
+    for (int half = kGateBlock / 2; half > 0; half >>= 1) {
+        if (static_cast<int>(threadIdx.x) < half) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + half];
+            red[1][threadIdx.x] += red[1][threadIdx.x + half];
+            const unsigned o = red[2][threadIdx.x + half];
+            if (o > red[2][threadIdx.x]) red[2][threadIdx.x] = o;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        unsigned* slot = partial + 4 * static_cast<size_t>(blockIdx.x);
+        slot[0] = red[0][0]; slot[1] = red[1][0]; slot[2] = red[2][0]; slot[3] = 0u;
+    }
+}
+// One workgroup.  accumulate != 0 folds the new counts into what `out` already holds
+// (a second comparison graded into the same verdict).
+__global__ __launch_bounds__(kGateBlock) void gate_finish_kernel(const unsigned* partial, int nslots, unsigned* out,
+                                                                  int accumulate)
+{
+    __shared__ unsigned red[3][kGateBlock];
+    unsigned a = 0, b = 0, c = 0;
+    for (int s = threadIdx.x; s < nslots; s += kGateBlock) {
+        a += partial[4 * s]; b += partial[4 * s + 1];
+        const unsigned m = partial[4 * s + 2];
+        c = m > c ? m : c;
+    }
+    red[0][threadIdx.x] = a; red[1][threadIdx.x] = b; red[2][threadIdx.x] = c;
+    __syncthreads();
+    for (int half = kGateBlock / 2; half > 0; half >>= 1) {
+        if (static_cast<int>(threadIdx.x) < half) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + half];
+            red[1][threadIdx.x] += red[1][threadIdx.x + half];
+            const unsigned o = red[2][threadIdx.x + half];
+            if (o > red[2][threadIdx.x]) red[2][threadIdx.x] = o;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (accumulate) {
+            out[0] += red[0][0]; out[1] += red[1][0];
+            if (red[2][0] > out[2]) out[2] = red[2][0];
+        } else {
+            out[0] = red[0][0]; out[1] = red[1][0]; out[2] = red[2][0]; out[3] = 0u;
+        }
+    }
+}
+
+int gate_grid(long long n)
+{
+    const long long per_wg = static_cast<long long>(kGateBlock) * 16;     // at least 16 elements per thread
+    return static_cast<int>(std::max<long long>(1, std::min<long long>(kGateMaxGrid, (n + per_wg - 1) / per_wg)));
+}
+
+// Both stages of the gate on `stream`: xb/rb are the element sizes of the y and residual
+// streams, `partial` holds at least gate_grid(n) slots, `out` four counters.  Asynchronous.
+int launch_gate(const void* y, const void* y_ref, const void* r, const void* r_ref, long long n, int xb, int rb,
+                unsigned tol, unsigned* partial, unsigned* out, bool accumulate, hipStream_t stream)
+{
+    const dim3 block(kGateBlock), grid(static_cast<unsigned>(gate_grid(n)));
+    if (xb == 2 && rb == 2) hipLaunchKernelGGL((gate_partial_kernel<2, 2>), grid, block, 0, stream, y, y_ref, r, r_ref, n, tol, partial);
+    else if (xb == 2) hipLaunchKernelGGL((gate_partial_kernel<2, 4>), grid, block, 0, stream, y, y_ref, r, r_ref, n, tol, partial);
+    else hipLaunchKernelGGL((gate_partial_kernel<4, 4>), grid, block, 0, stream, y, y_ref, r, r_ref, n, tol, partial);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(gate_finish_kernel, dim3(1), block, 0, stream, partial, static_cast<int>(grid.x), out, accumulate ? 1 : 0);
+    HIP_TRY(hipGetLastError());
+    return ADDRMS_OK;
 }
 
 int fill(void* p, int64_t n, int es, bool bf, uint32_t seed, float lo, float hi, bool bell, hipStream_t st)
@@ -257,13 +338,13 @@ struct Harness {
         const size_t want = 2 * (static_cast<size_t>(hw().last_level_cache_bytes) +
                                  static_cast<size_t>(hw().l2_bytes_per_xcd) * hw().xcds);
         nsets = rotate ? static_cast<int>(std::min<size_t>(32, std::max<size_t>(2, (want + set - 1) / set))) : 1;
-        const size_t total = set * (nsets + 2) + pad(wbytes) + pad(256);
+        const size_t total = set * (nsets + 2) + pad(wbytes) + pad(256 + kGateScratchBytes);
         HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), total));
         char* p = pool;
         auto take = [&](size_t b, size_t skew) { char* q = p + skew; p += pad(b); return q; };
         x0 = take(xbytes, 0); r0 = take(rbytes, kSkew); yref = take(xbytes, 0); rref = take(rbytes, kSkew);
         w = take(wbytes, 0);
-        counts = reinterpret_cast<unsigned*>(take(256, 0));
+        counts = reinterpret_cast<unsigned*>(take(256 + kGateScratchBytes, 0));   // 4 result counters, then the gate's slots
         for (int i = 0; i < nsets; ++i) { xs.push_back(take(xbytes, 0)); rs.push_back(take(rbytes, kSkew)); }
         HIP_TRY(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
         HIP_TRY(hipEventCreate(&ev0));
@@ -314,16 +395,9 @@ struct Harness {
         HIP_TRY(hipMemcpyAsync(rs[0], r0, rbytes, hipMemcpyDeviceToDevice, stream));
         int st = run_on(c, f, 0);
         if (st != ADDRMS_OK) return st;
-        {
-            const long long n = static_cast<long long>(M) * N;
-            const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
-            HIP_TRY(hipMemsetAsync(counts, 0, 16, stream));
-            const int xb = x_bytes(dtype), rb = r_bytes(dtype);
-            if (xb == 2 && rb == 2) hipLaunchKernelGGL((compare_kernel<2, 2>), grid, block, 0, stream, xs[0], yref, rs[0], rref, n, 1u, counts);
-            else if (xb == 2) hipLaunchKernelGGL((compare_kernel<2, 4>), grid, block, 0, stream, xs[0], yref, rs[0], rref, n, 1u, counts);
-            else hipLaunchKernelGGL((compare_kernel<4, 4>), grid, block, 0, stream, xs[0], yref, rs[0], rref, n, 1u, counts);
-            HIP_TRY(hipGetLastError());
-        }
+        st = launch_gate(xs[0], yref, rs[0], rref, static_cast<long long>(M) * N, x_bytes(dtype), r_bytes(dtype), 1u,
+                         counts + 64, counts, false, stream);
+        if (st != ADDRMS_OK) return st;
         unsigned h[4] = {0, 0, 0, 0};
         HIP_TRY(hipMemcpyAsync(h, counts, 16, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
@@ -432,11 +506,11 @@ struct SiluHarness {
         const size_t want = 2 * (static_cast<size_t>(hw().last_level_cache_bytes) +
                                  static_cast<size_t>(hw().l2_bytes_per_xcd) * hw().xcds);
         nsets = rotate ? static_cast<int>(std::min<size_t>(32, std::max<size_t>(2, (want + set - 1) / set))) : 1;
-        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), set * nsets + pad(outbytes) + pad(256)));
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), set * nsets + pad(outbytes) + pad(256 + kGateScratchBytes)));
         char* p = pool;
         auto take = [&](size_t b, size_t skew) { char* q = p + skew; p += pad(b); return q; };
         ref = take(outbytes, 0);
-        counts = reinterpret_cast<unsigned*>(take(256, 0));
+        counts = reinterpret_cast<unsigned*>(take(256 + kGateScratchBytes, 0));
         for (int i = 0; i < nsets; ++i) { ins.push_back(take(inbytes, 0)); outs.push_back(take(outbytes, 4096)); }
         HIP_TRY(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking));
         HIP_TRY(hipEventCreate(&ev0));
@@ -471,15 +545,10 @@ struct SiluHarness {
         HIP_TRY(hipMemsetAsync(outs[0], 0xff, outbytes, stream));     // stale output must not pass for a result
         int st = launch_silumul(f, c, ins[0], outs[0], M, d, stream);
         if (st != ADDRMS_OK) return st;
-        const long long n = static_cast<long long>(M) * d;
-        const dim3 block(256), grid(static_cast<unsigned>((n + 255) / 256));
-        HIP_TRY(hipMemsetAsync(counts, 0, 16, stream));
         // the residual slots of the comparison are fed the same buffer twice: only the output is graded
-        if (x_bytes(dtype) == 2)
-            hipLaunchKernelGGL((compare_kernel<2, 2>), grid, block, 0, stream, outs[0], ref, ref, ref, n, 1u, counts);
-        else
-            hipLaunchKernelGGL((compare_kernel<4, 4>), grid, block, 0, stream, outs[0], ref, ref, ref, n, 1u, counts);
-        HIP_TRY(hipGetLastError());
+        st = launch_gate(outs[0], ref, ref, ref, static_cast<long long>(M) * d, x_bytes(dtype), x_bytes(dtype), 1u,
+                         counts + 64, counts, false, stream);
+        if (st != ADDRMS_OK) return st;
         unsigned h[4] = {0, 0, 0, 0};
         HIP_TRY(hipMemcpyAsync(h, counts, 16, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
@@ -534,12 +603,12 @@ struct MergeHarness {
         const size_t want = 2 * (static_cast<size_t>(hw().last_level_cache_bytes) +
                                  static_cast<size_t>(hw().l2_bytes_per_xcd) * hw().xcds);
         nsets = rotate ? static_cast<int>(std::min<size_t>(32, std::max<size_t>(2, (want + set - 1) / set))) : 1;
-        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), set * nsets + pad(vbytes) + pad(sbytes) + pad(256)));
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&pool), set * nsets + pad(vbytes) + pad(sbytes) + pad(256 + kGateScratchBytes)));
         char* p = pool;
         auto take = [&](size_t b, size_t skew) { char* q = p + skew; p += pad(b); return q; };
         vref = take(vbytes, 0);
         sref = reinterpret_cast<float*>(take(sbytes, 0));
-        counts = reinterpret_cast<unsigned*>(take(256, 0));
+        counts = reinterpret_cast<unsigned*>(take(256 + kGateScratchBytes, 0));
         for (int i = 0; i < nsets; ++i) {
             Set s;
             s.va = take(vbytes, 0); s.vb = take(vbytes, 4096); s.vo = take(vbytes, 8192);
@@ -593,15 +662,12 @@ struct MergeHarness {
         HIP_TRY(hipMemsetAsync(sets[0].so, 0xff, sbytes, stream));
         const int st = run_set(f, c, sets[0], sets[0].vo, sets[0].so);
         if (st != ADDRMS_OK) return st;
-        HIP_TRY(hipMemsetAsync(counts, 0, 16, stream));
-        const long long n = static_cast<long long>(rows) * d;
-        const dim3 block(256);
         // merged outputs within 1 ulp of the reference; merged scores bit-identical
-        hipLaunchKernelGGL((compare_kernel<2, 2>), dim3(static_cast<unsigned>((n + 255) / 256)), block, 0, stream,
-                           sets[0].vo, vref, vref, vref, n, 1u, counts);
-        hipLaunchKernelGGL((compare_kernel<4, 4>), dim3(static_cast<unsigned>((rows + 255) / 256)), block, 0, stream,
-                           sets[0].so, sref, sref, sref, static_cast<long long>(rows), 0u, counts);
-        HIP_TRY(hipGetLastError());
+        int gs = launch_gate(sets[0].vo, vref, vref, vref, static_cast<long long>(rows) * d, 2, 2, 1u, counts + 64, counts,
+                             false, stream);
+        if (gs == ADDRMS_OK)
+            gs = launch_gate(sets[0].so, sref, sref, sref, static_cast<long long>(rows), 4, 4, 0u, counts + 64, counts, true, stream);
+        if (gs != ADDRMS_OK) return gs;
         unsigned h[4] = {0, 0, 0, 0};
         HIP_TRY(hipMemcpyAsync(h, counts, 16, hipMemcpyDeviceToHost, stream));
         HIP_TRY(hipStreamSynchronize(stream));
@@ -885,6 +951,45 @@ int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype
     else
         return fail(ADDRMS_ERR_INVALID_ARG, "unexpected residual/x size ratio");
     HIP_TRY(hipGetLastError());
+    return ADDRMS_OK;
+}
+
+// ---- the gate on caller buffers ----------------------------------------------------------
+
+namespace {
+int check_gate_args(const void* y, const void* y_ref, const void* r, const void* r_ref, int64_t n, int dtype,
+                    const addrms_gate_counts* out)
+{
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (n < 0) return fail(ADDRMS_ERR_INVALID_ARG, "n must be >= 0 (got %lld)", (long long)n);
+    if (n > kGateMaxElems)
+        return fail(ADDRMS_ERR_INVALID_ARG, "n=%lld exceeds the %lld elements the gate's 32-bit counters can count",
+                    (long long)n, kGateMaxElems);
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "counts_out is NULL");
+    if (n > 0 && (!y || !y_ref || !r || !r_ref)) return fail(ADDRMS_ERR_INVALID_ARG, "y, y_ref, residual and residual_ref must not be NULL");
+    if (!aligned(y, x_bytes(dtype)) || !aligned(y_ref, x_bytes(dtype)) || !aligned(r, r_bytes(dtype)) ||
+        !aligned(r_ref, r_bytes(dtype)) || !aligned(out, 16))
+        return fail(ADDRMS_ERR_MISALIGNED, "tensors must be aligned to their element size and counts_out to 16 bytes");
+    return ADDRMS_OK;
+}
+
+}  // namespace
+
+int addrms_gate_probe(const void* y, const void* y_ref, const void* residual, const void* residual_ref, int64_t n,
+                      int dtype, uint32_t tol, addrms_gate_counts* counts_out, void* stream)
+{
+    int st = check_gate_args(y, y_ref, residual, residual_ref, n, dtype, counts_out);
+    if (st != ADDRMS_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n == 0) { HIP_TRY(hipMemsetAsync(counts_out, 0, sizeof *counts_out, s)); HIP_TRY(hipStreamSynchronize(s)); return ADDRMS_OK; }
+    unsigned* partial = nullptr;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&partial), static_cast<size_t>(gate_grid(n)) * 4 * sizeof(unsigned)));
+    st = launch_gate(y, y_ref, residual, residual_ref, n, x_bytes(dtype), r_bytes(dtype), tol, partial,
+                     reinterpret_cast<unsigned*>(counts_out), false, s);
+    const hipError_t e = hipStreamSynchronize(s);
+    (void)hipFree(partial);
+    if (st != ADDRMS_OK) return st;
+    if (e != hipSuccess) return fail(ADDRMS_ERR_HIP, "hipStreamSynchronize failed: %s", hipGetErrorString(e));
     return ADDRMS_OK;
 }
 
