@@ -413,6 +413,18 @@ typedef struct addrms_gate_counts {
 int addrms_gate_probe(const void* y, const void* y_ref, const void* residual, const void* residual_ref, int64_t n,
                       int dtype, uint32_t tol, addrms_gate_counts* counts_out, void* stream);
 
+/* addrms_gate_probe for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments and the same verdict in counts_out, but the
+ * per-workgroup partial counts live in a 64 KiB array that is part of the library's device code (one copy per GPU,
+ * held until the process ends), so this call allocates nothing, frees nothing and does not wait: both kernels
+ * are only enqueued on `stream`, and counts_out is valid once the stream has reached them.  Nothing in it is a
+ * memset, so a capturing caller records two kernel nodes.  n beyond 2^32-1 is INVALID_ARG as above (the array
+ * itself never limits n: a launch uses at most 4096 slots whatever n is).  Every call on a GPU shares that GPU's
+ * array: calls that may overlap in time on one GPU (different streams, concurrent graphs) race on it and must be
+ * serialised by the caller; calls on one stream are ordered and safe. */
+int addrms_gate_probe_noalloc(const void* y, const void* y_ref, const void* residual, const void* residual_ref,
+                              int64_t n, int dtype, uint32_t tol, addrms_gate_counts* counts_out, void* stream);
+
 /* Calibration kernel with the operator's traffic and none of its arithmetic:
  * reads [M,N] of x and of residual and writes both back (bitwise complemented),
  * 16 bytes per lane, streaming cache policy, three 256-thread workgroups per CU

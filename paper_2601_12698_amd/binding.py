@@ -247,6 +247,8 @@ SIGNATURES = {
     "addrms_stream_probe": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p]),
     "addrms_gate_probe": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int, ctypes.c_uint32, c_void_p,
                                   c_void_p]),
+    "addrms_gate_probe_noalloc": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int, ctypes.c_uint32,
+                                          c_void_p, c_void_p]),
     "addrms_algorithmic_bytes": (c_int64, [c_int64, c_int64, c_int]),
     "silumul_run": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, POINTER(Cfg), c_void_p]),
     "silumul_default_cfg": (c_int, [c_int64, c_int, POINTER(Cfg)]),
@@ -677,6 +679,13 @@ def addrms_gate_probe(y, y_ref, residual, residual_ref, dtype, tol: int, counts_
     n, dt = _gate_args(y, y_ref, residual, residual_ref, dtype, counts_out)
     _check(load().addrms_gate_probe(_ptr(y), _ptr(y_ref), _ptr(residual), _ptr(residual_ref), n, dt, int(tol),
                                     _ptr(counts_out), _stream_ptr(stream, y)))
+
+
+def addrms_gate_probe_noalloc(y, y_ref, residual, residual_ref, dtype, tol: int, counts_out, stream=None) -> None:
+    """Same verdict as addrms_gate_probe; allocates nothing and does not wait for the stream."""
+    n, dt = _gate_args(y, y_ref, residual, residual_ref, dtype, counts_out)
+    _check(load().addrms_gate_probe_noalloc(_ptr(y), _ptr(y_ref), _ptr(residual), _ptr(residual_ref), n, dt, int(tol),
+                                            _ptr(counts_out), _stream_ptr(stream, y)))
 
 
 # ---- silu_and_mul (include/silumul.h) -------------------------------------------------

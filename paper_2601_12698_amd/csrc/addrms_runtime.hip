@@ -26,7 +26,12 @@ static const DispatchEntry kDispatch[] = {
 
 using namespace addrms_host;
 
-constexpr int kGateScratchSlots = 4096;   // most partial-count slots one gate launch uses
+// Partial-count slots of addrms_gate_probe_noalloc: device memory that belongs to the loaded
+// code object, one copy per GPU, so the entry point needs no allocation.  Host code never
+// uses this name as an address; it asks the runtime for the device address once per device
+// (gate_scratch_on_current_device) and passes that pointer around.
+constexpr int kGateScratchSlots = 4096;
+static __device__ __align__(256) unsigned scratch[kGateScratchSlots * 4];
 
 namespace {
 
@@ -973,6 +978,26 @@ int check_gate_args(const void* y, const void* y_ref, const void* r, const void*
     return ADDRMS_OK;
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned* g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up on the first call there.
+int gate_scratch_on_current_device(unsigned** out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ADDRMS_ERR_HIP, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        unsigned* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+        if (!p) return fail(ADDRMS_ERR_HIP, "hipGetSymbolAddress returned a null address for the gate scratch");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ADDRMS_OK;
+}
 }  // namespace
 
 int addrms_gate_probe(const void* y, const void* y_ref, const void* residual, const void* residual_ref, int64_t n,
@@ -991,6 +1016,20 @@ int addrms_gate_probe(const void* y, const void* y_ref, const void* residual, co
     if (st != ADDRMS_OK) return st;
     if (e != hipSuccess) return fail(ADDRMS_ERR_HIP, "hipStreamSynchronize failed: %s", hipGetErrorString(e));
     return ADDRMS_OK;
+}
+
+int addrms_gate_probe_noalloc(const void* y, const void* y_ref, const void* residual, const void* residual_ref, int64_t n,
+                              int dtype, uint32_t tol, addrms_gate_counts* counts_out, void* stream)
+{
+    int st = check_gate_args(y, y_ref, residual, residual_ref, n, dtype, counts_out);
+    if (st != ADDRMS_OK) return st;
+    unsigned* partial = nullptr;
+    st = gate_scratch_on_current_device(&partial);
+    if (st != ADDRMS_OK) return st;
+    // n == 0 goes through the kernels as well (one workgroup, empty slice): nothing here may be a memset
+    // that a capturing caller would record
+    return launch_gate(y, y_ref, residual, residual_ref, n, x_bytes(dtype), r_bytes(dtype), tol, partial,
+                       reinterpret_cast<unsigned*>(counts_out), false, static_cast<hipStream_t>(stream));
 }
 
 // ---- silu_and_mul ----------------------------------------------------------------------
