@@ -29,7 +29,7 @@
 extern "C" {
 #endif
 
-#define ADDRMS_VERSION_STRING "0.1.0"
+#define ADDRMS_VERSION_STRING "0.2.0"
 
 /* ---- status codes ------------------------------------------------------- */
 typedef enum addrms_status {
@@ -62,9 +62,14 @@ enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguou
        ADDRMS_FLAG_TWO_PASS = 8,      /* rows too long for the register row cache: read the row
                                          twice (sum of squares, then outputs); feasible only
                                          where no single-pass configuration covers N            */
-       ADDRMS_FLAG_LDS_CACHE = 16 };  /* rows somewhat too long for the registers: still one pass,
+       ADDRMS_FLAG_LDS_CACHE = 16,    /* rows somewhat too long for the registers: still one pass,
                                          the row cache continues in the workgroup's LDS (up to
                                          160 KB per CU, so about 73 K elements per row)          */
+       ADDRMS_FLAG_DEFER_STORE = 32 };/* the residual is written after the row reduction, the whole
+                                         row at once and then the whole y row, instead of chunk by
+                                         chunk while the row is still being read: a workgroup reads
+                                         in one phase and writes in one phase (register-cached form
+                                         only; results are the same bits)                         */
 
 typedef struct addrms_cfg {
     int32_t vec;              /* elements per thread per vector access: 1, 2, 4, 8        */
@@ -76,7 +81,9 @@ typedef struct addrms_cfg {
     int32_t max_waves_per_simd; /* 0 = as many as fit; 1..7 = cap on resident waves per SIMD,
                                  imposed by padding the workgroup's LDS allocation (fewer
                                  requests in flight can raise mixed read/write HBM efficiency) */
-    int32_t reserved;         /* must be 0                                                */
+    int32_t walk;             /* persistent grids only: 0 = as many workgroups as are resident
+                                 on the chip; 4, 16 = that many times more, so that each walks
+                                 fewer row blocks (between the persistent and the ordinary grid) */
 } addrms_cfg;
 
 /* ---- run ------------------------------------------------------------------
@@ -150,8 +157,9 @@ enum { ADDRMS_SEARCH_GUIDED = 0, ADDRMS_SEARCH_EXHAUSTIVE = 1 };
  * them round by round; a search can be restricted to a subset). */
 enum { ADDRMS_FAMILY_STREAMING = 1,      /* non-temporal cache policy (ADDRMS_FLAG_NONTEMPORAL)              */
        ADDRMS_FAMILY_OCCUPANCY_CAP = 2,  /* max_waves_per_simd != 0                                          */
-       ADDRMS_FAMILY_GRID_MAPPING = 4,   /* XCD-contiguous mapping and the persistent grid                   */
-       ADDRMS_FAMILY_BASE_ONLY = 8 };    /* none of the above: the base template only                        */
+       ADDRMS_FAMILY_GRID_MAPPING = 4,   /* XCD-contiguous mapping, the persistent grid and its walk length  */
+       ADDRMS_FAMILY_BASE_ONLY = 8,      /* none of these: the base template only                            */
+       ADDRMS_FAMILY_STORE_PHASE = 16 }; /* deferred residual store (ADDRMS_FLAG_DEFER_STORE)                */
 /* Hints for the guided search, derived from profiler counters of an earlier round
  * (Algorithm 1 line 9, Suggest): they decide which neighbouring cfgs are tried first
  * and add a sweep mode; they never remove a candidate. */
@@ -266,14 +274,14 @@ int addrms_select_general_with_backend(const addrms_shape* shapes, int32_t n, in
 
 /* ---- the outer loop (Algorithm 1 lines 6-32) with a fixed strategy list ----------
  * Round 0 uses the base template; each later round adds one strategy family (streaming
- * cache policy, occupancy cap, grid mapping) in that order -- the deterministic stand-in
+ * cache policy, occupancy cap, grid mapping, store phase) in that order -- the deterministic stand-in
  * for the planning agent's suggestions.  Per round: Validate the new family on the first
  * shape against the base default's output and roll it back if it fails (lines 13-14);
  * search every shape within the families enabled so far (lines 19-21); SelectGeneral and
  * BuildSpecialized (22-23); score = minus the geometric-mean speed-up of the specialised
  * table over the per-shape defaults (line 27); keep the incumbent (28-30).  Every round is
  * appended to budget->log_path as an "event":"round" line. */
-#define ADDRMS_MAX_ROUNDS 4
+#define ADDRMS_MAX_ROUNDS 5
 typedef struct addrms_round_info {
     int32_t families;          /* ADDRMS_FAMILY_* bits enabled in this round (0 = base only)  */
     int32_t pass;              /* 1 if the family added in this round passed validation       */
@@ -380,8 +388,11 @@ int addrms_table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, 
 int addrms_table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out);
 int64_t addrms_table_size(void);
 void addrms_table_clear(void);
-/* Text file, one entry per line.  load replaces nothing on failure: a missing
- * or malformed file returns ADDRMS_ERR_IO and leaves the table as it was. */
+/* Text file: a format line, "arch gfx950", "library <version>", then one entry per line.
+ * load replaces nothing on failure: a missing or malformed file, one written for another
+ * architecture or by a library of another major.minor version (whose kernel instances, and
+ * with them feasibility and timings, differ) returns ADDRMS_ERR_IO and leaves the table as
+ * it was. */
 int addrms_table_save(const char* path);
 int addrms_table_load(const char* path);
 

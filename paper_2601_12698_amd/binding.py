@@ -27,9 +27,10 @@ FLAG_NONTEMPORAL = 2
 FLAG_PERSISTENT = 4
 FLAG_TWO_PASS = 8
 FLAG_LDS_CACHE = 16
+FLAG_DEFER_STORE = 32
 SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
-FAMILY_STREAMING, FAMILY_OCCUPANCY_CAP, FAMILY_GRID_MAPPING, FAMILY_BASE_ONLY = 1, 2, 4, 8
-MAX_ROUNDS = 4
+FAMILY_STREAMING, FAMILY_OCCUPANCY_CAP, FAMILY_GRID_MAPPING, FAMILY_BASE_ONLY, FAMILY_STORE_PHASE = 1, 2, 4, 8, 16
+MAX_ROUNDS = 5
 HINT_LOWER_OCCUPANCY, HINT_HIGHER_OCCUPANCY, HINT_FEWER_LARGER_WORKGROUPS, HINT_WIDER_VECTORS = 1, 2, 4, 8
 MAX_TOPK = 8
 
@@ -52,27 +53,27 @@ class AddrmsError(RuntimeError):
 class Cfg(Structure):
     _fields_ = [("vec", c_int32), ("threads_per_row", c_int32), ("rows_per_wg", c_int32),
                 ("reduce", c_int32), ("unroll", c_int32), ("flags", c_int32),
-                ("max_waves_per_simd", c_int32), ("reserved", c_int32)]
+                ("max_waves_per_simd", c_int32), ("walk", c_int32)]
 
-    def as_tuple(self) -> Tuple[int, int, int, int, int, int, int]:
+    def as_tuple(self) -> Tuple[int, int, int, int, int, int, int, int]:
         return (self.vec, self.threads_per_row, self.rows_per_wg, self.reduce, self.unroll, self.flags,
-                self.max_waves_per_simd)
+                self.max_waves_per_simd, self.walk)
 
     def as_dict(self) -> dict:
         return dict(vec=self.vec, threads_per_row=self.threads_per_row, rows_per_wg=self.rows_per_wg,
                     reduce=self.reduce, unroll=self.unroll, flags=self.flags,
-                    max_waves_per_simd=self.max_waves_per_simd)
+                    max_waves_per_simd=self.max_waves_per_simd, walk=self.walk)
 
     def __repr__(self) -> str:
         return ("Cfg(vec=%d, threads_per_row=%d, rows_per_wg=%d, reduce=%d, unroll=%d, flags=%d, "
-                "max_waves_per_simd=%d)" % self.as_tuple())
+                "max_waves_per_simd=%d, walk=%d)" % self.as_tuple())
 
 
 def make_cfg(vec: int, threads_per_row: int, rows_per_wg: int = 1, reduce: int = REDUCE_WAVE,
-             unroll: int = 1, flags: int = 0, max_waves_per_simd: int = 0) -> Cfg:
+             unroll: int = 1, flags: int = 0, max_waves_per_simd: int = 0, walk: int = 0) -> Cfg:
     c = Cfg()
-    c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd = (
-        vec, threads_per_row, rows_per_wg, reduce, unroll, flags, max_waves_per_simd)
+    c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd, c.walk = (
+        vec, threads_per_row, rows_per_wg, reduce, unroll, flags, max_waves_per_simd, walk)
     return c
 
 

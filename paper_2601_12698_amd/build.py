@@ -105,10 +105,10 @@ def build(force: bool = False, jobs: int = 8, verbose: bool = False) -> str:
     for text in remarks:
         res.update(parse_remarks(text))
     rows = []
-    for op, dt, vec, cpt, unr, nt, _maxt in gen_kernels.instances():
-        r = res.get(gen_kernels.name(op, dt, vec, cpt, unr, nt))
+    for op, dt, vec, cpt, unr, nt, df, _maxt in gen_kernels.instances():
+        r = res.get(gen_kernels.name(op, dt, vec, cpt, unr, nt, df))
         if r is None or any(k not in r for k in ("vgprs", "agprs", "sgprs", "scratch", "lds", "occupancy")):
-            raise RuntimeError(f"no resource report for {gen_kernels.name(op, dt, vec, cpt, unr, nt)}")
+            raise RuntimeError(f"no resource report for {gen_kernels.name(op, dt, vec, cpt, unr, nt, df)}")
         rows.append(f"    {{{r['vgprs']}, {r['agprs']}, {r['sgprs']}, {r['scratch']}, {r['lds']}, {r['occupancy']}}},")
     gen_kernels._write(os.path.join(BUILD, "gen_resources.inc"), "\n".join(rows) + "\n")
 

@@ -61,21 +61,23 @@ const char* op_name(int op)
     return op == OP_SILUMUL ? "silu_and_mul" : op == OP_MERGE ? "merge_attn_states" : "add_rmsnorm";
 }
 
-static uint32_t inst_key(int op, int dt, int vec, int cpt, int unr, int nt)
+static uint32_t inst_key(int op, int dt, int vec, int cpt, int unr, int nt, int df)
 {
     return (static_cast<uint32_t>(op) << 28) | (static_cast<uint32_t>(dt) << 24) | (static_cast<uint32_t>(vec) << 16) |
-           (static_cast<uint32_t>(cpt) << 8) | (static_cast<uint32_t>(unr) << 1) | static_cast<uint32_t>(nt);
+           (static_cast<uint32_t>(cpt) << 8) | (static_cast<uint32_t>(unr) << 2) | (static_cast<uint32_t>(df) << 1) |
+           static_cast<uint32_t>(nt);
 }
 
-int find_instance(int op, int dt, int vec, int cpt, int unr, int nt)
+int find_instance(int op, int dt, int vec, int cpt, int unr, int nt, int df)
 {
     static const std::unordered_map<uint32_t, int> index = [] {
         std::unordered_map<uint32_t, int> m;
         for (int i = 0; i < n_instances(); ++i)
-            m[inst_key(kInstances[i].op, kInstances[i].dt, kInstances[i].vec, kInstances[i].cpt, kInstances[i].unr, kInstances[i].nt)] = i;
+            m[inst_key(kInstances[i].op, kInstances[i].dt, kInstances[i].vec, kInstances[i].cpt, kInstances[i].unr, kInstances[i].nt,
+                       kInstances[i].df)] = i;
         return m;
     }();
-    auto it = index.find(inst_key(op, dt, vec, cpt, unr, nt));
+    auto it = index.find(inst_key(op, dt, vec, cpt, unr, nt, df));
     return it == index.end() ? -1 : it->second;
 }
 
@@ -117,6 +119,7 @@ const char* dtype_name(int dtype)
 static const int kVecs[] = {8, 4, 2, 1};
 static const int kRows[] = {1, 2, 4, 8, 16};
 static const int kUnrolls[] = {1, 2, 4, 8};
+static const int kWalks[] = {0, 4, 16};
 
 static bool in_set(int v, const int* set, size_t n)
 {
@@ -131,22 +134,22 @@ bool cfg_equal(const addrms_cfg& a, const addrms_cfg& b)
 {
     return a.vec == b.vec && a.threads_per_row == b.threads_per_row && a.rows_per_wg == b.rows_per_wg &&
            a.reduce == b.reduce && a.unroll == b.unroll && a.flags == b.flags &&
-           a.max_waves_per_simd == b.max_waves_per_simd;
+           a.max_waves_per_simd == b.max_waves_per_simd && a.walk == b.walk;
 }
 uint64_t cfg_key(const addrms_cfg& c)
 {
     return (static_cast<uint64_t>(c.vec) << 40) | (static_cast<uint64_t>(c.threads_per_row) << 28) |
            (static_cast<uint64_t>(c.rows_per_wg) << 20) | (static_cast<uint64_t>(c.reduce) << 16) |
            (static_cast<uint64_t>(c.unroll) << 12) | (static_cast<uint64_t>(c.max_waves_per_simd & 0xf) << 8) |
-           static_cast<uint64_t>(c.flags & 0xff);
+           static_cast<uint64_t>(c.flags & 0xff) | (static_cast<uint64_t>(c.walk & 0xff) << 48);
 }
 std::string cfg_json(const addrms_cfg& c)
 {
-    char buf[224];
+    char buf[256];
     snprintf(buf, sizeof buf,
              "{\"vec\":%d,\"threads_per_row\":%d,\"rows_per_wg\":%d,\"reduce\":%d,\"unroll\":%d,\"flags\":%d,"
-             "\"max_waves_per_simd\":%d}",
-             c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd);
+             "\"max_waves_per_simd\":%d,\"walk\":%d}",
+             c.vec, c.threads_per_row, c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd, c.walk);
     return buf;
 }
 
@@ -183,6 +186,7 @@ bool cfg_in_families(const addrms_cfg& c, int mask)
     if ((c.flags & ADDRMS_FLAG_NONTEMPORAL) && !(mask & ADDRMS_FAMILY_STREAMING)) return false;
     if (c.max_waves_per_simd != 0 && !(mask & ADDRMS_FAMILY_OCCUPANCY_CAP)) return false;
     if ((c.flags & (ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_PERSISTENT)) && !(mask & ADDRMS_FAMILY_GRID_MAPPING)) return false;
+    if ((c.flags & ADDRMS_FLAG_DEFER_STORE) && !(mask & ADDRMS_FAMILY_STORE_PHASE)) return false;
     return true;
 }
 
@@ -200,22 +204,27 @@ int64_t n_workgroups(const addrms_cfg& c, int64_t M, int wgs_per_cu)
 {
     const int64_t blocks = n_row_blocks(c, M);
     if (!(c.flags & ADDRMS_FLAG_PERSISTENT)) return blocks;
-    return std::min<int64_t>(blocks, static_cast<int64_t>(hw().compute_units) * std::max(1, wgs_per_cu));
+    return std::min<int64_t>(blocks, static_cast<int64_t>(hw().compute_units) * std::max(1, wgs_per_cu) * std::max(1, c.walk));
 }
 
 // ---- the rules ------------------------------------------------------------------
 static Feas infeasible(const char* rule, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+// Walking the whole grid rejects millions of points whose rationale nobody reads: the walk
+// switches the text off and keeps only the rule tag.
+static thread_local bool g_rationale_wanted = true;
 static Feas infeasible(const char* rule, const char* fmt, ...)
 {
-    char buf[384];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
-    va_end(ap);
     Feas f;
     f.status = ADDRMS_ERR_INFEASIBLE_CFG;
     f.rule = rule;
-    f.reason = buf;
+    if (g_rationale_wanted) {
+        char buf[384];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        f.reason = buf;
+    }
     return f;
 }
 
@@ -261,10 +270,21 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
         return infeasible("grid", "reduce=%d: %s has no reduction; the knob must stay 0", c.reduce, op_name(op));
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
     if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT | ADDRMS_FLAG_TWO_PASS |
-                    ADDRMS_FLAG_LDS_CACHE))
+                    ADDRMS_FLAG_LDS_CACHE | ADDRMS_FLAG_DEFER_STORE))
         return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
     const bool two_pass = (c.flags & ADDRMS_FLAG_TWO_PASS) != 0;
     const bool lds_cache = (c.flags & ADDRMS_FLAG_LDS_CACHE) != 0;
+    const bool defer = (c.flags & ADDRMS_FLAG_DEFER_STORE) != 0;
+    if (defer && op != OP_ADDRMS)
+        return infeasible("grid", "flags=0x%x: %s has no residual stream whose store could be deferred", c.flags, op_name(op));
+    if (defer && (two_pass || lds_cache))
+        return infeasible("grid", "flags=0x%x: the deferred residual store exists for the register-cached form only (the "
+                          "two-pass form writes everything in its second pass anyway)", c.flags);
+    if (c.walk != 0 && c.walk != 4 && c.walk != 16)
+        return infeasible("grid", "walk=%d: must be 0 (grid = resident workgroups) or 4 or 16 times as many", c.walk);
+    if (c.walk != 0 && !(c.flags & ADDRMS_FLAG_PERSISTENT))
+        return infeasible("grid", "walk=%d sizes a persistent grid; without ADDRMS_FLAG_PERSISTENT there is one workgroup per "
+                          "row block and nothing to size", c.walk);
     if ((two_pass || lds_cache) && op != OP_ADDRMS)
         return infeasible("grid", "flags=0x%x: only add+RMSNorm has forms for long rows", c.flags);
     if (two_pass && lds_cache)
@@ -274,7 +294,6 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     if (c.max_waves_per_simd < 0 || c.max_waves_per_simd >= L.max_waves_per_simd)
         return infeasible("grid", "max_waves_per_simd=%d: must be 0 (no cap) or 1..%d", c.max_waves_per_simd,
                           L.max_waves_per_simd - 1);
-    if (c.reserved) return infeasible("grid", "reserved field must be zero");
 
     const int xb = x_bytes(dtype), rb = r_bytes(dtype);
     // -- vectorisation and alignment
@@ -354,7 +373,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
 
     // -- compiled instance and its resources
     const int cpt_code = two_pass ? 0 : lds_cache ? kLdsCacheCptBase + kLdsCacheRegElems / c.vec : static_cast<int>(need);
-    const int idx = find_instance(op, dtype, c.vec, cpt_code, c.unroll, (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0);
+    const int idx = find_instance(op, dtype, c.vec, cpt_code, c.unroll, (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0, defer ? 1 : 0);
     if (idx < 0)
         return infeasible("no_instance", "no compiled instance for dtype=%s vec=%d chunks=%lld unroll=%d", dtype_name(dtype), c.vec,
                           (long long)need, c.unroll);
@@ -404,9 +423,11 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
         return infeasible("occupancy", "workgroup of %d waves at %d registers per lane does not fit one CU (%d wave slots by "
                           "registers, %d bytes of LDS)", o.waves_per_wg, regs, waves_cu_regs, o.lds_bytes);
     o.waves_per_simd = (wgs * o.waves_per_wg + L.simds_per_cu - 1) / L.simds_per_cu;
-    if ((c.flags & ADDRMS_FLAG_PERSISTENT) && n_row_blocks(c, M) <= static_cast<int64_t>(L.compute_units) * wgs)
-        return infeasible("persistent_identity", "all %lld row blocks are resident at once (%d CUs x %d workgroups): a "
-                          "persistent grid is the ordinary grid", (long long)n_row_blocks(c, M), L.compute_units, wgs);
+    if ((c.flags & ADDRMS_FLAG_PERSISTENT) &&
+        n_row_blocks(c, M) <= static_cast<int64_t>(L.compute_units) * wgs * std::max(1, c.walk))
+        return infeasible("persistent_identity", "all %lld row blocks get a workgroup of their own (%d CUs x %d workgroups x "
+                          "walk %d): this persistent grid is the ordinary grid", (long long)n_row_blocks(c, M),
+                          L.compute_units, wgs, std::max(1, c.walk));
     if (o.waves_per_simd < kMinWavesPerSimd && (relax & RELAX_OCCUPANCY_FLOOR)) {
         if (!f.soft_rule[0]) f.soft_rule = "occupancy_floor";
     } else if (o.waves_per_simd < kMinWavesPerSimd)
@@ -420,6 +441,7 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
                std::map<std::string, int64_t>* pruned, int op, int relax)
 {
     int64_t grid = 0;
+    struct Quiet { bool was; Quiet() : was(g_rationale_wanted) { g_rationale_wanted = false; } ~Quiet() { g_rationale_wanted = was; } } quiet;
     std::vector<int> tprs = {8, 16, 32};
     for (int t = 64; t <= hw().max_threads_per_wg; t += 64) tprs.push_back(t);
     for (int vec : kVecs)
@@ -427,15 +449,27 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
             for (int rows : kRows)
                 for (int red = 0; red < 2; ++red)
                     for (int unr : kUnrolls)
-                        for (int flags = 0; flags < 32; ++flags)
+                        for (int flags = 0; flags < 64; ++flags)
                             for (int cap = 0; cap < hw().max_waves_per_simd; ++cap) {
-                                ++grid;
-                                addrms_cfg c{};
-                                c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;
-                                c.reduce = red; c.unroll = unr; c.flags = flags; c.max_waves_per_simd = cap;
-                                const Feas f = check_cfg(c, M, N, dtype, op, relax);
-                                if (f.status == ADDRMS_OK) { if (out) out->push_back(c); }
-                                else if (pruned) ++(*pruned)[f.rule];
+                                // A longer grid (walk) exists for persistent cfgs only, and whatever rejects the
+                                // resident-size grid rejects the longer ones as well (a grid that already covers
+                                // every row block still does when it is longer): they are checked one by one only
+                                // where walk = 0 is feasible, and counted under the same rule otherwise.
+                                const Feas* base = nullptr;
+                                Feas f0;
+                                for (int walk : kWalks) {
+                                    if (walk != 0 && !(flags & ADDRMS_FLAG_PERSISTENT)) continue;   // no such grid point
+                                    ++grid;
+                                    if (base && base->status != ADDRMS_OK) { if (pruned) ++(*pruned)[base->rule]; continue; }
+                                    addrms_cfg c{};
+                                    c.vec = vec; c.threads_per_row = tpr; c.rows_per_wg = rows;
+                                    c.reduce = red; c.unroll = unr; c.flags = flags; c.max_waves_per_simd = cap;
+                                    c.walk = walk;
+                                    const Feas f = check_cfg(c, M, N, dtype, op, relax);
+                                    if (walk == 0) { f0 = f; base = &f0; }
+                                    if (f.status == ADDRMS_OK) { if (out) out->push_back(c); }
+                                    else if (pruned) ++(*pruned)[f.rule];
+                                }
                             }
     if (n_grid) *n_grid = grid;
 }

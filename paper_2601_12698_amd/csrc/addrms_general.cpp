@@ -179,7 +179,7 @@ int run_tune_rounds(const addrms_shape* shapes, int n, int dtype, const addrms_b
     addrms_budget b{};
     if (budget) b = *budget;
     static const int kOrder[ADDRMS_MAX_ROUNDS] = {0, ADDRMS_FAMILY_STREAMING, ADDRMS_FAMILY_OCCUPANCY_CAP,
-                                                  ADDRMS_FAMILY_GRID_MAPPING};
+                                                  ADDRMS_FAMILY_GRID_MAPPING, ADDRMS_FAMILY_STORE_PHASE};
     addrms_rounds_report rep{};
     rep.best_round = -1;
     double best_score = 0.0;

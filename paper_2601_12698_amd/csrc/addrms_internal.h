@@ -47,14 +47,14 @@ constexpr int kNumOps = 3;
 const char* op_name(int op);
 
 // ---- kernel instances ------------------------------------------------------
-struct Instance { int op, dt, vec, cpt, unr, nt, maxt; };
+struct Instance { int op, dt, vec, cpt, unr, nt, df, maxt; };
 struct InstanceRes { int vgprs, agprs, sgprs, scratch, lds_static, occupancy; };
 
 int n_instances();
 const Instance& instance(int idx);
 const InstanceRes& instance_res(int idx);
 // Index of the instance with exactly these knob values, or -1.
-int find_instance(int op, int dt, int vec, int cpt, int unr, int nt);
+int find_instance(int op, int dt, int vec, int cpt, int unr, int nt, int df = 0);
 bool cpt_supported(int op, int cpt);
 
 // ---- storage formats -------------------------------------------------------

@@ -14,12 +14,17 @@
 //             LDS-staged tree
 //   NT    non-temporal (streaming) cache policy on the x and residual loads
 //         and stores; the weight vector always uses the default policy
+//   DEFER residual stored after the row reduction, all of its chunks first and
+//         then those of y, instead of chunk by chunk as the sums are formed: a
+//         workgroup then reads in one phase and writes in one phase, and no load
+//         is ever issued behind a store whose acknowledgement the wave would have
+//         to wait for (loads and stores share one in-order counter on this target)
 //   flags   : XCD-contiguous mapping of workgroups to rows; persistent grid
 //             (set by the host through the grid size: fewer workgroups than
 //             row blocks makes each workgroup loop with a prefetch)
 //
-// VEC, CPT, UNR and NT are compile-time; the rest are launch-time and uniform
-// over the workgroup.
+// VEC, CPT, UNR, NT and DEFER are compile-time; the rest are launch-time and
+// uniform over the workgroup.
 //
 // Arithmetic per row (what every instantiation must reproduce bit for bit):
 //   h = f32(x) + f32(r)                       one fp32 add
@@ -36,7 +41,7 @@ namespace addrms {
 enum : int { DT_BF16 = 0, DT_FP16 = 1, DT_FP16_RES32 = 2, DT_FP32 = 3 };
 enum : int { RED_WAVE = 0, RED_LDS = 1 };
 enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u, FLAG_PERSISTENT = 4u, FLAG_TWO_PASS = 8u,
-                  FLAG_LDS_CACHE = 16u };
+                  FLAG_LDS_CACHE = 16u, FLAG_DEFER_STORE = 32u };
 
 template <int DT> struct dt_traits;
 template <> struct dt_traits<DT_BF16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = true;  };
@@ -309,7 +314,7 @@ __device__ __forceinline__ void load_group(const char* xbase, const char* rbase,
 // next block before reducing the current one, so that it always has requests
 // in flight.  Every workgroup leaves the loop after its last block; there is
 // no waiting between workgroups.
-template <int DT, int VEC, int CPT, int UNR, bool NT>
+template <int DT, int VEC, int CPT, int UNR, bool NT, bool DEFER>
 __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restrict__ rp,
                                             const void* __restrict__ wp, float eps, double inv_n,
                                             int64_t M, int32_t N, uint32_t flags, int32_t reduce,
@@ -359,9 +364,11 @@ __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restr
                     for (int e = 0; e < VEC; ++e)
                         h[c][e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
                     if (ra.row_ok && col <= nlast) {
-                        raw_t<RB * VEC> out;
-                        pack_vec<RB, BF, VEC>(h[c], out);
-                        st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), out);
+                        if constexpr (!DEFER) {
+                            raw_t<RB * VEC> out;
+                            pack_vec<RB, BF, VEC>(h[c], out);
+                            st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), out);
+                        }
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) {
                             const double hd = static_cast<double>(h[c][e]);
@@ -394,6 +401,17 @@ __device__ __forceinline__ void addrms_body(void* __restrict__ xp, void* __restr
         const double ss = row_sum(acc, reduce, tpr, lane, ry, lds + parity * lds_region);
         const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
 
+        if constexpr (DEFER) {      // the write phase: the whole residual row, then the whole y row
+#pragma unroll
+            for (int c = 0; c < CPT; ++c) {
+                const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+                if (ra.row_ok && col <= nlast) {
+                    raw_t<RB * VEC> out;
+                    pack_vec<RB, BF, VEC>(h[c], out);
+                    st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), out);
+                }
+            }
+        }
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
             const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;

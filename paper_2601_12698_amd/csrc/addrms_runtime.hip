@@ -19,7 +19,7 @@
 // Declarations of every kernel instance and the table of their addresses, in
 // the order of the instance list the deriver uses.
 #include "gen_dispatch_decl.inc"
-struct DispatchEntry { int op, dt, vec, cpt, unr, nt; const void* fn; };
+struct DispatchEntry { int op, dt, vec, cpt, unr, nt, df; const void* fn; };
 static const DispatchEntry kDispatch[] = {
 #include "gen_dispatch_rows.inc"
 };
@@ -49,7 +49,7 @@ bool dispatch_consistent()
         for (int i = 0; i < n_instances(); ++i) {
             const Instance& in = instance(i);
             const DispatchEntry& d = kDispatch[i];
-            if (d.op != in.op || d.dt != in.dt || d.vec != in.vec || d.cpt != in.cpt || d.unr != in.unr || d.nt != in.nt) return false;
+            if (d.op != in.op || d.dt != in.dt || d.vec != in.vec || d.cpt != in.cpt || d.unr != in.unr || d.nt != in.nt || d.df != in.df) return false;
         }
         return true;
     }();

@@ -143,7 +143,8 @@ struct Searcher {
     //               largest workgroup and the deepest load batching the class admits
     //   capped      (only with the lower-occupancy hint) streaming with about half the
     //               resident waves
-    enum Mode { kPlain = 0, kStreaming = 1, kPersistent = 2, kCapped = 3 };
+    //   deferred    streaming with the residual store deferred to the write phase
+    enum Mode { kPlain = 0, kStreaming = 1, kPersistent = 2, kCapped = 3, kDeferred = 4 };
     std::vector<int> class_representatives(Mode mode) const
     {
         std::map<std::pair<int, int>, std::pair<double, int>> best;   // class -> (score, index)
@@ -152,12 +153,17 @@ struct Searcher {
             if (c.reduce != ADDRMS_REDUCE_WAVE || (c.max_waves_per_simd != 0) != (mode == kCapped)) continue;
             const double threads = static_cast<double>(c.threads_per_row) * c.rows_per_wg;
             double score;
+            if (c.walk != 0) continue;                  // walk lengths are reached by descent only
             if (mode == kPersistent) {
-                if (!(c.flags & ADDRMS_FLAG_PERSISTENT) || !(c.flags & ADDRMS_FLAG_NONTEMPORAL)) continue;
+                if (!(c.flags & ADDRMS_FLAG_PERSISTENT) || !(c.flags & ADDRMS_FLAG_NONTEMPORAL) ||
+                    (c.flags & ADDRMS_FLAG_DEFER_STORE)) continue;
                 score = -threads - 0.1 * c.unroll - ((c.flags & ADDRMS_FLAG_XCD_CONTIG) ? 0.01 : 0.0);
             } else {
                 // (the long-row form is part of the class, not of the mode)
-                if ((c.flags & ~kFormBits) != (mode == kPlain ? 0 : ADDRMS_FLAG_NONTEMPORAL)) continue;
+                const int want_flags = mode == kPlain ? 0
+                                       : mode == kDeferred ? (ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_DEFER_STORE)
+                                                           : ADDRMS_FLAG_NONTEMPORAL;
+                if ((c.flags & ~kFormBits) != want_flags) continue;
                 const int want_unroll = std::min(2, cands[i].res.chunks_per_thread);
                 score = fabs(log2(threads / 256.0)) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
                 if (mode == kCapped) score += 0.5 * fabs(static_cast<double>(c.max_waves_per_simd) - 4.0);
@@ -185,7 +191,12 @@ struct Searcher {
         { addrms_cfg n = c; n.reduce ^= 1; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_XCD_CONTIG; push(n); }
         { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_NONTEMPORAL; push(n); }
-        { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_PERSISTENT; push(n); }
+        { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_PERSISTENT; n.walk = 0; push(n); }
+        { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_DEFER_STORE; push(n); }
+        if (c.flags & ADDRMS_FLAG_PERSISTENT) {        // walk length: one step longer, one step shorter
+            { addrms_cfg n = c; n.walk = c.walk == 0 ? 4 : c.walk * 4; push(n); }
+            if (c.walk != 0) { addrms_cfg n = c; n.walk = c.walk == 4 ? 0 : c.walk / 4; push(n); }
+        }
         if (c.flags & kFormBits) { addrms_cfg n = c; n.flags ^= kFormBits; push(n); }   // the other long-row form
         // occupancy cap: one step tighter, one step looser (0 = uncapped sits above the natural occupancy)
         {
@@ -367,7 +378,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
                 if (best_plain == 0.0 || s.cands[i].us < best_plain) best_plain = s.cands[i].us;
             }
         }
-        std::vector<Searcher::Mode> modes = {Searcher::kStreaming, Searcher::kPersistent};
+        std::vector<Searcher::Mode> modes = {Searcher::kStreaming, Searcher::kDeferred, Searcher::kPersistent};
         if (b.hints & ADDRMS_HINT_LOWER_OCCUPANCY) modes.push_back(Searcher::kCapped);
         for (Searcher::Mode mode : modes)
             for (int i : s.class_representatives(mode)) {
@@ -376,6 +387,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
                 auto it = plain_us.find({c.vec + 16 * (c.flags & kFormBits), c.threads_per_row});
                 if (it != plain_us.end() && it->second > 2.0 * best_plain) continue;
                 s.eval(i, mode == Searcher::kStreaming ? "sweep_streaming"
+                          : mode == Searcher::kDeferred ? "sweep_deferred"
                           : mode == Searcher::kPersistent ? "sweep_persistent" : "sweep_capped",
                        b.coarse_warmup, b.coarse_reps);
             }

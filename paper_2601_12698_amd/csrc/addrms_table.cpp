@@ -55,7 +55,22 @@ int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out, int op)
     return ADDRMS_OK;
 }
 
-static const char kMagic[] = "addrms-table 3 gfx950";
+// File form: a format line, the architecture the entries were measured on, the library
+// version that wrote them, then one entry per line.  Timings and feasibility are facts
+// about one architecture and one set of compiled kernel instances, so a file written for
+// another architecture or by a library of another major.minor version is refused whole.
+static const char kMagic[] = "addrms-table 4";
+static const char kArch[] = "gfx950";
+
+static bool same_major_minor(const char* a, const char* b)
+{
+    int dots = 0;
+    for (; *a && *b; ++a, ++b) {
+        if (*a != *b) return false;
+        if (*a == '.' && ++dots == 2) return true;
+    }
+    return *a == *b;
+}
 
 }  // namespace addrms_host
 
@@ -95,12 +110,13 @@ int addrms_table_save(const char* path)
     std::lock_guard<std::mutex> lock(g_mu);
     FILE* f = fopen(path, "w");
     if (!f) return fail(ADDRMS_ERR_IO, "cannot open %s for writing", path);
-    fprintf(f, "%s\n# operator dtype M N vec threads_per_row rows_per_wg reduce unroll flags max_waves_per_simd mean_us\n", kMagic);
+    fprintf(f, "%s\narch %s\nlibrary %s\n# operator dtype M N vec threads_per_row rows_per_wg reduce unroll flags "
+               "max_waves_per_simd walk mean_us\n", kMagic, kArch, ADDRMS_VERSION_STRING);
     for (const auto& kv : table()) {
         const addrms_cfg& c = kv.second.cfg;
-        fprintf(f, "%d %d %lld %lld %d %d %d %d %d %d %d %.6f\n", std::get<0>(kv.first), std::get<1>(kv.first),
+        fprintf(f, "%d %d %lld %lld %d %d %d %d %d %d %d %d %.6f\n", std::get<0>(kv.first), std::get<1>(kv.first),
                 (long long)std::get<3>(kv.first), (long long)std::get<2>(kv.first), c.vec, c.threads_per_row,
-                c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd, kv.second.us);
+                c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd, c.walk, kv.second.us);
     }
     const bool bad = ferror(f) != 0;
     if (fclose(f) != 0 || bad) return fail(ADDRMS_ERR_IO, "write to %s failed", path);
@@ -115,7 +131,7 @@ int addrms_table_load(const char* path)
     char line[512];
     std::map<Key, Entry> staged;
     int lineno = 0;
-    bool have_magic = false;
+    bool have_magic = false, have_arch = false, have_version = false;
     while (fgets(line, sizeof line, f)) {
         ++lineno;
         size_t len = strlen(line);
@@ -123,17 +139,35 @@ int addrms_table_load(const char* path)
         if (!have_magic) {
             if (strcmp(line, kMagic) != 0) {
                 fclose(f);
-                return fail(ADDRMS_ERR_IO, "%s: not an addrms table for gfx950 (bad first line)", path);
+                return fail(ADDRMS_ERR_IO, "%s: not an addrms table of this format (first line is not \"%s\")", path, kMagic);
             }
             have_magic = true;
             continue;
         }
+        if (!have_arch) {
+            if (strncmp(line, "arch ", 5) != 0 || strcmp(line + 5, kArch) != 0) {
+                fclose(f);
+                return fail(ADDRMS_ERR_IO, "%s: written for \"%s\", this library runs on \"arch %s\": timings and feasible "
+                            "regions do not carry over", path, line, kArch);
+            }
+            have_arch = true;
+            continue;
+        }
+        if (!have_version) {
+            if (strncmp(line, "library ", 8) != 0 || !same_major_minor(line + 8, ADDRMS_VERSION_STRING)) {
+                fclose(f);
+                return fail(ADDRMS_ERR_IO, "%s: written by \"%s\", this is library %s: the kernel instances differ", path, line,
+                            ADDRMS_VERSION_STRING);
+            }
+            have_version = true;
+            continue;
+        }
         if (len == 0 || line[0] == '#') continue;
         int op, dtype; long long M, N; addrms_cfg c{}; double us; int used = 0;
-        const int got = sscanf(line, "%d %d %lld %lld %d %d %d %d %d %d %d %lf %n", &op, &dtype, &M, &N, &c.vec,
+        const int got = sscanf(line, "%d %d %lld %lld %d %d %d %d %d %d %d %d %lf %n", &op, &dtype, &M, &N, &c.vec,
                                &c.threads_per_row, &c.rows_per_wg, &c.reduce, &c.unroll, &c.flags,
-                               &c.max_waves_per_simd, &us, &used);
-        if (got != 12 || op < 0 || op >= kNumOps || static_cast<size_t>(used) != len) {
+                               &c.max_waves_per_simd, &c.walk, &us, &used);
+        if (got != 13 || op < 0 || op >= kNumOps || static_cast<size_t>(used) != len) {
             fclose(f);
             return fail(ADDRMS_ERR_IO, "%s:%d: malformed entry", path, lineno);
         }
@@ -145,7 +179,7 @@ int addrms_table_load(const char* path)
         staged[Key(op, dtype, N, M)] = Entry{c, us};
     }
     fclose(f);
-    if (!have_magic) return fail(ADDRMS_ERR_IO, "%s: empty file", path);
+    if (!have_magic || !have_arch || !have_version) return fail(ADDRMS_ERR_IO, "%s: header incomplete (format, arch and library lines)", path);
     std::lock_guard<std::mutex> lock(g_mu);
     for (const auto& kv : staged) table()[kv.first] = kv.second;
     return ADDRMS_OK;

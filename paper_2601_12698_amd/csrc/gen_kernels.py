@@ -1,7 +1,8 @@
 """Writes the instantiation list of the kernel template.
 
 The templates in ``addrms_kernel.h`` and ``silumul_kernel.h`` have four
-compile-time knobs (VEC, CPT, UNR, NT) per storage format.  CPT = 0 names the
+compile-time knobs (VEC, CPT, UNR, NT) per storage format; the register-cached
+form of add+RMSNorm has a fifth, DF (residual store deferred to the write phase).  CPT = 0 names the
 two-pass form of add+RMSNorm, which loops over the row instead of caching it
 (rows beyond the register row cache), and CPT = 100 + k the single-pass form
 whose cache continues in LDS after k register-held chunks.  This script emits,
@@ -43,7 +44,7 @@ SILU_CPTS = (1, 2, 3, 4, 5, 6, 7, 8)
 
 
 def instances():
-    """(op, dt, vec, cpt, unr, nt, maxt) of every compiled kernel, in table order."""
+    """(op, dt, vec, cpt, unr, nt, df, maxt) of every compiled kernel, in table order."""
     for op, dts, cpts in ((OP_ADDRMS, DTS, CPTS), (OP_SILUMUL, SILU_DTS, SILU_CPTS),
                           (OP_MERGE, MERGE_DTS, MERGE_CPTS)):
         for dt in dts:
@@ -58,21 +59,22 @@ def instances():
                             continue
                         maxt = 1024 if vec * cpt <= BIG_ELEMS else 256
                         for nt in (0, 1):
-                            yield op, dt, vec, cpt, unr, nt, maxt
+                            for df in ((0, 1) if op == OP_ADDRMS else (0,)):
+                                yield op, dt, vec, cpt, unr, nt, df, maxt
                 if op == OP_ADDRMS:                  # two-pass form: no row cache, any row length
                     for unr in UNRS:
                         for nt in (0, 1):
-                            yield op, dt, vec, 0, unr, nt, 1024
+                            yield op, dt, vec, 0, unr, nt, 0, 1024
                     reg_cpt = BIG_ELEMS // vec       # LDS-extended cache: registers filled to the 1024-thread bound
                     for unr in UNRS:
                         if unr > reg_cpt:
                             continue
                         for nt in (0, 1):
-                            yield op, dt, vec, LDS_CACHE_BASE + reg_cpt, unr, nt, 1024
+                            yield op, dt, vec, LDS_CACHE_BASE + reg_cpt, unr, nt, 0, 1024
 
 
-def name(op, dt, vec, cpt, unr, nt):
-    return f"{OP_PREFIX[op]}_k_d{dt}_v{vec}_c{cpt}_u{unr}_n{nt}"
+def name(op, dt, vec, cpt, unr, nt, df=0):
+    return f"{OP_PREFIX[op]}_k_d{dt}_v{vec}_c{cpt}_u{unr}_n{nt}" + ("_s1" if df else "")
 
 
 ARGS = {
@@ -83,7 +85,7 @@ ARGS = {
                "long long rows, int d, unsigned flags, unsigned nblocks"),
 }
 CALL = {
-    OP_ADDRMS: "addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}, {nt}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);",
+    OP_ADDRMS: "addrms::addrms_body<{dt}, {vec}, {cpt}, {unr}, {nt}, {df}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);",
     OP_SILUMUL: "addrms::silumul_body<{dt}, {vec}, {cpt}, {unr}, {nt}>(x, out, M, d, flags, nblocks);",
     OP_MERGE: ("addrms::mergestates_body<{dt}, {vec}, {cpt}, {unr}, {nt}>"
                "(va, sa, vb, sb, vo, so, rows, d, flags, nblocks);"),
@@ -97,26 +99,27 @@ HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h", OP_MERGE
 def main(outdir: str) -> None:
     os.makedirs(outdir, exist_ok=True)
     units = {}
-    for op, dt, vec, cpt, unr, nt, maxt in instances():
-        units.setdefault((op, dt, vec), []).append((cpt, unr, nt, maxt))
+    for op, dt, vec, cpt, unr, nt, df, maxt in instances():
+        units.setdefault((op, dt, vec), []).append((cpt, unr, nt, df, maxt))
     for (op, dt, vec), lst in units.items():
         lines = [f'#include "{HEADER[op]}"', ""]
-        for cpt, unr, nt, maxt in lst:
+        for cpt, unr, nt, df, maxt in lst:
             fmt = CALL[op]
             if op == OP_ADDRMS and cpt == 0:
                 fmt = TWO_PASS_CALL
             elif op == OP_ADDRMS and cpt >= LDS_CACHE_BASE:
                 fmt = LDS_CACHE_CALL
-            call = fmt.format(dt=dt, vec=vec, cpt=cpt % LDS_CACHE_BASE, unr=unr, nt="true" if nt else "false")
-            lines.append(f'extern "C" __global__ __launch_bounds__({maxt}) void {name(op, dt, vec, cpt, unr, nt)}'
+            call = fmt.format(dt=dt, vec=vec, cpt=cpt % LDS_CACHE_BASE, unr=unr, nt="true" if nt else "false",
+                              df="true" if df else "false")
+            lines.append(f'extern "C" __global__ __launch_bounds__({maxt}) void {name(op, dt, vec, cpt, unr, nt, df)}'
                          f"({ARGS[op]})\n{{ {call} }}")
         _write(os.path.join(outdir, f"kern_{OP_PREFIX[op]}_d{dt}_v{vec}.hip"), "\n".join(lines) + "\n")
     decl, table, inst = [], [], []
-    for op, dt, vec, cpt, unr, nt, maxt in instances():
-        n = name(op, dt, vec, cpt, unr, nt)
+    for op, dt, vec, cpt, unr, nt, df, maxt in instances():
+        n = name(op, dt, vec, cpt, unr, nt, df)
         decl.append(f'extern "C" __global__ void {n}({ARGS[op]});')
-        table.append(f"    {{{op}, {dt}, {vec}, {cpt}, {unr}, {nt}, reinterpret_cast<const void*>(&{n})}},")
-        inst.append(f"    {{{op}, {dt}, {vec}, {cpt}, {unr}, {nt}, {maxt}}},")
+        table.append(f"    {{{op}, {dt}, {vec}, {cpt}, {unr}, {nt}, {df}, reinterpret_cast<const void*>(&{n})}},")
+        inst.append(f"    {{{op}, {dt}, {vec}, {cpt}, {unr}, {nt}, {df}, {maxt}}},")
     _write(os.path.join(outdir, "gen_dispatch_decl.inc"), "\n".join(decl) + "\n")
     _write(os.path.join(outdir, "gen_dispatch_rows.inc"), "\n".join(table) + "\n")
     _write(os.path.join(outdir, "gen_instances.inc"), "\n".join(inst) + "\n")

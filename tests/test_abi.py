@@ -38,7 +38,7 @@ def test_struct_sizes_match_c_layout():
     assert ctypes.sizeof(B.Resources) == 64
     assert ctypes.sizeof(B.Budget) == 8 + 4 * 10 + 8 + 8
     assert ctypes.sizeof(B.RoundInfo) == 4 + 4 + 8 + 8 + 32
-    assert ctypes.sizeof(B.RoundsReport) == 4 + 4 + 8 + 4 * 56 + ctypes.sizeof(B.GeneralReport)
+    assert ctypes.sizeof(B.RoundsReport) == 4 + 4 + 8 + B.MAX_ROUNDS * 56 + ctypes.sizeof(B.GeneralReport)
     assert ctypes.sizeof(B.GeneralReport) == 8 + 8 * 4 + 8 * 16 * 3 + 32 * 16
     assert ctypes.sizeof(B.Shape) == 16
     assert ctypes.sizeof(B.TuneReport) == 8 * 5 + 8 * 4 + 32 * 2 + 8 + 32 * 8 + 8 * 8

@@ -28,7 +28,12 @@ KNOWN_INFEASIBLE = [
     (B.make_cfg(8, 256, 3), 4096, 4096, "bf16", "rows_per_wg"),
     (B.make_cfg(8, 256, 1, reduce=2), 4096, 4096, "bf16", "reduce"),
     (B.make_cfg(8, 256, 1, unroll=3), 4096, 4096, "bf16", "unroll"),
-    (B.make_cfg(8, 256, 1, flags=32), 4096, 4096, "bf16", "flags"),
+    (B.make_cfg(8, 256, 1, flags=64), 4096, 4096, "bf16", "flags"),
+    (B.make_cfg(8, 256, 1, unroll=2, flags=8 | 32), 4096, 65536, "bf16", "deferred residual store exists for the register-cached form only"),
+    (B.make_cfg(8, 1024, 1, unroll=2, flags=16 | 32), 4096, 40960, "bf16", "deferred residual store exists for the register-cached form only"),
+    (B.make_cfg(8, 256, 1, unroll=2, walk=4), 32768, 4096, "bf16", "walk=4 sizes a persistent grid"),
+    (B.make_cfg(8, 256, 1, unroll=2, flags=4, walk=3), 32768, 4096, "bf16", "walk=3"),
+    (B.make_cfg(8, 256, 1, unroll=2, flags=4, walk=16), 8192, 4096, "bf16", "persistent grid is the ordinary grid"),
     (B.make_cfg(8, 256, 1, unroll=2, flags=4), 1024, 4096, "bf16", "persistent grid is the ordinary grid"),
     (B.make_cfg(8, 256, 1), 4096, 4100, "bf16", "does not divide"),
     (B.make_cfg(8, 256, 1), 4096, 4096, "fp32", "wider than"),
@@ -67,7 +72,9 @@ def test_bad_shape_and_dtype_codes():
                                        (8192, 1000, "fp16_res32"), (8192, 2880, "fp16_res32"), (128, 11008, "fp32")])
 def test_enumeration_is_exactly_the_feasible_subset(M, N, dtype):
     cfgs, grid = B.addrms_enumerate_feasible(M, N, dtype)
-    assert grid == 4 * 19 * 5 * 2 * 4 * 32 * 8          # vec, threads/row, rows/wg, reduce, unroll, 5 flag bits, cap
+    # vec, threads/row, rows/wg, reduce, unroll, cap; 6 flag bits, and for the half of them with a persistent grid
+    # two more walk lengths
+    assert grid == (4 * 19 * 5 * 2 * 4 * 8) * (64 + 32 * 2)
     assert not any(c.flags & (B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE) for c in cfgs)   # these rows fit the register cache
     assert 0 < len(cfgs) < grid
     seen = set()
@@ -90,7 +97,7 @@ def test_enumeration_counts_are_stable():
     register allocation (it decides which occupancy caps bind), so only the scale is pinned."""
     got = {k: len(B.addrms_enumerate_feasible(*k)[0]) for k in
            [(4096, 4096, "bf16"), (16, 4096, "bf16"), (256, 8192, "bf16"), (32768, 7168, "bf16")]}
-    assert 5000 < got[(4096, 4096, "bf16")] < 30000
+    assert 10000 < got[(4096, 4096, "bf16")] < 60000
     assert got[(16, 4096, "bf16")] < got[(4096, 4096, "bf16")]      # fewer rows: fewer row packings, no XCD map
     assert all(v > 100 for v in got.values())
 
@@ -166,7 +173,7 @@ def test_default_cfg():
             assert feas(d, M, N, dtype)[0] == 0, (N, dtype, M, d)
         assert d.reduce == B.REDUCE_WAVE and d.flags == 0 and d.max_waves_per_simd == 0
     d = B.addrms_default_cfg(4096, "bf16")
-    assert d.as_tuple() == (8, 256, 1, 0, 2, 0, 0)
+    assert d.as_tuple() == (8, 256, 1, 0, 2, 0, 0, 0)
     assert B.load().addrms_default_cfg(1 << 30, B.BF16, B.Cfg()) == B.ERR_UNSUPPORTED_SHAPE
     assert "row cache" in B.addrms_last_error()
 
@@ -228,3 +235,27 @@ def test_row_length_bound_of_the_register_cache(dtype):
             B.addrms_default_cfg(N, dtype)
         assert e.value.status == B.ERR_UNSUPPORTED_SHAPE
         assert B.addrms_enumerate_feasible(4, N, dtype)[0] == []      # the feasible region is empty, not an error
+
+
+def test_deferred_store_and_walk_are_part_of_the_region():
+    """The deferred residual store doubles the register-cached part of the region (another instance, same launch
+    shapes); the walk length multiplies only persistent cfgs, and only while the longer grid is still shorter than
+    the list of row blocks."""
+    M, N, dt = 32768, 7168, "bf16"
+    cfgs, _ = B.addrms_enumerate_feasible(M, N, dt)
+    plain = [c for c in cfgs if not c.flags & B.FLAG_DEFER_STORE]
+    deferred = [c for c in cfgs if c.flags & B.FLAG_DEFER_STORE]
+    assert deferred and 0.9 * len(plain) <= len(deferred) <= len(plain)      # a few differ where register counts move a cap
+    assert all(c.walk in (0, 4, 16) for c in cfgs)
+    assert all(c.flags & B.FLAG_PERSISTENT for c in cfgs if c.walk)
+    assert {c.walk for c in cfgs if c.flags & B.FLAG_PERSISTENT} == {0, 4, 16}
+    # the instance is another one: resources are reported for it
+    base = B.make_cfg(8, 448, 1, unroll=1, flags=B.FLAG_NONTEMPORAL)
+    d = B.make_cfg(8, 448, 1, unroll=1, flags=B.FLAG_NONTEMPORAL | B.FLAG_DEFER_STORE)
+    (s0, _, r0), (s1, _, r1) = feas(base, M, N, dt), feas(d, M, N, dt)
+    assert s0 == 0 and s1 == 0 and r0.chunks_per_thread == r1.chunks_per_thread == 2
+    # on a small problem a 16-fold grid covers every row block: pruned as the ordinary grid
+    small, _ = B.addrms_enumerate_feasible(4096, 4096, dt)
+    assert sum(1 for c in small if c.walk == 16) < sum(1 for c in small if c.walk == 4) < sum(1 for c in small if c.flags & B.FLAG_PERSISTENT and c.walk == 0)
+    # the two further operators have no residual stream and therefore no such flag
+    assert B.silumul_cfg_feasible(B.make_cfg(8, 704, 1, flags=B.FLAG_DEFER_STORE), 4096, 11008, "bf16")[0] == B.ERR_INFEASIBLE_CFG

@@ -59,9 +59,10 @@ def test_odd_width_mixed_dtype(oracle, N):
     assert all(s["n_diff"] == 0 for s in out.values())
 
 
-@pytest.mark.parametrize("m,n", [(128, 4096), (2048, 8192), (128, 11008), (256, 13824), (512, 14336)])
+@pytest.mark.parametrize("m,n", [(128, 4096), (256, 4096), (1024, 4096), (2048, 8192), (128, 11008), (256, 13824),
+                                 (512, 14336), (1024, 8192)])
 def test_fp32_shapes(oracle, m, n):
-    """fp32 storage on (m, n) shapes of the kind the paper lists for its fp32 kernel
+    """fp32 storage on the eight (m, n) shapes the paper lists for its fp32 kernel
     (Section 4, Kernels).  The output is fp32, so it sees the last bits of rstd:
     bit-exact is still expected because rstd itself is reproduced exactly."""
     wl = W.Workload(f"fp32_{m}x{n}", m, n, "fp32", 1e-6, 100 + m + n)
@@ -89,7 +90,9 @@ def test_every_feasible_cfg_matches_the_oracle_at_benchmark_size(oracle, wl):
     r_ref_d = torch.from_numpy(res_ref.view(np.int16 if res_ref.itemsize == 2 else np.int32)).to(dev)
     x, r = torch.empty_like(x0), torch.empty_like(r0)
     cfgs, _ = B.addrms_enumerate_feasible(wl.M, wl.N, wl.dtype)
-    stride = 3 if wl.M * wl.N > (1 << 27) else 1          # the 1.9 GB shape: every third cfg keeps the test short
+    stride = 7 if wl.M * wl.N > (1 << 27) else 1          # the 1.9 GB shape: every seventh cfg keeps the test short (7 is
+                                                          # coprime to every loop length of the enumeration, so each value
+                                                          # of each knob is still met)
     picked = cfgs[::stride]
     print(f"{wl.name}: {len(picked)} of {len(cfgs)} feasible cfgs", flush=True)
     bad = []

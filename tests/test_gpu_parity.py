@@ -254,7 +254,8 @@ def test_runs_on_a_side_stream(oracle):
     with torch.cuda.stream(s):
         B.addrms_run(case.x, case.r, case.w, wl.eps, wl.M, wl.N, wl.dtype, None, stream=s)
     s.synchronize()
-    compare(W.to_bits(case.x), W.to_bits(case.r), y_ref, res_ref, "bf16", "side stream")
+    st = compare(W.to_bits(case.x), W.to_bits(case.r), y_ref, res_ref, "bf16", "side stream")
+    assert st["n_diff"] == 0, st
 
 
 def _run_raw(x, r, w, eps, dtype, cfg=None):

@@ -135,8 +135,9 @@ def test_rounds_on_device(tmp_path):
     shapes = [(4096, 4096), (2048, 8192)]
     g, rep = B.addrms_tune_rounds(shapes, "bf16", B.make_budget(log_path=log, warmup=5, reps=30))
     print(json.dumps(rep.as_dict()["rounds"]), flush=True)
-    assert rep.n_rounds == 4 and all(rep.rounds[i].passed for i in range(4))
-    scores = [rep.rounds[i].score for i in range(4)]
+    assert rep.n_rounds == B.MAX_ROUNDS == 5 and all(rep.rounds[i].passed for i in range(5))
+    assert rep.rounds[4].families & B.FAMILY_STORE_PHASE
+    scores = [rep.rounds[i].score for i in range(5)]
     assert scores[1] < scores[0] - 0.03            # the non-temporal policy is worth well over 3 %
     assert min(scores) == scores[rep.best_round]
     assert rep.rounds[0].general.flags == 0 and rep.rounds[0].general.max_waves_per_simd == 0

@@ -20,6 +20,7 @@ def cost(M, N):
         us *= 0.97 if c.max_waves_per_simd in (4, 5, 6) else 1.0             # a cap pays a little
         us *= 1.04 if c.flags & B.FLAG_PERSISTENT else 1.0                   # the persistent grid does not
         us *= 1.01 if c.flags & B.FLAG_XCD_CONTIG else 1.0
+        us *= 0.97 if c.flags & B.FLAG_DEFER_STORE else 1.0                  # one read phase, one write phase
         us *= 1.05 if c.reduce else 1.0
         return us
     return f
@@ -35,24 +36,25 @@ def backend(validate=lambda c: True):
 def test_rounds_add_families_and_keep_the_best(tmp_path):
     log = str(tmp_path / "rounds.jsonl")
     g, rep = B.addrms_tune_rounds_with_backend(SHAPES, DT, B.make_budget(log_path=log), backend())
-    assert rep.n_rounds == 4
-    fam = [rep.rounds[i].families for i in range(4)]
-    assert fam == [0, B.FAMILY_STREAMING, B.FAMILY_STREAMING | B.FAMILY_OCCUPANCY_CAP,
-                   B.FAMILY_STREAMING | B.FAMILY_OCCUPANCY_CAP | B.FAMILY_GRID_MAPPING]
-    assert all(rep.rounds[i].passed for i in range(4))
+    assert rep.n_rounds == 5
+    fam = [rep.rounds[i].families for i in range(5)]
+    three = B.FAMILY_STREAMING | B.FAMILY_OCCUPANCY_CAP | B.FAMILY_GRID_MAPPING
+    assert fam == [0, B.FAMILY_STREAMING, B.FAMILY_STREAMING | B.FAMILY_OCCUPANCY_CAP, three, three | B.FAMILY_STORE_PHASE]
+    assert all(rep.rounds[i].passed for i in range(5))
     # round 0 may only use the base template
     r0 = rep.rounds[0].general
     assert r0.flags == 0 and r0.max_waves_per_simd == 0
     assert rep.rounds[1].general.flags == B.FLAG_NONTEMPORAL
-    scores = [rep.rounds[i].score for i in range(4)]
+    scores = [rep.rounds[i].score for i in range(5)]
     assert scores[1] < scores[0] - 0.1                  # streaming is a structural gain
     assert scores[2] <= scores[1] + 1e-9                # more families never hurt the specialised table
-    assert rep.best_round == min(range(4), key=lambda i: scores[i])
+    assert scores[4] < scores[3] - 0.01                 # so is the deferred store in this landscape
+    assert rep.best_round == min(range(5), key=lambda i: scores[i])
     assert -rep.rounds[rep.best_round].score == pytest.approx(rep.best.geomean_speedup_specialized)
     assert not (g.flags & B.FLAG_PERSISTENT) and g.flags & B.FLAG_NONTEMPORAL
     lines = [json.loads(l) for l in open(log)]
     rounds = [l for l in lines if l["event"] == "round"]
-    assert [l["round"] for l in rounds] == [0, 1, 2, 3] and rounds[-1]["incumbent"] == rep.best_round
+    assert [l["round"] for l in rounds] == [0, 1, 2, 3, 4] and rounds[-1]["incumbent"] == rep.best_round
 
 
 def test_a_family_that_fails_validation_is_rolled_back():

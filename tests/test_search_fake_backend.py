@@ -73,7 +73,7 @@ def test_exhaustive_is_the_argmin():
     rec = Recorder(cost)
     best, n = true_best(cost)
     got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE), rec.measure, rec.validate)
-    assert got.as_tuple() == best.as_tuple() == (8, 512, 2, 0, 1, 2, 4)
+    assert got.as_tuple() == best.as_tuple() == (8, 512, 2, 0, 1, 2, 4, 0)
     assert rep.n_feasible == n == rep.n_measured and rep.n_failed == 0
     assert len(set(rec.validated)) == n                      # every candidate went through the gate
     assert rep.best_us == pytest.approx(cost(best)) and rep.default_us == pytest.approx(cost(B.addrms_default_cfg(N, DT)))

@@ -53,15 +53,29 @@ def test_save_load_round_trip(tmp_path):
     assert B.addrms_table_lookup(8192, 1000, "fp16_res32").as_tuple() == b.as_tuple()
 
 
+HDR = "addrms-table 4\narch gfx950\nlibrary %s\n" % B.addrms_version().split()[0]
+GOOD = "0 0 1 8192 8 1024 1 0 1 0 0 0 3.0\n"
+
+
 @pytest.mark.parametrize("content", [
     "",                                                     # empty
-    "not a table\n0 0 1 8192 8 1024 1 0 1 0 0 3.0\n",         # wrong magic
-    "addrms-table 2 gfx950\n0 1 8192 8 1024 1 0 1 0 0 3.0\n",  # older format version
-    "addrms-table 3 gfx950\n0 0 1 8192 8 1024 1 0 1 0\n",      # truncated entry
-    "addrms-table 3 gfx950\n0 0 1 8192 8 1024 1 0 1 0 0 3.0 junk\n",
-    "addrms-table 3 gfx950\n0 0 4096 4096 8 1024 1 0 1 0 0 3.0\n",   # parses, but cfg infeasible for that shape
-    "addrms-table 3 gfx950\n0 7 1 8192 8 1024 1 0 1 0 0 3.0\n",      # bad dtype
-    "addrms-table 3 gfx950\n5 0 1 8192 8 1024 1 0 1 0 0 3.0\n",      # unknown operator
+    "not a table\n" + GOOD,                                 # wrong magic
+    "addrms-table 3 gfx950\n0 0 1 8192 8 1024 1 0 1 0 0 3.0\n",   # older format version
+    "addrms-table 4\n" + GOOD,                              # no arch line
+    "addrms-table 4\narch gfx950\n" + GOOD,                 # no library line
+    "addrms-table 4\narch gfx942\nlibrary 0.2.0\n" + GOOD,  # tuned on another architecture
+    "addrms-table 4\narch gfx9500\nlibrary 0.2.0\n" + GOOD,
+    "addrms-table 4\narch gfx950\nlibrary 0.1.0\n" + GOOD,  # written by a library with other kernel instances
+    "addrms-table 4\narch gfx950\nlibrary 1.2.0\n" + GOOD,
+    "addrms-table 4\narch gfx950\nlibrary 0.20.0\n" + GOOD,
+    HDR,                                                    # a header alone is a valid, empty table: must NOT fail (see below)
+    HDR + "0 0 1 8192 8 1024 1 0 1 0 0\n",                  # truncated entry
+    HDR + "0 0 1 8192 8 1024 1 0 1 0 0 3.0\n",              # entry of the previous format (no walk column)
+    HDR + "0 0 1 8192 8 1024 1 0 1 0 0 0 3.0 junk\n",
+    HDR + "0 0 4096 4096 8 1024 1 0 1 0 0 0 3.0\n",         # parses, but cfg infeasible for that shape
+    HDR + "0 7 1 8192 8 1024 1 0 1 0 0 0 3.0\n",            # bad dtype
+    HDR + "5 0 1 8192 8 1024 1 0 1 0 0 0 3.0\n",            # unknown operator
+    HDR + "0 0 1 8192 8 1024 1 0 1 0 0 4 3.0\n",            # a walk length without a persistent grid
 ])
 def test_corrupt_file_leaves_table_unchanged(tmp_path, content):
     keep = B.make_cfg(8, 1024, 1)
@@ -69,6 +83,10 @@ def test_corrupt_file_leaves_table_unchanged(tmp_path, content):
     path = str(tmp_path / "bad.txt")
     with open(path, "w") as f:
         f.write(content)
+    if content == HDR:                                      # control: the header itself is accepted
+        B.addrms_table_load(path)
+        assert B.addrms_table_size() == 1
+        return
     with pytest.raises(B.AddrmsError) as e:
         B.addrms_table_load(path)
     assert e.value.status == B.ERR_IO
@@ -101,3 +119,26 @@ def test_two_pass_entries_round_trip_and_resolve_long_rows(tmp_path):
     assert B.addrms_table_lookup(4096, 40960, "bf16").as_tuple() == c.as_tuple()
     assert B.addrms_table_lookup(100, 40960, "bf16").as_tuple() == c.as_tuple()
     assert B.addrms_table_lookup(100, 40968, "bf16") is None
+
+
+def test_file_names_its_architecture_and_library_and_a_patch_release_may_read_it(tmp_path):
+    c = B.make_cfg(8, 256, 1, unroll=2, flags=B.FLAG_NONTEMPORAL | B.FLAG_PERSISTENT | B.FLAG_DEFER_STORE, walk=4)
+    B.addrms_table_insert(32768, 4096, "bf16", c, 100.0)
+    path = str(tmp_path / "t.txt")
+    B.addrms_table_save(path)
+    lines = open(path).read().splitlines()
+    assert lines[0] == "addrms-table 4" and lines[1] == "arch gfx950"
+    version = B.addrms_version().split()[0]
+    assert lines[2] == "library " + version
+    major, minor, _ = version.split(".")
+    with open(path, "w") as f:                              # same major.minor, another patch level: same instances
+        f.write("\n".join([lines[0], lines[1], f"library {major}.{minor}.99"] + lines[3:]) + "\n")
+    B.addrms_table_clear()
+    B.addrms_table_load(path)
+    got = B.addrms_table_lookup(32768, 4096, "bf16")
+    assert got.as_tuple() == c.as_tuple() and got.walk == 4
+    with open(path, "w") as f:
+        f.write("\n".join([lines[0], "arch gfx90a", lines[2]] + lines[3:]) + "\n")
+    with pytest.raises(B.AddrmsError) as e:
+        B.addrms_table_load(path)
+    assert e.value.status == B.ERR_IO and "gfx90a" in e.value.message
