@@ -1,22 +1,32 @@
 #!/usr/bin/env python3
 """Benchmark of the fused residual-add + RMSNorm hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--op addrms|silumul|mergestates]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--op addrms|silumul|mergestates]
 
-Workload: the prefill shape M=4096, N=4096, bf16 storage (seed 1), the
-configuration the headline metric is quoted on.  One step = one in-place launch
-of the operator through the C ABI over one batch resident in HBM.  The launches
-rotate through enough buffer sets that every step streams from HBM rather
-than from the 256 MB last-level cache.
+Headline workload: the large prefill shape M=32768, N=7168, bf16 storage with 1 % outliers
+(seed 3), the largest of the benchmark configurations that one GPU holds (1.88 GB moved per
+step).  One step = one in-place launch of the operator through the C ABI over one batch that
+is already resident in HBM.  The launches rotate through enough buffer sets that every step
+streams from HBM rather than from the 256 MB last-level cache.
 
-Before the timed region the library's guided search tunes the launch
-configuration (its cost is reported, not timed as steps).  The same protocol
-is then run with the untuned default configuration.  One JSON line is printed.
+Before the timed region the library's guided search tunes the launch configuration (its cost
+is reported, not timed as steps).  Then, for the headline workload:
+  * W untimed warm-up steps and exactly K timed steps of the tuned configuration, bracketed
+    by device synchronisation (`value`, `ms_per_step`), with HIP events on the launch stream
+    around the same K steps (`roofline`);
+  * the same for the untuned default configuration (`default_cfg`);
+  * blocks of launches of the default and the tuned configuration in alternation, each block
+    timed with events, and the median block of each (`interleaved`): clock or thermal drift
+    hits both alike and a slow first block does not decide the ratio;
+  * the library's copy-like calibration kernel over the same buffers (`copy_probe`): the
+    same bytes with none of the arithmetic, the practical ceiling of this traffic pattern.
+All five benchmark configurations (smoke, prefill, the decode sweep, large prefill, the three
+odd-width mixed-precision shapes) are then tuned and timed by the library's own measurement
+harness (20 warm-up + 100 timed launches, twice, rotated buffers) and listed under `configs`.
+One JSON line is printed.
 
---op silumul / --op mergestates time the two further operators that sit behind
-the same tuner (gated activation 4096 x 11008 bf16; merge of two partial
-attention states, 768 x 32 x 256 bf16) with the same protocol and print the
-same kind of line; the default, and the headline figure, is the fused add+RMSNorm.
+--op silumul / --op mergestates time the two further operators that sit behind the same
+tuner with the same protocol and print the same kind of line.
 """
 from __future__ import annotations
 
@@ -24,6 +34,7 @@ import argparse
 import ctypes
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -35,18 +46,30 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 LLC_BYTES = 256 << 20           # Infinity Cache
 L2_TOTAL_BYTES = 8 * (4 << 20)
 SKEW_BYTES = 4096               # residual base is skewed against x by one 4 KiB interleave unit
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "addrms_hbm_traffic.md")
+METRIC = "fused add+RMSNorm achieved HBM GB/s (% of peak), tuned vs default cfg"
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) on the named workload,
-# scaled by the same counters on the library's calibration kernel of known size (summaries under profiles/).
-MEASURED_TRAFFIC_BYTES = {"prefill_4096x4096_bf16": 134361400,
-                          "large_prefill_32768x7168_bf16_outliers": 1879214200,
-                          "odd_width_8192xN_fp16_res32[N=1000]": 99665000}
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the tuned configuration of `workload_name`, as the profiler's FETCH_SIZE and
+    WRITE_SIZE counters measured them (rows of the table in profiles/addrms_hbm_traffic.md, which
+    `python -m paper_2601_12698_amd.signals --traffic-report` writes).  None if the workload was not measured."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.split("|")]
+                if len(cells) >= 9 and cells[1] == workload_name and cells[2] == "tuned":
+                    return {"bytes": int(cells[6]), "cfg": cells[3], "over_algorithmic": float(cells[8])}
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def device_info(torch):
     p = torch.cuda.get_device_properties(0)
     info = {"name": p.name, "arch": getattr(p, "gcnArchName", ""), "compute_units": p.multi_processor_count,
             "memory_gib": round(p.total_memory / 2 ** 30, 1)}
+    # clocks as far as the runtime exposes them (kHz); the driver's own power-state records sit beside this line
     for key in ("clock_rate", "memory_clock_rate", "memory_bus_width", "L2_cache_size"):
         v = getattr(p, key, None)
         if v:
@@ -59,6 +82,8 @@ def pick_workload(W, name):
         return W.PREFILL
     if name == "large_prefill":
         return W.LARGE_PREFILL
+    if name == "smoke":
+        return W.SMOKE
     if name.startswith("odd_width_") and int(name[10:]) in W.ODD_WIDTH_N:
         return W.ODD_WIDTH.with_cols(int(name[10:]))
     if name.startswith("decode_") and int(name[7:]) in W.DECODE_M:
@@ -70,23 +95,24 @@ def pick_workload(W, name):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the table of all five benchmark configurations (profiler runs want the headline kernels only)")
     ap.add_argument("--tune-log", default=None, help="write the search's JSON-lines log here")
     ap.add_argument("--exhaustive", action="store_true", help="tune by exhaustive search instead of guided")
     ap.add_argument("--cfg", default=None,
                     help="skip the search and time this configuration: vec,threads_per_row,rows_per_wg,reduce,unroll,"
-                         "flags,max_waves_per_simd (used for profiler runs, whose overhead would mislead the search)")
-    ap.add_argument("--workload", default="prefill",
-                    help="addrms workload: prefill (default; the configuration the headline metric is quoted on), "
-                         "large_prefill, odd_width_5120, odd_width_2880, odd_width_1000 or decode_<M>; the others "
-                         "serve profiling and the report, not the headline")
+                         "flags,max_waves_per_simd[,walk] (used for profiler runs, whose overhead would mislead the search)")
+    ap.add_argument("--workload", default="large_prefill",
+                    help="addrms workload of the headline: large_prefill (default; the largest benchmark configuration "
+                         "one GPU holds), prefill, smoke, odd_width_5120, odd_width_2880, odd_width_1000 or decode_<M>")
     ap.add_argument("--op", default="addrms", choices=("addrms", "silumul", "mergestates"),
                     help="operator to time (default: the fused add+RMSNorm hot path)")
     ap.add_argument("--probe", action="store_true",
-                    help="time the library's copy-like calibration kernel (same traffic, no arithmetic) over the "
-                         "same buffers instead of the operator; used to calibrate profiler byte counters")
+                    help="time only the library's copy-like calibration kernel (same traffic, no arithmetic) over the "
+                         "same buffers; used to calibrate profiler byte counters")
     return ap.parse_args()
 
 
@@ -110,51 +136,75 @@ def carve_sets(torch, wl, W, nsets):
     return pool, xs, rs
 
 
-def time_steps(torch, lib, B, args_per_set, cfg, warmup, steps, stream):  # noqa: D401
-    """Returns (wall seconds for `steps` launches, event milliseconds for the same)."""
-    n = len(args_per_set)
-    cfg_ref = ctypes.byref(cfg) if cfg is not None else None
-    sp = int(stream.cuda_stream)
-    k = 0
-    for _ in range(warmup):
-        a = args_per_set[k % n]; k += 1
-        st = lib.addrms_run(a[0], a[1], a[2], a[3], a[4], a[5], a[6], cfg_ref, sp)
-        if st != 0:
-            raise RuntimeError(B.addrms_last_error())
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(steps):
-        a = args_per_set[k % n]; k += 1
-        st = lib.addrms_run(a[0], a[1], a[2], a[3], a[4], a[5], a[6], cfg_ref, sp)
-        if st != 0:
-            raise RuntimeError(B.addrms_last_error())
-    e1.record(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    return t1 - t0, e0.elapsed_time(e1)
+def make_sets(torch, W, wl, d, dtype_id):
+    """Resident inputs, rotated so that each step misses the last-level cache."""
+    set_bytes = wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
+    nsets = min(256, max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // set_bytes)))
+    pool, xs, rs = carve_sets(torch, wl, W, nsets)
+    w = d["w"].cuda()
+    x0, r0 = d["x"].cuda(), d["r"].cuda()
+    for x, r in zip(xs, rs):
+        x.copy_(x0)
+        r.copy_(r0)
+    args = [(x.data_ptr(), r.data_ptr(), w.data_ptr(), wl.eps, wl.M, wl.N, dtype_id) for x, r in zip(xs, rs)]
+    return (pool, xs, rs, w), nsets, args
 
 
-def time_probe(torch, lib, B, args_per_set, warmup, steps, stream):
-    n = len(args_per_set)
-    sp = int(stream.cuda_stream)
-    k = 0
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    for phase, count in (("warmup", warmup), ("timed", steps)):
-        if phase == "timed":
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            e0.record(stream)
+class Runner:
+    """Enqueues launches on one stream, rotating over the buffer sets."""
+
+    def __init__(self, torch, lib, B, args_per_set, stream):
+        self.torch, self.lib, self.B, self.args, self.stream = torch, lib, B, args_per_set, stream
+        self.sp = int(stream.cuda_stream)
+        self.k = 0
+
+    def run(self, cfg, count):
+        ref = ctypes.byref(cfg) if cfg is not None else None
+        run, args, n, sp = self.lib.addrms_run, self.args, len(self.args), self.sp
         for _ in range(count):
-            a = args_per_set[k % n]; k += 1
-            if lib.addrms_stream_probe(a[0], a[1], a[4], a[5], a[6], sp) != 0:
-                raise RuntimeError(B.addrms_last_error())
-    e1.record(stream)
-    torch.cuda.synchronize()
-    return time.perf_counter() - t0, e0.elapsed_time(e1)
+            a = args[self.k % n]
+            self.k += 1
+            if run(a[0], a[1], a[2], a[3], a[4], a[5], a[6], ref, sp) != 0:
+                raise RuntimeError(self.B.addrms_last_error())
+
+    def probe(self, count):
+        fn, args, n, sp = self.lib.addrms_stream_probe, self.args, len(self.args), self.sp
+        for _ in range(count):
+            a = args[self.k % n]
+            self.k += 1
+            if fn(a[0], a[1], a[4], a[5], a[6], sp) != 0:
+                raise RuntimeError(self.B.addrms_last_error())
+
+    def timed(self, launch, warmup, steps):
+        """`launch(count)` enqueues count steps.  Returns (wall seconds, event milliseconds) for exactly `steps`
+        steps after `warmup` untimed ones, the timed region bracketed by device synchronisation."""
+        torch = self.torch
+        launch(warmup)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(self.stream)
+        launch(steps)
+        e1.record(self.stream)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, e0.elapsed_time(e1)
+
+    def interleaved(self, launchers, blocks, per_block):
+        """Alternates between the launchers, `blocks` blocks each of `per_block` launches, one event pair per block;
+        returns the per-launch microseconds of every block, per launcher."""
+        torch = self.torch
+        ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(blocks)]
+              for _ in launchers]
+        for launch in launchers:
+            launch(min(per_block, 5))
+        for b in range(blocks):
+            for i, launch in enumerate(launchers):
+                ev[i][b][0].record(self.stream)
+                launch(per_block)
+                ev[i][b][1].record(self.stream)
+        torch.cuda.synchronize()
+        return [[e0.elapsed_time(e1) * 1e3 / per_block for e0, e1 in row] for row in ev]
 
 
 def cpu_baseline(W, wl, d, nbytes):
@@ -174,40 +224,66 @@ def cpu_baseline(W, wl, d, nbytes):
         spent += time.perf_counter() - t0
         passes += 1
     per = spent / passes
+    rows_1 = min(wl.M, 4096)                                                  # a slice on one core: 1.9 GB would take 3 s
     t0 = time.perf_counter()
-    oracle.addrms(xb, rb, wb, wl.eps, dt, nthreads=1)                         # one pass on one core
-    one = time.perf_counter() - t0
+    oracle.addrms(xb[:rows_1], rb[:rows_1], wb, wl.eps, dt, nthreads=1)
+    one = (time.perf_counter() - t0) * wl.M / rows_1
     return {"value": nbytes / per * 1e-9, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "sample": f"{passes} full passes over {wl.name} ({wl.M}x{wl.N}), rows split over {cores} threads; "
-                      "plus one pass on a single thread",
+                      f"plus {rows_1} rows on a single thread, scaled to the full shape",
             "ms_per_step": per * 1e3, "tokens_per_s": wl.M / per,
             "single_thread": {"value": nbytes / one * 1e-9, "unit": "GB/s", "cores": 1, "ms_per_step": one * 1e3}}
 
 
-def make_sets(torch, B, W, wl, d, dtype_id):
-    """Resident inputs, rotated so that each step misses the last-level cache."""
-    set_bytes = wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
-    nsets = min(256, max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // set_bytes)))
-    pool, xs, rs = carve_sets(torch, wl, W, nsets)
-    w = d["w"].cuda()
-    x0, r0 = d["x"].cuda(), d["r"].cuda()
-    for x, r in zip(xs, rs):
-        x.copy_(x0)
-        r.copy_(r0)
-    args = [(x.data_ptr(), r.data_ptr(), w.data_ptr(), wl.eps, wl.M, wl.N, dtype_id) for x, r in zip(xs, rs)]
-    return (pool, xs, rs, w), nsets, args
-
-
 def run_probe(a, torch, lib, B, W, wl, d, dtype_id):
-    keep, nsets, args = make_sets(torch, B, W, wl, d, dtype_id)
-    stream = torch.cuda.current_stream()
-    wall, ev = time_probe(torch, lib, B, args, a.warmup, a.steps, stream)
+    keep, nsets, args = make_sets(torch, W, wl, d, dtype_id)
+    r = Runner(torch, lib, B, args, torch.cuda.current_stream())
+    wall, ev = r.timed(r.probe, a.warmup, a.steps)
     moved = 2 * wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
     print(json.dumps({"metric": "stream probe (read and write back x and residual, no arithmetic)",
                       "value": round(moved / (wall / a.steps) * 1e-9, 1), "unit": "GB/s", "n_gpus": 1,
                       "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(wall / a.steps * 1e3, 6),
                       "kernel_us": round(ev / a.steps * 1e3, 3), "bytes_per_step": moved,
                       "config": {"workload": wl.name, "rotating_buffer_sets": nsets}}))
+
+
+def configs_table(B, W, headline_name, headline_entry):
+    """All five benchmark configurations through the library's own harness: guided search, then the confirmation
+    protocol (2 x (20 warm-up + 100 timed launches), buffers rotated past the last-level cache) for the winner
+    and for the default cfg.  Shapes under about 1 MB of traffic are bound by launch latency, not by HBM."""
+    shapes = [W.SMOKE, W.PREFILL] + [W.DECODE.with_rows(m) for m in W.DECODE_M] + [W.LARGE_PREFILL] + \
+             [W.ODD_WIDTH.with_cols(n) for n in W.ODD_WIDTH_N]
+    out = []
+    for wl in shapes:
+        if wl.name == headline_name and headline_entry is not None:
+            out.append(headline_entry)
+            continue
+        nbytes = B.addrms_algorithmic_bytes(wl.M, wl.N, wl.dtype)
+        t0 = time.perf_counter()
+        cfg, rep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
+        out.append(config_entry(wl, nbytes, cfg, rep, (time.perf_counter() - t0) * 1e3))
+    return out
+
+
+def config_entry(wl, nbytes, cfg, rep, search_ms):
+    gbps = nbytes / rep.best_us * 1e-3
+    return {"workload": wl.name, "M": wl.M, "N": wl.N, "storage": wl.dtype, "bytes": nbytes,
+            "tuned_us": round(rep.best_us, 3), "default_us": round(rep.default_us, 3),
+            "speedup": round(rep.default_us / rep.best_us, 4) if rep.best_us > 0 else None,
+            "tuned_gbps": round(gbps, 1), "frac": round(gbps / HBM_PEAK_GBPS, 4),
+            "tokens_per_s": round(wl.M / (rep.best_us * 1e-6), 1), "cfg": list(cfg.as_tuple()),
+            "search_ms": round(search_ms, 1), "n_measured": rep.n_measured, "n_feasible": rep.n_feasible}
+
+
+def bounded_cpu_passes(fn, t_budget=12.0):
+    fn()
+    passes, spent = 0, 0.0
+    while spent < t_budget and passes < 5000:
+        t0 = time.perf_counter()
+        fn()
+        spent += time.perf_counter() - t0
+        passes += 1
+    return spent / passes, passes
 
 
 def timed_loop(torch, launch, nsets, warmup, steps, stream):
@@ -225,17 +301,6 @@ def timed_loop(torch, launch, nsets, warmup, steps, stream):
     e1.record(stream)
     torch.cuda.synchronize()
     return time.perf_counter() - t0, e0.elapsed_time(e1)
-
-
-def bounded_cpu_passes(fn, t_budget=12.0):
-    fn()
-    passes, spent = 0, 0.0
-    while spent < t_budget and passes < 5000:
-        t0 = time.perf_counter()
-        fn()
-        spent += time.perf_counter() - t0
-        passes += 1
-    return spent / passes, passes
 
 
 def run_other_op(a, torch, lib, B, W):
@@ -342,6 +407,9 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (rows are independent, so more GPUs "
               "means sharding rows with no communication); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if a.steps < 1 or a.warmup < 0:
+        print("need --steps >= 1 and --warmup >= 0", file=sys.stderr)
+        sys.exit(2)
     import torch
 
     from paper_2601_12698_amd import binding as B
@@ -376,24 +444,35 @@ def main():
         if st != 0:
             print(f"--cfg is not feasible: {why}", file=sys.stderr)
             sys.exit(2)
-        rep = B.TuneReport()
+        rep = None
     else:
         tuned, rep = B.addrms_tune(wl.M, wl.N, wl.dtype, budget)
     tune_wall = time.perf_counter() - t0
     default = B.addrms_default_cfg(wl.N, wl.dtype)
 
-    keep, nsets, args = make_sets(torch, B, W, wl, d, dtype_id)
+    keep, nsets, args = make_sets(torch, W, wl, d, dtype_id)
     stream = torch.cuda.current_stream()
+    r = Runner(torch, lib, B, args, stream)
 
-    wall_d, ev_d = time_steps(torch, lib, B, args, default, a.warmup, a.steps, stream)
-    wall_t, ev_t = time_steps(torch, lib, B, args, tuned, a.warmup, a.steps, stream)
+    run_default = lambda n: r.run(default, n)
+    run_tuned = lambda n: r.run(tuned, n)
+    wall_d, ev_d = r.timed(run_default, a.warmup, a.steps)
+    wall_t, ev_t = r.timed(run_tuned, a.warmup, a.steps)                   # the K timed steps of the headline
+    wall_p, ev_p = r.timed(r.probe, a.warmup, a.steps)
+    blocks, per_block = 7, max(5, min(a.steps, 40))
+    blk_d, blk_t, blk_p = r.interleaved([run_default, run_tuned, r.probe], blocks, per_block)
 
     ms_step = wall_t / a.steps * 1e3
     value = nbytes / (wall_t / a.steps) * 1e-9
     kernel_us = ev_t / a.steps * 1e3
     achieved = nbytes / (kernel_us * 1e-6) * 1e-9
+    probe_bytes = 2 * wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
+    probe_us = ev_p / a.steps * 1e3
+    probe_gbps = probe_bytes / (probe_us * 1e-6) * 1e-9
+    med_d, med_t, med_p = (statistics.median(v) for v in (blk_d, blk_t, blk_p))
+    traffic = measured_traffic(wl.name)
     out = {
-        "metric": "fused add+RMSNorm achieved HBM GB/s (% of peak), tuned vs default cfg",
+        "metric": METRIC,
         "value": round(value, 1),
         "unit": "GB/s",
         "n_gpus": 1,
@@ -414,15 +493,38 @@ def main():
                         "kernel_us": round(ev_d / a.steps * 1e3, 3),
                         "pct_of_peak": round(100.0 * nbytes / (wall_d / a.steps) * 1e-9 / HBM_PEAK_GBPS, 2)},
         "tuned_over_default": round(wall_d / wall_t, 4),
-        "tune": {"strategy": "given" if a.cfg else "exhaustive" if a.exhaustive else "guided", "wall_ms": round(tune_wall * 1e3, 1),
-                 "n_grid": rep.n_grid, "n_feasible": rep.n_feasible, "n_measured": rep.n_measured,
-                 "n_failed": rep.n_failed, "best_found_at": rep.best_found_at,
-                 "time_to_best_ms": round(rep.time_to_best_ms, 2), "best_us": round(rep.best_us, 3),
-                 "default_us": round(rep.default_us, 3)},
+        "interleaved": {"blocks": blocks, "launches_per_block": per_block,
+                        "tuned_us_median": round(med_t, 3), "default_us_median": round(med_d, 3),
+                        "probe_us_median": round(med_p, 3), "tuned_over_default": round(med_d / med_t, 4),
+                        "tuned_gbps_median": round(nbytes / med_t * 1e-3, 1),
+                        "tuned_frac_median": round(nbytes / med_t * 1e-3 / HBM_PEAK_GBPS, 4),
+                        "tuned_us_blocks": [round(v, 2) for v in blk_t],
+                        "default_us_blocks": [round(v, 2) for v in blk_d]},
+        "copy_probe": {"what": "library calibration kernel: reads and writes back x and residual over the same buffers, "
+                               "no arithmetic, streaming policy, three 256-thread workgroups per CU",
+                       "value": round(probe_gbps, 1), "unit": "GB/s", "kernel_us": round(probe_us, 3),
+                       "frac_of_peak": round(probe_gbps / HBM_PEAK_GBPS, 4),
+                       "operator_frac_of_probe": round(achieved / probe_gbps, 4),
+                       "operator_frac_of_probe_interleaved": round((nbytes / med_t) / (probe_bytes / med_p), 4)},
+        "tune": {"strategy": "given" if a.cfg else "exhaustive" if a.exhaustive else "guided", "wall_ms": round(tune_wall * 1e3, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic["bytes"] if traffic else None,
+                     "traffic_source": (f"profiles/{os.path.basename(TRAFFIC_FILE)}: FETCH_SIZE + WRITE_SIZE of cfg "
+                                        f"{traffic['cfg']}, {traffic['over_algorithmic']:.4f} x algorithmic") if traffic else None,
                      "kernel_us": round(kernel_us, 3), "algorithmic_bytes": nbytes},
     }
+    headline_entry = None
+    if rep is not None:
+        out["tune"].update({"n_grid": rep.n_grid, "n_feasible": rep.n_feasible, "n_measured": rep.n_measured,
+                            "n_failed": rep.n_failed, "best_found_at": rep.best_found_at,
+                            "time_to_best_ms": round(rep.time_to_best_ms, 2), "best_us": round(rep.best_us, 3),
+                            "default_us": round(rep.default_us, 3)})
+        headline_entry = config_entry(wl, nbytes, tuned, rep, tune_wall * 1e3)
+    del r, keep, args
+    torch.cuda.empty_cache()
+    if not a.no_configs:
+        out["configs"] = configs_table(B, W, wl.name, headline_entry)
     out["device"] = device_info(torch)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W, wl, d, nbytes)

@@ -85,6 +85,23 @@ def child_main(spec_path: str) -> int:
     return 0
 
 
+def child_probe_main(spec_path: str) -> int:
+    """Runs inside the profiler: the library's calibration kernel (known traffic) on the spec's shape."""
+    import torch
+
+    from . import workloads as W
+    spec = json.load(open(spec_path))
+    M, N, dtype = spec["M"], spec["N"], spec["dtype"]
+    nsets = 3
+    xs = [torch.randn(M, N, device="cuda").to(W.x_torch_dtype(dtype)) for _ in range(nsets)]
+    rs = [torch.randn(M, N, device="cuda").to(W.r_torch_dtype(dtype)) for _ in range(nsets)]
+    torch.cuda.synchronize()
+    for k in range(spec["launches"]):
+        B.addrms_stream_probe(xs[k % nsets], rs[k % nsets], M, N, dtype)
+    torch.cuda.synchronize()
+    return 0
+
+
 def _read_counter_csv(outdir: str) -> List[dict]:
     rows = []
     for root, _dirs, files in os.walk(outdir):
@@ -150,6 +167,91 @@ def collect(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float = 1e-6
     return records
 
 
+def collect_probe(M: int, N: int, dtype: str, counters: Sequence[str] = ("FETCH_SIZE", "WRITE_SIZE"),
+                  workdir: Optional[str] = None, timeout_s: int = 180) -> Dict[str, float]:
+    """Mean counter values per launch of the calibration kernel (reads and writes back x and residual of the
+    shape, nothing else), one profiler run per counter; the first launch is discarded."""
+    rocprof = shutil.which("rocprofv3")
+    if rocprof is None:
+        raise RuntimeError("rocprofv3 is not on PATH")
+    tmp = workdir or tempfile.mkdtemp(prefix="addrms_probe_")
+    os.makedirs(tmp, exist_ok=True)
+    spec_path = os.path.join(tmp, "probe_spec.json")
+    with open(spec_path, "w") as f:
+        json.dump({"M": M, "N": N, "dtype": dtype, "launches": LAUNCHES_PER_CFG + 2}, f)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ)
+    env["PYTHONPATH"] = root + os.pathsep + env.get("PYTHONPATH", "")
+    env.setdefault("TMPDIR", "/tmp")
+    out = {}
+    for i, name in enumerate(counters):
+        outdir = os.path.join(tmp, f"probe_pass{i}")
+        cmd = [rocprof, "--pmc", name, "--output-format", "csv", "-d", outdir, "-o", "sig", "--",
+               sys.executable, "-m", "paper_2601_12698_amd.signals", "--child-probe", spec_path]
+        r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
+                           timeout=timeout_s)
+        if r.returncode != 0:
+            raise RuntimeError(f"rocprofv3 probe pass {name} failed ({r.returncode}):\n{r.stdout[-2000:]}")
+        vals = [float(x["Counter_Value"]) for x in _read_counter_csv(outdir)
+                if "stream_probe_kernel" in x["Kernel_Name"] and x["Counter_Name"] == name]
+        if len(vals) < 2:
+            raise RuntimeError(f"{name}: no dispatches of the calibration kernel in the profiler output")
+        out[name] = sum(vals[1:]) / len(vals[1:])
+    if workdir is None:
+        shutil.rmtree(tmp, ignore_errors=True)
+    return out
+
+
+TRAFFIC_WORKLOADS = ("large_prefill", "prefill", "odd_width_5120", "odd_width_2880", "odd_width_1000")
+
+
+def traffic_report(path: str, names: Sequence[str] = TRAFFIC_WORKLOADS) -> List[dict]:
+    """HBM traffic per launch of the tuned and the default configuration of each named benchmark workload:
+    search (child process), FETCH_SIZE and WRITE_SIZE of both cfgs (one profiler run per counter), the same
+    counters on the calibration kernel of known traffic on the same shape (which gives bytes per counter unit),
+    written as a table that bench.py reads its `roofline.traffic` from."""
+    from . import workloads as W
+    rows, lines = [], []
+    for name in names:
+        wl = (W.LARGE_PREFILL if name == "large_prefill" else W.PREFILL if name == "prefill"
+              else W.ODD_WIDTH.with_cols(int(name[10:])))
+        r0 = _run_stage(["--stage-tune", str(wl.M), str(wl.N), wl.dtype, "--eps", repr(wl.eps), "--top-k", "1", "--hints", "0"])
+        cfgs = [B.make_cfg(**r0["cfg"]), B.make_cfg(**r0["default_cfg"])]
+        recs = collect(cfgs, wl.M, wl.N, wl.dtype, wl.eps, passes=(("FETCH_SIZE",), ("WRITE_SIZE",)))
+        # The plain copy kernel always runs in its symmetric 16-bit form (one aligned 16-byte piece of each stream per
+        # lane, whole cache lines per wave): with an fp32 residual beside 16-bit x its two pieces per lane leave the
+        # chip as half-line writes, which the write counter then sees as more than the bytes stored.
+        probe = collect_probe(wl.M, wl.N, "bf16")
+        stream_bytes = wl.M * wl.N * 4                                               # the probe reads and writes this much
+        fetch_unit = stream_bytes / probe["FETCH_SIZE"]
+        write_unit = stream_bytes / probe["WRITE_SIZE"]
+        alg = W.algorithmic_bytes(wl.M, wl.N, wl.dtype)
+        for which, cfg, rec, us in (("tuned", cfgs[0], recs[0], r0["us"]), ("default", cfgs[1], recs[1], r0["default_us"])):
+            rd = rec["counters"]["FETCH_SIZE"] * fetch_unit
+            wr = rec["counters"]["WRITE_SIZE"] * write_unit
+            row = {"workload": wl.name, "which": which, "cfg": cfg.as_tuple(), "read_bytes": rd, "write_bytes": wr,
+                   "total_bytes": rd + wr, "algorithmic_bytes": alg, "ratio": (rd + wr) / alg, "us": us,
+                   "fetch_units": rec["counters"]["FETCH_SIZE"], "write_units": rec["counters"]["WRITE_SIZE"],
+                   "fetch_unit_bytes": fetch_unit, "write_unit_bytes": write_unit}
+            rows.append(row)
+            lines.append("| %s | %s | %s | %d | %d | %d | %d | %.5f | %.2f | %.1f | %.1f | %.2f | %.2f |" % (
+                wl.name, which, ",".join(str(v) for v in cfg.as_tuple()), round(rd), round(wr), round(rd + wr), alg,
+                (rd + wr) / alg, us, rec["counters"]["FETCH_SIZE"], rec["counters"]["WRITE_SIZE"], fetch_unit, write_unit))
+    with open(path, "w") as f:
+        f.write("# HBM traffic per launch of addrms: profiler counters scaled by a kernel of known traffic (MI355X)\n\n"
+                "Command (no GPU work happens in the orchestrating process; searches and profiled launches run in child\n"
+                "processes, one `rocprofv3 --pmc <counter>` run per counter and per kernel kind):\n\n"
+                "    python -m paper_2601_12698_amd.signals --traffic-report profiles/addrms_hbm_traffic.md\n\n"
+                "Per workload: guided search, then FETCH_SIZE and WRITE_SIZE (mean of three launches after one discarded,\n"
+                "three rotating buffer sets) of the tuned and the default cfg, and of the library's calibration kernel (a plain\n"
+                "copy kernel: 16-bit x and residual of the same M x N, read and written back once, 4*M*N bytes each way): that\n"
+                "fixes the bytes per counter unit (last two columns; the counters' nominal units are 2 KiB and 1 KiB here).  cfg = vec, threads_per_row, rows_per_wg, reduce, unroll, flags, max_waves_per_simd, walk.\n"
+                "bench.py takes `roofline.traffic` from the `total bytes` column of the `tuned` row of its workload.\n\n"
+                "| workload | which | cfg | read bytes | written bytes | total bytes | algorithmic bytes | total / algorithmic | us (search) | FETCH_SIZE | WRITE_SIZE | bytes per FETCH unit | bytes per WRITE unit |\n"
+                "|---|---|---|---|---|---|---|---|---|---|---|---|---|\n" + "\n".join(lines) + "\n")
+    return rows
+
+
 HBM_PEAK_BYTES_PER_S = 8.0e12
 
 
@@ -203,7 +305,8 @@ def _run_stage(args: List[str], timeout_s: int = 600) -> dict:
 def stage_tune(M: int, N: int, dtype: str, eps: float, hints: int, log_path: Optional[str], top_k: int) -> dict:
     """(child process) One search; prints the winner and the Top-K as JSON."""
     cfg, rep = B.addrms_tune(M, N, dtype, B.make_budget(eps=eps, log_path=log_path, hints=hints))
-    return {"cfg": cfg.as_dict(), "us": rep.best_us, "default_us": rep.default_us, "n_measured": rep.n_measured,
+    return {"cfg": cfg.as_dict(), "default_cfg": rep.default_cfg.as_dict(), "us": rep.best_us, "default_us": rep.default_us,
+            "n_measured": rep.n_measured,
             "wall_ms": rep.wall_ms,
             "topk": [{"cfg": rep.topk[i].as_dict(), "us": rep.topk_us[i]} for i in range(min(top_k, rep.n_topk))]}
 
@@ -253,6 +356,9 @@ def tune_with_signals(M: int, N: int, dtype: str, eps: float = 1e-6, log_path: O
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--child", default=None, help="(internal) run the launches of a spec file")
+    ap.add_argument("--child-probe", default=None, help="(internal) run the calibration kernel of a spec file")
+    ap.add_argument("--traffic-report", default=None, metavar="PATH",
+                    help="measure HBM traffic of the tuned and default cfgs of the benchmark workloads and write the table")
     ap.add_argument("--stage-tune", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
                     help="(internal) run one search in this process and print its result as JSON")
     ap.add_argument("--stage-table", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
@@ -268,6 +374,12 @@ def main(argv=None) -> int:
     a = ap.parse_args(argv)
     if a.child:
         return child_main(a.child)
+    if a.child_probe:
+        return child_probe_main(a.child_probe)
+    if a.traffic_report:
+        for row in traffic_report(a.traffic_report):
+            print(json.dumps(row))
+        return 0
     if a.stage_tune:
         m, n, dt = a.stage_tune
         print(json.dumps(stage_tune(int(m), int(n), dt, a.eps, a.hints, a.log, a.top_k)))
