@@ -200,7 +200,11 @@ int oracle_addrms(const void *x, const void *r, const void *w, float eps,
 #pragma omp parallel for num_threads(nthreads) schedule(static)
     for (int64_t i = 0; i < M; ++i) {
         float *h = (float *)malloc((size_t)N * sizeof(float));
-        if (!h) { failed = 1; continue; }
+        if (!h) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
         for (int64_t j = 0; j < N; ++j) {
             float xf = load_x(x, i * N + j, dtype);
             float rf = load_r(r, i * N + j, dtype);

@@ -292,20 +292,28 @@ def test_against_torch_cpu(oracle, dtype):
 
 
 def test_uses_unrounded_sum_for_normalisation(oracle):
-    """y is computed from the fp32 sum, not from the rounded residual_out: pick
-    h = 1 + 2^-9 (not a bf16 value) and check y reflects the unrounded h."""
+    """y is computed from the fp32 sum, not from the rounded residual_out.  Every element has x = 1 and
+    r = 2^-9, so h = 1 + 2^-9 in fp32 (not a bf16 value; residual_out rounds to 1.0, tie to even) and, with
+    w = 1, the two readings land in different bf16 cells:
+        unrounded h:  y = h * rstd = 1 / sqrt(1 + eps / h^2) = 1 - 5e-7      -> bf16 1.0          (0x3f80)
+        rounded h:    y = 1 * rstd = 1 / sqrt(h^2 + eps)     = 0.998050...   -> bf16 1 - 2^-9     (0x3f7f)
+    (bf16 values just below 1 are 2^-9 apart: 0.998046875 and 1.0; the midpoint is 0.9990234375.)"""
     N = 8
-    # x = 1, r = 2^-9: fp32 sum 1.001953125, bf16 rounding gives 1.0 (tie to even)
-    x = np.full((1, N), oracle.f32_to_bf16(1.0), dtype=np.uint16)
-    r = np.full((1, N), oracle.f32_to_bf16(2.0 ** -9), dtype=np.uint16)
-    w = np.full((N,), oracle.f32_to_bf16(255.0), dtype=np.uint16)
+    one, tiny = 0x3f80, 0x3b00                      # bf16 bit patterns of 1.0 and 2^-9
+    x = np.full((1, N), one, dtype=np.uint16)
+    r = np.full((1, N), tiny, dtype=np.uint16)
+    w = np.full((N,), one, dtype=np.uint16)
     y, res, rstd = oracle.addrms(x, r, w, 1e-6, 0, return_rstd=True)
-    assert np.all(res == oracle.f32_to_bf16(1.0))
-    h = np.float32(1.0) + np.float32(2.0 ** -9)
-    want = oracle.f32_to_bf16((h * rstd[0]) * np.float32(255.0))
-    alt = oracle.f32_to_bf16((np.float32(1.0) * rstd[0]) * np.float32(255.0))
-    assert np.all(y == want)
-    assert rstd[0] == np.float32(1.0 / math.sqrt(float(h) ** 2 + float(np.float32(1e-6))))
+    assert np.all(res == one)
+    h = 1.0 + 2.0 ** -9
+    exact_rstd = 1.0 / math.sqrt(h * h + float(np.float32(1e-6)))
+    assert rstd[0] == np.float32(exact_rstd)
+    want_value, alt_value = h * exact_rstd, 1.0 * exact_rstd
+    midpoint = 1.0 - 2.0 ** -10
+    assert alt_value < midpoint - 1e-4 and want_value > midpoint + 1e-4     # the two readings are far from the boundary
+    want, alt = one, 0x3f7f
+    assert want != alt
+    assert np.all(y == want), [hex(v) for v in y.ravel()]
 
 
 def test_threads_do_not_change_results(oracle):
