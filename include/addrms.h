@@ -180,9 +180,14 @@ typedef struct addrms_budget {
     int32_t skip_validation; /* nonzero: do not gate candidates on correctness (tests only)*/
     float   eps;             /* eps used for the tuning launches; 0 = 1e-6                 */
     int32_t hints;           /* ADDRMS_HINT_* bits; 0 = none                               */
-    const char* log_path;    /* host; JSON-lines log of every candidate; NULL = none       */
+    const char* log_path;    /* host; JSON-lines log of every candidate; NULL = none.  If the
+                                file already holds a search of the same operator, shape and
+                                format made on this architecture by this library version,
+                                candidates it screened are not measured again (their logged
+                                times and gate verdicts stand); only the Top-K confirmation
+                                is repeated.  The search is appended to the file.            */
     int32_t family_mask;     /* ADDRMS_FAMILY_* bits the search may use; 0 = all of them   */
-    int32_t reserved1;
+    int32_t no_resume;       /* nonzero: ignore what log_path already holds, measure anew   */
 } addrms_budget;
 
 #define ADDRMS_MAX_TOPK 8
@@ -199,8 +204,8 @@ typedef struct addrms_tune_report {
     addrms_cfg best;
     addrms_cfg default_cfg;
     int32_t n_topk;
-    int32_t reserved0;
-    addrms_cfg topk[ADDRMS_MAX_TOPK];    /* confirmed candidates, fastest first            */
+    int32_t n_resumed;       /* candidates whose screening result came from the log         */
+    addrms_cfg topk[ADDRMS_MAX_TOPK];    /* confirmed candidates (the default among them), fastest first */
     double  topk_us[ADDRMS_MAX_TOPK];
 } addrms_tune_report;
 

@@ -92,19 +92,19 @@ class Budget(Structure):
                 ("top_k", c_int32), ("warmup", c_int32), ("reps", c_int32), ("coarse_warmup", c_int32),
                 ("coarse_reps", c_int32), ("skip_validation", c_int32), ("eps", c_float),
                 ("hints", c_int32), ("log_path", c_char_p),
-                ("family_mask", c_int32), ("reserved1", c_int32)]
+                ("family_mask", c_int32), ("no_resume", c_int32)]
 
 
 class TuneReport(Structure):
     _fields_ = [("n_grid", c_int64), ("n_feasible", c_int64), ("n_measured", c_int64), ("n_failed", c_int64),
                 ("best_found_at", c_int64), ("best_us", c_double), ("default_us", c_double),
                 ("wall_ms", c_double), ("time_to_best_ms", c_double), ("best", Cfg), ("default_cfg", Cfg),
-                ("n_topk", c_int32), ("reserved0", c_int32), ("topk", Cfg * MAX_TOPK),
+                ("n_topk", c_int32), ("n_resumed", c_int32), ("topk", Cfg * MAX_TOPK),
                 ("topk_us", c_double * MAX_TOPK)]
 
     def as_dict(self) -> dict:
         return dict(n_grid=self.n_grid, n_feasible=self.n_feasible, n_measured=self.n_measured,
-                    n_failed=self.n_failed, best_found_at=self.best_found_at, best_us=self.best_us,
+                    n_failed=self.n_failed, n_resumed=self.n_resumed, best_found_at=self.best_found_at, best_us=self.best_us,
                     default_us=self.default_us, wall_ms=self.wall_ms, time_to_best_ms=self.time_to_best_ms,
                     best=self.best.as_dict(), default_cfg=self.default_cfg.as_dict(),
                     topk=[(self.topk[i].as_dict(), self.topk_us[i]) for i in range(self.n_topk)])
@@ -404,11 +404,12 @@ def addrms_enumerate_feasible(M: int, N: int, dtype) -> Tuple[List[Cfg], int]:
 def make_budget(max_wall_ms: float = 0.0, max_candidates: int = 0, strategy: int = SEARCH_GUIDED, top_k: int = 0,
                 warmup: int = 0, reps: int = 0, coarse_warmup: int = 0, coarse_reps: int = 0,
                 skip_validation: bool = False, eps: float = 0.0, log_path: Optional[str] = None,
-                hints: int = 0, family_mask: int = 0) -> Budget:
+                hints: int = 0, family_mask: int = 0, no_resume: bool = False) -> Budget:
     b = Budget()
     b.max_wall_ms, b.max_candidates, b.strategy, b.top_k = max_wall_ms, max_candidates, strategy, top_k
     b.warmup, b.reps, b.coarse_warmup, b.coarse_reps = warmup, reps, coarse_warmup, coarse_reps
     b.skip_validation, b.eps, b.hints, b.family_mask = int(skip_validation), eps, hints, family_mask
+    b.no_resume = int(no_resume)
     b.log_path = log_path.encode() if log_path else None
     return b
 

@@ -28,7 +28,6 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
     if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
     if (M <= 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "the audit needs M > 0 and N > 0");
     if (!be.measure) return fail(ADDRMS_ERR_INVALID_ARG, "backend has no measure function");
-    if (budget && (budget->reserved1 != 0)) return fail(ADDRMS_ERR_INVALID_ARG, "budget.reserved1 must be 0");
     const int warm = budget && budget->coarse_warmup > 0 ? budget->coarse_warmup : 3;
     const int reps = budget && budget->coarse_reps > 0 ? budget->coarse_reps : 15;
     const int per_class = budget && budget->max_candidates > 0 ? budget->max_candidates : 0;   // pruned classes; 0 = all

@@ -58,6 +58,8 @@ struct Searcher {
     std::vector<Cand> cands;
     std::unordered_map<uint64_t, int> index;
     int64_t n_measured = 0, n_failed = 0;
+    int32_t n_resumed = 0;
+    std::unordered_map<uint64_t, std::pair<double, bool>> resumed;   // cfg key -> (screening time, passed) from an earlier log
     Clock::time_point t0 = Clock::now();
     FILE* log = nullptr;
     double bytes = 0.0;
@@ -98,6 +100,17 @@ struct Searcher {
         Cand& c = cands[i];
         if (c.tried) return !c.failed;
         c.tried = true;
+        {   // measured in an earlier run of the same search (same architecture, library, operator, shape): take that
+            auto it = resumed.find(cfg_key(c.cfg));
+            if (it != resumed.end()) {
+                ++n_resumed;
+                if (!it->second.second) { c.failed = true; return false; }
+                c.us = it->second.first;
+                c.order = 0;
+                c.at_ms = elapsed_ms();
+                return true;
+            }
+        }
         if (!b.skip_validation && be.validate && be.validate(be.user, &c.cfg) != 0) {
             c.failed = true;
             ++n_failed;
@@ -285,6 +298,81 @@ struct Searcher {
     }
 };
 
+// ---- resume: what an earlier run already measured ---------------------------------------
+// The log is a list of searches, each opened by a "begin" line that names architecture, library
+// version, operator, shape and format.  Screening results ("eval" lines other than the
+// confirmation re-tests) that follow a matching "begin" are facts about this very search problem
+// and need not be measured again; anything else in the file is ignored.
+bool json_str(const char* line, const char* key, char* out, size_t cap)
+{
+    char pat[48];
+    snprintf(pat, sizeof pat, "\"%s\":\"", key);
+    const char* p = strstr(line, pat);
+    if (!p) return false;
+    p += strlen(pat);
+    size_t n = 0;
+    while (*p && *p != '"' && n + 1 < cap) out[n++] = *p++;
+    out[n] = '\0';
+    return *p == '"';
+}
+bool json_num(const char* line, const char* key, double* out)
+{
+    char pat[48];
+    snprintf(pat, sizeof pat, "\"%s\":", key);
+    const char* p = strstr(line, pat);
+    if (!p) return false;
+    char* end = nullptr;
+    const double v = strtod(p + strlen(pat), &end);
+    if (end == p + strlen(pat)) return false;
+    *out = v;
+    return true;
+}
+bool version_compatible(const char* a, const char* b)      // same major.minor
+{
+    int dots = 0;
+    for (; *a && *b; ++a, ++b) {
+        if (*a != *b) return false;
+        if (*a == '.' && ++dots == 2) return true;
+    }
+    return *a == *b;
+}
+void load_resume(const char* path, int op, int64_t M, int64_t N, int dtype,
+                 std::unordered_map<uint64_t, std::pair<double, bool>>* out)
+{
+    FILE* f = fopen(path, "r");
+    if (!f) return;
+    char line[2048];
+    bool active = false;
+    while (fgets(line, sizeof line, f)) {
+        char ev[16] = "";
+        if (!json_str(line, "event", ev, sizeof ev)) continue;
+        if (!strcmp(ev, "begin")) {
+            char s_op[32] = "", s_dt[16] = "", s_arch[16] = "", s_lib[16] = "";
+            double m = 0, n = 0;
+            active = json_str(line, "op", s_op, sizeof s_op) && json_str(line, "dtype", s_dt, sizeof s_dt) &&
+                     json_str(line, "arch", s_arch, sizeof s_arch) && json_str(line, "library", s_lib, sizeof s_lib) &&
+                     json_num(line, "M", &m) && json_num(line, "N", &n) && !strcmp(s_op, op_name(op)) &&
+                     !strcmp(s_dt, dtype_name(dtype)) && !strcmp(s_arch, "gfx950") &&
+                     version_compatible(s_lib, ADDRMS_VERSION_STRING) && static_cast<int64_t>(m) == M &&
+                     static_cast<int64_t>(n) == N;
+            continue;
+        }
+        if (!active || strcmp(ev, "eval")) continue;
+        char phase[24] = "";
+        if (!json_str(line, "phase", phase, sizeof phase) || !strcmp(phase, "confirm")) continue;
+        const char* p = strstr(line, "\"cfg\":{");
+        addrms_cfg c{};
+        if (!p || sscanf(p, "\"cfg\":{\"vec\":%d,\"threads_per_row\":%d,\"rows_per_wg\":%d,\"reduce\":%d,\"unroll\":%d,"
+                            "\"flags\":%d,\"max_waves_per_simd\":%d,\"walk\":%d}", &c.vec, &c.threads_per_row, &c.rows_per_wg,
+                         &c.reduce, &c.unroll, &c.flags, &c.max_waves_per_simd, &c.walk) != 8) continue;
+        double us = 0.0;
+        const bool pass = strstr(line, "\"pass\":true") != nullptr;
+        if (pass && !(json_num(line, "us", &us) && us > 0.0)) continue;
+        (*out)[cfg_key(c)] = {us, pass};
+    }
+    fclose(f);
+}
+
 void fill_defaults(addrms_budget* b)
 {
     if (b->top_k <= 0) b->top_k = 5;
@@ -348,9 +436,11 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     const int i_default = s.find(dflt);
 
     if (b.log_path) {
+        if (!b.no_resume) load_resume(b.log_path, op, M, N, dtype, &s.resumed);
         s.log = fopen(b.log_path, "a");
         if (!s.log) return fail(ADDRMS_ERR_IO, "cannot open log %s", b.log_path);
-        fprintf(s.log, "{\"event\":\"begin\",\"op\":\"%s\",\"M\":%lld,\"N\":%lld,\"dtype\":\"%s\",\"strategy\":\"%s\",\"n_grid\":%lld,"
+        fprintf(s.log, "{\"event\":\"begin\",\"arch\":\"gfx950\",\"library\":\"" ADDRMS_VERSION_STRING "\",\"op\":\"%s\",\"M\":%lld,"
+                       "\"N\":%lld,\"dtype\":\"%s\",\"strategy\":\"%s\",\"n_grid\":%lld,"
                        "\"n_feasible\":%lld,\"default\":%s,\"pruned\":{",
                 op_name(op), (long long)M, (long long)N, dtype_name(dtype),
                 b.strategy == ADDRMS_SEARCH_GUIDED ? "guided" : "exhaustive",
@@ -437,7 +527,7 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
         if (cnt[k] == 0) continue;
         const double mean = sum[k] / cnt[k];
         if (confirm[k] == i_default) default_us = mean;
-        if (k < top.size()) confirmed.push_back({mean, confirm[k]});
+        confirmed.push_back({mean, confirm[k]});      // the default competes too: the winner is the argmin of what was confirmed
     }
     if (confirmed.empty()) {
         if (s.log) { fprintf(s.log, "{\"event\":\"end\",\"status\":\"no_result\"}\n"); fclose(s.log); }
@@ -459,8 +549,9 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
         report->time_to_best_ms = win.at_ms;
         report->best = win.cfg;
         report->default_cfg = dflt;
-        report->n_topk = static_cast<int32_t>(confirmed.size());
-        for (size_t k = 0; k < confirmed.size(); ++k) {
+        report->n_topk = static_cast<int32_t>(std::min<size_t>(confirmed.size(), ADDRMS_MAX_TOPK));
+        report->n_resumed = s.n_resumed;
+        for (size_t k = 0; k < static_cast<size_t>(report->n_topk); ++k) {
             report->topk[k] = s.cands[confirmed[k].second].cfg;
             report->topk_us[k] = confirmed[k].first;
         }
@@ -468,9 +559,9 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
     }
     if (s.log) {
         fprintf(s.log, "{\"event\":\"end\",\"status\":\"ok\",\"best\":%s,\"best_us\":%.4f,\"default_us\":%.4f,"
-                       "\"n_measured\":%lld,\"n_failed\":%lld,\"best_found_at\":%lld,\"time_to_best_ms\":%.3f,"
+                       "\"n_measured\":%lld,\"n_resumed\":%d,\"n_failed\":%lld,\"best_found_at\":%lld,\"time_to_best_ms\":%.3f,"
                        "\"wall_ms\":%.3f}\n",
-                cfg_json(win.cfg).c_str(), confirmed.front().first, default_us, (long long)s.n_measured,
+                cfg_json(win.cfg).c_str(), confirmed.front().first, default_us, (long long)s.n_measured, s.n_resumed,
                 (long long)s.n_failed, (long long)win.order, win.at_ms, s.elapsed_ms());
         fclose(s.log);
     }

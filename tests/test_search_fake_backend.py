@@ -77,7 +77,7 @@ def test_exhaustive_is_the_argmin():
     assert rep.n_feasible == n == rep.n_measured and rep.n_failed == 0
     assert len(set(rec.validated)) == n                      # every candidate went through the gate
     assert rep.best_us == pytest.approx(cost(best)) and rep.default_us == pytest.approx(cost(B.addrms_default_cfg(N, DT)))
-    assert rep.n_topk == 5 and list(rep.topk_us[:5]) == sorted(rep.topk_us[:5])
+    assert rep.n_topk == 6 and list(rep.topk_us[:6]) == sorted(rep.topk_us[:6])     # the Top-5 and the default
     assert (20, 100) in rec.protocols                        # the paper's 20 warm-up + 100 timed runs
 
 
@@ -194,3 +194,75 @@ def test_search_over_the_long_row_forms():
     # where only two passes fit, the search still works
     g2, grep2 = B.addrms_tune_with_backend(m, 1 << 20, DT, B.make_budget(), rec.measure, rec.validate)
     assert g2.flags & B.FLAG_TWO_PASS and grep2.default_cfg.flags == B.FLAG_TWO_PASS
+
+
+def test_second_search_resumes_from_the_log(tmp_path):
+    """A search whose log already holds the same problem (architecture, library, operator, shape, format) does not
+    screen anything again: it takes the logged times and gate verdicts and repeats only the Top-K confirmation."""
+    path = str(tmp_path / "tune.jsonl")
+    bad_output = lambda c: c.vec == 4
+    rec = Recorder(lambda c: cost(c, 0.02), fail_validate=bad_output)
+    first, rep1 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=path), rec.measure, rec.validate)
+    assert rep1.n_resumed == 0 and rep1.n_measured > 50 and rep1.n_failed > 0
+    screened = set(rec.measured)
+    rec2 = Recorder(lambda c: cost(c, 0.02), fail_validate=bad_output)
+    second, rep2 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=path), rec2.measure, rec2.validate)
+    assert second.as_tuple() == first.as_tuple()
+    assert rep2.n_measured == 0 and rep2.n_resumed == rep1.n_measured + rep1.n_failed
+    assert rec2.validated == []                                  # logged verdicts stand, failures included
+    assert rec2.protocols == {(20, 100)}                         # nothing but the confirmation protocol ran
+    assert set(rec2.measured) <= screened and len(set(rec2.measured)) <= 6
+    assert rep2.best_us == pytest.approx(rep1.best_us)
+    begins = [json.loads(l) for l in open(path) if '"begin"' in l]
+    assert len(begins) == 2 and begins[0]["arch"] == "gfx950" and begins[0]["library"] == B.addrms_version().split()[0]
+    # another shape, another format or no_resume: the log does not apply
+    rec3 = Recorder(lambda c: cost(c, 0.02))
+    _, rep3 = B.addrms_tune_with_backend(M * 2, N, DT, B.make_budget(log_path=path), rec3.measure, rec3.validate)
+    assert rep3.n_resumed == 0 and rep3.n_measured > 50
+    _, rep4 = B.addrms_tune_with_backend(M, N, "fp16", B.make_budget(log_path=path), rec3.measure, rec3.validate)
+    assert rep4.n_resumed == 0
+    _, rep5 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=path, no_resume=True), rec3.measure, rec3.validate)
+    assert rep5.n_resumed == 0 and rep5.n_measured > 50
+    # a log written on another architecture or by a library with other kernel instances is ignored
+    foreign = str(tmp_path / "foreign.jsonl")
+    with open(foreign, "w") as f:
+        for l in open(path):
+            f.write(l.replace('"arch":"gfx950"', '"arch":"gfx942"'))
+    _, rep6 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=foreign), rec3.measure, rec3.validate)
+    assert rep6.n_resumed == 0
+    old = str(tmp_path / "old.jsonl")
+    with open(old, "w") as f:
+        for l in open(path):
+            f.write(l.replace('"library":"%s"' % B.addrms_version().split()[0], '"library":"0.1.0"'))
+    _, rep7 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=old), rec3.measure, rec3.validate)
+    assert rep7.n_resumed == 0
+    # a partial log (the first run was cut short) resumes what it has and measures the rest
+    part = str(tmp_path / "part.jsonl")
+    lines = open(path).read().splitlines()
+    first_end = next(i for i, l in enumerate(lines) if '"event":"end"' in l)
+    with open(part, "w") as f:
+        f.write("\n".join(lines[:first_end // 2]) + "\n")
+    rec8 = Recorder(lambda c: cost(c, 0.02), fail_validate=bad_output)
+    eighth, rep8 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=part), rec8.measure, rec8.validate)
+    assert 0 < rep8.n_resumed < rep2.n_resumed and rep8.n_measured > 0
+    assert eighth.as_tuple() == first.as_tuple()
+
+
+def test_default_wins_when_it_confirms_fastest():
+    """Screening is short and noisy; if the default cfg is the fastest under the confirmation protocol it is the
+    argmin of measured run time and must be returned (with a speed-up of one), not the best of the others."""
+    default = B.addrms_default_cfg(N, DT).as_tuple()
+
+    def measure(c, warmup, reps):
+        us = cost(c)
+        if c.as_tuple() == default:
+            return us * 3.0 if reps < 100 else 1.0          # screens badly, confirms fastest
+        return us
+
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(), measure)
+    assert got.as_tuple() == default
+    assert rep.best_us == pytest.approx(1.0) and rep.default_us == pytest.approx(1.0)
+    assert rep.topk[0].as_tuple() == default and rep.n_topk == 6
+    # and the usual case is unchanged: the default confirms slower and does not win
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(), lambda c, w, r: cost(c))
+    assert got.as_tuple() != default and rep.default_us > rep.best_us
