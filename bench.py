@@ -139,7 +139,7 @@ def carve_sets(torch, wl, W, nsets):
 def make_sets(torch, W, wl, d, dtype_id):
     """Resident inputs, rotated so that each step misses the last-level cache."""
     set_bytes = wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
-    nsets = min(256, max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // set_bytes)))
+    nsets = min(256, max(2, -(-4 * (LLC_BYTES + L2_TOTAL_BYTES) // set_bytes)))
     pool, xs, rs = carve_sets(torch, wl, W, nsets)
     w = d["w"].cuda()
     x0, r0 = d["x"].cuda(), d["r"].cuda()
@@ -314,7 +314,7 @@ def run_other_op(a, torch, lib, B, W):
         nbytes = B.silumul_algorithmic_bytes(wl.M, wl.d, wl.dtype)
         tune, feasible, default_of, run = B.silumul_tune, B.silumul_cfg_feasible, B.silumul_default_cfg, lib.silumul_run
         x0 = W.generate_gated(wl)
-        nsets = max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // nbytes))
+        nsets = max(2, -(-4 * (LLC_BYTES + L2_TOTAL_BYTES) // nbytes))
         xs = [x0.cuda() for _ in range(nsets)]
         outs = [torch.empty((wl.M, wl.d), dtype=x0.dtype, device="cuda") for _ in range(nsets)]
         dt = B.DTYPE_IDS[wl.dtype]
@@ -328,7 +328,7 @@ def run_other_op(a, torch, lib, B, W):
         tune, feasible, default_of, run = (B.mergestates_tune, B.mergestates_cfg_feasible, B.mergestates_default_cfg,
                                            lib.mergestates_run)
         t0 = W.generate_merge(wl)
-        nsets = max(2, -(-2 * (LLC_BYTES + L2_TOTAL_BYTES) // nbytes))
+        nsets = max(2, -(-4 * (LLC_BYTES + L2_TOTAL_BYTES) // nbytes))
         sets = [{k: v.cuda() for k, v in t0.items()} for _ in range(nsets)]
         for s_ in sets:
             s_["vo"] = torch.empty_like(s_["va"])

@@ -65,6 +65,13 @@ enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguou
        ADDRMS_FLAG_LDS_CACHE = 16,    /* rows somewhat too long for the registers: still one pass,
                                          the row cache continues in the workgroup's LDS (up to
                                          160 KB per CU, so about 73 K elements per row)          */
+       ADDRMS_FLAG_ALIGNED_SPAN = 64, /* rows that are not whole cache lines (N = 1000): a workgroup
+                                         owns rows_per_wg rows that together ARE whole lines and walks
+                                         them as one flat span of 16-byte pieces, so that every
+                                         wave-wide access is aligned and every line is written whole
+                                         by one instruction; row sums come from a segmented reduction
+                                         in LDS.  threads_per_row x rows_per_wg threads share the span;
+                                         vec x residual element size must be 16 bytes                */
        ADDRMS_FLAG_DEFER_STORE = 32 };/* the residual is written after the row reduction, the whole
                                          row at once and then the whole y row, instead of chunk by
                                          chunk while the row is still being read: a workgroup reads

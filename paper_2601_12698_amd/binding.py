@@ -28,6 +28,7 @@ FLAG_PERSISTENT = 4
 FLAG_TWO_PASS = 8
 FLAG_LDS_CACHE = 16
 FLAG_DEFER_STORE = 32
+FLAG_ALIGNED_SPAN = 64
 SEARCH_GUIDED, SEARCH_EXHAUSTIVE = 0, 1
 FAMILY_STREAMING, FAMILY_OCCUPANCY_CAP, FAMILY_GRID_MAPPING, FAMILY_BASE_ONLY, FAMILY_STORE_PHASE = 1, 2, 4, 8, 16
 MAX_ROUNDS = 5

@@ -270,8 +270,15 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
         return infeasible("grid", "reduce=%d: %s has no reduction; the knob must stay 0", c.reduce, op_name(op));
     if (!in_set(c.unroll, kUnrolls, 4)) return infeasible("grid", "unroll=%d: must be 1, 2, 4 or 8", c.unroll);
     if (c.flags & ~(ADDRMS_FLAG_XCD_CONTIG | ADDRMS_FLAG_NONTEMPORAL | ADDRMS_FLAG_PERSISTENT | ADDRMS_FLAG_TWO_PASS |
-                    ADDRMS_FLAG_LDS_CACHE | ADDRMS_FLAG_DEFER_STORE))
+                    ADDRMS_FLAG_LDS_CACHE | ADDRMS_FLAG_DEFER_STORE | ADDRMS_FLAG_ALIGNED_SPAN))
         return infeasible("grid", "flags=0x%x: unknown bits set", c.flags);
+    const bool span = (c.flags & ADDRMS_FLAG_ALIGNED_SPAN) != 0;
+    if (span && op != OP_ADDRMS)
+        return infeasible("grid", "flags=0x%x: only add+RMSNorm has the aligned-span form", c.flags);
+    if (span && (c.flags & (ADDRMS_FLAG_TWO_PASS | ADDRMS_FLAG_LDS_CACHE | ADDRMS_FLAG_PERSISTENT)))
+        return infeasible("grid", "flags=0x%x: the aligned-span form is a register-cached single pass over an ordinary grid", c.flags);
+    if (span && c.reduce != ADDRMS_REDUCE_WAVE)
+        return infeasible("grid", "reduce=%d: the aligned-span form has its own segmented reduction; the knob must stay 0", c.reduce);
     const bool two_pass = (c.flags & ADDRMS_FLAG_TWO_PASS) != 0;
     const bool lds_cache = (c.flags & ADDRMS_FLAG_LDS_CACHE) != 0;
     const bool defer = (c.flags & ADDRMS_FLAG_DEFER_STORE) != 0;
@@ -303,7 +310,20 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     if (c.vec * xb > L.max_access_bytes)
         return infeasible("access_width", "vec=%d x %d-byte elements is %d bytes per lane: wider than the %d-byte global access",
                           c.vec, xb, c.vec * xb, L.max_access_bytes);
-    (void)rb;   // the residual stream may take two accesses (fp32 residual at vec=8)
+    // (the residual stream may take two accesses: fp32 residual at vec=8; not so in the aligned-span form)
+    if (span) {
+        if (c.vec * rb != L.max_access_bytes)
+            return infeasible("span_piece", "vec=%d x %d-byte residual elements is %d bytes: the aligned-span form moves the residual "
+                              "in %d-byte pieces, one access per lane", c.vec, rb, c.vec * rb, L.max_access_bytes);
+        const int64_t xspan = static_cast<int64_t>(c.rows_per_wg) * N * xb, rspan = static_cast<int64_t>(c.rows_per_wg) * N * rb;
+        if (xspan % kLineBytes != 0 || rspan % kLineBytes != 0)
+            return infeasible("span_alignment", "%d rows of N=%lld are %lld and %lld bytes: not whole %d-byte cache lines, so "
+                              "consecutive workgroups would still share lines", c.rows_per_wg, (long long)N, (long long)xspan,
+                              (long long)rspan, kLineBytes);
+        if ((N * xb) % kLineBytes == 0 && (N * rb) % kLineBytes == 0)
+            return infeasible("span_needless", "rows of N=%lld are whole cache lines already (%lld and %lld bytes): the ordinary "
+                              "form is aligned and needs no segmented reduction", (long long)N, (long long)(N * xb), (long long)(N * rb));
+    }
 
     // -- launch validity
     const int threads = c.threads_per_row * c.rows_per_wg;
@@ -350,6 +370,8 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                           "holds %d (more would spill or leave under %d waves per SIMD)",
                           (long long)N, c.threads_per_row, c.vec, (long long)(need * c.vec), kMaxElemsPerThread,
                           kMinWavesPerSimd);
+    if (span && need != 1 && need != 2 && need != 4)
+        return infeasible("no_instance", "chunks per thread = %lld: the aligned-span form exists for 1, 2 and 4", (long long)need);
     if (!two_pass && !lds_cache && !cpt_supported(op, static_cast<int>(need)))
         return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (%s)", (long long)need,
                           op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : op == OP_MERGE ? "1-4 exist" : "1-8 exist");
@@ -372,7 +394,8 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                           2 * L.xcds);
 
     // -- compiled instance and its resources
-    const int cpt_code = two_pass ? 0 : lds_cache ? kLdsCacheCptBase + kLdsCacheRegElems / c.vec : static_cast<int>(need);
+    const int cpt_code = two_pass ? 0 : lds_cache ? kLdsCacheCptBase + kLdsCacheRegElems / c.vec
+                         : span ? kSpanCptBase + static_cast<int>(need) : static_cast<int>(need);
     const int idx = find_instance(op, dtype, c.vec, cpt_code, c.unroll, (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0, defer ? 1 : 0);
     if (idx < 0)
         return infeasible("no_instance", "no compiled instance for dtype=%s vec=%d chunks=%lld unroll=%d", dtype_name(dtype), c.vec,
@@ -384,6 +407,8 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     o.vgprs = r.vgprs; o.agprs = r.agprs; o.sgprs = r.sgprs; o.scratch_bytes = r.scratch;
     o.max_threads = in.maxt;
     o.lds_bytes = reduction_lds_bytes(c, op) + static_cast<int>(lds_cache_bytes) + r.lds_static;
+    if (span)   // one fp64 sum per piece slot, then one fp32 rstd per row (rounded up to whole doubles)
+        o.lds_bytes = threads * static_cast<int>(need) * 8 + round_up(c.rows_per_wg * 4, 8) + r.lds_static;
     o.waves_per_wg = threads / L.wave_size;
     if (r.scratch > 0 && (relax & RELAX_SCRATCH)) {
         if (!f.soft_rule[0]) f.soft_rule = "scratch";
@@ -449,7 +474,7 @@ void enumerate(int64_t M, int64_t N, int dtype, std::vector<addrms_cfg>* out, in
             for (int rows : kRows)
                 for (int red = 0; red < 2; ++red)
                     for (int unr : kUnrolls)
-                        for (int flags = 0; flags < 64; ++flags)
+                        for (int flags = 0; flags < 128; ++flags)
                             for (int cap = 0; cap < hw().max_waves_per_simd; ++cap) {
                                 // A longer grid (walk) exists for persistent cfgs only, and whatever rejects the
                                 // resident-size grid rejects the longer ones as well (a grid that already covers

@@ -39,6 +39,8 @@ constexpr int kMinWavesPerSimd = 2;
 constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
 constexpr int kLdsCacheRegElems = 32;     // LDS-extended form: values per thread kept in registers (1024-thread bound)
 constexpr int kLdsCacheCptBase = 100;    // its instances carry cpt = 100 + register-held chunks
+constexpr int kSpanCptBase = 200;        // aligned-span form: cpt = 200 + chunks per thread
+constexpr int kLineBytes = 128;          // cache line of the L2 / memory side
 constexpr int64_t kMaxTwoPassElemsPerWg = 1ll << 28;   // two-pass form: rows_per_wg * N elements, 32-bit byte offsets
 
 // ---- operators that go through the tuner ------------------------------------

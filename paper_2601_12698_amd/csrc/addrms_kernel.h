@@ -41,7 +41,7 @@ namespace addrms {
 enum : int { DT_BF16 = 0, DT_FP16 = 1, DT_FP16_RES32 = 2, DT_FP32 = 3 };
 enum : int { RED_WAVE = 0, RED_LDS = 1 };
 enum : uint32_t { FLAG_XCD_CONTIG = 1u, FLAG_NONTEMPORAL = 2u, FLAG_PERSISTENT = 4u, FLAG_TWO_PASS = 8u,
-                  FLAG_LDS_CACHE = 16u, FLAG_DEFER_STORE = 32u };
+                  FLAG_LDS_CACHE = 16u, FLAG_DEFER_STORE = 32u, FLAG_ALIGNED_SPAN = 64u };
 
 template <int DT> struct dt_traits;
 template <> struct dt_traits<DT_BF16>       { static constexpr int XB = 2, RB = 2; static constexpr bool BF = true;  };
@@ -695,6 +695,137 @@ __device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void
                     st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), out);
                 }
             }
+        }
+    }
+}
+
+// Aligned-span form, for rows whose byte length is not a whole number of cache lines (N = 1000:
+// 2000 and 4000 bytes).  In the forms above a wave's access starts wherever its row starts, so
+// every access straddles lines that a neighbouring wave - often of another workgroup - also
+// touches, and partly written lines have to be merged on the way to memory.  Here a workgroup
+// owns blockDim.y consecutive rows whose combined length IS a whole number of lines (the host
+// checks that), treats them as one flat span of 16-byte pieces (VEC elements; a piece never
+// straddles two rows because VEC divides N) and maps piece p = c * T + t to thread t: every
+// wave-wide access is one aligned, contiguous kilobyte (half of that for the 16-bit stream of
+// the mixed format) and every line is written whole by one instruction.  The price is a
+// segmented reduction, since row boundaries fall inside waves: each piece's sum of squares
+// goes to LDS, one wave per row adds that row's pieces (strided, then the cross-lane
+// butterfly), and the row's rstd is left in LDS for every piece of the row.
+// LDS: T * CPT doubles (piece sums), then blockDim.y floats (rstd per row).
+template <int DT, int VEC, int CPT, int UNR, bool NT, bool DEFER>
+__device__ __forceinline__ void addrms_span_body(void* __restrict__ xp, void* __restrict__ rp,
+                                                 const void* __restrict__ wp, float eps, double inv_n,
+                                                 int64_t M, int32_t N, uint32_t flags, int32_t reduce,
+                                                 uint32_t nblocks)
+{
+    using T_ = dt_traits<DT>;
+    constexpr int XB = T_::XB, RB = T_::RB;
+    constexpr bool BF = T_::BF;
+    static_assert(VEC * XB <= 16 && VEC * RB <= 16, "one access per stream and piece");
+    extern __shared__ double lds[];
+    (void)reduce; (void)nblocks;
+
+    const uint32_t T = blockDim.x * blockDim.y, R = blockDim.y;
+    const uint32_t t = threadIdx.y * blockDim.x + threadIdx.x;
+    uint32_t blk = blockIdx.x;
+    if (flags & FLAG_XCD_CONTIG) blk = xcd_contiguous(blk, gridDim.x);
+    const int64_t row0 = static_cast<int64_t>(blk) * R;
+    const int64_t left = M - row0;
+    const uint32_t rows_here = left < static_cast<int64_t>(R) ? static_cast<uint32_t>(left) : R;
+    const uint32_t P = static_cast<uint32_t>(N) / VEC;            // pieces per row
+    const uint32_t S = rows_here * P;                             // pieces of this span
+    char* xspan = static_cast<char*>(xp) + row0 * N * XB;
+    char* rspan = static_cast<char*>(rp) + row0 * N * RB;
+    const char* wbase = static_cast<const char*>(wp);
+    double* part = lds;
+    float* rstd_s = reinterpret_cast<float*>(lds + static_cast<size_t>(T) * CPT);
+
+    float h[CPT][VEC];
+#pragma unroll
+    for (int g = 0; g < CPT; g += UNR) {
+        raw_t<XB * VEC> xv[UNR];
+        raw_t<RB * VEC> rv[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (g + u < CPT) {
+                const uint32_t p = static_cast<uint32_t>(g + u) * T + t;
+                const uint32_t pc = p < S ? p : S - 1u;           // idle threads re-read the last piece
+                ld_raw<XB * VEC, NT>(xspan + static_cast<uint64_t>(pc * (VEC * XB)), xv[u]);
+                ld_raw<RB * VEC, NT>(rspan + static_cast<uint64_t>(pc * (VEC * RB)), rv[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (g + u < CPT) {
+                const int c = g + u;
+                const uint32_t p = static_cast<uint32_t>(c) * T + t;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    h[c][e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                if (p < S) {
+                    if constexpr (!DEFER) {
+                        raw_t<RB * VEC> out;
+                        pack_vec<RB, BF, VEC>(h[c], out);
+                        st_raw<RB * VEC, NT>(rspan + static_cast<uint64_t>(p * (VEC * RB)), out);
+                    }
+                    double acc = 0.0;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const double hd = static_cast<double>(h[c][e]);
+                        acc = __builtin_fma(hd, hd, acc);
+                    }
+                    part[p] = acc;
+                }
+            }
+        }
+        if (g + UNR < CPT) __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    {
+        const uint32_t wv = t >> 6, l = t & 63u, nw = T >> 6;
+        for (uint32_t k = wv; k < rows_here; k += nw) {           // uniform over the wave
+            double s = 0.0;
+            for (uint32_t j = l; j < P; j += 64u) s += part[k * P + j];
+            s = wave_group_sum(s, 64u);
+            if (l == 0u) rstd_s[k] = rsqrt_to_f32(__builtin_fma(s, inv_n, static_cast<double>(eps)));
+        }
+    }
+    __syncthreads();
+
+    uint32_t prow[CPT];
+    raw_t<XB * VEC> wv_[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const uint32_t p = static_cast<uint32_t>(c) * T + t;
+        const uint32_t pc = p < S ? p : S - 1u;
+        prow[c] = pc / P;
+        ld_raw<XB * VEC>(wbase + static_cast<uint64_t>((pc - prow[c] * P) * (VEC * XB)), wv_[c]);
+    }
+    if constexpr (DEFER) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const uint32_t p = static_cast<uint32_t>(c) * T + t;
+            if (p < S) {
+                raw_t<RB * VEC> out;
+                pack_vec<RB, BF, VEC>(h[c], out);
+                st_raw<RB * VEC, NT>(rspan + static_cast<uint64_t>(p * (VEC * RB)), out);
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const uint32_t p = static_cast<uint32_t>(c) * T + t;
+        const float rstd = rstd_s[prow[c]];
+        float y[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float tt = h[c][e] * rstd;
+            y[e] = tt * get_elem<XB, BF>(wv_[c], e);
+        }
+        if (p < S) {
+            raw_t<XB * VEC> out;
+            pack_vec<XB, BF, VEC>(y, out);
+            st_raw<XB * VEC, NT>(xspan + static_cast<uint64_t>(p * (VEC * XB)), out);
         }
     }
 }

@@ -38,7 +38,8 @@ namespace {
 
 using Clock = std::chrono::steady_clock;
 constexpr double kShortKernelUs = 10.0;
-constexpr int kFormBits = ADDRMS_FLAG_TWO_PASS | ADDRMS_FLAG_LDS_CACHE;
+constexpr int kFormBits = ADDRMS_FLAG_TWO_PASS | ADDRMS_FLAG_LDS_CACHE | ADDRMS_FLAG_ALIGNED_SPAN;
+constexpr int kLongRowBits = ADDRMS_FLAG_TWO_PASS | ADDRMS_FLAG_LDS_CACHE;
 
 struct Cand {
     addrms_cfg cfg{};
@@ -210,7 +211,8 @@ struct Searcher {
             { addrms_cfg n = c; n.walk = c.walk == 0 ? 4 : c.walk * 4; push(n); }
             if (c.walk != 0) { addrms_cfg n = c; n.walk = c.walk == 4 ? 0 : c.walk / 4; push(n); }
         }
-        if (c.flags & kFormBits) { addrms_cfg n = c; n.flags ^= kFormBits; push(n); }   // the other long-row form
+        if (c.flags & kLongRowBits) { addrms_cfg n = c; n.flags ^= kLongRowBits; push(n); }   // the other long-row form
+        else { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_ALIGNED_SPAN; n.reduce = 0; push(n); }   // into or out of the aligned-span form
         // occupancy cap: one step tighter, one step looser (0 = uncapped sits above the natural occupancy)
         {
             const int natural = cands[i].res.waves_per_simd;

@@ -33,6 +33,9 @@ X_BYTES = {0: 2, 1: 2, 2: 2, 3: 4}      # bytes per x element of each format
 MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 values per thread
 BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
 LDS_CACHE_BASE = 100                    # cpt code of the LDS-extended form: 100 + register-held chunks
+SPAN_BASE = 200                         # cpt code of the aligned-span form: 200 + chunks per thread
+SPAN_CPTS = (1, 2, 4)
+R_BYTES = {0: 2, 1: 2, 2: 4, 3: 4}      # bytes per residual element of each format
 
 
 OP_ADDRMS, OP_SILUMUL, OP_MERGE = 0, 1, 2
@@ -65,6 +68,14 @@ def instances():
                     for unr in UNRS:
                         for nt in (0, 1):
                             yield op, dt, vec, 0, unr, nt, 0, 1024
+                    if vec * X_BYTES[dt] <= 16 and vec * R_BYTES[dt] == 16:   # aligned-span form: 16-byte residual pieces
+                        for cpt in SPAN_CPTS:
+                            for unr in UNRS:
+                                if unr > cpt:
+                                    continue
+                                for nt in (0, 1):
+                                    for df in (0, 1):
+                                        yield op, dt, vec, SPAN_BASE + cpt, unr, nt, df, 1024
                     reg_cpt = BIG_ELEMS // vec       # LDS-extended cache: registers filled to the 1024-thread bound
                     for unr in UNRS:
                         if unr > reg_cpt:
@@ -93,6 +104,8 @@ CALL = {
 TWO_PASS_CALL = "addrms::addrms_twopass_body<{dt}, {vec}, {unr}, {nt}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);"
 LDS_CACHE_CALL = ("addrms::addrms_ldscache_body<{dt}, {vec}, {cpt}, {unr}, {nt}>"
                   "(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);")
+SPAN_CALL = ("addrms::addrms_span_body<{dt}, {vec}, {cpt}, {unr}, {nt}, {df}>"
+             "(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);")
 HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h", OP_MERGE: "mergestates_kernel.h"}
 
 
@@ -107,6 +120,8 @@ def main(outdir: str) -> None:
             fmt = CALL[op]
             if op == OP_ADDRMS and cpt == 0:
                 fmt = TWO_PASS_CALL
+            elif op == OP_ADDRMS and cpt >= SPAN_BASE:
+                fmt = SPAN_CALL
             elif op == OP_ADDRMS and cpt >= LDS_CACHE_BASE:
                 fmt = LDS_CACHE_CALL
             call = fmt.format(dt=dt, vec=vec, cpt=cpt % LDS_CACHE_BASE, unr=unr, nt="true" if nt else "false",

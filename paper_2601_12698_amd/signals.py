@@ -203,6 +203,8 @@ def collect_probe(M: int, N: int, dtype: str, counters: Sequence[str] = ("FETCH_
 
 
 TRAFFIC_WORKLOADS = ("large_prefill", "prefill", "odd_width_5120", "odd_width_2880", "odd_width_1000")
+# further cfgs measured beside the tuned and the default one: the aligned-span form on the shape it was built for
+TRAFFIC_EXTRA = {"odd_width_1000": (("aligned_span", (4, 128, 8, 0, 2, 98, 0, 0)),)}
 
 
 def traffic_report(path: str, names: Sequence[str] = TRAFFIC_WORKLOADS) -> List[dict]:
@@ -217,6 +219,8 @@ def traffic_report(path: str, names: Sequence[str] = TRAFFIC_WORKLOADS) -> List[
               else W.ODD_WIDTH.with_cols(int(name[10:])))
         r0 = _run_stage(["--stage-tune", str(wl.M), str(wl.N), wl.dtype, "--eps", repr(wl.eps), "--top-k", "1", "--hints", "0"])
         cfgs = [B.make_cfg(**r0["cfg"]), B.make_cfg(**r0["default_cfg"])]
+        extra = TRAFFIC_EXTRA.get(name, ())
+        cfgs += [B.make_cfg(*t) for _label, t in extra]
         recs = collect(cfgs, wl.M, wl.N, wl.dtype, wl.eps, passes=(("FETCH_SIZE",), ("WRITE_SIZE",)))
         # The plain copy kernel always runs in its symmetric 16-bit form (one aligned 16-byte piece of each stream per
         # lane, whole cache lines per wave): with an fp32 residual beside 16-bit x its two pieces per lane leave the
@@ -226,7 +230,9 @@ def traffic_report(path: str, names: Sequence[str] = TRAFFIC_WORKLOADS) -> List[
         fetch_unit = stream_bytes / probe["FETCH_SIZE"]
         write_unit = stream_bytes / probe["WRITE_SIZE"]
         alg = W.algorithmic_bytes(wl.M, wl.N, wl.dtype)
-        for which, cfg, rec, us in (("tuned", cfgs[0], recs[0], r0["us"]), ("default", cfgs[1], recs[1], r0["default_us"])):
+        measured = [("tuned", cfgs[0], recs[0], r0["us"]), ("default", cfgs[1], recs[1], r0["default_us"])]
+        measured += [(label, cfgs[2 + i], recs[2 + i], float("nan")) for i, (label, _t) in enumerate(extra)]
+        for which, cfg, rec, us in measured:
             rd = rec["counters"]["FETCH_SIZE"] * fetch_unit
             wr = rec["counters"]["WRITE_SIZE"] * write_unit
             row = {"workload": wl.name, "which": which, "cfg": cfg.as_tuple(), "read_bytes": rd, "write_bytes": wr,

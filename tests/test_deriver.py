@@ -28,7 +28,13 @@ KNOWN_INFEASIBLE = [
     (B.make_cfg(8, 256, 3), 4096, 4096, "bf16", "rows_per_wg"),
     (B.make_cfg(8, 256, 1, reduce=2), 4096, 4096, "bf16", "reduce"),
     (B.make_cfg(8, 256, 1, unroll=3), 4096, 4096, "bf16", "unroll"),
-    (B.make_cfg(8, 256, 1, flags=64), 4096, 4096, "bf16", "flags"),
+    (B.make_cfg(8, 256, 1, flags=128), 4096, 4096, "bf16", "flags"),
+    (B.make_cfg(4, 128, 4, unroll=2, flags=64), 8192, 1000, "fp16_res32", "not whole 128-byte cache lines"),
+    (B.make_cfg(4, 256, 4, flags=64), 8192, 1024, "fp16_res32", "whole cache lines already"),
+    (B.make_cfg(8, 128, 8, flags=64), 8192, 1000, "fp16_res32", "16-byte pieces"),
+    (B.make_cfg(4, 128, 8, reduce=1, unroll=2, flags=64), 8192, 1000, "fp16_res32", "its own segmented reduction"),
+    (B.make_cfg(4, 128, 8, unroll=2, flags=64 | 4), 65536, 1000, "fp16_res32", "ordinary grid"),
+    (B.make_cfg(4, 32, 16, unroll=2, flags=64), 8192, 1000, "fp16_res32", "exists for 1, 2 and 4"),
     (B.make_cfg(8, 256, 1, unroll=2, flags=8 | 32), 4096, 65536, "bf16", "deferred residual store exists for the register-cached form only"),
     (B.make_cfg(8, 1024, 1, unroll=2, flags=16 | 32), 4096, 40960, "bf16", "deferred residual store exists for the register-cached form only"),
     (B.make_cfg(8, 256, 1, unroll=2, walk=4), 32768, 4096, "bf16", "walk=4 sizes a persistent grid"),
@@ -72,9 +78,9 @@ def test_bad_shape_and_dtype_codes():
                                        (8192, 1000, "fp16_res32"), (8192, 2880, "fp16_res32"), (128, 11008, "fp32")])
 def test_enumeration_is_exactly_the_feasible_subset(M, N, dtype):
     cfgs, grid = B.addrms_enumerate_feasible(M, N, dtype)
-    # vec, threads/row, rows/wg, reduce, unroll, cap; 6 flag bits, and for the half of them with a persistent grid
+    # vec, threads/row, rows/wg, reduce, unroll, cap; 7 flag bits, and for the half of them with a persistent grid
     # two more walk lengths
-    assert grid == (4 * 19 * 5 * 2 * 4 * 8) * (64 + 32 * 2)
+    assert grid == (4 * 19 * 5 * 2 * 4 * 8) * (128 + 64 * 2)
     assert not any(c.flags & (B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE) for c in cfgs)   # these rows fit the register cache
     assert 0 < len(cfgs) < grid
     seen = set()
@@ -259,3 +265,21 @@ def test_deferred_store_and_walk_are_part_of_the_region():
     assert sum(1 for c in small if c.walk == 16) < sum(1 for c in small if c.walk == 4) < sum(1 for c in small if c.flags & B.FLAG_PERSISTENT and c.walk == 0)
     # the two further operators have no residual stream and therefore no such flag
     assert B.silumul_cfg_feasible(B.make_cfg(8, 704, 1, flags=B.FLAG_DEFER_STORE), 4096, 11008, "bf16")[0] == B.ERR_INFEASIBLE_CFG
+
+
+def test_aligned_span_form_is_offered_only_where_rows_are_not_whole_lines():
+    """N = 1000: rows of 2000 and 4000 bytes; eight of them are whole 128-byte lines.  The span cfgs are
+    those whose rows_per_wg makes the span line-aligned, with 16-byte residual pieces."""
+    for dt, vec in (("fp16_res32", 4), ("bf16", 8), ("fp32", 4)):
+        cfgs, _ = B.addrms_enumerate_feasible(8192, 1000, dt)
+        span = [c for c in cfgs if c.flags & B.FLAG_ALIGNED_SPAN]
+        assert span and all(c.vec == vec and c.reduce == 0 and not c.flags & B.FLAG_PERSISTENT for c in span)
+        xb = 4 if dt == "fp32" else 2
+        assert all((c.rows_per_wg * 1000 * xb) % 128 == 0 for c in span)
+        assert {c.flags & B.FLAG_DEFER_STORE for c in span} == {0, B.FLAG_DEFER_STORE}
+    for n in (4096, 7168, 5120, 2880, 1024):                 # whole lines already: nothing to offer
+        cfgs, _ = B.addrms_enumerate_feasible(8192, n, "fp16_res32")
+        assert not any(c.flags & B.FLAG_ALIGNED_SPAN for c in cfgs)
+    c = B.make_cfg(4, 128, 8, unroll=2, flags=B.FLAG_ALIGNED_SPAN | B.FLAG_NONTEMPORAL)
+    st, _, res = feas(c, 8192, 1000, "fp16_res32")
+    assert st == 0 and res.chunks_per_thread == 2 and res.lds_bytes == 1024 * 2 * 8 + 32

@@ -34,7 +34,7 @@ def test_default_and_feasibility_rules():
 
 def test_enumeration_has_no_reduction_variants():
     cfgs, grid = B.silumul_enumerate_feasible(4096, 11008, "bf16")
-    assert grid == (4 * 19 * 5 * 2 * 4 * 8) * (64 + 32 * 2) and len(cfgs) > 500
+    assert grid == (4 * 19 * 5 * 2 * 4 * 8) * (128 + 64 * 2) and len(cfgs) > 500
     assert all(c.reduce == 0 for c in cfgs)
     for c in cfgs[::37]:
         assert B.silumul_cfg_feasible(c, 4096, 11008, "bf16")[0] == 0
