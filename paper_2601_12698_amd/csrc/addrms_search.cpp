@@ -37,7 +37,8 @@ namespace addrms_host {
 namespace {
 
 using Clock = std::chrono::steady_clock;
-constexpr double kShortKernelUs = 10.0;
+constexpr double kShortKernelUs = 100.0;
+constexpr double kScreenTargetUs = 2000.0;
 constexpr int kFormBits = ADDRMS_FLAG_TWO_PASS | ADDRMS_FLAG_LDS_CACHE | ADDRMS_FLAG_ALIGNED_SPAN;
 constexpr int kLongRowBits = ADDRMS_FLAG_TWO_PASS | ADDRMS_FLAG_LDS_CACHE;
 
@@ -125,11 +126,12 @@ struct Searcher {
             log_eval(phase, c, false, -1.0, warmup, reps);
             return false;
         }
-        // Launch-bound shapes (a few microseconds per launch) time noisily with a short protocol
-        // and cost next to nothing to time longer: repeat with eight times the repetitions.
+        // Short kernels time noisily with a short protocol and cost next to nothing to time longer: repeat the
+        // screening with as many repetitions as fill about two milliseconds (at most eight times as many).
         if (us < kShortKernelUs && reps <= b.coarse_reps) {
+            const int more = std::min(reps * 8, std::max(reps, static_cast<int>(kScreenTargetUs / us)));
             double again = 0.0;
-            if (be.measure(be.user, &c.cfg, warmup, reps * 8, &again) == 0 && again > 0.0) us = again;
+            if (more > reps && be.measure(be.user, &c.cfg, warmup, more, &again) == 0 && again > 0.0) us = again;
         }
         ++n_measured;
         c.us = us;
