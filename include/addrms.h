@@ -64,7 +64,10 @@ enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguou
                                          where no single-pass configuration covers N            */
        ADDRMS_FLAG_LDS_CACHE = 16,    /* rows somewhat too long for the registers: still one pass,
                                          the row cache continues in the workgroup's LDS (up to
-                                         160 KB per CU, so about 73 K elements per row)          */
+                                         160 KB per CU, so about 73 K elements per row).  Together
+                                         with ADDRMS_FLAG_TWO_PASS: the hybrid form for rows beyond
+                                         that -- registers and LDS hold what they can, and only the
+                                         rest of each row is read twice                           */
        ADDRMS_FLAG_ALIGNED_SPAN = 64, /* rows that are not whole cache lines (N = 1000): a workgroup
                                          owns rows_per_wg rows that together ARE whole lines and walks
                                          them as one flat span of 16-byte pieces, so that every

@@ -63,9 +63,9 @@ const char* op_name(int op)
 
 static uint32_t inst_key(int op, int dt, int vec, int cpt, int unr, int nt, int df)
 {
-    return (static_cast<uint32_t>(op) << 28) | (static_cast<uint32_t>(dt) << 24) | (static_cast<uint32_t>(vec) << 16) |
+    return (static_cast<uint32_t>(op) << 28) | (static_cast<uint32_t>(dt) << 25) | (static_cast<uint32_t>(vec) << 20) |
            (static_cast<uint32_t>(cpt) << 8) | (static_cast<uint32_t>(unr) << 2) | (static_cast<uint32_t>(df) << 1) |
-           static_cast<uint32_t>(nt);
+           static_cast<uint32_t>(nt);      // cpt codes reach 300 + 32: twelve bits
 }
 
 int find_instance(int op, int dt, int vec, int cpt, int unr, int nt, int df)
@@ -279,12 +279,14 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
         return infeasible("grid", "flags=0x%x: the aligned-span form is a register-cached single pass over an ordinary grid", c.flags);
     if (span && c.reduce != ADDRMS_REDUCE_WAVE)
         return infeasible("grid", "reduce=%d: the aligned-span form has its own segmented reduction; the knob must stay 0", c.reduce);
-    const bool two_pass = (c.flags & ADDRMS_FLAG_TWO_PASS) != 0;
-    const bool lds_cache = (c.flags & ADDRMS_FLAG_LDS_CACHE) != 0;
+    // both long-row flags together name the hybrid form: what fits stays on the chip, the rest is read twice
+    const bool hybrid = (c.flags & ADDRMS_FLAG_TWO_PASS) && (c.flags & ADDRMS_FLAG_LDS_CACHE);
+    const bool two_pass = (c.flags & ADDRMS_FLAG_TWO_PASS) != 0 && !hybrid;
+    const bool lds_cache = (c.flags & ADDRMS_FLAG_LDS_CACHE) != 0 && !hybrid;
     const bool defer = (c.flags & ADDRMS_FLAG_DEFER_STORE) != 0;
     if (defer && op != OP_ADDRMS)
         return infeasible("grid", "flags=0x%x: %s has no residual stream whose store could be deferred", c.flags, op_name(op));
-    if (defer && (two_pass || lds_cache))
+    if (defer && (two_pass || lds_cache || hybrid))
         return infeasible("grid", "flags=0x%x: the deferred residual store exists for the register-cached form only (the "
                           "two-pass form writes everything in its second pass anyway)", c.flags);
     if (c.walk != 0 && c.walk != 4 && c.walk != 16)
@@ -292,11 +294,9 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     if (c.walk != 0 && !(c.flags & ADDRMS_FLAG_PERSISTENT))
         return infeasible("grid", "walk=%d sizes a persistent grid; without ADDRMS_FLAG_PERSISTENT there is one workgroup per "
                           "row block and nothing to size", c.walk);
-    if ((two_pass || lds_cache) && op != OP_ADDRMS)
+    if ((two_pass || lds_cache || hybrid) && op != OP_ADDRMS)
         return infeasible("grid", "flags=0x%x: only add+RMSNorm has forms for long rows", c.flags);
-    if (two_pass && lds_cache)
-        return infeasible("grid", "flags=0x%x: the two-pass form and the LDS-extended cache exclude each other", c.flags);
-    if ((two_pass || lds_cache) && (c.flags & ADDRMS_FLAG_PERSISTENT))
+    if ((two_pass || lds_cache || hybrid) && (c.flags & ADDRMS_FLAG_PERSISTENT))
         return infeasible("grid", "flags=0x%x: the long-row forms have no persistent grid", c.flags);
     if (c.max_waves_per_simd < 0 || c.max_waves_per_simd >= L.max_waves_per_simd)
         return infeasible("grid", "max_waves_per_simd=%d: must be 0 (no cap) or 1..%d", c.max_waves_per_simd,
@@ -350,12 +350,19 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
         }
     } else if (lds_cache) {
         const int64_t reg_chunks = kLdsCacheRegElems / c.vec;
-        // (a chunk count that fits the registers but has no plain instance - 17 to 32 one-element chunks, say -
-        // runs here with nothing parked: the register part of this form clamps its unused chunks)
-        if (need <= reg_chunks && cpt_supported(op, static_cast<int>(need)))
+        // Needless where the plain form takes the same launch shape: it has an instance for this chunk count and that
+        // instance admits this workgroup size (32 cached values up to 1024 threads, 64 up to 256).  A chunk count that
+        // fits this form's 48 register values but not a plain instance - 17 to 32 one-element chunks, or 33 to 48
+        // values in a workgroup of more than 256 threads - runs here with nothing parked: the register part clamps
+        // its unused chunks.
+        const bool plain_takes_it = cpt_supported(op, static_cast<int>(need)) && need * c.vec <= kMaxElemsPerThread &&
+                                    (need * c.vec <= kMaxElemsPerThread / 2 || c.threads_per_row * c.rows_per_wg <= 256);
+        if (need <= reg_chunks && plain_takes_it)
             return infeasible("lds_cache_needless", "N=%lld over %d threads at vec=%d is %lld chunks per thread: they fit the "
-                              "registers, there is nothing to park in LDS", (long long)N, c.threads_per_row, c.vec, (long long)need);
-        lds_cache_bytes = static_cast<int64_t>(c.rows_per_wg) * std::max<int64_t>(0, need - reg_chunks) * per_pass * 4;
+                              "registers of the plain form, there is nothing to park in LDS", (long long)N, c.threads_per_row,
+                              c.vec, (long long)need);
+        f.lds_chunks = static_cast<int>(std::max<int64_t>(0, need - reg_chunks));
+        lds_cache_bytes = static_cast<int64_t>(c.rows_per_wg) * f.lds_chunks * per_pass * 4;
         if (lds_cache_bytes + reduction_lds_bytes(c, op) > L.lds_bytes_per_cu)
             return infeasible("lds_cache_too_big", "parking %lld chunks per thread takes %lld bytes of LDS per workgroup; a CU has %d",
                               (long long)std::max<int64_t>(0, need - reg_chunks), (long long)lds_cache_bytes, L.lds_bytes_per_cu);
@@ -365,6 +372,28 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                                   "a detour through LDS is obviously inefficient", (long long)N);
             if (!f.soft_rule[0]) f.soft_rule = "lds_cache_needless";
         }
+    } else if (hybrid) {
+        const int64_t reg_chunks = kLdsCacheRegElems / c.vec;
+        if (N * c.rows_per_wg > kMaxTwoPassElemsPerWg)
+            return infeasible("row_too_long", "N=%lld x rows_per_wg=%d exceeds the %lld elements a workgroup addresses with "
+                              "32-bit offsets", (long long)N, c.rows_per_wg, (long long)kMaxTwoPassElemsPerWg);
+        const int64_t chunk_bytes = static_cast<int64_t>(c.rows_per_wg) * per_pass * 4;     // one parked chunk of every thread
+        const int64_t fit = (L.lds_bytes_per_cu - reduction_lds_bytes(c, op)) / chunk_bytes;
+        if (need <= reg_chunks + fit)
+            return infeasible("hybrid_needless", "N=%lld over %d threads at vec=%d is %lld chunks per thread: registers (%lld) and "
+                              "LDS (%lld) hold them all, nothing has to be read twice", (long long)N, c.threads_per_row, c.vec,
+                              (long long)need, (long long)reg_chunks, (long long)fit);
+        if (single_pass_covers(N, dtype, op)) {
+            if (!(relax & RELAX_TWO_PASS_NEEDLESS))
+                return infeasible("two_pass_needless", "N=%lld fits the register row cache of a single-pass configuration: "
+                                  "reading part of every row twice is obviously inefficient", (long long)N);
+            if (!f.soft_rule[0]) f.soft_rule = "two_pass_needless";
+        }
+        if (fit < 1)
+            return infeasible("hybrid_no_lds", "not one chunk per thread fits the LDS of a CU at this workgroup size: this is the "
+                              "two-pass form");
+        f.lds_chunks = static_cast<int>(fit);
+        lds_cache_bytes = fit * chunk_bytes;
     } else if (need * c.vec > kMaxElemsPerThread)
         return infeasible("row_cache", "N=%lld over %d threads at vec=%d needs %lld values per thread in registers; the row cache "
                           "holds %d (more would spill or leave under %d waves per SIMD)",
@@ -372,7 +401,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                           kMinWavesPerSimd);
     if (span && need != 1 && need != 2 && need != 4)
         return infeasible("no_instance", "chunks per thread = %lld: the aligned-span form exists for 1, 2 and 4", (long long)need);
-    if (!two_pass && !lds_cache && !cpt_supported(op, static_cast<int>(need)))
+    if (!two_pass && !lds_cache && !hybrid && !cpt_supported(op, static_cast<int>(need)))
         return infeasible("no_instance", "chunks per thread = %lld has no compiled instance (%s)", (long long)need,
                           op == OP_ADDRMS ? "1-8, 10, 12, 14, 16 exist" : op == OP_MERGE ? "1-4 exist" : "1-8 exist");
     f.res.chunks_per_thread = static_cast<int>(need);
@@ -394,7 +423,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                           2 * L.xcds);
 
     // -- compiled instance and its resources
-    const int cpt_code = two_pass ? 0 : lds_cache ? kLdsCacheCptBase + kLdsCacheRegElems / c.vec
+    const int cpt_code = two_pass ? 0 : (hybrid || lds_cache) ? kLdsCacheCptBase + kLdsCacheRegElems / c.vec
                          : span ? kSpanCptBase + static_cast<int>(need) : static_cast<int>(need);
     const int idx = find_instance(op, dtype, c.vec, cpt_code, c.unroll, (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0, defer ? 1 : 0);
     if (idx < 0)
@@ -532,7 +561,14 @@ int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op)
             c.reduce = ADDRMS_REDUCE_WAVE; c.unroll = 2; c.flags = ADDRMS_FLAG_LDS_CACHE;
             if (check_cfg(c, big_m, N, dtype, op).status == ADDRMS_OK) { *out = c; return ADDRMS_OK; }
         }
-    if (op == OP_ADDRMS)   // longer still: the two-pass form, widest vector, largest workgroup
+    if (op == OP_ADDRMS)   // longer still: registers and LDS hold what they can, only the rest of a row is read twice
+        for (int vec : kVecs) {
+            addrms_cfg c{};
+            c.vec = vec; c.threads_per_row = hw().max_threads_per_wg; c.rows_per_wg = 1;
+            c.reduce = ADDRMS_REDUCE_WAVE; c.unroll = 2; c.flags = ADDRMS_FLAG_LDS_CACHE | ADDRMS_FLAG_TWO_PASS;
+            if (check_cfg(c, big_m, N, dtype, op).status == ADDRMS_OK) { *out = c; return ADDRMS_OK; }
+        }
+    if (op == OP_ADDRMS)   // (kept for completeness: the plain two-pass form, widest vector, largest workgroup)
         for (int vec : kVecs) {
             addrms_cfg c{};
             c.vec = vec; c.threads_per_row = hw().max_threads_per_wg; c.rows_per_wg = 1;

@@ -37,9 +37,10 @@ const HwLimits& hw();
 // Floors below which a launch shape is pruned as obviously inefficient.
 constexpr int kMinWavesPerSimd = 2;
 constexpr int kMaxElemsPerThread = 64;   // register row cache, fp32 values per thread
-constexpr int kLdsCacheRegElems = 32;     // LDS-extended form: values per thread kept in registers (1024-thread bound)
-constexpr int kLdsCacheCptBase = 100;    // its instances carry cpt = 100 + register-held chunks
 constexpr int kSpanCptBase = 200;        // aligned-span form: cpt = 200 + chunks per thread
+constexpr int kLdsCacheCptBase = 300;    // forms with the row cache continued in LDS: cpt = 300 + register-held chunks
+constexpr int kLdsCacheRegElems = 48;    // their values per thread kept in registers (a 1024-thread workgroup leaves each lane
+                                         // 128 registers; 64 cached values spill)
 constexpr int kLineBytes = 128;          // cache line of the L2 / memory side
 constexpr int64_t kMaxTwoPassElemsPerWg = 1ll << 28;   // two-pass form: rows_per_wg * N elements, 32-bit byte offsets
 
@@ -81,6 +82,7 @@ struct Feas {
     std::string reason;
     int inst = -1;              // instance index when one was selected
     int dyn_lds = 0;            // dynamic LDS bytes of the launch (reduction scratch, row cache, occupancy padding)
+    int lds_chunks = -1;        // forms with the cache continued in LDS: chunks per thread parked there (-1: another form)
     addrms_resources res{};
 };
 Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op = OP_ADDRMS, int relax = 0);

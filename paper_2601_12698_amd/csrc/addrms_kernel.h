@@ -537,24 +537,25 @@ __device__ __forceinline__ void addrms_twopass_body(void* __restrict__ xp, void*
     }
 }
 
-// Single pass with the row cache extended into LDS, for rows somewhat beyond what the
-// registers hold.  The first CPT chunks of a thread stay in registers exactly as in
-// addrms_body; the fp32 sums of its further chunks are parked in the thread's own slots
-// of the workgroup's LDS allocation (after the reduction scratch) and read back by the
-// same thread once rstd is known.  No other thread touches those slots, so the only
-// barrier is the reduction's.  Every byte of x and residual is still read once and
-// written once.  lds_cache_off: byte offset of the cache region in the dynamic LDS.
+// Hybrid form for rows beyond what registers and LDS hold together (both long-row flags set).
+// The first CPT chunks of a thread stay in registers (48 values: a 1024-thread workgroup leaves
+// each lane 128 registers), the next `lds_chunks` are parked in LDS as in addrms_ldscache_body, and only the remaining chunks are treated as in the
+// two-pass form: summed in pass 1 without being written, re-read in pass 2 (backwards, so that
+// what pass 1 pulled through the caches last is asked for first) to form both outputs.  The
+// part of the row that is read twice shrinks from all of it to what does not fit on the chip.
+// lds_chunks comes from the host, which sized the LDS allocation (it travels in the kernel
+// argument the persistent forms use for the number of row blocks); fewer chunks than CPT +
+// lds_chunks simply leave the tail of the register part idle (clamped loads, no stores).
 template <int DT, int VEC, int CPT, int UNR, bool NT>
-__device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void* __restrict__ rp,
-                                                     const void* __restrict__ wp, float eps, double inv_n,
-                                                     int64_t M, int32_t N, uint32_t flags, int32_t reduce,
-                                                     uint32_t nblocks)
+__device__ __forceinline__ void addrms_hybrid_body(void* __restrict__ xp, void* __restrict__ rp,
+                                                   const void* __restrict__ wp, float eps, double inv_n,
+                                                   int64_t M, int32_t N, uint32_t flags, int32_t reduce,
+                                                   uint32_t lds_chunks)
 {
     using T = dt_traits<DT>;
     constexpr int XB = T::XB, RB = T::RB;
     constexpr bool BF = T::BF;
     extern __shared__ double lds[];
-    (void)nblocks;
 
     const uint32_t tpr = blockDim.x, rpw = blockDim.y;
     const uint32_t lane = threadIdx.x, ry = threadIdx.y;
@@ -567,12 +568,11 @@ __device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void
     const uint32_t stride = tpr * VEC;
     const uint32_t nlast = n - VEC;
     const uint32_t col0 = lane * VEC;
-    const uint32_t reg_span = stride * CPT;                               // elements of a row held in registers
-    const uint32_t extra = n > reg_span ? (n - reg_span + stride - 1u) / stride : 0u;   // chunks per thread parked in LDS
-    // reduction scratch first (doubles), then the cache: [row][chunk][lane][VEC] floats
+    const uint32_t need = (n + stride - 1u) / stride;                      // chunks per thread (host: need > CPT + lds_chunks)
+    const uint32_t first_streamed = CPT + lds_chunks;
     const uint32_t red_doubles = (reduce == RED_WAVE) ? (tpr > 64u ? rpw * 16u : 0u) : rpw * tpr;
-    float* cache = reinterpret_cast<float*>(lds + red_doubles) + (static_cast<size_t>(ry) * extra * tpr + lane) * VEC;
-    const uint32_t cache_step = tpr * VEC;                                // floats between a thread's consecutive chunks
+    float* cache = reinterpret_cast<float*>(lds + red_doubles) + (static_cast<size_t>(ry) * lds_chunks * tpr + lane) * VEC;
+    const uint32_t cache_step = tpr * VEC;
 
     float h[CPT][VEC];
     double acc = 0.0;
@@ -604,13 +604,13 @@ __device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void
         }
         if (g + UNR < CPT) __builtin_amdgcn_sched_barrier(0);
     }
-    // ---- LDS part: uniform trip count, UNR chunks in flight
-    for (uint32_t e0 = 0; e0 < extra; e0 += UNR) {
+    // ---- LDS part
+    for (uint32_t e0 = 0; e0 < lds_chunks; e0 += UNR) {
         raw_t<XB * VEC> xv[UNR];
         raw_t<RB * VEC> rv[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            if (e0 + u < extra) {
+            if (e0 + u < lds_chunks) {
                 const uint32_t col = col0 + (CPT + e0 + u) * stride;
                 const uint32_t colc = col < nlast ? col : nlast;
                 ld_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + colc) * XB), xv[u]);
@@ -619,7 +619,7 @@ __device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            if (e0 + u < extra) {
+            if (e0 + u < lds_chunks) {
                 const uint32_t col = col0 + (CPT + e0 + u) * stride;
                 float hx[VEC];
 #pragma unroll
@@ -641,26 +641,82 @@ __device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void
             }
         }
     }
-
-    raw_t<XB * VEC> wv[CPT];
+    // ---- streamed part, pass 1: sum only (default cache policy: pass 2 asks for the same lines again)
+    for (uint32_t c0 = first_streamed; c0 < need; c0 += UNR) {
+        raw_t<XB * VEC> xv[UNR];
+        raw_t<RB * VEC> rv[UNR];
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-        const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
-        const uint32_t colc = col < nlast ? col : nlast;
-        ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(colc * XB), wv[c]);
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + (c0 + u) * stride;
+            if (c0 + u < need && col < n) {
+                ld_raw<XB * VEC, false>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), xv[u]);
+                ld_raw<RB * VEC, false>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), rv[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + (c0 + u) * stride;
+            if (ra.row_ok && c0 + u < need && col < n) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float hs = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                    const double hd = static_cast<double>(hs);
+                    acc = __builtin_fma(hd, hd, acc);
+                }
+            }
+        }
     }
 
     const double ss = row_sum(acc, reduce, tpr, lane, ry, lds);
     const float rstd = rsqrt_to_f32(__builtin_fma(ss, inv_n, static_cast<double>(eps)));
 
+    // ---- streamed part, pass 2, backwards
+    for (uint32_t k = need; k > first_streamed;) {
+        const uint32_t span_chunks = (k - first_streamed) < static_cast<uint32_t>(UNR) ? (k - first_streamed) : static_cast<uint32_t>(UNR);
+        const uint32_t c0 = k - span_chunks;
+        raw_t<XB * VEC> xv[UNR], wx[UNR];
+        raw_t<RB * VEC> rv[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + (c0 + u) * stride;
+            if (static_cast<uint32_t>(u) < span_chunks && col < n) {
+                ld_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), xv[u]);
+                ld_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), rv[u]);
+                ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(col * XB), wx[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const uint32_t col = col0 + (c0 + u) * stride;
+            if (ra.row_ok && static_cast<uint32_t>(u) < span_chunks && col < n) {
+                float hs[VEC], y[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    hs[e] = get_elem<XB, BF>(xv[u], e) + get_elem<RB, BF && RB == 2>(rv[u], e);
+                    const float t = hs[e] * rstd;
+                    y[e] = t * get_elem<XB, BF>(wx[u], e);
+                }
+                raw_t<RB * VEC> rout;
+                pack_vec<RB, BF, VEC>(hs, rout);
+                st_raw<RB * VEC, NT>(ra.rbase + static_cast<uint64_t>((ra.rowoff + col) * RB), rout);
+                raw_t<XB * VEC> yout;
+                pack_vec<XB, BF, VEC>(y, yout);
+                st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), yout);
+            }
+        }
+        k = c0;
+    }
+    // ---- register part (weights fetched as they are needed: the registers are full of the row)
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
         const uint32_t col = col0 + static_cast<uint32_t>(c) * stride;
+        raw_t<XB * VEC> wv;
+        ld_raw<XB * VEC>(wbase + static_cast<uint64_t>((col < nlast ? col : nlast) * XB), wv);
         float y[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const float t = h[c][e] * rstd;
-            y[e] = t * get_elem<XB, BF>(wv[c], e);
+            y[e] = t * get_elem<XB, BF>(wv, e);
         }
         if (ra.row_ok && col <= nlast) {
             raw_t<XB * VEC> out;
@@ -668,11 +724,12 @@ __device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void
             st_raw<XB * VEC, NT>(ra.xbase + static_cast<uint64_t>((ra.rowoff + col) * XB), out);
         }
     }
-    for (uint32_t e0 = 0; e0 < extra; e0 += UNR) {
+    // ---- LDS part
+    for (uint32_t e0 = 0; e0 < lds_chunks; e0 += UNR) {
         raw_t<XB * VEC> wx[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            if (e0 + u < extra) {
+            if (e0 + u < lds_chunks) {
                 const uint32_t col = col0 + (CPT + e0 + u) * stride;
                 const uint32_t colc = col < nlast ? col : nlast;
                 ld_raw<XB * VEC>(wbase + static_cast<uint64_t>(colc * XB), wx[u]);
@@ -680,7 +737,7 @@ __device__ __forceinline__ void addrms_ldscache_body(void* __restrict__ xp, void
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            if (e0 + u < extra) {
+            if (e0 + u < lds_chunks) {
                 const uint32_t col = col0 + (CPT + e0 + u) * stride;
                 const float* slot = cache + static_cast<size_t>(e0 + u) * cache_step;
                 float y[VEC];

@@ -89,7 +89,9 @@ int launch(const Feas& f, const addrms_cfg& c, void* x, void* r, const void* w, 
     int n = static_cast<int>(N);
     unsigned flags = static_cast<unsigned>(c.flags);
     int reduce = c.reduce;
-    unsigned nblocks = static_cast<unsigned>(n_row_blocks(c, M));
+    // the last argument is the number of row blocks (persistent grids walk them), or, for the forms that
+    // continue the row cache in LDS, the chunks per thread the LDS allocation holds
+    unsigned nblocks = f.lds_chunks >= 0 ? static_cast<unsigned>(f.lds_chunks) : static_cast<unsigned>(n_row_blocks(c, M));
     void* args[] = {&x, &r, &w, &eps, &inv_n, &m, &n, &flags, &reduce, &nblocks};
     return launch_instance(f, c, M, OP_ADDRMS, args, stream);
 }

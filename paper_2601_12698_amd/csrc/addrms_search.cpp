@@ -213,7 +213,11 @@ struct Searcher {
             { addrms_cfg n = c; n.walk = c.walk == 0 ? 4 : c.walk * 4; push(n); }
             if (c.walk != 0) { addrms_cfg n = c; n.walk = c.walk == 4 ? 0 : c.walk / 4; push(n); }
         }
-        if (c.flags & kLongRowBits) { addrms_cfg n = c; n.flags ^= kLongRowBits; push(n); }   // the other long-row form
+        if (c.flags & kLongRowBits) {                                // the other long-row forms
+            { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_TWO_PASS; push(n); }
+            { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_LDS_CACHE; push(n); }
+            { addrms_cfg n = c; n.flags ^= kLongRowBits; push(n); }
+        }
         else { addrms_cfg n = c; n.flags ^= ADDRMS_FLAG_ALIGNED_SPAN; n.reduce = 0; push(n); }   // into or out of the aligned-span form
         // occupancy cap: one step tighter, one step looser (0 = uncapped sits above the natural occupancy)
         {

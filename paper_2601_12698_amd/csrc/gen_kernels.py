@@ -4,8 +4,9 @@ The templates in ``addrms_kernel.h`` and ``silumul_kernel.h`` have four
 compile-time knobs (VEC, CPT, UNR, NT) per storage format; the register-cached
 form of add+RMSNorm has a fifth, DF (residual store deferred to the write phase).  CPT = 0 names the
 two-pass form of add+RMSNorm, which loops over the row instead of caching it
-(rows beyond the register row cache), and CPT = 100 + k the single-pass form
-whose cache continues in LDS after k register-held chunks.  This script emits,
+(rows beyond the register row cache), CPT = 200 + k the aligned-span form with
+k chunks per thread, and CPT = 300 + k the form whose cache continues in LDS
+after k register-held chunks (and re-reads what fits neither).  This script emits,
 into a build directory:
 
   kern_<op>_d<DT>_v<VEC>.hip  one translation unit per (operator, format, vector width),
@@ -32,8 +33,8 @@ UNRS = (1, 2, 4, 8)
 X_BYTES = {0: 2, 1: 2, 2: 2, 3: 4}      # bytes per x element of each format
 MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 values per thread
 BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
-LDS_CACHE_BASE = 100                    # cpt code of the LDS-extended form: 100 + register-held chunks
 SPAN_BASE = 200                         # cpt code of the aligned-span form: 200 + chunks per thread
+HYBRID_BASE = 300                       # cpt code of the hybrid long-row form: 300 + register-held chunks
 SPAN_CPTS = (1, 2, 4)
 R_BYTES = {0: 2, 1: 2, 2: 4, 3: 4}      # bytes per residual element of each format
 
@@ -76,12 +77,13 @@ def instances():
                                 for nt in (0, 1):
                                     for df in (0, 1):
                                         yield op, dt, vec, SPAN_BASE + cpt, unr, nt, df, 1024
-                    reg_cpt = BIG_ELEMS // vec       # LDS-extended cache: registers filled to the 1024-thread bound
+                    hyb_cpt = 48 // vec              # row cache continued in LDS: 48 values in registers, then LDS; what fits
+                                                     # neither (hybrid form) is read twice
                     for unr in UNRS:
-                        if unr > reg_cpt:
+                        if unr > hyb_cpt:
                             continue
                         for nt in (0, 1):
-                            yield op, dt, vec, LDS_CACHE_BASE + reg_cpt, unr, nt, 0, 1024
+                            yield op, dt, vec, HYBRID_BASE + hyb_cpt, unr, nt, 0, 1024
 
 
 def name(op, dt, vec, cpt, unr, nt, df=0):
@@ -102,8 +104,8 @@ CALL = {
                "(va, sa, vb, sb, vo, so, rows, d, flags, nblocks);"),
 }
 TWO_PASS_CALL = "addrms::addrms_twopass_body<{dt}, {vec}, {unr}, {nt}>(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);"
-LDS_CACHE_CALL = ("addrms::addrms_ldscache_body<{dt}, {vec}, {cpt}, {unr}, {nt}>"
-                  "(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);")
+HYBRID_CALL = ("addrms::addrms_hybrid_body<{dt}, {vec}, {cpt}, {unr}, {nt}>"
+               "(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);")
 SPAN_CALL = ("addrms::addrms_span_body<{dt}, {vec}, {cpt}, {unr}, {nt}, {df}>"
              "(x, r, w, eps, inv_n, M, N, flags, reduce, nblocks);")
 HEADER = {OP_ADDRMS: "addrms_kernel.h", OP_SILUMUL: "silumul_kernel.h", OP_MERGE: "mergestates_kernel.h"}
@@ -120,11 +122,11 @@ def main(outdir: str) -> None:
             fmt = CALL[op]
             if op == OP_ADDRMS and cpt == 0:
                 fmt = TWO_PASS_CALL
+            elif op == OP_ADDRMS and cpt >= HYBRID_BASE:
+                fmt = HYBRID_CALL
             elif op == OP_ADDRMS and cpt >= SPAN_BASE:
                 fmt = SPAN_CALL
-            elif op == OP_ADDRMS and cpt >= LDS_CACHE_BASE:
-                fmt = LDS_CACHE_CALL
-            call = fmt.format(dt=dt, vec=vec, cpt=cpt % LDS_CACHE_BASE, unr=unr, nt="true" if nt else "false",
+            call = fmt.format(dt=dt, vec=vec, cpt=cpt % 100, unr=unr, nt="true" if nt else "false",
                               df="true" if df else "false")
             lines.append(f'extern "C" __global__ __launch_bounds__({maxt}) void {name(op, dt, vec, cpt, unr, nt, df)}'
                          f"({ARGS[op]})\n{{ {call} }}")

@@ -136,15 +136,20 @@ def test_occupancy_model_matches_compiler_report():
             if cpt == 0:       # two-pass instance: selected by the flag, for a row beyond the register cache
                 c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_TWO_PASS | (B.FLAG_NONTEMPORAL if nt else 0))
                 st, why, _ = feas(c, 4096, vec * 1024 * 40, dtype)
-            elif cpt >= 100:   # LDS-extended instance: registers full (cpt - 100 chunks), one more chunk parked in LDS
-                c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_LDS_CACHE | (B.FLAG_NONTEMPORAL if nt else 0))
-                st, why, _ = feas(c, 4096, vec * 1024 * (cpt - 100 + 1), dtype)
+            elif cpt >= 300:   # hybrid instance: registers full (cpt - 300 chunks), LDS full, one more chunk read twice
+                fit = (160 * 1024 - 128) // (1024 * vec * 4)
+                c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_LDS_CACHE | B.FLAG_TWO_PASS | (B.FLAG_NONTEMPORAL if nt else 0))
+                st, why, _ = feas(c, 4096, vec * 1024 * (cpt - 300 + fit + 1), dtype)
+            elif cpt >= 200:   # aligned-span instance
+                c = B.make_cfg(vec, 128, 8, unroll=unr, flags=B.FLAG_ALIGNED_SPAN | (B.FLAG_NONTEMPORAL if nt else 0))
+                st, why, _ = feas(c, 4096, 1000 if (cpt - 200) * vec * 128 >= 1000 else vec * 125 * (cpt - 200), dtype)
             else:
                 c = B.make_cfg(vec, 64, 1, unroll=unr, flags=B.FLAG_NONTEMPORAL if nt else 0)
                 st, why, _ = feas(c, 4096, vec * 64 * cpt, dtype)
             assert st == B.ERR_INFEASIBLE_CFG and "spills" in why, (name, why)
             spilled += 1
-    assert checked >= 1000 and spilled < 0.02 * checked
+    # (most of the spilling instances are hybrid long-row ones: 48 cached values at some load depths do not fit 128 registers)
+    assert checked >= 1000 and spilled < 0.05 * checked
     # and the library's table carries the same numbers
     c = B.make_cfg(8, 64, 1, unroll=2)
     st, _, res = feas(c, 4096, 4096, "bf16")
@@ -188,7 +193,8 @@ def test_default_cfg():
 def test_row_length_bound_of_the_register_cache(dtype):
     """1024 threads x 32 cached values, at most 16 accesses per thread: even N up to 32768 and odd N up to
     16384 run in the plain single-pass form; beyond that the row cache continues in LDS while 160 KB hold
-    the rest, then the two-pass form takes over up to 2^28 elements; beyond that nothing is feasible."""
+    the rest; then the hybrid form (registers and LDS hold what they can, the rest is read twice) and the plain
+    two-pass form take over up to 2^28 elements; beyond that nothing is feasible."""
     long_forms = B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE
     for N in (32768, 32766, 32764, 16383, 16381):
         c = B.addrms_default_cfg(N, dtype)
@@ -206,21 +212,24 @@ def test_row_length_bound_of_the_register_cache(dtype):
         c = B.addrms_default_cfg(N, dtype)
         assert c.flags == B.FLAG_LDS_CACHE and c.vec == 1 and c.threads_per_row == 1024
         st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
-        assert st == 0 and 17 <= res.chunks_per_thread <= 32 and res.lds_bytes <= 128, why
+        assert st == 0 and 17 <= res.chunks_per_thread <= 32 and res.lds_bytes <= 128, why      # nothing parked
     for N in (32770, 40960, 65536):
         c = B.addrms_default_cfg(N, dtype)          # somewhat beyond the registers: one pass, the rest parked in LDS
         assert c.flags == B.FLAG_LDS_CACHE and N % c.vec == 0 and c.threads_per_row == 1024 and c.rows_per_wg == 1
         st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
         assert st == 0, why
-        parked = res.chunks_per_thread - 32 // c.vec
-        assert parked >= 1 and res.lds_bytes >= parked * 1024 * c.vec * 4 and res.lds_bytes <= 160 * 1024
+        parked = max(0, res.chunks_per_thread - 48 // c.vec)      # 48 values per thread stay in registers
+        assert parked >= (1 if N > 49152 else 0) and res.lds_bytes >= parked * 1024 * c.vec * 4 and res.lds_bytes <= 160 * 1024
         assert res.scratch_bytes == 0
     for N in (32767 * 4 + 1, 1 << 20, 1 << 28):
-        c = B.addrms_default_cfg(N, dtype)          # too long for LDS as well: read the row twice
-        assert c.flags == B.FLAG_TWO_PASS and N % c.vec == 0 and c.threads_per_row == 1024 and c.rows_per_wg == 1
+        c = B.addrms_default_cfg(N, dtype)          # too long for LDS as well: what does not fit the chip is read twice
+        assert c.flags == long_forms and N % c.vec == 0 and c.threads_per_row == 1024 and c.rows_per_wg == 1
         st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
         assert st == 0, why
         assert res.chunks_per_thread == -(-N // (c.vec * 1024)) and res.scratch_bytes == 0
+        assert 100 * 1024 < res.lds_bytes <= 160 * 1024          # the LDS part is as large as a CU allows
+        two = B.make_cfg(c.vec, 1024, 1, unroll=2, flags=B.FLAG_TWO_PASS)
+        assert B.addrms_cfg_feasible(two, 4, N, dtype)[0] == 0     # the plain two-pass form stays available
         st, why, _ = B.addrms_cfg_feasible(B.make_cfg(c.vec, 1024, 1, unroll=2, flags=B.FLAG_LDS_CACHE), 4, N, dtype)
         assert st == B.ERR_INFEASIBLE_CFG and "bytes of LDS" in why, why
     for N in (65536, 100001):
@@ -232,7 +241,7 @@ def test_row_length_bound_of_the_register_cache(dtype):
         assert st == B.ERR_INFEASIBLE_CFG and ("row cache" in why or "compiled for workgroups" in why), why
     st, why, _ = B.addrms_cfg_feasible(B.make_cfg(8 if dtype != "fp32" else 4, 1024, 1, flags=B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE),
                                        4, 65536, dtype)
-    assert st == B.ERR_INFEASIBLE_CFG and "exclude each other" in why
+    assert st == B.ERR_INFEASIBLE_CFG and "nothing has to be read twice" in why
     # a workgroup addresses rows_per_wg * N elements with 32-bit byte offsets
     st, why, _ = B.addrms_cfg_feasible(B.make_cfg(1, 64, 2, flags=B.FLAG_TWO_PASS), 4, (1 << 28) - 1, dtype)
     assert st == B.ERR_INFEASIBLE_CFG and "32-bit offsets" in why

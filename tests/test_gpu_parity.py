@@ -122,11 +122,13 @@ def test_rows_beyond_the_template_are_refused_before_launch():
 
 @pytest.mark.parametrize("dtype,M,N", [("bf16", 5, 32770), ("bf16", 3, 65536), ("fp16", 4, 40001), ("fp16_res32", 3, 49152),
                                        ("fp32", 2, 100000), ("bf16", 37, 36864), ("fp32", 1, 1 << 20), ("bf16", 7, 20001),
-                                       ("fp32", 6, 32767), ("bf16", 3, 73720)])
+                                       ("fp32", 6, 32767), ("bf16", 3, 73720), ("bf16", 5, 131072), ("fp16_res32", 3, 99992),
+                                       ("fp16", 2, 262146)])
 def test_long_row_forms_beyond_the_register_cache(oracle, dtype, M, N):
     """Rows that no plain single-pass configuration holds run with the row cache continued in LDS (one pass)
-    while 160 KB suffice, and in the two-pass form (read, sum, read again, write) beyond.  Same arithmetic,
-    same bar: bit-identical to the oracle over a spread of the configurations of each form."""
+    while 160 KB suffice; beyond that in the hybrid form (registers and LDS hold what they can, the rest of the row
+    is read twice) or the plain two-pass form (read, sum, read again, write).  Same arithmetic, same bar:
+    bit-identical to the oracle over a spread of the configurations of each form."""
     long_forms = B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE
     wl = _wl(M, N, dtype, 1200 + N % 89)
     d = W.generate(wl)
@@ -136,9 +138,11 @@ def test_long_row_forms_beyond_the_register_cache(oracle, dtype, M, N):
     assert dflt.flags & long_forms
     cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
     assert cfgs and all(c.flags & long_forms for c in cfgs)
-    by_form = {f: [c for c in cfgs if c.flags & f] for f in (B.FLAG_TWO_PASS, B.FLAG_LDS_CACHE)}
-    print(f"{wl.name}: two-pass {len(by_form[B.FLAG_TWO_PASS])}, lds-cache {len(by_form[B.FLAG_LDS_CACHE])} feasible, "
-          f"default {dflt.as_tuple()}", flush=True)
+    by_form = {f: [c for c in cfgs if c.flags & long_forms == f] for f in (B.FLAG_TWO_PASS, B.FLAG_LDS_CACHE, long_forms)}
+    print(f"{wl.name}: two-pass {len(by_form[B.FLAG_TWO_PASS])}, lds-cache {len(by_form[B.FLAG_LDS_CACHE])}, hybrid "
+          f"{len(by_form[long_forms])} feasible, default {dflt.as_tuple()}", flush=True)
+    if N > 80000:
+        assert by_form[long_forms] and dflt.flags & long_forms == long_forms
     picks = [None]
     for lst in by_form.values():
         picks += lst[:: max(1, len(lst) // 50)]

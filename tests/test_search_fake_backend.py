@@ -171,19 +171,20 @@ def test_argument_errors():
 
 
 def test_search_over_the_long_row_forms():
-    """Rows beyond the register cache: the region holds the two long-row forms only (cache continued in LDS,
-    or two passes) and both strategies work across them."""
+    """Rows beyond the register cache: the region holds the long-row forms only (cache continued in LDS, two
+    passes, or the hybrid of the two) and both strategies work across them."""
     m, n = 512, 65536
     long_forms = B.FLAG_TWO_PASS | B.FLAG_LDS_CACHE
 
     def cost2(c):
         assert c.flags & long_forms and not c.flags & B.FLAG_PERSISTENT
-        return cost(c) * (3.0 if c.flags & B.FLAG_TWO_PASS else 1.5)
+        form = c.flags & long_forms
+        return cost(c) * (3.0 if form == B.FLAG_TWO_PASS else 2.0 if form == long_forms else 1.5)
 
     cfgs, _ = B.addrms_enumerate_feasible(m, n, DT)
-    assert {c.flags & long_forms for c in cfgs} == {B.FLAG_TWO_PASS, B.FLAG_LDS_CACHE}
+    assert {c.flags & long_forms for c in cfgs} == {B.FLAG_TWO_PASS, B.FLAG_LDS_CACHE, long_forms}
     best = min(cfgs, key=cost2)
-    assert best.flags & B.FLAG_LDS_CACHE
+    assert best.flags & long_forms == B.FLAG_LDS_CACHE
     rec = Recorder(cost2)
     e, erep = B.addrms_tune_with_backend(m, n, DT, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE), rec.measure, rec.validate)
     assert e.as_tuple() == best.as_tuple() and erep.n_measured == len(cfgs) == erep.n_feasible
@@ -193,7 +194,7 @@ def test_search_over_the_long_row_forms():
     assert grep.default_cfg.flags == B.FLAG_LDS_CACHE and grep.default_cfg.threads_per_row == 1024
     # where only two passes fit, the search still works
     g2, grep2 = B.addrms_tune_with_backend(m, 1 << 20, DT, B.make_budget(), rec.measure, rec.validate)
-    assert g2.flags & B.FLAG_TWO_PASS and grep2.default_cfg.flags == B.FLAG_TWO_PASS
+    assert g2.flags & B.FLAG_TWO_PASS and grep2.default_cfg.flags == long_forms
 
 
 def test_second_search_resumes_from_the_log(tmp_path):
