@@ -585,6 +585,56 @@ int default_cfg(int64_t N, int dtype, addrms_cfg* out, std::string* why, int op)
     return ADDRMS_ERR_UNSUPPORTED_SHAPE;
 }
 
+// ---- the host-only entry points, once for all three operators ------------------------
+int export_default_cfg(int op, int64_t N, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    std::string why;
+    const int st = default_cfg(N, dtype, out, &why, op);
+    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
+}
+
+int export_cfg_feasible(int op, const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, char* reason, size_t reason_len,
+                        addrms_resources* res)
+{
+    if (reason && reason_len) reason[0] = '\0';
+    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
+    const Feas f = check_cfg(*cfg, M, N, dtype, op);
+    if (res) *res = f.res;
+    if (f.status != ADDRMS_OK) {
+        if (reason && reason_len) snprintf(reason, reason_len, "%s", f.reason.c_str());
+        return fail(f.status, "%s", f.reason.c_str());
+    }
+    return ADDRMS_OK;
+}
+
+int64_t export_enumerate_feasible(int op, int64_t M, int64_t N, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid)
+{
+    if (!dtype_valid(dtype, op)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for %s", dtype, op_name(op));
+    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "the number of rows must be >= 0 and the row length > 0");
+    if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
+    std::vector<addrms_cfg> v;
+    enumerate(M, N, dtype, &v, n_grid, nullptr, op);
+    const int64_t n = static_cast<int64_t>(v.size());
+    for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
+    return n;
+}
+
+int export_table_lookup(int op, int64_t M, int64_t N, int dtype, addrms_cfg* out)
+{
+    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
+    const int st = table_lookup(M, N, dtype, out, op);
+    return st == ADDRMS_OK ? st : fail(st, "no %s table entry usable for %lld rows of %lld, dtype=%d", op_name(op),
+                                       (long long)M, (long long)N, dtype);
+}
+
+int64_t export_algorithmic_bytes(int op, int64_t M, int64_t N, int dtype)
+{
+    if (!dtype_valid(dtype, op)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for %s", dtype, op_name(op));
+    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "the number of rows must be >= 0 and the row length > 0");
+    return algorithmic_bytes(op, M, N, dtype);
+}
+
 }  // namespace addrms_host
 
 // ---- C ABI -------------------------------------------------------------------------
@@ -595,12 +645,7 @@ extern "C" {
 const char* addrms_last_error(void) { return last_error(); }
 const char* addrms_version(void) { return ADDRMS_VERSION_STRING " (gfx950)"; }
 
-int64_t addrms_algorithmic_bytes(int64_t M, int64_t N, int dtype)
-{
-    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
-    return algorithmic_bytes(OP_ADDRMS, M, N, dtype);
-}
+int64_t addrms_algorithmic_bytes(int64_t M, int64_t N, int dtype) { return export_algorithmic_bytes(OP_ADDRMS, M, N, dtype); }
 
 int addrms_get_hw_limits(addrms_hw_limits* out)
 {
@@ -617,38 +662,17 @@ int addrms_get_hw_limits(addrms_hw_limits* out)
     return ADDRMS_OK;
 }
 
-int addrms_default_cfg(int64_t N, int dtype, addrms_cfg* out)
-{
-    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
-    std::string why;
-    const int st = default_cfg(N, dtype, out, &why);
-    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
-}
+int addrms_default_cfg(int64_t N, int dtype, addrms_cfg* out) { return export_default_cfg(OP_ADDRMS, N, dtype, out); }
 
 int addrms_cfg_feasible(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype,
                         char* reason, size_t reason_len, addrms_resources* res)
 {
-    if (reason && reason_len) reason[0] = '\0';
-    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
-    const Feas f = check_cfg(*cfg, M, N, dtype);
-    if (res) *res = f.res;
-    if (f.status != ADDRMS_OK) {
-        if (reason && reason_len) snprintf(reason, reason_len, "%s", f.reason.c_str());
-        return fail(f.status, "%s", f.reason.c_str());
-    }
-    return ADDRMS_OK;
+    return export_cfg_feasible(OP_ADDRMS, cfg, M, N, dtype, reason, reason_len, res);
 }
 
 int64_t addrms_enumerate_feasible(int64_t M, int64_t N, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid)
 {
-    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
-    if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
-    std::vector<addrms_cfg> v;
-    enumerate(M, N, dtype, &v, n_grid, nullptr);
-    const int64_t n = static_cast<int64_t>(v.size());
-    for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
-    return n;
+    return export_enumerate_feasible(OP_ADDRMS, M, N, dtype, out, cap, n_grid);
 }
 
 }  // extern "C"

@@ -128,6 +128,14 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
 // True if cfg only uses strategy families allowed by mask (0 = all).
 bool cfg_in_families(const addrms_cfg& c, int family_mask);
 
+// ---- host-only entry points, operator-indexed (the exported names are thin wrappers) ----
+int export_default_cfg(int op, int64_t N, int dtype, addrms_cfg* out);
+int export_cfg_feasible(int op, const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, char* reason, size_t reason_len,
+                        addrms_resources* res);
+int64_t export_enumerate_feasible(int op, int64_t M, int64_t N, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid);
+int export_table_lookup(int op, int64_t M, int64_t N, int dtype, addrms_cfg* out);
+int64_t export_algorithmic_bytes(int op, int64_t M, int64_t N, int dtype);
+
 // ---- error text ------------------------------------------------------------
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();

@@ -313,6 +313,7 @@ int fill(void* p, int64_t n, int es, bool bf, uint32_t seed, float lo, float hi,
 // sets that the timed launches rotate through so that their combined footprint
 // exceeds the last-level caches.
 struct Harness {
+    static constexpr int kOp = OP_ADDRMS;
     int64_t M = 0, N = 0;
     int dtype = 0;
     float eps = 1e-6f;
@@ -481,17 +482,12 @@ struct Harness {
     }
 };
 
-int backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<Harness*>(user)->validate(*cfg); }
-int backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
-{
-    return static_cast<Harness*>(user)->measure(*cfg, warmup, reps, us);
-}
-
 std::mutex g_tune_mu;
 
 // ---- measurement harness of silu_and_mul: one pristine input, a reference output, and
 // rotating (input, output) pairs; the operator is out of place, so nothing is restored.
 struct SiluHarness {
+    static constexpr int kOp = OP_SILUMUL;
     int64_t M = 0, d = 0;
     int dtype = 0;
     int nsets = 0;
@@ -505,7 +501,7 @@ struct SiluHarness {
 
     static size_t pad(size_t b) { return (b + 65535) / 65536 * 65536 + 65536; }
 
-    int init(int64_t m, int64_t dd, int dt, bool rotate)
+    int init(int64_t m, int64_t dd, int dt, float /*eps: the operator has none*/, bool rotate)
     {
         M = m; d = dd; dtype = dt;
         inbytes = static_cast<size_t>(M) * 2 * d * x_bytes(dt);
@@ -587,6 +583,7 @@ struct SiluHarness {
 // ---- measurement harness of merge_attn_states: rotating (v_a, v_b, s_a, s_b, v_out, s_out)
 // sets plus a reference output; out of place, nothing to restore.
 struct MergeHarness {
+    static constexpr int kOp = OP_MERGE;
     int64_t rows = 0, d = 0;
     int dtype = 0;
     int nsets = 0;
@@ -602,7 +599,7 @@ struct MergeHarness {
 
     static size_t pad(size_t b) { return (b + 65535) / 65536 * 65536 + 65536; }
 
-    int init(int64_t r, int64_t dd, int dt, bool rotate)
+    int init(int64_t r, int64_t dd, int dt, float /*eps: the operator has none*/, bool rotate)
     {
         rows = r; d = dd; dtype = dt;
         vbytes = static_cast<size_t>(rows) * d * x_bytes(dt);
@@ -703,61 +700,127 @@ struct MergeHarness {
         return ADDRMS_OK;
     }
 };
-int merge_backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<MergeHarness*>(user)->validate(*cfg); }
-int merge_backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
+// ---- one implementation of the tuner's device entry points for all three operators --------
+// H is the operator's harness (Harness, SiluHarness, MergeHarness): same interface, own buffers,
+// own launch and own gate; H::kOp selects the operator's part of the deriver, search and table.
+template <class H> int backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<H*>(user)->validate(*cfg); }
+template <class H> int backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
 {
-    return static_cast<MergeHarness*>(user)->measure(*cfg, warmup, reps, us);
+    return static_cast<H*>(user)->measure(*cfg, warmup, reps, us);
 }
 
-int silu_backend_validate(void* user, const addrms_cfg* cfg) { return static_cast<SiluHarness*>(user)->validate(*cfg); }
-int silu_backend_measure(void* user, const addrms_cfg* cfg, int warmup, int reps, double* us)
-{
-    return static_cast<SiluHarness*>(user)->measure(*cfg, warmup, reps, us);
-}
+float budget_eps(const addrms_budget* b) { return (b && b->eps > 0.0f) ? b->eps : 1e-6f; }
 
-// Backend factory over the device harness: one Harness per shape, reference output from
-// that shape's default cfg.
-struct HarnessFactory { float eps; };
-int factory_open(void* user, int64_t M, int64_t N, int dtype, addrms_backend* out)
+// S_ref comes from the default cfg; should a tiny M make that one infeasible, from the first feasible cfg.
+template <class H> int reference_cfg(int64_t M, int64_t N, int dtype, addrms_cfg* out)
 {
-    auto* h = new Harness();
-    addrms_cfg dflt{};
     std::string why;
-    int st = default_cfg(N, dtype, &dflt, &why);
-    if (st == ADDRMS_OK) st = h->init(M, N, dtype, static_cast<HarnessFactory*>(user)->eps, true);
-    if (st == ADDRMS_OK) st = h->make_reference(dflt);
-    if (st != ADDRMS_OK) { delete h; return st; }
-    out->user = h;
-    out->validate = backend_validate;
-    out->measure = backend_measure;
-    return 0;
+    const int st = default_cfg(N, dtype, out, &why, H::kOp);
+    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
+    if (check_cfg(*out, M, N, dtype, H::kOp).status == ADDRMS_OK) return ADDRMS_OK;
+    std::vector<addrms_cfg> v;
+    enumerate(M, N, dtype, &v, nullptr, nullptr, H::kOp);
+    if (v.empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
+    *out = v.front();
+    return ADDRMS_OK;
 }
-void factory_close(void*, addrms_backend* be) { delete static_cast<Harness*>(be->user); }
 
-// The same for the two further operators (no eps, so no state).
-template <class H, int OP, int (*VALIDATE)(void*, const addrms_cfg*), int (*MEASURE)(void*, const addrms_cfg*, int, int, double*)>
-int op_factory_open(void*, int64_t M, int64_t N, int dtype, addrms_backend* out)
+// Backend factory over the device harness: one harness per shape, reference output from that shape's default cfg.
+struct HarnessFactory { float eps; };
+template <class H> int factory_open(void* user, int64_t M, int64_t N, int dtype, addrms_backend* out)
 {
     auto* h = new H();
-    addrms_cfg dflt{};
-    std::string why;
-    int st = default_cfg(N, dtype, &dflt, &why, OP);
-    if (st == ADDRMS_OK) st = h->init(M, N, dtype, true);
-    if (st == ADDRMS_OK) st = h->make_reference(dflt);
+    addrms_cfg ref{};
+    int st = reference_cfg<H>(M, N, dtype, &ref);
+    if (st == ADDRMS_OK) st = h->init(M, N, dtype, static_cast<HarnessFactory*>(user)->eps, true);
+    if (st == ADDRMS_OK) st = h->make_reference(ref);
     if (st != ADDRMS_OK) { delete h; return st; }
     out->user = h;
-    out->validate = VALIDATE;
-    out->measure = MEASURE;
+    out->validate = backend_validate<H>;
+    out->measure = backend_measure<H>;
     return 0;
 }
-template <class H>
-void op_factory_close(void*, addrms_backend* be) { delete static_cast<H*>(be->user); }
+template <class H> void factory_close(void*, addrms_backend* be) { delete static_cast<H*>(be->user); }
+
+int check_op_shape(int op, int64_t M, int64_t N, int dtype, const char* what)
+{
+    if (!dtype_valid(dtype, op)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d for %s", dtype, op_name(op));
+    if (M <= 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "%s needs a positive number of rows and a positive row length", what);
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    return ADDRMS_OK;
+}
 
 int check_shapes(const addrms_shape* shapes, int32_t n)
 {
     if (!shapes) return fail(ADDRMS_ERR_INVALID_ARG, "shapes is NULL");
     if (n < 1 || n > ADDRMS_MAX_SHAPES) return fail(ADDRMS_ERR_INVALID_ARG, "n must be 1..%d", ADDRMS_MAX_SHAPES);
     return ADDRMS_OK;
+}
+
+// Algorithm 1 lines 18-21 and 23 for one shape on the current device.
+template <class H> int tune_on_device(int64_t M, int64_t N, int dtype, const addrms_budget* budget, addrms_cfg* out_cfg,
+                                      addrms_tune_report* report)
+{
+    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
+    int st = check_op_shape(H::kOp, M, N, dtype, "tuning");
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    addrms_cfg ref{};
+    st = reference_cfg<H>(M, N, dtype, &ref);
+    if (st != ADDRMS_OK) return st;
+    H h;
+    st = h.init(M, N, dtype, budget_eps(budget), true);
+    if (st != ADDRMS_OK) return st;
+    st = h.make_reference(ref);
+    if (st != ADDRMS_OK) return st;
+    addrms_backend be{&h, backend_validate<H>, backend_measure<H>};
+    addrms_tune_report local{};
+    st = run_search(M, N, dtype, budget, be, out_cfg, &local, H::kOp);
+    if (st != ADDRMS_OK) return st;
+    if (report) *report = local;
+    return table_insert(M, N, dtype, *out_cfg, local.best_us, H::kOp);
+}
+
+// Line 22 (SelectGeneral) and the outer loop, over a set of shapes.
+template <class H> int select_general_on_device(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                                                addrms_cfg* out_general, addrms_general_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    const int st = check_shapes(shapes, n);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    HarnessFactory hf{budget_eps(budget)};
+    addrms_backend_factory fac{&hf, factory_open<H>, factory_close<H>};
+    return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report, H::kOp);
+}
+template <class H> int tune_rounds_on_device(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
+                                             addrms_cfg* out_general, addrms_rounds_report* report)
+{
+    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
+    const int st = check_shapes(shapes, n);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    HarnessFactory hf{budget_eps(budget)};
+    addrms_backend_factory fac{&hf, factory_open<H>, factory_close<H>};
+    return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report, H::kOp);
+}
+
+// Mean time of one cfg (NULL: table, else default) on library-allocated buffers.
+template <class H> int measure_on_device(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,
+                                         int rotate, double* mean_us)
+{
+    if (!mean_us) return fail(ADDRMS_ERR_INVALID_ARG, "mean_us is NULL");
+    if (reps <= 0 || warmup < 0) return fail(ADDRMS_ERR_INVALID_ARG, "need reps > 0 and warmup >= 0");
+    int st = check_op_shape(H::kOp, M, N, dtype, "measuring");
+    if (st != ADDRMS_OK) return st;
+    addrms_cfg c{};
+    st = resolve_cfg(cfg, M, N, dtype, &c, H::kOp);
+    if (st != ADDRMS_OK) return st;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    H h;
+    st = h.init(M, N, dtype, eps, rotate != 0);
+    if (st != ADDRMS_OK) return st;
+    return h.measure(c, warmup, reps, mean_us);
 }
 
 }  // namespace
@@ -789,54 +852,19 @@ int addrms_run(void* x, void* residual, const void* weight, float eps, int64_t M
 int addrms_tune(int64_t M, int64_t N, int dtype, const addrms_budget* budget, addrms_cfg* out_cfg,
                 addrms_tune_report* report)
 {
-    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
-    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M <= 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs M > 0 and N > 0");
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    addrms_cfg dflt{};
-    std::string why;
-    int st = default_cfg(N, dtype, &dflt, &why);
-    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
-    Harness h;
-    const float eps = (budget && budget->eps > 0.0f) ? budget->eps : 1e-6f;
-    st = h.init(M, N, dtype, eps, true);
-    if (st != ADDRMS_OK) return st;
-    // S_ref: the default configuration's output on the pristine inputs.
-    if (check_cfg(dflt, M, N, dtype).status != ADDRMS_OK) {
-        std::vector<addrms_cfg> v;
-        enumerate(M, N, dtype, &v, nullptr, nullptr);
-        if (v.empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
-        dflt = v.front();
-    }
-    st = h.make_reference(dflt);
-    if (st != ADDRMS_OK) return st;
-    addrms_backend be{&h, backend_validate, backend_measure};
-    addrms_tune_report local{};
-    st = run_search(M, N, dtype, budget, be, out_cfg, &local);
-    if (st != ADDRMS_OK) return st;
-    if (report) *report = local;
-    return addrms_table_insert(M, N, dtype, out_cfg, local.best_us);
+    return tune_on_device<Harness>(M, N, dtype, budget, out_cfg, report);
 }
 
 int addrms_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
                           addrms_cfg* out_general, addrms_general_report* report)
 {
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    HarnessFactory hf{(budget && budget->eps > 0.0f) ? budget->eps : 1e-6f};
-    addrms_backend_factory fac{&hf, factory_open, factory_close};
-    return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report);
+    return select_general_on_device<Harness>(shapes, n, dtype, budget, out_general, report);
 }
 
 int addrms_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
                        addrms_cfg* out_general, addrms_rounds_report* report)
 {
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    HarnessFactory hf{(budget && budget->eps > 0.0f) ? budget->eps : 1e-6f};
-    addrms_backend_factory fac{&hf, factory_open, factory_close};
-    return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report);
+    return tune_rounds_on_device<Harness>(shapes, n, dtype, budget, out_general, report);
 }
 
 int addrms_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget, addrms_audit_report* report)
@@ -847,40 +875,22 @@ int addrms_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* bud
     if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
     std::lock_guard<std::mutex> lock(g_tune_mu);
     addrms_cfg dflt{};
-    std::string why;
-    int st = default_cfg(N, dtype, &dflt, &why);
-    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
-    Harness h;
-    st = h.init(M, N, dtype, (budget && budget->eps > 0.0f) ? budget->eps : 1e-6f, true);
+    int st = reference_cfg<Harness>(M, N, dtype, &dflt);
     if (st != ADDRMS_OK) return st;
-    if (check_cfg(dflt, M, N, dtype).status != ADDRMS_OK) {
-        std::vector<addrms_cfg> v;
-        enumerate(M, N, dtype, &v, nullptr, nullptr);
-        if (v.empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
-        dflt = v.front();
-    }
+    Harness h;
+    st = h.init(M, N, dtype, budget_eps(budget), true);
+    if (st != ADDRMS_OK) return st;
     st = h.make_reference(dflt);     // the reference comes from a configuration every rule retains
     if (st != ADDRMS_OK) return st;
     h.relax = RELAX_ALL;
-    addrms_backend be{&h, backend_validate, backend_measure};
+    addrms_backend be{&h, backend_validate<Harness>, backend_measure<Harness>};
     return run_audit_rules(M, N, dtype, budget, be, report);
 }
 
 int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,
                    int rotate, double* mean_us)
 {
-    if (!mean_us) return fail(ADDRMS_ERR_INVALID_ARG, "mean_us is NULL");
-    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M <= 0 || N <= 0 || reps <= 0 || warmup < 0) return fail(ADDRMS_ERR_INVALID_ARG, "need M, N, reps > 0 and warmup >= 0");
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    addrms_cfg c{};
-    int st = resolve_cfg(cfg, M, N, dtype, &c);
-    if (st != ADDRMS_OK) return st;
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    Harness h;
-    st = h.init(M, N, dtype, eps, rotate != 0);
-    if (st != ADDRMS_OK) return st;
-    return h.measure(c, warmup, reps, mean_us);
+    return measure_on_device<Harness>(cfg, M, N, dtype, eps, warmup, reps, rotate, mean_us);
 }
 
 int addrms_measure_stats(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps, int warmup, int reps,
@@ -1057,38 +1067,17 @@ int silumul_run(const void* x, void* out, int64_t M, int64_t d, int dtype, const
     return launch_silumul(f, c, x, out, M, d, static_cast<hipStream_t>(stream));
 }
 
-int silumul_default_cfg(int64_t d, int dtype, addrms_cfg* out)
-{
-    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
-    std::string why;
-    const int st = default_cfg(d, dtype, out, &why, OP_SILUMUL);
-    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
-}
+int silumul_default_cfg(int64_t d, int dtype, addrms_cfg* out) { return export_default_cfg(OP_SILUMUL, d, dtype, out); }
 
 int silumul_cfg_feasible(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, char* reason, size_t reason_len,
                          addrms_resources* res)
 {
-    if (reason && reason_len) reason[0] = '\0';
-    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
-    const Feas f = check_cfg(*cfg, M, d, dtype, OP_SILUMUL);
-    if (res) *res = f.res;
-    if (f.status != ADDRMS_OK) {
-        if (reason && reason_len) snprintf(reason, reason_len, "%s", f.reason.c_str());
-        return fail(f.status, "%s", f.reason.c_str());
-    }
-    return ADDRMS_OK;
+    return export_cfg_feasible(OP_SILUMUL, cfg, M, d, dtype, reason, reason_len, res);
 }
 
 int64_t silumul_enumerate_feasible(int64_t M, int64_t d, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid)
 {
-    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and d > 0");
-    if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
-    std::vector<addrms_cfg> v;
-    enumerate(M, d, dtype, &v, n_grid, nullptr, OP_SILUMUL);
-    const int64_t n = static_cast<int64_t>(v.size());
-    for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
-    return n;
+    return export_enumerate_feasible(OP_SILUMUL, M, d, dtype, out, cap, n_grid);
 }
 
 int silumul_tune_with_backend(int64_t M, int64_t d, int dtype, const addrms_budget* budget, const addrms_backend* backend,
@@ -1101,83 +1090,30 @@ int silumul_tune_with_backend(int64_t M, int64_t d, int dtype, const addrms_budg
 int silumul_tune(int64_t M, int64_t d, int dtype, const addrms_budget* budget, addrms_cfg* out_cfg,
                  addrms_tune_report* report)
 {
-    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
-    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M <= 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs M > 0 and d > 0");
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    addrms_cfg dflt{};
-    std::string why;
-    int st = default_cfg(d, dtype, &dflt, &why, OP_SILUMUL);
-    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
-    SiluHarness h;
-    st = h.init(M, d, dtype, true);
-    if (st != ADDRMS_OK) return st;
-    st = h.make_reference(dflt);
-    if (st != ADDRMS_OK) return st;
-    addrms_backend be{&h, silu_backend_validate, silu_backend_measure};
-    addrms_tune_report local{};
-    st = run_search(M, d, dtype, budget, be, out_cfg, &local, OP_SILUMUL);
-    if (st != ADDRMS_OK) return st;
-    if (report) *report = local;
-    return table_insert(M, d, dtype, *out_cfg, local.best_us, OP_SILUMUL);
+    return tune_on_device<SiluHarness>(M, d, dtype, budget, out_cfg, report);
 }
 
 int silumul_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
                            addrms_cfg* out_general, addrms_general_report* report)
 {
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    const int st = check_shapes(shapes, n);
-    if (st != ADDRMS_OK) return st;
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    addrms_backend_factory fac{nullptr, op_factory_open<SiluHarness, OP_SILUMUL, silu_backend_validate, silu_backend_measure>,
-                               op_factory_close<SiluHarness>};
-    return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report, OP_SILUMUL);
+    return select_general_on_device<SiluHarness>(shapes, n, dtype, budget, out_general, report);
 }
 
 int silumul_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
                         addrms_cfg* out_general, addrms_rounds_report* report)
 {
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    const int st = check_shapes(shapes, n);
-    if (st != ADDRMS_OK) return st;
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    addrms_backend_factory fac{nullptr, op_factory_open<SiluHarness, OP_SILUMUL, silu_backend_validate, silu_backend_measure>,
-                               op_factory_close<SiluHarness>};
-    return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report, OP_SILUMUL);
+    return tune_rounds_on_device<SiluHarness>(shapes, n, dtype, budget, out_general, report);
 }
 
 int silumul_measure(const addrms_cfg* cfg, int64_t M, int64_t d, int dtype, int warmup, int reps, int rotate,
                     double* mean_us)
 {
-    if (!mean_us) return fail(ADDRMS_ERR_INVALID_ARG, "mean_us is NULL");
-    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M <= 0 || d <= 0 || reps <= 0 || warmup < 0) return fail(ADDRMS_ERR_INVALID_ARG, "need M, d, reps > 0 and warmup >= 0");
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    addrms_cfg c{};
-    int st = resolve_cfg(cfg, M, d, dtype, &c, OP_SILUMUL);
-    if (st != ADDRMS_OK) return st;
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    SiluHarness h;
-    st = h.init(M, d, dtype, rotate != 0);
-    if (st != ADDRMS_OK) return st;
-    return h.measure(c, warmup, reps, mean_us);
+    return measure_on_device<SiluHarness>(cfg, M, d, dtype, 0.0f, warmup, reps, rotate, mean_us);
 }
 
-int silumul_table_lookup(int64_t M, int64_t d, int dtype, addrms_cfg* out)
-{
-    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
-    const int st = table_lookup(M, d, dtype, out, OP_SILUMUL);
-    return st == ADDRMS_OK ? st : fail(st, "no silu_and_mul table entry usable for M=%lld d=%lld dtype=%d",
-                                       (long long)M, (long long)d, dtype);
-}
+int silumul_table_lookup(int64_t M, int64_t d, int dtype, addrms_cfg* out) { return export_table_lookup(OP_SILUMUL, M, d, dtype, out); }
 
-int64_t silumul_algorithmic_bytes(int64_t M, int64_t d, int dtype)
-{
-    if (!dtype_valid(dtype, OP_SILUMUL)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (M < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and d > 0");
-    return algorithmic_bytes(OP_SILUMUL, M, d, dtype);
-}
+int64_t silumul_algorithmic_bytes(int64_t M, int64_t d, int dtype) { return export_algorithmic_bytes(OP_SILUMUL, M, d, dtype); }
 
 // ---- merge_attn_states -----------------------------------------------------------------
 
@@ -1202,126 +1138,52 @@ int mergestates_run(const void* v_a, const float* s_a, const void* v_b, const fl
     return launch_mergestates(f, c, v_a, s_a, v_b, s_b, v_out, s_out, rows, d, static_cast<hipStream_t>(stream));
 }
 
-int mergestates_default_cfg(int64_t d, int dtype, addrms_cfg* out)
-{
-    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
-    std::string why;
-    const int st = default_cfg(d, dtype, out, &why, OP_MERGE);
-    return st == ADDRMS_OK ? st : fail(st, "%s", why.c_str());
-}
+int mergestates_default_cfg(int64_t d, int dtype, addrms_cfg* out) { return export_default_cfg(OP_MERGE, d, dtype, out); }
 
 int mergestates_cfg_feasible(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, char* reason, size_t reason_len,
-                             addrms_resources* res)
+                         addrms_resources* res)
 {
-    if (reason && reason_len) reason[0] = '\0';
-    if (!cfg) return fail(ADDRMS_ERR_INVALID_ARG, "cfg is NULL");
-    const Feas f = check_cfg(*cfg, rows, d, dtype, OP_MERGE);
-    if (res) *res = f.res;
-    if (f.status != ADDRMS_OK) {
-        if (reason && reason_len) snprintf(reason, reason_len, "%s", f.reason.c_str());
-        return fail(f.status, "%s", f.reason.c_str());
-    }
-    return ADDRMS_OK;
+    return export_cfg_feasible(OP_MERGE, cfg, rows, d, dtype, reason, reason_len, res);
 }
 
 int64_t mergestates_enumerate_feasible(int64_t rows, int64_t d, int dtype, addrms_cfg* out, int64_t cap, int64_t* n_grid)
 {
-    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (rows < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "rows must be >= 0 and d > 0");
-    if (cap < 0 || (cap > 0 && !out)) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL with cap > 0");
-    std::vector<addrms_cfg> v;
-    enumerate(rows, d, dtype, &v, n_grid, nullptr, OP_MERGE);
-    const int64_t n = static_cast<int64_t>(v.size());
-    for (int64_t i = 0; i < std::min(n, cap); ++i) out[i] = v[i];
-    return n;
+    return export_enumerate_feasible(OP_MERGE, rows, d, dtype, out, cap, n_grid);
 }
 
-int mergestates_tune_with_backend(int64_t rows, int64_t d, int dtype, const addrms_budget* budget,
-                                  const addrms_backend* backend, addrms_cfg* out_cfg, addrms_tune_report* report)
+int mergestates_tune_with_backend(int64_t rows, int64_t d, int dtype, const addrms_budget* budget, const addrms_backend* backend,
+                              addrms_cfg* out_cfg, addrms_tune_report* report)
 {
     if (!backend) return fail(ADDRMS_ERR_INVALID_ARG, "backend is NULL");
     return run_search(rows, d, dtype, budget, *backend, out_cfg, report, OP_MERGE);
 }
 
 int mergestates_tune(int64_t rows, int64_t d, int dtype, const addrms_budget* budget, addrms_cfg* out_cfg,
-                     addrms_tune_report* report)
+                 addrms_tune_report* report)
 {
-    if (!out_cfg) return fail(ADDRMS_ERR_INVALID_ARG, "out_cfg is NULL");
-    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (rows <= 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "tuning needs rows > 0 and d > 0");
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    addrms_cfg dflt{};
-    std::string why;
-    int st = default_cfg(d, dtype, &dflt, &why, OP_MERGE);
-    if (st != ADDRMS_OK) return fail(st, "%s", why.c_str());
-    MergeHarness h;
-    st = h.init(rows, d, dtype, true);
-    if (st != ADDRMS_OK) return st;
-    st = h.make_reference(dflt);
-    if (st != ADDRMS_OK) return st;
-    addrms_backend be{&h, merge_backend_validate, merge_backend_measure};
-    addrms_tune_report local{};
-    st = run_search(rows, d, dtype, budget, be, out_cfg, &local, OP_MERGE);
-    if (st != ADDRMS_OK) return st;
-    if (report) *report = local;
-    return table_insert(rows, d, dtype, *out_cfg, local.best_us, OP_MERGE);
+    return tune_on_device<MergeHarness>(rows, d, dtype, budget, out_cfg, report);
 }
 
 int mergestates_select_general(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
-                               addrms_cfg* out_general, addrms_general_report* report)
+                           addrms_cfg* out_general, addrms_general_report* report)
 {
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    const int st = check_shapes(shapes, n);
-    if (st != ADDRMS_OK) return st;
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    addrms_backend_factory fac{nullptr, op_factory_open<MergeHarness, OP_MERGE, merge_backend_validate, merge_backend_measure>,
-                               op_factory_close<MergeHarness>};
-    return run_select_general(shapes, n, dtype, budget, fac, true, out_general, report, OP_MERGE);
+    return select_general_on_device<MergeHarness>(shapes, n, dtype, budget, out_general, report);
 }
 
 int mergestates_tune_rounds(const addrms_shape* shapes, int32_t n, int dtype, const addrms_budget* budget,
-                            addrms_cfg* out_general, addrms_rounds_report* report)
+                        addrms_cfg* out_general, addrms_rounds_report* report)
 {
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    const int st = check_shapes(shapes, n);
-    if (st != ADDRMS_OK) return st;
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    addrms_backend_factory fac{nullptr, op_factory_open<MergeHarness, OP_MERGE, merge_backend_validate, merge_backend_measure>,
-                               op_factory_close<MergeHarness>};
-    return run_tune_rounds(shapes, n, dtype, budget, fac, true, out_general, report, OP_MERGE);
+    return tune_rounds_on_device<MergeHarness>(shapes, n, dtype, budget, out_general, report);
 }
 
 int mergestates_measure(const addrms_cfg* cfg, int64_t rows, int64_t d, int dtype, int warmup, int reps, int rotate,
-                        double* mean_us)
+                    double* mean_us)
 {
-    if (!mean_us) return fail(ADDRMS_ERR_INVALID_ARG, "mean_us is NULL");
-    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (rows <= 0 || d <= 0 || reps <= 0 || warmup < 0) return fail(ADDRMS_ERR_INVALID_ARG, "need rows, d, reps > 0 and warmup >= 0");
-    if (!dispatch_consistent()) return fail(ADDRMS_ERR_INVALID_ARG, "library was built with inconsistent kernel tables");
-    addrms_cfg c{};
-    int st = resolve_cfg(cfg, rows, d, dtype, &c, OP_MERGE);
-    if (st != ADDRMS_OK) return st;
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    MergeHarness h;
-    st = h.init(rows, d, dtype, rotate != 0);
-    if (st != ADDRMS_OK) return st;
-    return h.measure(c, warmup, reps, mean_us);
+    return measure_on_device<MergeHarness>(cfg, rows, d, dtype, 0.0f, warmup, reps, rotate, mean_us);
 }
 
-int mergestates_table_lookup(int64_t rows, int64_t d, int dtype, addrms_cfg* out)
-{
-    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
-    const int st = table_lookup(rows, d, dtype, out, OP_MERGE);
-    return st == ADDRMS_OK ? st : fail(st, "no merge_attn_states table entry usable for rows=%lld d=%lld dtype=%d",
-                                       (long long)rows, (long long)d, dtype);
-}
+int mergestates_table_lookup(int64_t rows, int64_t d, int dtype, addrms_cfg* out) { return export_table_lookup(OP_MERGE, rows, d, dtype, out); }
 
-int64_t mergestates_algorithmic_bytes(int64_t rows, int64_t d, int dtype)
-{
-    if (!dtype_valid(dtype, OP_MERGE)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
-    if (rows < 0 || d <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "rows must be >= 0 and d > 0");
-    return algorithmic_bytes(OP_MERGE, rows, d, dtype);
-}
+int64_t mergestates_algorithmic_bytes(int64_t rows, int64_t d, int dtype) { return export_algorithmic_bytes(OP_MERGE, rows, d, dtype); }
 
 }  // extern "C"

@@ -84,13 +84,7 @@ int addrms_table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg* cfg, 
     return table_insert(M, N, dtype, *cfg, mean_us, OP_ADDRMS);
 }
 
-int addrms_table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out)
-{
-    if (!out) return fail(ADDRMS_ERR_INVALID_ARG, "out is NULL");
-    const int st = table_lookup(M, N, dtype, out);
-    return st == ADDRMS_OK ? st : fail(st, "no table entry usable for M=%lld N=%lld dtype=%d",
-                                       (long long)M, (long long)N, dtype);
-}
+int addrms_table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out) { return export_table_lookup(OP_ADDRMS, M, N, dtype, out); }
 
 int64_t addrms_table_size(void)
 {
