@@ -54,11 +54,13 @@ def probe_us(wl, reps=50) -> float:
         return (v + align - 1) // align * align
 
     stride = up(nx) + up(nr) + 2 * align
-    nsets = int(max(2, min(32, -(-2 * (288 << 20) // (nx + nr)))))
+    nsets = int(max(2, min(32, -(-4 * (288 << 20) // (nx + nr)))))
     pool = torch.zeros(stride * nsets + align, dtype=torch.uint8, device="cuda")
     base = (-pool.data_ptr()) % align
-    xs = [pool[base + i * stride: base + i * stride + nx] for i in range(nsets)]
-    rs = [pool[base + i * stride + up(nx) + skew: base + i * stride + up(nx) + skew + nr] for i in range(nsets)]
+    xt, rt = W.x_torch_dtype(wl.dtype), W.r_torch_dtype(wl.dtype)
+    xs = [pool[base + i * stride: base + i * stride + nx].view(xt) for i in range(nsets)]
+    rs = [pool[base + i * stride + up(nx) + skew: base + i * stride + up(nx) + skew + nr].view(rt)
+          for i in range(nsets)]
     for i in range(10):
         B.addrms_stream_probe(xs[i % nsets], rs[i % nsets], wl.M, wl.N, wl.dtype)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -121,6 +123,9 @@ def main(argv=None) -> int:
                     help="also tune rows beyond the register row cache (LDS-extended cache or two-pass form)")
     ap.add_argument("--graph-decode", action="store_true",
                     help="decode shapes: per-launch time of a chain of launches issued eagerly vs replayed from a HIP graph")
+    ap.add_argument("--row-scan", action="store_true",
+                    help="time against the number of rows for N = 1000 and N = 1024 (fp16 x, fp32 residual): separates the fixed "
+                         "cost of a launch from the per-row rate, and rows that are whole cache lines from rows that are not")
     ap.add_argument("--audit", action="store_true",
                     help="time what the deriver's efficiency rules prune beside what they retain (three shapes)")
     a = ap.parse_args(argv)
@@ -129,7 +134,7 @@ def main(argv=None) -> int:
         return 2
     B.addrms_table_clear()
     print("| workload | M x N | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tokens/s | probe GB/s | "
-          "tuned cfg (vec, threads/row, rows/wg, reduce, unroll, flags, cap) | feasible | timed | search ms |")
+          "tuned cfg (vec, threads/row, rows/wg, reduce, unroll, flags, cap, walk) | feasible | timed | search ms |")
     print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for wl in shapes():
         nbytes = B.addrms_algorithmic_bytes(wl.M, wl.N, wl.dtype)
@@ -192,7 +197,8 @@ def main(argv=None) -> int:
                       f"{rep.default_us[i] / rep.general_us[i]:.3f} | {rep.default_us[i] / rep.specialized_us[i]:.3f} | "
                       f"{rep.specialized[i].as_tuple()} |", flush=True)
     if a.long_rows:
-        print("\nRows beyond the register row cache (flags 16: cache continued in LDS, one pass; flags 8: two passes), tuned vs default:\n")
+        print("\nRows beyond the register row cache (flags 16: cache continued in LDS, one pass; flags 8: two passes; flags 24: "
+              "hybrid, only what fits neither registers nor LDS is read twice), tuned vs default:\n")
         print("| M x N | dtype | default us | tuned us | speedup | tuned GB/s (algorithmic) | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
         print("|---|---|---|---|---|---|---|---|---|---|---|")
         for M, N, dtype in ((4096, 40960, "bf16"), (2048, 65536, "bf16"), (1024, 131072, "bf16"),
@@ -205,6 +211,27 @@ def main(argv=None) -> int:
             print(f"| {M} x {N} | {dtype} | {rep.default_us:.1f} | {rep.best_us:.1f} | {rep.default_us / rep.best_us:.3f} | "
                   f"{gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | {cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | "
                   f"{wall:.0f} |", flush=True)
+    if a.row_scan:
+        print("\nTime against the number of rows (fp16 x and weight, fp32 residual; tuned per shape): t = t0 + M * slope by "
+              "least squares; t0 is what a launch costs before any row streams, bytes per row / slope the rate the rows "
+              "stream at:\n")
+        print("| N | M | tuned us | GB/s | % of 8 TB/s | tuned cfg |")
+        print("|---|---|---|---|---|---|")
+        for N in (1000, 1024):
+            pts = []
+            for M in (8192, 16384, 32768, 65536):
+                nbytes = B.addrms_algorithmic_bytes(M, N, "fp16_res32")
+                cfg, rep = B.addrms_tune(M, N, "fp16_res32", B.make_budget())
+                pts.append((M, rep.best_us))
+                print(f"| {N} | {M} | {rep.best_us:.2f} | {nbytes / rep.best_us * 1e-3:.0f} | "
+                      f"{nbytes / rep.best_us * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | {cfg.as_tuple()} |", flush=True)
+            n = len(pts)
+            sx, sy = sum(p[0] for p in pts), sum(p[1] for p in pts)
+            sxx, sxy = sum(p[0] * p[0] for p in pts), sum(p[0] * p[1] for p in pts)
+            slope = (n * sxy - sx * sy) / (n * sxx - sx * sx)
+            t0 = (sy - slope * sx) / n
+            print(f"| {N} | fit | t0 = {t0:.2f} us | {12 * N / slope * 1e-3:.0f} GB/s asymptotic | "
+                  f"{12 * N / slope * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | slope {slope * 1e3:.3f} ns per row |", flush=True)
     if a.graph_decode:
         print("\nDecode shapes, chain of 64 launches, tuned cfg: microseconds per launch issued eagerly vs from a HIP graph:\n")
         print("| M x N | cfg | eager us | graph us |")

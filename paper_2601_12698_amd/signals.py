@@ -365,6 +365,10 @@ def main(argv=None) -> int:
     ap.add_argument("--child-probe", default=None, help="(internal) run the calibration kernel of a spec file")
     ap.add_argument("--traffic-report", default=None, metavar="PATH",
                     help="measure HBM traffic of the tuned and default cfgs of the benchmark workloads and write the table")
+    ap.add_argument("--counters", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
+                    help="collect the default counter passes for the cfgs given with --cfgs and print one JSON record each")
+    ap.add_argument("--cfgs", default=None,
+                    help="semicolon-separated cfgs for --counters: vec,threads_per_row,rows_per_wg,reduce,unroll,flags,cap,walk")
     ap.add_argument("--stage-tune", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
                     help="(internal) run one search in this process and print its result as JSON")
     ap.add_argument("--stage-table", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
@@ -382,6 +386,15 @@ def main(argv=None) -> int:
         return child_main(a.child)
     if a.child_probe:
         return child_probe_main(a.child_probe)
+    if a.counters:
+        cfgs = [B.make_cfg(*[int(v) for v in t.split(",")]) for t in (a.cfgs or "").split(";") if t.strip()]
+        if not cfgs:
+            ap.error("--counters needs --cfgs")
+        m, n, dt = a.counters
+        for c, rec in zip(cfgs, collect(cfgs, int(m), int(n), dt, a.eps)):
+            print(json.dumps({"cfg": list(c.as_tuple()), "counters": {k: round(v, 3) for k, v in rec["counters"].items()},
+                              "derived": {k: round(v, 5) for k, v in rec["derived"].items()}}))
+        return 0
     if a.traffic_report:
         for row in traffic_report(a.traffic_report):
             print(json.dumps(row))
