@@ -19,7 +19,10 @@ is reported, not timed as steps).  Then, for the headline workload:
     timed with events, and the median block of each (`interleaved`): clock or thermal drift
     hits both alike and a slow first block does not decide the ratio;
   * the library's copy-like calibration kernel over the same buffers (`copy_probe`): the
-    same bytes with none of the arithmetic, the practical ceiling of this traffic pattern.
+    same bytes with none of the arithmetic, the practical ceiling of this traffic pattern;
+  * the same copy under the operator's constraint (`row_probe`): a workgroup holds a whole
+    row of both streams across a barrier before it writes anything, best over workgroup
+    sizes and occupancy caps -- what the row-wise reduction costs by its structure alone.
 All five benchmark configurations (smoke, prefill, the decode sweep, large prefill, the three
 odd-width mixed-precision shapes) are then tuned and timed by the library's own measurement
 harness (20 warm-up + 100 timed launches, twice, rotated buffers) and listed under `configs`.
@@ -174,6 +177,38 @@ class Runner:
             self.k += 1
             if fn(a[0], a[1], a[4], a[5], a[6], sp) != 0:
                 raise RuntimeError(self.B.addrms_last_error())
+
+    def row_probe(self, threads, wgs, count):
+        fn, args, n, sp = self.lib.addrms_row_probe, self.args, len(self.args), self.sp
+        for _ in range(count):
+            a = args[self.k % n]
+            self.k += 1
+            if fn(a[0], a[1], a[4], a[5], a[6], threads, wgs, sp) != 0:
+                raise RuntimeError(self.B.addrms_last_error())
+
+    def best_row_probe(self, row_x_bytes, launches=12):
+        """The row-holding copy over its workgroup sizes and occupancy caps: (us, threads, wgs per CU) of the fastest,
+        or None where a row is not a whole number of 16-byte pieces."""
+        if row_x_bytes % 16:
+            return None
+        pieces = row_x_bytes // 16
+        shapes = sorted({min(1024, -(-(-(-pieces // c)) // 64) * 64) for c in (1, 2, 3, 4, 6, 8, 12, 16)})
+        best = None
+        for t in shapes:
+            chunks = -(-pieces // t)
+            if chunks > 16 or (chunks - 1) * t >= pieces:
+                continue
+            for wgs in (1, 2, 3, 4, 6, 8):
+                if wgs * t > 2048:
+                    continue
+                _, ev = self.timed(lambda n: self.row_probe(t, wgs, n), 3, launches)
+                us = ev * 1e3 / launches
+                if best is None or us < best[0]:
+                    best = (us, t, wgs)
+        if best is None:
+            return None
+        _, ev = self.timed(lambda n: self.row_probe(best[1], best[2], n), 5, 4 * launches)     # the winner, timed longer
+        return (ev * 1e3 / (4 * launches), best[1], best[2])
 
     def timed(self, launch, warmup, steps):
         """`launch(count)` enqueues count steps.  Returns (wall seconds, event milliseconds) for exactly `steps`
@@ -374,6 +409,13 @@ def run_other_op(a, torch, lib, B, W):
         "default_cfg": {"cfg": default.as_dict(), "value": round(nbytes / (wall_d / a.steps) * 1e-9, 1),
                         "ms_per_step": round(wall_d / a.steps * 1e3, 6), "kernel_us": round(ev_d / a.steps * 1e3, 3)},
         "tuned_over_default": round(wall_d / wall_t, 4),
+        "row_probe": None if row_best is None else {
+            "what": "copy under the operator's constraint: one workgroup holds a whole row of both streams, meets at a "
+                    "barrier, then writes it back; no arithmetic; best over workgroup sizes and occupancy caps",
+            "value": round(probe_bytes / row_best[0] * 1e-3, 1), "unit": "GB/s", "kernel_us": round(row_best[0], 3),
+            "frac_of_peak": round(probe_bytes / row_best[0] * 1e-3 / HBM_PEAK_GBPS, 4),
+            "threads_per_row": row_best[1], "wgs_per_cu": row_best[2],
+            "operator_over_row_probe": round((nbytes / kernel_us) / (probe_bytes / row_best[0]), 4)},
         "tune": {"strategy": "given" if a.cfg else "exhaustive" if a.exhaustive else "guided",
                  "wall_ms": round(tune_wall * 1e3, 1), "n_grid": rep.n_grid, "n_feasible": rep.n_feasible,
                  "n_measured": rep.n_measured, "n_failed": rep.n_failed, "best_us": round(rep.best_us, 3),
@@ -462,6 +504,8 @@ def main():
     blocks, per_block = 7, max(5, min(a.steps, 40))
     blk_d, blk_t, blk_p = r.interleaved([run_default, run_tuned, r.probe], blocks, per_block)
 
+    row_best = r.best_row_probe(wl.N * W.x_bytes(wl.dtype))
+
     ms_step = wall_t / a.steps * 1e3
     value = nbytes / (wall_t / a.steps) * 1e-9
     kernel_us = ev_t / a.steps * 1e3
@@ -506,6 +550,13 @@ def main():
                        "frac_of_peak": round(probe_gbps / HBM_PEAK_GBPS, 4),
                        "operator_frac_of_probe": round(achieved / probe_gbps, 4),
                        "operator_frac_of_probe_interleaved": round((nbytes / med_t) / (probe_bytes / med_p), 4)},
+        "row_probe": None if row_best is None else {
+            "what": "copy under the operator's constraint: one workgroup holds a whole row of both streams, meets at a "
+                    "barrier, then writes it back; no arithmetic; best over workgroup sizes and occupancy caps",
+            "value": round(probe_bytes / row_best[0] * 1e-3, 1), "unit": "GB/s", "kernel_us": round(row_best[0], 3),
+            "frac_of_peak": round(probe_bytes / row_best[0] * 1e-3 / HBM_PEAK_GBPS, 4),
+            "threads_per_row": row_best[1], "wgs_per_cu": row_best[2],
+            "operator_over_row_probe": round((nbytes / kernel_us) / (probe_bytes / row_best[0]), 4)},
         "tune": {"strategy": "given" if a.cfg else "exhaustive" if a.exhaustive else "guided", "wall_ms": round(tune_wall * 1e3, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -459,6 +459,19 @@ int addrms_gate_probe_noalloc(const void* y, const void* y_ref, const void* resi
  * profiler's HBM counters).  Same argument meaning as addrms_run. */
 int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype, void* stream);
 
+/* The calibration traffic under the operator's constraint (Section 3.3: the organisation of registers and
+ * shared memory is what a row-wise normalisation has to tune): one workgroup of threads_per_row threads owns one
+ * row, every thread reads all its 16-byte pieces of both streams (at most 16 per stream), the workgroup meets at
+ * a barrier -- where the operator has its row sum -- and only then writes the row back (bitwise complemented),
+ * streaming cache policy.  wgs_per_cu > 0 caps the resident workgroups per CU through the dynamic LDS allocation
+ * (0: no cap).  Swept over threads_per_row and wgs_per_cu it measures what holding a row across a reduction
+ * costs by itself; the reports print its best beside the operator.  Same argument meaning and alignment rules
+ * as addrms_stream_probe, except that each row of x must be a multiple of 16 bytes.  Asynchronous on `stream`;
+ * allocates nothing.  threads_per_row must be a multiple of 64 in [64, 1024] that covers a row in at most 16
+ * pieces per thread without idle whole chunks, else ADDRMS_ERR_INFEASIBLE_CFG. */
+int addrms_row_probe(void* x, void* residual, int64_t M, int64_t N, int dtype, int threads_per_row, int wgs_per_cu,
+                     void* stream);
+
 /* What the HIP runtime on the current device reports for the kernel instance and
  * launch shape a cfg selects: registers and scratch from the loaded code object,
  * resident workgroups per CU from the runtime's occupancy query.  Fills vgprs

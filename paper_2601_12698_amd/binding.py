@@ -247,6 +247,7 @@ SIGNATURES = {
     "addrms_device_resources": (c_int, [POINTER(Cfg), c_int64, c_int64, c_int, POINTER(Resources)]),
     "addrms_rstd_probe": (c_int, [c_void_p, c_int64, c_int64, c_float, c_void_p, c_void_p]),
     "addrms_stream_probe": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, c_void_p]),
+    "addrms_row_probe": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_void_p]),
     "addrms_gate_probe": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int, ctypes.c_uint32, c_void_p,
                                   c_void_p]),
     "addrms_gate_probe_noalloc": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int, ctypes.c_uint32,
@@ -656,6 +657,16 @@ def addrms_stream_probe(x, residual, M: int, N: int, dtype, stream=None) -> None
     _expect_device_tensor("x", x, M * N, _X_ELEM[dt])
     _expect_device_tensor("residual", residual, M * N, _R_ELEM[dt])
     _check(load().addrms_stream_probe(_ptr(x), _ptr(residual), M, N, _dtype_id(dtype), _stream_ptr(stream, x)))
+
+
+def addrms_row_probe(x, residual, M: int, N: int, dtype, threads_per_row: int, wgs_per_cu: int = 0, stream=None) -> None:
+    dt = _dtype_id(dtype)
+    if dt not in _X_ELEM:
+        raise ValueError(f"unknown dtype {dtype!r}")
+    _expect_device_tensor("x", x, M * N, _X_ELEM[dt])
+    _expect_device_tensor("residual", residual, M * N, _R_ELEM[dt])
+    _check(load().addrms_row_probe(_ptr(x), _ptr(residual), M, N, dt, int(threads_per_row), int(wgs_per_cu),
+                                   _stream_ptr(stream, x)))
 
 
 class GateCounts(Structure):

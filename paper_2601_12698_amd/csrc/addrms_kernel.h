@@ -214,6 +214,20 @@ __device__ __forceinline__ double wave_group_sum(double v, uint32_t width)
     return v;
 }
 
+// Workgroup barrier that orders LDS traffic only.  The generic barrier also makes a wave wait until every global
+// load and store it has issued is complete: a workgroup would wait for the acknowledgement of the stores it has
+// just issued, and for loads it has issued ahead for its next row block, each time it reduces a row.  In these
+// kernels threads exchange data through LDS alone (no thread reads global memory that another thread of the same
+// launch wrote), so global traffic may stay in flight across the barrier.
+__device__ __forceinline__ void wg_sync_lds()
+{
+#ifdef ADDRMS_FULL_BARRIER
+    __syncthreads();
+#else
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#endif
+}
+
 // Row sum of per-thread partials; result identical in all threads of the row.
 // lds: RED_WAVE needs rows_per_wg * 16 doubles, RED_LDS needs one double per thread.
 __device__ __forceinline__ double row_sum(double part, int reduce, uint32_t tpr, uint32_t lane, uint32_t ry,
@@ -225,19 +239,19 @@ __device__ __forceinline__ double row_sum(double part, int reduce, uint32_t tpr,
         const uint32_t nw = tpr >> 6;
         double* slot = lds + ry * 16u;
         if ((lane & 63u) == 0u) slot[lane >> 6] = wsum;
-        __syncthreads();
+        wg_sync_lds();
         double total = slot[0];
         for (uint32_t i = 1; i < nw; ++i) total += slot[i];
         return total;
     }
     double* buf = lds + ry * tpr;
     buf[lane] = part;
-    __syncthreads();
+    wg_sync_lds();
     uint32_t cur = tpr;
     while (cur > 1u) {
         const uint32_t half = (cur + 1u) >> 1;
         if (lane + half < cur) buf[lane] += buf[lane + half];
-        __syncthreads();
+        wg_sync_lds();
         cur = half;
     }
     return buf[0];
@@ -837,7 +851,7 @@ __device__ __forceinline__ void addrms_span_body(void* __restrict__ xp, void* __
         }
         if (g + UNR < CPT) __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
+    wg_sync_lds();
     {
         const uint32_t wv = t >> 6, l = t & 63u, nw = T >> 6;
         for (uint32_t k = wv; k < rows_here; k += nw) {           // uniform over the wave
@@ -847,7 +861,7 @@ __device__ __forceinline__ void addrms_span_body(void* __restrict__ xp, void* __
             if (l == 0u) rstd_s[k] = rsqrt_to_f32(__builtin_fma(s, inv_n, static_cast<double>(eps)));
         }
     }
-    __syncthreads();
+    wg_sync_lds();
 
     uint32_t prow[CPT];
     raw_t<XB * VEC> wv_[CPT];

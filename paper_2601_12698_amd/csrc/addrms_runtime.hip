@@ -157,6 +157,52 @@ __global__ __launch_bounds__(256) void stream_probe_kernel(addrms::u32x4* a, add
     for (int k = 0; k < B_PER_A; ++k) __builtin_nontemporal_store(~vb[k], b + B_PER_A * i + k);
 }
 
+// The same traffic under the operator's constraint: a workgroup owns one whole row, every thread reads all its
+// 16-byte pieces of the row from both streams, the workgroup meets at a barrier (where the operator would have
+// its row sum), and only then is anything written.  No arithmetic beyond the complement.  What this kernel
+// reaches, over workgroup sizes and occupancy caps, is what holding a row across a reduction costs by itself.
+template <int CPT, int B_PER_A>
+__global__ __launch_bounds__(1024) void row_probe_kernel(addrms::u32x4* a, addrms::u32x4* b, long long M, unsigned pieces)
+{
+    const long long row = blockIdx.x;
+    if (row >= M) return;                                   // uniform over the workgroup
+    addrms::u32x4* ar = a + row * pieces;
+    addrms::u32x4* br = b + row * pieces * B_PER_A;
+    addrms::u32x4 va[CPT], vb[CPT][B_PER_A];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const unsigned p = static_cast<unsigned>(c) * blockDim.x + threadIdx.x;
+        const unsigned pc = p < pieces ? p : pieces - 1u;   // tail lanes re-read the last piece
+        va[c] = __builtin_nontemporal_load(ar + pc);
+#pragma unroll
+        for (int k = 0; k < B_PER_A; ++k) vb[c][k] = __builtin_nontemporal_load(br + B_PER_A * pc + k);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const unsigned p = static_cast<unsigned>(c) * blockDim.x + threadIdx.x;
+        if (p < pieces) {
+#pragma unroll
+            for (int k = 0; k < B_PER_A; ++k) __builtin_nontemporal_store(~vb[c][k], br + B_PER_A * p + k);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const unsigned p = static_cast<unsigned>(c) * blockDim.x + threadIdx.x;
+        if (p < pieces) __builtin_nontemporal_store(~va[c], ar + p);
+    }
+}
+
+template <int B_PER_A>
+static const void* row_probe_instance(int chunks, int* cpt_out)
+{
+#define ROW_PROBE_CASE(C) if (chunks <= C) { *cpt_out = C; return reinterpret_cast<const void*>(&row_probe_kernel<C, B_PER_A>); }
+    ROW_PROBE_CASE(1) ROW_PROBE_CASE(2) ROW_PROBE_CASE(3) ROW_PROBE_CASE(4) ROW_PROBE_CASE(6) ROW_PROBE_CASE(8)
+    ROW_PROBE_CASE(12) ROW_PROBE_CASE(16)
+#undef ROW_PROBE_CASE
+    return nullptr;
+}
+
 // Synthetic activations for the tuner's own buffers: a counter-based hash mapped
 // to a roughly unit-variance symmetric distribution (sum of four uniforms).
 __device__ __forceinline__ uint32_t mix32(uint32_t v)
@@ -969,6 +1015,45 @@ int addrms_stream_probe(void* x, void* residual, int64_t M, int64_t N, int dtype
     else
         return fail(ADDRMS_ERR_INVALID_ARG, "unexpected residual/x size ratio");
     HIP_TRY(hipGetLastError());
+    return ADDRMS_OK;
+}
+
+int addrms_row_probe(void* x, void* residual, int64_t M, int64_t N, int dtype, int threads_per_row, int wgs_per_cu,
+                     void* stream)
+{
+    if (!dtype_valid(dtype)) return fail(ADDRMS_ERR_UNSUPPORTED_DTYPE, "unsupported dtype %d", dtype);
+    if (M < 0 || N <= 0) return fail(ADDRMS_ERR_INVALID_ARG, "M must be >= 0 and N > 0");
+    if (M == 0) return ADDRMS_OK;
+    if (!x || !residual) return fail(ADDRMS_ERR_INVALID_ARG, "x and residual must not be NULL");
+    if (M > 0x7fffffffLL) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "one workgroup per row: M must fit a grid dimension");
+    const int64_t row_xb = N * x_bytes(dtype), row_rb = N * r_bytes(dtype);
+    if (row_xb % 16 != 0 || !aligned(x, 16) || !aligned(residual, 16))
+        return fail(ADDRMS_ERR_MISALIGNED, "the probe moves 16 bytes per lane: a row of x must be a multiple of 16 bytes "
+                    "and both bases 16-byte aligned");
+    if (threads_per_row < 64 || threads_per_row > 1024 || threads_per_row % 64 != 0)
+        return fail(ADDRMS_ERR_INVALID_ARG, "threads_per_row must be a multiple of 64 in [64, 1024]");
+    if (wgs_per_cu < 0 || wgs_per_cu > 16) return fail(ADDRMS_ERR_INVALID_ARG, "wgs_per_cu must be in [0, 16]");
+    const int64_t pieces = row_xb / 16;
+    const int64_t chunks = (pieces + threads_per_row - 1) / threads_per_row;
+    if (chunks > 16 || (chunks - 1) * threads_per_row >= pieces)
+        return fail(ADDRMS_ERR_INFEASIBLE_CFG, "threads_per_row must cover the row in at most 16 pieces per thread");
+    int cpt = 0;
+    const void* fn = nullptr;
+    if (row_rb == row_xb) fn = row_probe_instance<1>(static_cast<int>(chunks), &cpt);
+    else if (row_rb == 2 * row_xb) fn = row_probe_instance<2>(static_cast<int>(chunks), &cpt);
+    else return fail(ADDRMS_ERR_INVALID_ARG, "unexpected residual/x size ratio");
+    if (!fn) return fail(ADDRMS_ERR_INFEASIBLE_CFG, "no probe instance for %d pieces per thread", static_cast<int>(chunks));
+    // occupancy cap by LDS padding, as the operator's cfgs impose theirs
+    // (just more than would let one more workgroup fit)
+    const unsigned lds = wgs_per_cu > 0 ? static_cast<unsigned>(160 * 1024 / (wgs_per_cu + 1) / 1280 * 1280 + 1280) : 0u;
+    if (lds > 64u * 1024u) HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    addrms::u32x4* xa = static_cast<addrms::u32x4*>(x);
+    addrms::u32x4* ra = static_cast<addrms::u32x4*>(residual);
+    long long m = M;
+    unsigned np = static_cast<unsigned>(pieces);
+    void* args[] = {&xa, &ra, &m, &np};
+    HIP_TRY(hipLaunchKernel(fn, dim3(static_cast<unsigned>(M)), dim3(static_cast<unsigned>(threads_per_row)), args, lds,
+                            static_cast<hipStream_t>(stream)));
     return ADDRMS_OK;
 }
 
