@@ -370,7 +370,10 @@ int addrms_audit_rules_with_backend(int64_t M, int64_t N, int dtype, const addrm
  * in addrms_run) on (M, N, dtype) over `reps` launches after `warmup`, on
  * library-allocated synthetic buffers.  rotate != 0 cycles through enough
  * buffer sets to exceed the last-level caches; rotate == 0 reuses one set
- * (a cache-warm figure).  Blocking; allocates and frees device memory. */
+ * (a cache-warm figure).  A batch shorter than 30 ms is preceded by that much
+ * untimed running of the same kernel and then timed again, so that a call made
+ * on an idle device does not time rising clocks.  Blocking; allocates and frees
+ * device memory. */
 int addrms_measure(const addrms_cfg* cfg, int64_t M, int64_t N, int dtype, float eps,
                    int warmup, int reps, int rotate, double* mean_us);
 

@@ -40,13 +40,20 @@ def shapes():
         yield W.ODD_WIDTH.with_cols(n)
 
 
-def probe_us(wl, reps=50) -> float:
-    """Mean time of the calibration kernel over rotated buffers (0 if the shape does not meet
-    its 16-byte granularity).  Buffers are carved from one pool the way the tuner's harness and
-    bench.py lay theirs out: 64 KiB-aligned, the residual skewed by 4 KiB against x."""
+class _Shape:
+    def __init__(self, M, N, dtype):
+        self.M, self.N, self.dtype = M, N, dtype
+
+
+def probes_us(wl, reps=50):
+    """Mean times of the two calibration kernels over rotated buffers: the plain copy (0 if the shape does not meet
+    its 16-byte granularity) and the best row-holding copy over workgroup sizes and occupancy caps, as
+    (us, threads per row, workgroups per CU) or None where a row is not whole 16-byte pieces or is too long.
+    Buffers are carved from one pool the way the tuner's harness and bench.py lay theirs out: 64 KiB-aligned, the
+    residual skewed by 4 KiB against x."""
     xb, rb = W.x_bytes(wl.dtype), W.r_bytes(wl.dtype)
     if (wl.M * wl.N * xb) % 16:
-        return 0.0
+        return 0.0, None
     nx, nr = wl.M * wl.N * xb, wl.M * wl.N * rb
     align, skew = 1 << 16, 4096
 
@@ -61,16 +68,41 @@ def probe_us(wl, reps=50) -> float:
     xs = [pool[base + i * stride: base + i * stride + nx].view(xt) for i in range(nsets)]
     rs = [pool[base + i * stride + up(nx) + skew: base + i * stride + up(nx) + skew + nr].view(rt)
           for i in range(nsets)]
-    for i in range(10):
-        B.addrms_stream_probe(xs[i % nsets], rs[i % nsets], wl.M, wl.N, wl.dtype)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for i in range(reps):
-        B.addrms_stream_probe(xs[i % nsets], rs[i % nsets], wl.M, wl.N, wl.dtype)
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / reps
+
+    def timed(launch, warm, n):
+        for i in range(warm):
+            launch(xs[i % nsets], rs[i % nsets])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            launch(xs[i % nsets], rs[i % nsets])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    plain = timed(lambda x, r: B.addrms_stream_probe(x, r, wl.M, wl.N, wl.dtype), 10, reps)
+    best = None
+    if (wl.N * xb) % 16 == 0:
+        pieces = wl.N * xb // 16
+        for t in sorted({min(1024, -(-(-(-pieces // c)) // 64) * 64) for c in (1, 2, 3, 4, 6, 8, 12, 16)}):
+            chunks = -(-pieces // t)
+            if chunks > 16 or (chunks - 1) * t >= pieces:
+                continue
+            for wgs in (1, 2, 3, 4, 6, 8):
+                if wgs * t > 2048:
+                    continue
+                us = timed(lambda x, r: B.addrms_row_probe(x, r, wl.M, wl.N, wl.dtype, t, wgs), 3, max(6, reps // 4))
+                if best is None or us < best[0]:
+                    best = (us, t, wgs)
+        if best is not None:
+            best = (timed(lambda x, r: B.addrms_row_probe(x, r, wl.M, wl.N, wl.dtype, best[1], best[2]), 5, reps),
+                    best[1], best[2])
+    return plain, best
+
+
+def _row_cell(best, moved):
+    return "-" if best is None else f"{moved / best[0] * 1e-3:.0f} ({best[1]} x {best[2]})"
 
 
 def graph_vs_eager_us(wl, cfg, chain=64, laps=20, nsets=8):
@@ -133,30 +165,36 @@ def main(argv=None) -> int:
         print("needs a GPU", file=sys.stderr)
         return 2
     B.addrms_table_clear()
-    print("| workload | M x N | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tokens/s | probe GB/s | "
+    print("| workload | M x N | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tokens/s | copy GB/s | "
+          "row-holding copy GB/s (threads x workgroups per CU) | "
           "tuned cfg (vec, threads/row, rows/wg, reduce, unroll, flags, cap, walk) | feasible | timed | search ms |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     for wl in shapes():
         nbytes = B.addrms_algorithmic_bytes(wl.M, wl.N, wl.dtype)
         t0 = time.perf_counter()
         cfg, rep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
         wall = (time.perf_counter() - t0) * 1e3
-        p = probe_us(wl)
+        p, rowp = probes_us(wl)
         moved = 2 * wl.M * wl.N * (W.x_bytes(wl.dtype) + W.r_bytes(wl.dtype))
         gbps = nbytes / rep.best_us * 1e-3
         print(f"| {wl.name} | {wl.M} x {wl.N} | {rep.default_us:.2f} | {rep.best_us:.2f} | "
               f"{rep.default_us / rep.best_us:.3f} | {gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | "
-              f"{wl.M / rep.best_us * 1e6:.3g} | {(moved / p * 1e-3) if p else float('nan'):.0f} | "
+              f"{wl.M / rep.best_us * 1e6:.3g} | {(moved / p * 1e-3) if p else float('nan'):.0f} | {_row_cell(rowp, moved)} | "
               f"{cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
     if a.exhaustive_prefill:
         wl = W.PREFILL
         g, grep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
         e, erep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps, strategy=B.SEARCH_EXHAUSTIVE))
-        tg = min(B.addrms_measure(g, wl.M, wl.N, wl.dtype) for _ in range(3))
-        te = min(B.addrms_measure(e, wl.M, wl.N, wl.dtype) for _ in range(3))
-        print(f"\nprefill: guided {g.as_tuple()} {tg:.2f} us after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
-              f"exhaustive {e.as_tuple()} {te:.2f} us after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms; "
-              f"regret {tg / te:.4f}")
+        tgs, tes = [], []
+        for _ in range(5):                      # alternating, so that drift after the long search hits both alike
+            tgs.append(B.addrms_measure(g, wl.M, wl.N, wl.dtype))
+            tes.append(B.addrms_measure(e, wl.M, wl.N, wl.dtype))
+        tg, te = sorted(tgs)[2], sorted(tes)[2]
+        print(f"\nprefill: guided {g.as_tuple()} after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
+              f"exhaustive {e.as_tuple()} after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms.  "
+              f"Confirmed inside their own searches (2 x (20 + 100) launches): {grep.best_us:.2f} us against {erep.best_us:.2f} us, "
+              f"regret {grep.best_us / erep.best_us:.4f}; measured afterwards in alternation on newly allocated buffers "
+              f"(median of 5 each): {tg:.2f} us against {te:.2f} us, regret {tg / te:.4f}")
     if a.silumul:
         print("\nsilu_and_mul (out[i,j] = silu(x[i,j]) * x[i,d+j]), tuned vs default:\n")
         print("| workload | M x d | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
@@ -199,8 +237,9 @@ def main(argv=None) -> int:
     if a.long_rows:
         print("\nRows beyond the register row cache (flags 16: cache continued in LDS, one pass; flags 8: two passes; flags 24: "
               "hybrid, only what fits neither registers nor LDS is read twice), tuned vs default:\n")
-        print("| M x N | dtype | default us | tuned us | speedup | tuned GB/s (algorithmic) | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
-        print("|---|---|---|---|---|---|---|---|---|---|---|")
+        print("| M x N | dtype | default us | tuned us | speedup | tuned GB/s (algorithmic) | % of 8 TB/s | copy GB/s | "
+              "row-holding copy GB/s (threads x workgroups per CU) | tuned cfg | feasible | timed | search ms |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
         for M, N, dtype in ((4096, 40960, "bf16"), (2048, 65536, "bf16"), (1024, 131072, "bf16"),
                             (2048, 49152, "fp16_res32"), (512, 262144, "fp32")):
             nbytes = B.addrms_algorithmic_bytes(M, N, dtype)
@@ -208,8 +247,10 @@ def main(argv=None) -> int:
             cfg, rep = B.addrms_tune(M, N, dtype, B.make_budget())
             wall = (time.perf_counter() - t0) * 1e3
             gbps = nbytes / rep.best_us * 1e-3
+            p, rowp = probes_us(_Shape(M, N, dtype), reps=24)
+            moved = 2 * M * N * (W.x_bytes(dtype) + W.r_bytes(dtype))
             print(f"| {M} x {N} | {dtype} | {rep.default_us:.1f} | {rep.best_us:.1f} | {rep.default_us / rep.best_us:.3f} | "
-                  f"{gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | {cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | "
+                  f"{gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | {moved / p * 1e-3:.0f} | {_row_cell(rowp, moved)} | {cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | "
                   f"{wall:.0f} |", flush=True)
     if a.row_scan:
         print("\nTime against the number of rows (fp16 x and weight, fp32 residual; tuned per shape): t = t0 + M * slope by "
