@@ -116,19 +116,37 @@ int run_select_general(const addrms_shape* shapes, int n, int dtype, const addrm
     }
     rep.n_pool = static_cast<int32_t>(cands.size());
 
-    // ---- time every candidate on every shape; defaults again with the same protocol
+    // ---- time every candidate on every shape; defaults again with the same protocol.  Three rounds, the default
+    // and every candidate once per round, each cfg keeping its fastest round: on launch-bound shapes one batch of a
+    // 3 us kernel scatters by several per cent, and a default timed once beside candidates timed once made the
+    // same cfg come out 8 % apart from itself.
+    constexpr int kRounds = 3;
     std::vector<std::vector<double>> us(cands.size(), std::vector<double>(n, -1.0));
     for (int i = 0; i < n; ++i) {
         OpenBackend ob(factory);
         if (ob.start(shapes[i].M, shapes[i].N, dtype) != 0)
             return fail(ADDRMS_ERR_HIP, "could not open a measurement backend for shape %d", i);
-        double d = 0.0;
-        if (ob.be.measure(ob.be.user, &defaults[i], warmup, reps, &d) == 0 && d > 0.0) rep.default_us[i] = d;
-        for (size_t k = 0; k < cands.size(); ++k) {
-            if (!b.skip_validation && ob.be.validate && ob.be.validate(ob.be.user, &cands[k]) != 0) continue;
-            double t = 0.0;
-            if (ob.be.measure(ob.be.user, &cands[k], warmup, reps, &t) == 0 && t > 0.0) us[k][i] = t;
+        std::vector<char> usable(cands.size(), 1);
+        double dbest = -1.0;
+        for (int round = 0; round < kRounds; ++round) {
+            double d = 0.0;
+            if (ob.be.measure(ob.be.user, &defaults[i], warmup, reps, &d) == 0 && d > 0.0 && (dbest < 0.0 || d < dbest)) dbest = d;
+            for (size_t k = 0; k < cands.size(); ++k) {
+                if (!usable[k]) continue;
+                if (round == 0 && !b.skip_validation && ob.be.validate && ob.be.validate(ob.be.user, &cands[k]) != 0) {
+                    usable[k] = 0;
+                    continue;
+                }
+                double t = 0.0;
+                if (ob.be.measure(ob.be.user, &cands[k], warmup, reps, &t) == 0 && t > 0.0) {
+                    if (us[k][i] < 0.0 || t < us[k][i]) us[k][i] = t;
+                } else {
+                    usable[k] = 0;
+                    us[k][i] = -1.0;
+                }
+            }
         }
+        if (dbest > 0.0) rep.default_us[i] = dbest;
     }
     int win = -1;
     double win_score = 0.0;
