@@ -57,9 +57,27 @@ FETCH_UNIT_BYTES = 65536.0 * 1024.0 / 32779.0
 WRITE_UNIT_BYTES = 1024.0
 
 
-def _spec(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float) -> dict:
+def _spec(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float, probes: Sequence[dict] = ()) -> dict:
     return {"M": M, "N": N, "dtype": dtype, "eps": eps, "launches": LAUNCHES_PER_CFG,
-            "cfgs": [c.as_dict() for c in cfgs]}
+            "cfgs": [c.as_dict() for c in cfgs], "probes": list(probes)}
+
+
+def parse_probes(text: str) -> List[dict]:
+    """"copy;rows:256,6" -> the plain calibration copy, then the row-holding copy with 256 threads per row and
+    at most six workgroups per CU."""
+    out = []
+    for t in (text or "").split(";"):
+        t = t.strip()
+        if not t:
+            continue
+        if t == "copy":
+            out.append({"kind": "copy"})
+        elif t.startswith("rows:"):
+            threads, wgs = (int(v) for v in t[5:].split(","))
+            out.append({"kind": "rows", "threads": threads, "wgs": wgs})
+        else:
+            raise ValueError(f"unknown probe {t!r}")
+    return out
 
 
 def child_main(spec_path: str) -> int:
@@ -80,6 +98,14 @@ def child_main(spec_path: str) -> int:
         cfg = B.make_cfg(**d)
         for _ in range(spec["launches"]):
             B.addrms_run(xs[k % nsets], rs[k % nsets], w, wl.eps, M, N, dtype, cfg)
+            k += 1
+        torch.cuda.synchronize()
+    for pr in spec.get("probes", []):
+        for _ in range(spec["launches"]):
+            if pr["kind"] == "copy":
+                B.addrms_stream_probe(xs[k % nsets], rs[k % nsets], M, N, dtype)
+            else:
+                B.addrms_row_probe(xs[k % nsets], rs[k % nsets], M, N, dtype, pr["threads"], pr["wgs"])
             k += 1
         torch.cuda.synchronize()
     return 0
@@ -115,8 +141,9 @@ def _read_counter_csv(outdir: str) -> List[dict]:
 
 def collect(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float = 1e-6,
             passes: Sequence[Sequence[str]] = DEFAULT_PASSES, workdir: Optional[str] = None,
-            timeout_s: int = 180) -> List[dict]:
-    """Counter values per configuration: ``[{cfg, counters: {name: mean}, derived: {...}}, ...]``."""
+            timeout_s: int = 180, probes: Sequence[dict] = ()) -> List[dict]:
+    """Counter values per configuration: ``[{cfg, counters: {name: mean}, derived: {...}}, ...]``, followed by one
+    record ``{probe, counters, derived}`` per calibration kernel asked for in `probes` (see parse_probes)."""
     rocprof = shutil.which("rocprofv3")
     if rocprof is None:
         raise RuntimeError("rocprofv3 is not on PATH")
@@ -124,12 +151,13 @@ def collect(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float = 1e-6
     os.makedirs(tmp, exist_ok=True)
     spec_path = os.path.join(tmp, "spec.json")
     with open(spec_path, "w") as f:
-        json.dump(_spec(cfgs, M, N, dtype, eps), f)
+        json.dump(_spec(cfgs, M, N, dtype, eps, probes), f)
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     env = dict(os.environ)
     env["PYTHONPATH"] = root + os.pathsep + env.get("PYTHONPATH", "")
     env.setdefault("TMPDIR", "/tmp")
-    records = [{"cfg": c.as_dict(), "counters": {}} for c in cfgs]
+    records = [{"cfg": c.as_dict(), "counters": {}} for c in cfgs] + [{"probe": dict(p), "counters": {}} for p in probes]
+    ours = ("addrms_k_", "stream_probe_kernel", "row_probe_kernel")
     for i, names in enumerate(passes):
         outdir = os.path.join(tmp, f"pass{i}")
         cmd = [rocprof, "--pmc", *names, "--output-format", "csv", "-d", outdir, "-o", "sig", "--",
@@ -138,14 +166,14 @@ def collect(cfgs: Sequence[B.Cfg], M: int, N: int, dtype: str, eps: float = 1e-6
                            timeout=timeout_s)
         if r.returncode != 0:
             raise RuntimeError(f"rocprofv3 pass {names} failed ({r.returncode}):\n{r.stdout[-2000:]}")
-        rows = [x for x in _read_counter_csv(outdir) if x["Kernel_Name"].startswith("addrms_k_")]
+        rows = [x for x in _read_counter_csv(outdir) if any(tag in x["Kernel_Name"] for tag in ours)]
         by_counter: Dict[str, List[float]] = {}
         for x in rows:
             by_counter.setdefault(x["Counter_Name"], []).append(float(x["Counter_Value"]))
         for name, vals in by_counter.items():
-            if len(vals) != LAUNCHES_PER_CFG * len(cfgs):
-                raise RuntimeError(f"{name}: expected {LAUNCHES_PER_CFG * len(cfgs)} dispatches, saw {len(vals)}")
-            for j in range(len(cfgs)):
+            if len(vals) != LAUNCHES_PER_CFG * len(records):
+                raise RuntimeError(f"{name}: expected {LAUNCHES_PER_CFG * len(records)} dispatches, saw {len(vals)}")
+            for j in range(len(records)):
                 chunk = vals[j * LAUNCHES_PER_CFG + 1:(j + 1) * LAUNCHES_PER_CFG]
                 records[j]["counters"][name] = sum(chunk) / len(chunk)
     from . import workloads as W
@@ -369,6 +397,9 @@ def main(argv=None) -> int:
                     help="collect the default counter passes for the cfgs given with --cfgs and print one JSON record each")
     ap.add_argument("--cfgs", default=None,
                     help="semicolon-separated cfgs for --counters: vec,threads_per_row,rows_per_wg,reduce,unroll,flags,cap,walk")
+    ap.add_argument("--probes", default=None,
+                    help="calibration kernels to count beside the cfgs of --counters: 'copy' and/or 'rows:THREADS,WGS_PER_CU', "
+                         "semicolon-separated")
     ap.add_argument("--stage-tune", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
                     help="(internal) run one search in this process and print its result as JSON")
     ap.add_argument("--stage-table", nargs=3, metavar=("M", "N", "DTYPE"), default=None,
@@ -391,8 +422,9 @@ def main(argv=None) -> int:
         if not cfgs:
             ap.error("--counters needs --cfgs")
         m, n, dt = a.counters
-        for c, rec in zip(cfgs, collect(cfgs, int(m), int(n), dt, a.eps)):
-            print(json.dumps({"cfg": list(c.as_tuple()), "counters": {k: round(v, 3) for k, v in rec["counters"].items()},
+        for j, rec in enumerate(collect(cfgs, int(m), int(n), dt, a.eps, probes=parse_probes(a.probes))):
+            what = {"cfg": list(cfgs[j].as_tuple())} if j < len(cfgs) else {"probe": rec["probe"]}
+            print(json.dumps({**what, "counters": {k: round(v, 3) for k, v in rec["counters"].items()},
                               "derived": {k: round(v, 5) for k, v in rec["derived"].items()}}))
         return 0
     if a.traffic_report:
