@@ -410,7 +410,11 @@ void addrms_table_clear(void);
  * load replaces nothing on failure: a missing or malformed file, one written for another
  * architecture or by a library of another major.minor version (whose kernel instances, and
  * with them feasibility and timings, differ) returns ADDRMS_ERR_IO and leaves the table as
- * it was. */
+ * it was.  save writes beside the target and renames over it.
+ * Tune cache: if the environment variable ADDRMS_TABLE_FILE names a file, the library loads it once, before the
+ * table is first consulted or extended (addrms_run with cfg == NULL, a lookup, an insertion, the end of a tuning
+ * call), and rewrites it after every insertion, so that what one process tuned is what the next one runs.  A
+ * file that exists but does not load is neither read nor overwritten. */
 int addrms_table_save(const char* path);
 int addrms_table_load(const char* path);
 

@@ -3,10 +3,12 @@
 // were never tuned, and a plain-text file form so a tuning run can be reused.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <map>
 #include <mutex>
+#include <string>
 #include <tuple>
 
 #include "addrms_internal.h"
@@ -23,17 +25,40 @@ static std::map<Key, Entry>& table()
     return t;
 }
 
+// The table file named by the environment variable ADDRMS_TABLE_FILE, if any, is the tune cache of the process:
+// read once before the table is first consulted or extended, rewritten after every insertion.  A file that exists
+// but cannot be loaded (another architecture, another library version, malformed) is left alone: nothing is read
+// from it and nothing is written over it.
+static std::once_flag g_cache_once;
+static std::string g_cache_path;     // empty: no cache file in use
+static void open_cache_once()
+{
+    std::call_once(g_cache_once, [] {
+        const char* p = getenv("ADDRMS_TABLE_FILE");
+        if (!p || !*p) return;
+        FILE* f = fopen(p, "r");
+        if (!f) { g_cache_path = p; return; }          // not there yet: the first insertion creates it
+        fclose(f);
+        if (addrms_table_load(p) == ADDRMS_OK) g_cache_path = p;
+    });
+}
+
 int table_insert(int64_t M, int64_t N, int dtype, const addrms_cfg& cfg, double mean_us, int op)
 {
     const Feas f = check_cfg(cfg, M, N, dtype, op);
     if (f.status != ADDRMS_OK) return fail(f.status, "%s", f.reason.c_str());
-    std::lock_guard<std::mutex> lock(g_mu);
-    table()[Key(op, dtype, N, M)] = Entry{cfg, mean_us};
+    open_cache_once();
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        table()[Key(op, dtype, N, M)] = Entry{cfg, mean_us};
+    }
+    if (!g_cache_path.empty()) return addrms_table_save(g_cache_path.c_str());
     return ADDRMS_OK;
 }
 
 int table_lookup(int64_t M, int64_t N, int dtype, addrms_cfg* out, int op)
 {
+    open_cache_once();
     std::lock_guard<std::mutex> lock(g_mu);
     auto& t = table();
     auto it = t.find(Key(op, dtype, N, M));
@@ -102,8 +127,10 @@ int addrms_table_save(const char* path)
 {
     if (!path) return fail(ADDRMS_ERR_INVALID_ARG, "path is NULL");
     std::lock_guard<std::mutex> lock(g_mu);
-    FILE* f = fopen(path, "w");
-    if (!f) return fail(ADDRMS_ERR_IO, "cannot open %s for writing", path);
+    // written beside the target and renamed over it, so that a reader never sees half a file
+    const std::string tmp = std::string(path) + ".tmp";
+    FILE* f = fopen(tmp.c_str(), "w");
+    if (!f) return fail(ADDRMS_ERR_IO, "cannot open %s for writing", tmp.c_str());
     fprintf(f, "%s\narch %s\nlibrary %s\n# operator dtype M N vec threads_per_row rows_per_wg reduce unroll flags "
                "max_waves_per_simd walk mean_us\n", kMagic, kArch, ADDRMS_VERSION_STRING);
     for (const auto& kv : table()) {
@@ -113,7 +140,8 @@ int addrms_table_save(const char* path)
                 c.rows_per_wg, c.reduce, c.unroll, c.flags, c.max_waves_per_simd, c.walk, kv.second.us);
     }
     const bool bad = ferror(f) != 0;
-    if (fclose(f) != 0 || bad) return fail(ADDRMS_ERR_IO, "write to %s failed", path);
+    if (fclose(f) != 0 || bad) { remove(tmp.c_str()); return fail(ADDRMS_ERR_IO, "write to %s failed", tmp.c_str()); }
+    if (rename(tmp.c_str(), path) != 0) { remove(tmp.c_str()); return fail(ADDRMS_ERR_IO, "cannot move %s to %s", tmp.c_str(), path); }
     return ADDRMS_OK;
 }
 

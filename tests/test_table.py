@@ -142,3 +142,45 @@ def test_file_names_its_architecture_and_library_and_a_patch_release_may_read_it
     with pytest.raises(B.AddrmsError) as e:
         B.addrms_table_load(path)
     assert e.value.status == B.ERR_IO and "gfx90a" in e.value.message
+
+
+def _run_py(code, env_extra):
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, PYTHONPATH=root, **env_extra)
+    r = subprocess.run([sys.executable, "-c", code], env=env, cwd=root, stdout=subprocess.PIPE, stderr=subprocess.STDOUT,
+                       text=True, timeout=300)
+    assert r.returncode == 0, r.stdout
+    return r.stdout
+
+
+def test_tune_cache_file_named_by_the_environment(tmp_path):
+    """ADDRMS_TABLE_FILE: what one process inserts is what the next process looks up, without either
+    calling save or load; a file the library cannot load is neither read nor overwritten."""
+    path = str(tmp_path / "cache.txt")
+    writer = ("from paper_2601_12698_amd import binding as B\n"
+              "assert B.addrms_table_size() == 0\n"
+              "B.addrms_table_insert(4096, 4096, 'bf16', B.make_cfg(8, 128, 8, 0, 4, 7, 0), 22.5)\n"
+              "B.addrms_table_insert(64, 8192, 'bf16', B.make_cfg(8, 512, 1, 0, 2, 0, 0), 3.5)\n")
+    _run_py(writer, {"ADDRMS_TABLE_FILE": path})
+    text = open(path).read().splitlines()
+    assert text[0].startswith("addrms-table") and text[1] == "arch gfx950" and len([l for l in text if l and l[0].isdigit()]) == 2
+    assert not os.path.exists(path + ".tmp")
+    reader = ("from paper_2601_12698_amd import binding as B\n"
+              "print(B.addrms_table_lookup(4096, 4096, 'bf16').as_tuple())\n"
+              "print(B.addrms_table_lookup(128, 8192, 'bf16').as_tuple())\n"
+              "print(B.addrms_table_size())\n")
+    out = _run_py(reader, {"ADDRMS_TABLE_FILE": path}).splitlines()
+    assert out[-3:] == ["(8, 128, 8, 0, 4, 7, 0, 0)", "(8, 512, 1, 0, 2, 0, 0, 0)", "2"]
+    # without the variable the same process sees an empty table
+    out = _run_py("from paper_2601_12698_amd import binding as B\nprint(B.addrms_table_lookup(4096, 4096, 'bf16'))\n"
+                  "print(B.addrms_table_size())\n", {"ADDRMS_TABLE_FILE": ""}).splitlines()
+    assert out[-2:] == ["None", "0"]
+    # a file for another architecture: not loaded, and an insertion does not write over it
+    foreign = str(tmp_path / "foreign.txt")
+    body = "addrms-table 4\narch gfx942\nlibrary 0.2.0\n0 0 4096 4096 8 128 8 0 4 7 0 0 22.5\n"
+    open(foreign, "w").write(body)
+    out = _run_py(writer.replace("assert B.addrms_table_size() == 0\n", "") + "print(B.addrms_table_size())\n",
+                  {"ADDRMS_TABLE_FILE": foreign}).splitlines()
+    assert out[-1] == "2" and open(foreign).read() == body
