@@ -199,7 +199,10 @@ def main(argv=None) -> int:
         print("\nsilu_and_mul (out[i,j] = silu(x[i,j]) * x[i,d+j]), tuned vs default:\n")
         print("| workload | M x d | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
         print("|---|---|---|---|---|---|---|---|---|---|---|")
-        for wl in (W.SILU_PREFILL, W.SILU_DECODE, W.SILU_FP16):
+        # the last shape is eight times the prefill one (2.2 GB per launch): what the kernel streams at once the
+        # fixed cost of a launch no longer shows
+        big = W.GatedWorkload("silu_32768x11008_bf16", 32768, 11008, "bf16", 14)
+        for wl in (W.SILU_PREFILL, W.SILU_DECODE, W.SILU_FP16, big):
             nbytes = B.silumul_algorithmic_bytes(wl.M, wl.d, wl.dtype)
             t0 = time.perf_counter()
             cfg, rep = B.silumul_tune(wl.M, wl.d, wl.dtype, B.make_budget())

@@ -2,6 +2,8 @@
 per-dispatch counter table and the rules that turn signals into search hints."""
 import os
 
+import pytest
+
 from paper_2601_12698_amd import binding as B
 from paper_2601_12698_amd import signals as S
 
@@ -82,3 +84,12 @@ def test_two_pass_re_reads_are_not_taken_for_waste():
     rec["cfg"]["flags"] = 2
     hints, why = S.suggest(rec, achieved_frac=0.6)
     assert hints & B.HINT_FEWER_LARGER_WORKGROUPS
+
+
+def test_probe_list_of_the_counters_command():
+    assert S.parse_probes(None) == [] and S.parse_probes(" ; ") == []
+    assert S.parse_probes("copy;rows:256,6") == [{"kind": "copy"}, {"kind": "rows", "threads": 256, "wgs": 6}]
+    with pytest.raises(ValueError):
+        S.parse_probes("columns:3")
+    spec = S._spec([], 8, 4096, "bf16", 1e-6, S.parse_probes("rows:448,3"))
+    assert spec["probes"] == [{"kind": "rows", "threads": 448, "wgs": 3}] and spec["cfgs"] == []
