@@ -9,8 +9,9 @@ step).  One step = one in-place launch of the operator through the C ABI over on
 is already resident in HBM.  The launches rotate through enough buffer sets that every step
 streams from HBM rather than from the 256 MB last-level cache.
 
-Before the timed region the library's guided search tunes the launch configuration (its cost
-is reported, not timed as steps).  Then, for the headline workload:
+Before the timed region the library's guided search tunes the launch configuration and its
+Top-K are re-tested once on the workload's own buffers, the fastest being kept (the cost of
+both is reported, not timed as steps).  Then, for the headline workload:
   * W untimed warm-up steps and exactly K timed steps of the tuned configuration, bracketed
     by device synchronisation (`value`, `ms_per_step`), with HIP events on the launch stream
     around the same K steps (`roofline`);
@@ -509,6 +510,21 @@ def main():
     stream = torch.cuda.current_stream()
     r = Runner(torch, lib, B, args, stream)
 
+    # The search ranked its Top-K on the library's own synthetic buffers; they are usually within a per cent of each
+    # other.  Re-test them once on this workload's buffers (alternating blocks, median block of each) and take the
+    # fastest: still part of tuning (Section 3.2's Top-K re-test), done before anything is timed as a step.
+    retest = None
+    if rep is not None and rep.n_topk > 1:
+        cands = [B.make_cfg(*rep.topk[i].as_tuple()) for i in range(rep.n_topk)]
+        t0 = time.perf_counter()
+        per = r.interleaved([(lambda n, c=c: r.run(c, n)) for c in cands], 5, max(5, min(40, int(4000 / max(rep.best_us, 1.0)))))
+        med = [statistics.median(v) for v in per]
+        pick = min(range(len(cands)), key=lambda i: med[i])
+        retest = {"candidates": [list(c.as_tuple()) for c in cands], "us_median": [round(v, 3) for v in med],
+                  "picked": pick, "wall_ms": round((time.perf_counter() - t0) * 1e3, 1)}
+        tuned = cands[pick]
+        tune_wall += retest["wall_ms"] * 1e-3
+
     run_default = lambda n: r.run(default, n)
     run_tuned = lambda n: r.run(tuned, n)
     wall_d, ev_d = r.timed(run_default, a.warmup, a.steps)
@@ -579,12 +595,14 @@ def main():
                      "kernel_us": round(kernel_us, 3), "algorithmic_bytes": nbytes},
     }
     headline_entry = None
+    if retest is not None:
+        out["tune"]["retest_on_workload_buffers"] = retest
     if rep is not None:
         out["tune"].update({"n_grid": rep.n_grid, "n_feasible": rep.n_feasible, "n_measured": rep.n_measured,
                             "n_failed": rep.n_failed, "best_found_at": rep.best_found_at,
                             "time_to_best_ms": round(rep.time_to_best_ms, 2), "best_us": round(rep.best_us, 3),
                             "default_us": round(rep.default_us, 3)})
-        headline_entry = config_entry(wl, nbytes, tuned, rep, tune_wall * 1e3)
+        headline_entry = config_entry(wl, nbytes, rep.best, rep, rep.wall_ms)      # as the library's harness saw it
     del r, keep, args
     torch.cuda.empty_cache()
     if not a.no_configs:
