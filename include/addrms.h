@@ -322,9 +322,10 @@ int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int d
  * The deriver prunes two kinds of configurations: invalid ones (a launch the hardware
  * or the compiled instance cannot take) and ones it calls obviously inefficient (at
  * most half the lanes of a row carrying data; fewer than two resident waves per SIMD;
- * an instance that spills registers; the two-pass form or the LDS-extended cache where
- * the registers of a single pass would do).  The second kind is a judgement, and this
- * call puts it to the test: it enumerates the grid with those five rules switched off,
+ * an instance that spills registers; the two-pass or hybrid form or the LDS-continued cache where
+ * the registers of a single pass would do; the aligned-span form where rows are whole cache
+ * lines anyway).  The second kind is a judgement, and this
+ * call puts it to the test: it enumerates the grid with those six rules switched off,
  * passes both the retained configurations and the ones each rule would have pruned
  * through the correctness gate and the screening protocol (budget.coarse_warmup /
  * coarse_reps, default 3 + 15 launches), and reports per rule how the pruned ones
@@ -335,10 +336,10 @@ int addrms_tune_rounds_with_backend(const addrms_shape* shapes, int32_t n, int d
  * best member is the yardstick); budget.max_wall_ms stops early (truncated = 1).  Nothing is added
  * to the table, and addrms_run still refuses the pruned configurations.  Blocking;
  * allocates and frees device memory. */
-#define ADDRMS_AUDIT_RULES 5
+#define ADDRMS_AUDIT_RULES 6
 typedef struct addrms_audit_rule {
     char    rule[24];          /* "lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless",
-                                  "lds_cache_needless"                                                 */
+                                  "lds_cache_needless", "span_needless"                                */
     int64_t n_pruned;          /* grid points this rule alone keeps out of the feasible region         */
     int32_t n_measured;        /* of those, validated and timed                                        */
     int32_t n_failed;          /* of those, failed the gate or the launch                              */

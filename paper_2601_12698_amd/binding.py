@@ -178,7 +178,7 @@ class RoundsReport(Structure):
                     best=self.best.as_dict())
 
 
-AUDIT_RULES = 5
+AUDIT_RULES = 6
 
 
 class AuditRule(Structure):

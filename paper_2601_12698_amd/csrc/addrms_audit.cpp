@@ -36,7 +36,7 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
 
     memset(report, 0, sizeof *report);
     static const char* kRules[ADDRMS_AUDIT_RULES] = {"lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless",
-                                                      "lds_cache_needless"};
+                                                      "lds_cache_needless", "span_needless"};
     for (int r = 0; r < ADDRMS_AUDIT_RULES; ++r) snprintf(report->rules[r].rule, sizeof report->rules[r].rule, "%s", kRules[r]);
 
     // class 0 = retained by every rule; class 1 + r = let through only because rule r was switched off

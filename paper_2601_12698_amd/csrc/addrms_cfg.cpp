@@ -320,9 +320,12 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
             return infeasible("span_alignment", "%d rows of N=%lld are %lld and %lld bytes: not whole %d-byte cache lines, so "
                               "consecutive workgroups would still share lines", c.rows_per_wg, (long long)N, (long long)xspan,
                               (long long)rspan, kLineBytes);
-        if ((N * xb) % kLineBytes == 0 && (N * rb) % kLineBytes == 0)
-            return infeasible("span_needless", "rows of N=%lld are whole cache lines already (%lld and %lld bytes): the ordinary "
-                              "form is aligned and needs no segmented reduction", (long long)N, (long long)(N * xb), (long long)(N * rb));
+        if ((N * xb) % kLineBytes == 0 && (N * rb) % kLineBytes == 0) {
+            if (!(relax & RELAX_SPAN_NEEDLESS))
+                return infeasible("span_needless", "rows of N=%lld are whole cache lines already (%lld and %lld bytes): the ordinary "
+                                  "form is aligned and needs no segmented reduction", (long long)N, (long long)(N * xb), (long long)(N * rb));
+            if (!f.soft_rule[0]) f.soft_rule = "span_needless";
+        }
     }
 
     // -- launch validity

@@ -73,7 +73,7 @@ const char* dtype_name(int dtype);
 // keep a launch valid (sizes, alignment, instance limits, LDS, at least one workgroup per
 // CU) and rules that only remove duplicates of another cfg can never be switched off.
 enum Relax : int { RELAX_LANE_UTILISATION = 1, RELAX_OCCUPANCY_FLOOR = 2, RELAX_SCRATCH = 4, RELAX_TWO_PASS_NEEDLESS = 8,
-                   RELAX_LDS_CACHE_NEEDLESS = 16, RELAX_ALL = 31 };
+                   RELAX_LDS_CACHE_NEEDLESS = 16, RELAX_SPAN_NEEDLESS = 32, RELAX_ALL = 63 };
 
 struct Feas {
     int status = ADDRMS_OK;

@@ -551,12 +551,16 @@ __device__ __forceinline__ void addrms_twopass_body(void* __restrict__ xp, void*
     }
 }
 
-// Hybrid form for rows beyond what registers and LDS hold together (both long-row flags set).
-// The first CPT chunks of a thread stay in registers (48 values: a 1024-thread workgroup leaves
-// each lane 128 registers), the next `lds_chunks` are parked in LDS as in addrms_ldscache_body, and only the remaining chunks are treated as in the
-// two-pass form: summed in pass 1 without being written, re-read in pass 2 (backwards, so that
-// what pass 1 pulled through the caches last is asked for first) to form both outputs.  The
-// part of the row that is read twice shrinks from all of it to what does not fit on the chip.
+// The one body of the forms whose row cache continues in LDS.  The first CPT chunks of a thread
+// stay in registers (48 values: a 1024-thread workgroup leaves each lane 128 registers); the fp32
+// sums of the next `lds_chunks` are parked in the thread's own slots of the workgroup's LDS
+// allocation (laid out [row][chunk][lane][vec] behind the reduction scratch, so no other thread
+// touches them) and read back once rstd is known.  LDS-continued cache: that covers the whole
+// row, one pass.  Hybrid form (both long-row flags, rows beyond registers + LDS): only the
+// remaining chunks are treated as in the two-pass form: summed in pass 1 without being written,
+// re-read in pass 2 (backwards, so that what pass 1 pulled through the caches last is asked for
+// first) to form both outputs.  The part of the row that is read twice shrinks from all of it to
+// what does not fit on the chip.
 // lds_chunks comes from the host, which sized the LDS allocation (it travels in the kernel
 // argument the persistent forms use for the number of row blocks); fewer chunks than CPT +
 // lds_chunks simply leave the tail of the register part idle (clamped loads, no stores).

@@ -184,7 +184,7 @@ struct Searcher {
                 score = fabs(log2(threads / 256.0)) + 0.1 * fabs(log2((double)c.unroll) - log2((double)want_unroll));
                 if (mode == kCapped) score += 0.5 * fabs(static_cast<double>(c.max_waves_per_simd) - 4.0);
             }
-            // widest vector first; the long-row forms (two-pass, LDS-extended cache) are classes of their own
+            // widest vector first; the long-row forms (two-pass, cache continued in LDS, hybrid) are classes of their own
             auto key = std::make_pair(-c.vec - 16 * (c.flags & kFormBits), c.threads_per_row);
             auto it = best.find(key);
             if (it == best.end() || score < it->second.first) best[key] = {score, i};

@@ -152,7 +152,7 @@ def main(argv=None) -> int:
                     help="also select one general cfg over the (m, n) shape lists the paper evaluates on "
                          "(Section 4: five fp16/bf16 shapes, eight fp32 shapes) and print general vs specialised")
     ap.add_argument("--long-rows", action="store_true",
-                    help="also tune rows beyond the register row cache (LDS-extended cache or two-pass form)")
+                    help="also tune rows beyond the register row cache (cache continued in LDS, hybrid or two-pass form)")
     ap.add_argument("--graph-decode", action="store_true",
                     help="decode shapes: per-launch time of a chain of launches issued eagerly vs replayed from a HIP graph")
     ap.add_argument("--row-scan", action="store_true",

@@ -1,7 +1,8 @@
 """The audit of the deriver's efficiency rules, driven by synthetic cost functions (no GPU).
 
-The audit switches the three judgement rules off (lane utilisation, occupancy floor,
-spilling instances), times retained and pruned configurations alike and says whether
+The audit switches the judgement rules off (lane utilisation, occupancy floor, spilling
+instances, long-row forms and the aligned span where the plain form would do), times
+retained and pruned configurations alike and says whether
 anything pruned beats the best retained one.  Here the "timings" are functions chosen
 so that the right answer is known.
 """
@@ -28,7 +29,7 @@ def _honest_cost(c, _w, _r):
 
 def test_struct_sizes():
     assert ctypes.sizeof(B.AuditRule) == 96
-    assert ctypes.sizeof(B.AuditReport) == 88 + B.AUDIT_RULES * 96 and B.AUDIT_RULES == 5
+    assert ctypes.sizeof(B.AuditReport) == 88 + B.AUDIT_RULES * 96 and B.AUDIT_RULES == 6
 
 
 def test_classes_partition_the_relaxed_grid():
@@ -37,7 +38,8 @@ def test_classes_partition_the_relaxed_grid():
     strict, _ = B.addrms_enumerate_feasible(M, N, DT)
     assert rep.n_retained == len(strict) == rep.n_retained_measured
     names = [r.rule.decode() for r in rep.rules]
-    assert names == ["lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless", "lds_cache_needless"]
+    assert names == ["lane_utilisation", "occupancy_floor", "scratch", "two_pass_needless", "lds_cache_needless",
+                     "span_needless"]
     lane = rep.rules[0]
     assert lane.n_pruned > 0 and lane.n_measured == lane.n_pruned
     assert len(seen) == len(set(seen)) == rep.n_retained + sum(r.n_measured for r in rep.rules)
@@ -46,7 +48,8 @@ def test_classes_partition_the_relaxed_grid():
     extra = [t for t in seen if t not in strict_set]
     assert len(extra) == sum(r.n_pruned for r in rep.rules)
     words = {"lane_utilisation": "lane slots", "occupancy_floor": "wave per SIMD", "scratch": "spills",
-             "two_pass_needless": "reading every row twice", "lds_cache_needless": "detour through LDS"}
+             "two_pass_needless": "reading every row twice", "lds_cache_needless": "detour through LDS",
+             "span_needless": "whole cache lines already"}
     n_lane = 0
     for t in extra[::17]:
         st, why, _ = B.addrms_cfg_feasible(B.make_cfg(*t), M, N, DT)

@@ -18,8 +18,8 @@ NOISE = 0.95     # 3 + 15 launches of a few microseconds each: allow 5 %
 
 @pytest.mark.parametrize("M,N,dtype,expect", [
     (2048, 1000, "fp16_res32", ("lane_utilisation", "occupancy_floor")),
-    (4096, 4096, "bf16", ("lane_utilisation", "occupancy_floor")),
-    (1024, 11008, "fp32", ("scratch",)),
+    (4096, 4096, "bf16", ("lane_utilisation", "occupancy_floor", "span_needless")),
+    (1024, 11008, "fp32", ("scratch", "span_needless")),
 ])
 def test_pruned_cfgs_are_correct_and_never_win(M, N, dtype, expect):
     # the retained region is always timed in full; each pruned class is sampled down to at most 4000 cfgs
