@@ -221,11 +221,7 @@ __device__ __forceinline__ double wave_group_sum(double v, uint32_t width)
 // launch wrote), so global traffic may stay in flight across the barrier.
 __device__ __forceinline__ void wg_sync_lds()
 {
-#ifdef ADDRMS_FULL_BARRIER
-    __syncthreads();
-#else
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#endif
 }
 
 // Row sum of per-thread partials; result identical in all threads of the row.
