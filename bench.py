@@ -492,7 +492,7 @@ def main():
 
     # ---- Level 2 of the tuner: feasible region + search (reported, not timed as steps)
     budget = B.make_budget(strategy=B.SEARCH_EXHAUSTIVE if a.exhaustive else B.SEARCH_GUIDED, eps=wl.eps,
-                           log_path=a.tune_log)
+                           log_path=a.tune_log, top_k=7)    # seven confirmed + the default: all re-tested below
     t0 = time.perf_counter()
     if a.cfg:
         tuned = B.make_cfg(*[int(v) for v in a.cfg.split(",")])

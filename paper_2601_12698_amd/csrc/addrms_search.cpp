@@ -12,14 +12,14 @@
 //   exhaustive  the plain definition: time every feasible cfg with the
 //               confirmation protocol, then re-test the Top-K;
 //   guided      (1) coarse sweep: one representative launch shape per
-//               (vec, threads_per_row) class, short protocol, in up to three
-//               modes (plain, streaming, persistent) because those corners are
-//               not connected by single-knob moves;
+//               (vec, threads_per_row, form) class, short protocol, in up to four
+//               modes (plain, streaming, deferred store, persistent) because those
+//               corners are not connected by single-knob moves;
 //               (2) descent: from the best few classes, move one knob at a time
 //               to the best unmeasured neighbour, trying first the moves that
 //               the static signals favour (more resident waves when the kernel
 //               is register-limited, more workgroups when the grid underfills
-//               the chip);
+//               the chip); then every occupancy cap and load batching around the two leading cfgs;
 //               (3) Top-K re-test with the confirmation protocol, interleaved
 //               so that clock drift hits all candidates alike.
 #include <math.h>
@@ -304,6 +304,23 @@ struct Searcher {
             cur = best;
         }
     }
+
+    // The occupancy cap and the load batching each move a good cfg by about one per cent either way, which is less
+    // than a descent step must gain to be taken next to the screening noise, so the descent often leaves them where
+    // it happened to start.  Around a leading cfg every combination of the two is cheap to try (a few dozen
+    // candidates at most).
+    void sweep_fine(int i, int warmup, int reps)
+    {
+        const addrms_cfg c = cands[i].cfg;
+        for (int u = 1; u <= 8; u *= 2)
+            for (int k = 0; k < hw().max_waves_per_simd && budget_left(); ++k) {
+                addrms_cfg n = c;
+                n.unroll = u;
+                n.max_waves_per_simd = k;
+                const int j = find(n);
+                if (j >= 0 && !cands[j].tried) eval(j, "fine", warmup, reps);
+            }
+    }
 };
 
 // ---- resume: what an earlier run already measured ---------------------------------------
@@ -502,6 +519,8 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
             if (starts.size() == 3) break;
         }
         for (int i : starts) s.descend(i, b.coarse_warmup, b.coarse_reps);
+        std::vector<int> lead = s.ranked();
+        for (size_t k = 0; k < lead.size() && k < 2; ++k) s.sweep_fine(lead[k], b.coarse_warmup, b.coarse_reps);
     }
 
     std::vector<int> order = s.ranked();
