@@ -19,7 +19,8 @@
 //               to the best unmeasured neighbour, trying first the moves that
 //               the static signals favour (more resident waves when the kernel
 //               is register-limited, more workgroups when the grid underfills
-//               the chip); then every occupancy cap and load batching around the two leading cfgs;
+//               the chip); then every occupancy cap and load batching around the best cfg of the
+//               three leading classes;
 //               (3) Top-K re-test with the confirmation protocol, interleaved
 //               so that clock drift hits all candidates alike.
 #include <math.h>
@@ -519,8 +520,18 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
             if (starts.size() == 3) break;
         }
         for (int i : starts) s.descend(i, b.coarse_warmup, b.coarse_reps);
-        std::vector<int> lead = s.ranked();
-        for (size_t k = 0; k < lead.size() && k < 2; ++k) s.sweep_fine(lead[k], b.coarse_warmup, b.coarse_reps);
+        // ... around the best cfg of each of the three leading (vec, threads_per_row, form) classes
+        std::vector<int> lead;
+        for (int i : s.ranked()) {
+            bool dup = false;
+            for (int j : lead)
+                dup = dup || (s.cands[j].cfg.vec == s.cands[i].cfg.vec &&
+                              s.cands[j].cfg.threads_per_row == s.cands[i].cfg.threads_per_row &&
+                              ((s.cands[j].cfg.flags ^ s.cands[i].cfg.flags) & kFormBits) == 0);
+            if (!dup) lead.push_back(i);
+            if (lead.size() == 3) break;
+        }
+        for (int i : lead) s.sweep_fine(i, b.coarse_warmup, b.coarse_reps);
     }
 
     std::vector<int> order = s.ranked();
