@@ -201,8 +201,8 @@ __device__ __forceinline__ double butterfly_add(double v)
     return v + other;       // a+b on one side, b+a on the other: identical bits
 }
 
-// Sum over aligned groups of `width` lanes (8, 16, 32 or 64); every lane of a
-// group ends with the same bits.
+// Sum over aligned groups of `width` lanes (8, 16 or 32: rows narrower than a wave;
+// 64 works too); every lane of a group ends with the same bits.
 __device__ __forceinline__ double wave_group_sum(double v, uint32_t width)
 {
     v = butterfly_add<1>(v);
@@ -899,7 +899,7 @@ __device__ __forceinline__ void addrms_span_body(void* __restrict__ xp, void* __
         for (uint32_t k = wv; k < rows_here; k += nw) {           // uniform over the wave
             double s = 0.0;
             for (uint32_t j = l; j < P; j += 64u) s += part[k * P + j];
-            s = wave_group_sum(s, 64u);
+            s = wave_total(s);
             if (l == 0u) rstd_s[k] = rsqrt_to_f32(__builtin_fma(s, inv_n, static_cast<double>(eps)));
         }
     }
