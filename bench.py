@@ -54,17 +54,44 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "addrms_hbm_traffic.md")
 METRIC = "fused add+RMSNorm achieved HBM GB/s (% of peak), tuned vs default cfg"
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per launch of the tuned configuration of `workload_name`, as the profiler's FETCH_SIZE and
-    WRITE_SIZE counters measured them (rows of the table in profiles/addrms_hbm_traffic.md, which
-    `python -m paper_2601_12698_amd.signals --traffic-report` writes).  None if the workload was not measured."""
+def measured_traffic(workload_name, cfg=None):
+    """HBM bytes per launch on `workload_name`, as the profiler's FETCH_SIZE and WRITE_SIZE counters measured them
+    (rows of the table in profiles/addrms_hbm_traffic.md, which `python -m paper_2601_12698_amd.signals
+    --traffic-report` writes): the row of exactly this cfg if the table has one, else the row of the cfg that was
+    the tuned one when the table was written.  None if the workload was not measured."""
+    want = ",".join(str(v) for v in cfg) if cfg is not None else None
+    found = None
     try:
         with open(TRAFFIC_FILE) as f:
             for line in f:
                 cells = [c.strip() for c in line.split("|")]
-                if len(cells) >= 9 and cells[1] == workload_name and cells[2] == "tuned":
-                    return {"bytes": int(cells[6]), "cfg": cells[3], "over_algorithmic": float(cells[8])}
+                if len(cells) >= 9 and cells[1] == workload_name and (cells[3] == want or (cells[2] == "tuned" and found is None)):
+                    found = {"bytes": int(cells[6]), "cfg": cells[3], "over_algorithmic": float(cells[8])}
+                    if cells[3] == want:
+                        break
     except (OSError, ValueError):
+        pass
+    return found
+
+
+def recorded_regret():
+    """Regret of the guided search against the exhaustive one on prefill 4096 x 4096, as the last run of
+    `python -m paper_2601_12698_amd.report --exhaustive-prefill` recorded it (the exhaustive search takes two
+    minutes of GPU time, too long to repeat in every bench run)."""
+    import re
+    path = os.path.join(ROOT, "profiles", "addrms_tuned_vs_default_all_configs.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("prefill: guided"):
+                    r = re.findall(r"regret ([0-9.]+)", line)
+                    n = re.findall(r"after (\d+) cfgs / (\d+) ms", line)
+                    if len(r) == 2 and len(n) == 2:
+                        return {"confirmed_in_search": float(r[0]), "re_measured_in_alternation": float(r[1]),
+                                "guided_cfgs": int(n[0][0]), "guided_ms": int(n[0][1]),
+                                "exhaustive_cfgs": int(n[1][0]), "exhaustive_ms": int(n[1][1]),
+                                "source": "profiles/" + os.path.basename(path)}
+    except OSError:
         pass
     return None
 
@@ -543,7 +570,7 @@ def main():
     probe_us = ev_p / a.steps * 1e3
     probe_gbps = probe_bytes / (probe_us * 1e-6) * 1e-9
     med_d, med_t, med_p = (statistics.median(v) for v in (blk_d, blk_t, blk_p))
-    traffic = measured_traffic(wl.name)
+    traffic = measured_traffic(wl.name, tuned.as_tuple())
     out = {
         "metric": METRIC,
         "value": round(value, 1),
@@ -594,6 +621,7 @@ def main():
                                         f"{traffic['cfg']}, {traffic['over_algorithmic']:.4f} x algorithmic") if traffic else None,
                      "kernel_us": round(kernel_us, 3), "algorithmic_bytes": nbytes},
     }
+    out["tune"]["regret_vs_exhaustive_on_prefill_4096x4096"] = recorded_regret()
     headline_entry = None
     if retest is not None:
         out["tune"]["retest_on_workload_buffers"] = retest

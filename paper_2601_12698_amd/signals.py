@@ -232,7 +232,10 @@ def collect_probe(M: int, N: int, dtype: str, counters: Sequence[str] = ("FETCH_
 
 TRAFFIC_WORKLOADS = ("large_prefill", "prefill", "odd_width_5120", "odd_width_2880", "odd_width_1000")
 # further cfgs measured beside the tuned and the default one: the aligned-span form on the shape it was built for
-TRAFFIC_EXTRA = {"odd_width_1000": (("aligned_span", (4, 128, 8, 0, 2, 98, 0, 0)),)}
+TRAFFIC_EXTRA = {"odd_width_1000": (("aligned_span", (4, 128, 8, 0, 2, 98, 0, 0)),),
+                 # the cfgs the search returns on the headline shape from run to run (all within a per cent of each other)
+                 "large_prefill": (("plateau_a", (8, 448, 1, 0, 1, 34, 6, 0)), ("plateau_b", (8, 448, 1, 0, 2, 34, 0, 0)),
+                                   ("plateau_c", (2, 512, 1, 0, 2, 34, 0, 0)), ("plateau_d", (8, 448, 1, 0, 1, 2, 6, 0)))}
 
 
 def traffic_report(path: str, names: Sequence[str] = TRAFFIC_WORKLOADS) -> List[dict]:
@@ -280,7 +283,10 @@ def traffic_report(path: str, names: Sequence[str] = TRAFFIC_WORKLOADS) -> List[
                 "three rotating buffer sets) of the tuned and the default cfg, and of the library's calibration kernel (a plain\n"
                 "copy kernel: 16-bit x and residual of the same M x N, read and written back once, 4*M*N bytes each way): that\n"
                 "fixes the bytes per counter unit (last two columns; the counters' nominal units are 2 KiB and 1 KiB here).  cfg = vec, threads_per_row, rows_per_wg, reduce, unroll, flags, max_waves_per_simd, walk.\n"
-                "bench.py takes `roofline.traffic` from the `total bytes` column of the `tuned` row of its workload.\n\n"
+                "Rows other than `tuned` and `default` are further cfgs of interest: `plateau_*` are cfgs the search returns on the\n"
+                "headline shape from run to run (all within a per cent of each other), `aligned_span` is the form built for rows\n"
+                "that are not whole cache lines.  bench.py takes `roofline.traffic` from the `total bytes` column of the row whose\n"
+                "cfg is the one it timed, else of the `tuned` row of its workload.\n\n"
                 "| workload | which | cfg | read bytes | written bytes | total bytes | algorithmic bytes | total / algorithmic | us (search) | FETCH_SIZE | WRITE_SIZE | bytes per FETCH unit | bytes per WRITE unit |\n"
                 "|---|---|---|---|---|---|---|---|---|---|---|---|---|\n" + "\n".join(lines) + "\n")
     return rows
