@@ -267,3 +267,24 @@ def test_default_wins_when_it_confirms_fastest():
     # and the usual case is unchanged: the default confirms slower and does not win
     got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(), lambda c, w, r: cost(c))
     assert got.as_tuple() != default and rep.default_us > rep.best_us
+
+
+def test_fine_sweep_finds_a_cap_and_batching_pair_no_single_move_reaches():
+    """Occupancy cap and load batching that only pay together (each alone costs a little): no descent step leads
+    there, the sweep around the leading cfgs does.  The winner is 1.5 % ahead of everything the descent can see."""
+    def fn(c):
+        us = cost(c)
+        # the optimum moved to 256 threads per row, where a row is two chunks per thread and unroll 2 exists
+        us *= (1.0 + 0.30 * abs(math.log2(c.threads_per_row / 256.0))) / (1.0 + 0.30 * abs(math.log2(c.threads_per_row / 512.0)))
+        if c.max_waves_per_simd == 6 and c.unroll == 2:
+            us *= 0.93                              # against cost()'s +3 % for unroll 2 and +4 % for cap 6
+        return us
+    rec = Recorder(fn)
+    best, n = true_best(fn)
+    assert best.max_waves_per_simd == 6 and best.unroll == 2
+    for alone in (B.make_cfg(best.vec, best.threads_per_row, best.rows_per_wg, best.reduce, 1, best.flags, 6),
+                  B.make_cfg(best.vec, best.threads_per_row, best.rows_per_wg, best.reduce, 2, best.flags, 4)):
+        assert fn(alone) > fn(B.make_cfg(best.vec, best.threads_per_row, best.rows_per_wg, best.reduce, 1, best.flags, 4))
+    got, rep = B.addrms_tune_with_backend(M, N, DT, B.make_budget(), rec.measure, rec.validate)
+    assert got.as_tuple() == best.as_tuple()
+    assert rep.n_measured <= 0.12 * n
