@@ -53,7 +53,7 @@ typedef enum addrms_dtype {
 } addrms_dtype;
 
 /* ---- the searchable parameter vector theta (Algorithm 1, Input) ------------ */
-enum { ADDRMS_REDUCE_WAVE = 0,   /* wave64 cross-lane butterfly, one LDS hop across waves */
+enum { ADDRMS_REDUCE_WAVE = 0,   /* wave64 cross-lane (DPP) sums, one LDS hop across waves */
        ADDRMS_REDUCE_LDS = 1 };  /* LDS-staged tree reduction                             */
 enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguous row range       */
        ADDRMS_FLAG_NONTEMPORAL = 2,   /* streaming cache policy on x/residual loads and stores    */

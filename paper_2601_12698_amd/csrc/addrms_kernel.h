@@ -10,7 +10,7 @@
 //         slice lives in registers between the two passes (register row cache)
 //   UNR   chunks whose loads are in flight before the first one is consumed
 //   threads_per_row, rows_per_wg : launch shape (blockDim.x, blockDim.y)
-//   reduce  : wave64 cross-lane butterfly + one LDS hop across waves, or an
+//   reduce  : wave64 cross-lane (DPP) sums + one LDS hop across waves, or an
 //             LDS-staged tree
 //   NT    non-temporal (streaming) cache policy on the x and residual loads
 //         and stores; the weight vector always uses the default policy
@@ -823,7 +823,7 @@ __device__ __forceinline__ void addrms_hybrid_body(void* __restrict__ xp, void* 
 // the mixed format) and every line is written whole by one instruction.  The price is a
 // segmented reduction, since row boundaries fall inside waves: each piece's sum of squares
 // goes to LDS, one wave per row adds that row's pieces (strided, then the cross-lane
-// butterfly), and the row's rstd is left in LDS for every piece of the row.
+// sum), and the row's rstd is left in LDS for every piece of the row.
 // LDS: T * CPT doubles (piece sums), then blockDim.y floats (rstd per row).
 template <int DT, int VEC, int CPT, int UNR, bool NT, bool DEFER>
 __device__ __forceinline__ void addrms_span_body(void* __restrict__ xp, void* __restrict__ rp,
