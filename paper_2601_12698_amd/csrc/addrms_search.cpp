@@ -25,6 +25,7 @@
 //               so that clock drift hits all candidates alike.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -66,6 +67,7 @@ struct Searcher {
     Clock::time_point t0 = Clock::now();
     FILE* log = nullptr;
     double bytes = 0.0;
+    int verbose = 0;
 
     Searcher(int64_t m, int64_t n, int dt, const addrms_budget& bud, const addrms_backend& backend)
         : M(m), N(n), dtype(dt), b(bud), be(backend) {}
@@ -139,6 +141,7 @@ struct Searcher {
         c.order = n_measured;
         c.at_ms = elapsed_ms();
         log_eval(phase, c, true, us, warmup, reps);
+        if (verbose > 1) fprintf(stderr, "[addrms] %-16s %s %.3f us\n", phase, cfg_json(c.cfg).c_str(), us);
         return true;
     }
 
@@ -324,6 +327,14 @@ struct Searcher {
     }
 };
 
+// Progress on stderr when the environment variable ADDRMS_VERBOSE is set to something other than "0": one line
+// when a search starts and one when it ends (2: also one per candidate).
+int verbosity()
+{
+    static const int v = [] { const char* e = getenv("ADDRMS_VERBOSE"); return (e && *e && strcmp(e, "0") != 0) ? atoi(e) > 1 ? 2 : 1 : 0; }();
+    return v;
+}
+
 // ---- resume: what an earlier run already measured ---------------------------------------
 // The log is a list of searches, each opened by a "begin" line that names architecture, library
 // version, operator, shape and format.  Screening results ("eval" lines other than the
@@ -460,6 +471,11 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
         s.cands.push_back(cd);
     }
     const int i_default = s.find(dflt);
+    s.verbose = verbosity();
+    if (s.verbose)
+        fprintf(stderr, "[addrms] %s search of %s %lld x %lld %s: %lld feasible of %lld grid points\n",
+                b.strategy == ADDRMS_SEARCH_GUIDED ? "guided" : "exhaustive", op_name(op), (long long)M, (long long)N,
+                dtype_name(dtype), (long long)feasible.size(), (long long)n_grid);
 
     if (b.log_path) {
         if (!b.no_resume) load_resume(b.log_path, op, M, N, dtype, &s.resumed);
@@ -595,6 +611,10 @@ int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, con
         }
         report->wall_ms = s.elapsed_ms();
     }
+    if (s.verbose)
+        fprintf(stderr, "[addrms] best %s %.3f us (default %.3f us) after %lld candidates (%d taken from the log, %lld failed) "
+                        "in %.0f ms\n", cfg_json(win.cfg).c_str(), confirmed.front().first, default_us, (long long)s.n_measured,
+                s.n_resumed, (long long)s.n_failed, s.elapsed_ms());
     if (s.log) {
         fprintf(s.log, "{\"event\":\"end\",\"status\":\"ok\",\"best\":%s,\"best_us\":%.4f,\"default_us\":%.4f,"
                        "\"n_measured\":%lld,\"n_resumed\":%d,\"n_failed\":%lld,\"best_found_at\":%lld,\"time_to_best_ms\":%.3f,"
