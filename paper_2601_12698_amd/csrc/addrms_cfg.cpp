@@ -341,6 +341,21 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
     const int64_t per_pass = static_cast<int64_t>(c.vec) * c.threads_per_row;
     const int64_t need = (N + per_pass - 1) / per_pass;
     int64_t lds_cache_bytes = 0;
+    // Long-row forms: values per thread kept in registers.  The instance compiled for at most 512 threads keeps 144
+    // instead of 48; it is taken where the 48-value instance cannot hold the whole row on the chip (registers + LDS)
+    // at this launch shape, the workgroup is small enough, and the instance exists and does not spill.
+    int64_t long_row_reg_elems = kLdsCacheRegElems;
+    int long_row_cpt_base = kLdsCacheCptBase;
+    if ((lds_cache || hybrid) && threads <= kLdsCacheBigMaxThreads && kLdsCacheBigRegElems % c.vec == 0) {
+        const int64_t chunk_bytes = static_cast<int64_t>(c.rows_per_wg) * per_pass * 4;
+        const int64_t fit = (L.lds_bytes_per_cu - reduction_lds_bytes(c, op)) / chunk_bytes;
+        const int big = find_instance(op, dtype, c.vec, kLdsCacheBigCptBase + kLdsCacheBigRegElems / c.vec, c.unroll,
+                                      (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0, 0);
+        if (need > kLdsCacheRegElems / c.vec + fit && big >= 0 && kInstanceRes[big].scratch == 0) {
+            long_row_reg_elems = kLdsCacheBigRegElems;
+            long_row_cpt_base = kLdsCacheBigCptBase;
+        }
+    }
     if (two_pass) {
         if (N * c.rows_per_wg > kMaxTwoPassElemsPerWg)
             return infeasible("row_too_long", "N=%lld x rows_per_wg=%d exceeds the %lld elements a workgroup addresses with "
@@ -352,7 +367,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
             if (!f.soft_rule[0]) f.soft_rule = "two_pass_needless";
         }
     } else if (lds_cache) {
-        const int64_t reg_chunks = kLdsCacheRegElems / c.vec;
+        const int64_t reg_chunks = long_row_reg_elems / c.vec;
         // Needless where the plain form takes the same launch shape: it has an instance for this chunk count and that
         // instance admits this workgroup size (32 cached values up to 1024 threads, 64 up to 256).  A chunk count that
         // fits this form's 48 register values but not a plain instance - 17 to 32 one-element chunks, or 33 to 48
@@ -376,7 +391,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
             if (!f.soft_rule[0]) f.soft_rule = "lds_cache_needless";
         }
     } else if (hybrid) {
-        const int64_t reg_chunks = kLdsCacheRegElems / c.vec;
+        const int64_t reg_chunks = long_row_reg_elems / c.vec;
         if (N * c.rows_per_wg > kMaxTwoPassElemsPerWg)
             return infeasible("row_too_long", "N=%lld x rows_per_wg=%d exceeds the %lld elements a workgroup addresses with "
                               "32-bit offsets", (long long)N, c.rows_per_wg, (long long)kMaxTwoPassElemsPerWg);
@@ -426,7 +441,7 @@ Feas check_cfg(const addrms_cfg& c, int64_t M, int64_t N, int dtype, int op, int
                           2 * L.xcds);
 
     // -- compiled instance and its resources
-    const int cpt_code = two_pass ? 0 : (hybrid || lds_cache) ? kLdsCacheCptBase + kLdsCacheRegElems / c.vec
+    const int cpt_code = two_pass ? 0 : (hybrid || lds_cache) ? long_row_cpt_base + static_cast<int>(long_row_reg_elems) / c.vec
                          : span ? kSpanCptBase + static_cast<int>(need) : static_cast<int>(need);
     const int idx = find_instance(op, dtype, c.vec, cpt_code, c.unroll, (c.flags & ADDRMS_FLAG_NONTEMPORAL) ? 1 : 0, defer ? 1 : 0);
     if (idx < 0)

@@ -35,6 +35,8 @@ MAX_ELEMS = 64                          # register row cache: VEC * CPT fp32 val
 BIG_ELEMS = 32                          # above this the instance is compiled for <= 256 threads
 SPAN_BASE = 200                         # cpt code of the aligned-span form: 200 + chunks per thread
 HYBRID_BASE = 300                       # cpt code of the hybrid long-row form: 300 + register-held chunks
+HYBRID_BIG_BASE = 400                   # the same body for workgroups of at most 512 threads: 400 + register-held chunks
+HYBRID_BIG_ELEMS = 144                  # ... which keeps this many values per thread in registers (vec 4 and 8 only)
 SPAN_CPTS = (1, 2, 4)
 R_BYTES = {0: 2, 1: 2, 2: 4, 3: 4}      # bytes per residual element of each format
 
@@ -84,6 +86,10 @@ def instances():
                             continue
                         for nt in (0, 1):
                             yield op, dt, vec, HYBRID_BASE + hyb_cpt, unr, nt, 0, 1024
+                    if vec in (4, 8) and X_BYTES[dt] == 2:   # half the threads, twice the registers per lane: 144 values
+                        for unr in (1, 2, 4):                # (with fp32 x, or eight chunks in flight, the body spills)
+                            for nt in (0, 1):
+                                yield op, dt, vec, HYBRID_BIG_BASE + HYBRID_BIG_ELEMS // vec, unr, nt, 0, 512
 
 
 def name(op, dt, vec, cpt, unr, nt, df=0):

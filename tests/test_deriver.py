@@ -136,6 +136,16 @@ def test_occupancy_model_matches_compiler_report():
             if cpt == 0:       # two-pass instance: selected by the flag, for a row beyond the register cache
                 c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_TWO_PASS | (B.FLAG_NONTEMPORAL if nt else 0))
                 st, why, _ = feas(c, 4096, vec * 1024 * 40, dtype)
+            elif cpt >= 400:   # 144-value long-row instance (<= 512 threads): a spilling one is never selected; the
+                               # 48-value instance of the same (vec, unroll, policy) stands in, if there is one and it
+                               # does not spill
+                fit = (160 * 1024 - 128) // (512 * vec * 4)
+                c = B.make_cfg(vec, 512, 1, unroll=unr, flags=B.FLAG_LDS_CACHE | B.FLAG_TWO_PASS | (B.FLAG_NONTEMPORAL if nt else 0))
+                st, why, res = feas(c, 4096, vec * 512 * (cpt - 400 + fit + 1), dtype)
+                assert (st == 0 and res.max_threads == 1024) or \
+                       (st == B.ERR_INFEASIBLE_CFG and ("spills" in why or "no compiled instance" in why)), (name, why)
+                spilled += 1
+                continue
             elif cpt >= 300:   # hybrid instance: registers full (cpt - 300 chunks), LDS full, one more chunk read twice
                 fit = (160 * 1024 - 128) // (1024 * vec * 4)
                 c = B.make_cfg(vec, 1024, 1, unroll=unr, flags=B.FLAG_LDS_CACHE | B.FLAG_TWO_PASS | (B.FLAG_NONTEMPORAL if nt else 0))
@@ -149,7 +159,7 @@ def test_occupancy_model_matches_compiler_report():
             assert st == B.ERR_INFEASIBLE_CFG and "spills" in why, (name, why)
             spilled += 1
     # (most of the spilling instances are hybrid long-row ones: 48 cached values at some load depths do not fit 128 registers)
-    assert checked >= 1000 and spilled < 0.05 * checked
+    assert checked >= 1000 and spilled < 0.06 * checked
     # and the library's table carries the same numbers
     c = B.make_cfg(8, 64, 1, unroll=2)
     st, _, res = feas(c, 4096, 4096, "bf16")
@@ -226,7 +236,7 @@ def test_row_length_bound_of_the_register_cache(dtype):
         assert c.flags == long_forms and N % c.vec == 0 and c.threads_per_row == 1024 and c.rows_per_wg == 1
         st, why, res = B.addrms_cfg_feasible(c, 4, N, dtype)
         assert st == 0, why
-        assert res.chunks_per_thread == -(-N // (c.vec * 1024)) and res.scratch_bytes == 0
+        assert res.chunks_per_thread == -(-N // (c.vec * c.threads_per_row)) and res.scratch_bytes == 0
         assert 100 * 1024 < res.lds_bytes <= 160 * 1024          # the LDS part is as large as a CU allows
         two = B.make_cfg(c.vec, 1024, 1, unroll=2, flags=B.FLAG_TWO_PASS)
         assert B.addrms_cfg_feasible(two, 4, N, dtype)[0] == 0     # the plain two-pass form stays available
@@ -292,3 +302,26 @@ def test_aligned_span_form_is_offered_only_where_rows_are_not_whole_lines():
     c = B.make_cfg(4, 128, 8, unroll=2, flags=B.FLAG_ALIGNED_SPAN | B.FLAG_NONTEMPORAL)
     st, _, res = feas(c, 8192, 1000, "fp16_res32")
     assert st == 0 and res.chunks_per_thread == 2 and res.lds_bytes == 1024 * 2 * 8 + 32
+
+
+def test_long_rows_in_small_workgroups_take_the_instance_with_the_larger_register_cache():
+    """Workgroups of at most 512 threads leave each lane 256 registers: where the 48-value instance cannot keep
+    the whole row on the chip, the long-row forms use the instance that keeps 144 values per thread."""
+    lds, two = B.FLAG_LDS_CACHE, B.FLAG_TWO_PASS
+    # 131072 bf16 over 512 threads of 8: 32 chunks per thread; 48-value instance: 6 + 9 in LDS; 144-value: 18 + 9
+    st, why, res = feas(B.make_cfg(8, 512, 1, unroll=2, flags=lds | two | B.FLAG_NONTEMPORAL), 1024, 131072, "bf16")
+    assert st == 0 and res.max_threads == 512 and res.vgprs + res.agprs > 200, (why, res.as_dict())
+    # the same row over 1024 threads stays with the 48-value instance
+    st, why, res = feas(B.make_cfg(8, 1024, 1, unroll=2, flags=lds | two | B.FLAG_NONTEMPORAL), 1024, 131072, "bf16")
+    assert st == 0 and res.max_threads == 1024 and res.vgprs + res.agprs <= 128
+    # 98304 elements over 512 threads: 24 chunks = 18 in registers + 6 in LDS: one pass where there was none
+    st, why, res = feas(B.make_cfg(8, 512, 1, unroll=2, flags=lds), 1024, 98304, "bf16")
+    assert st == 0 and res.max_threads == 512, why
+    st, why, _ = feas(B.make_cfg(8, 512, 1, unroll=2, flags=lds | two), 1024, 98304, "bf16")
+    assert st == B.ERR_INFEASIBLE_CFG and "nothing has to be read twice" in why
+    # a row the 48-value instance holds on the chip at 512 threads keeps that instance (two workgroups fit a CU)
+    st, why, res = feas(B.make_cfg(8, 512, 1, unroll=2, flags=lds), 1024, 49152, "bf16")
+    assert st == 0 and res.max_threads == 1024 and res.vgprs + res.agprs <= 128
+    # fp32: every 144-value instance spills, so the 48-value one stands in
+    st, why, res = feas(B.make_cfg(4, 512, 1, unroll=2, flags=lds | two), 512, 262144, "fp32")
+    assert st == 0 and res.max_threads == 1024, why

@@ -146,6 +146,14 @@ def test_long_row_forms_beyond_the_register_cache(oracle, dtype, M, N):
     picks = [None]
     for lst in by_form.values():
         picks += lst[:: max(1, len(lst) // 50)]
+    # the instances with the larger register cache (workgroups of at most 512 threads) are configurations like any other;
+    # make sure a spread of them is among the picks wherever the deriver offers them
+    big = [c for c in cfgs if c.threads_per_row * c.rows_per_wg <= 512 and c.flags & B.FLAG_LDS_CACHE
+           and B.addrms_cfg_feasible(c, M, N, dtype)[2].max_threads == 512]
+    picks += big[:: max(1, len(big) // 30)]
+    if dtype != "fp32" and N % 4 == 0 and N >= 98304:
+        assert big
+    print(f"   {len(big)} of them on the 144-value instances; {len(picks)} cfgs run", flush=True)
     for c in picks:
         y, res = case.run(c)
         assert compare(y, res, y_ref, res_ref, dtype, f"{wl.name} {c}")["n_diff"] == 0
