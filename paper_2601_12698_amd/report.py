@@ -105,19 +105,9 @@ def _row_cell(best, moved):
     return "-" if best is None else f"{moved / best[0] * 1e-3:.0f} ({best[1]} x {best[2]})"
 
 
-def graph_vs_eager_us(wl, cfg, chain=64, laps=20, nsets=8):
-    """Per-launch time of `chain` back-to-back launches (rotating over `nsets` buffer pairs):
-    issued one by one from the host, and replayed from a captured HIP graph."""
-    dev = torch.device("cuda")
-    d = W.generate(wl)
-    w = d["w"].to(dev)
-    xs = [d["x"].to(dev) for _ in range(nsets)]
-    rs = [d["r"].to(dev) for _ in range(nsets)]
-
-    def issue():
-        for i in range(chain):
-            B.addrms_run(xs[i % nsets], rs[i % nsets], w, wl.eps, wl.M, wl.N, wl.dtype, cfg)
-
+def _eager_and_graph_us(issue, chain, laps):
+    """Per-launch time of the `chain` launches that issue() makes: issued one by one from the host, and replayed
+    from a captured HIP graph."""
     def timed(fn):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         fn()
@@ -137,6 +127,35 @@ def graph_vs_eager_us(wl, cfg, chain=64, laps=20, nsets=8):
         issue()
     torch.cuda.synchronize()
     return eager, timed(g.replay)
+
+
+def graph_vs_eager_us(wl, cfg, chain=64, laps=20, nsets=8):
+    """Per-launch time of `chain` back-to-back launches (rotating over `nsets` buffer pairs):
+    issued one by one from the host, and replayed from a captured HIP graph."""
+    dev = torch.device("cuda")
+    d = W.generate(wl)
+    w = d["w"].to(dev)
+    xs = [d["x"].to(dev) for _ in range(nsets)]
+    rs = [d["r"].to(dev) for _ in range(nsets)]
+
+    def issue():
+        for i in range(chain):
+            B.addrms_run(xs[i % nsets], rs[i % nsets], w, wl.eps, wl.M, wl.N, wl.dtype, cfg)
+
+    return _eager_and_graph_us(issue, chain, laps)
+
+
+def launch_floor_us(chain=64, laps=20):
+    """What a launch costs when the kernel has next to nothing to do: the calibration copy on 16 bytes of each
+    stream (one workgroup, one active lane), chained and timed like the decode shapes."""
+    x = torch.zeros(8, dtype=torch.bfloat16, device="cuda")
+    r = torch.zeros(8, dtype=torch.bfloat16, device="cuda")
+
+    def issue():
+        for _ in range(chain):
+            B.addrms_stream_probe(x, r, 1, 8, "bf16")
+
+    return _eager_and_graph_us(issue, chain, laps)
 
 
 def main(argv=None) -> int:
@@ -285,6 +304,8 @@ def main(argv=None) -> int:
             cfg = B.addrms_table_lookup(wl.M, wl.N, wl.dtype) or B.addrms_default_cfg(wl.N, wl.dtype)
             eager, graph = graph_vs_eager_us(wl, cfg)
             print(f"| {wl.M} x {wl.N} | {cfg.as_tuple()} | {eager:.2f} | {graph:.2f} |", flush=True)
+        eager, graph = launch_floor_us()
+        print(f"| launch floor | (copy kernel on 16 bytes of each stream) | {eager:.2f} | {graph:.2f} |", flush=True)
     if a.audit:
         print("\nAudit of the efficiency rules (every cfg gated and timed, 3 + 15 launches):\n")
         print("| M x N | dtype | retained | best us | decile us | median us | rule | pruned | failed gate | best us | "
