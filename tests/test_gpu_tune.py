@@ -20,11 +20,13 @@ def clean_table():
 
 
 @pytest.mark.parametrize("M,N,dtype", [(4096, 4096, "bf16"), (8192, 1000, "fp16_res32"), (512, 14336, "fp32"),
-                                       (64, 8192, "bf16"), (64, 49152, "bf16")])
+                                       (64, 8192, "bf16"), (64, 49152, "bf16"), (16, 131072, "bf16")])
 def test_deriver_model_matches_device(M, N, dtype):
     """Registers, LDS, workgroup bound and resident workgroups per CU predicted by
     the host-side deriver equal what the HIP runtime reports for the loaded kernels."""
     cfgs, _ = B.addrms_enumerate_feasible(M, N, dtype)
+    if N == 131072:      # this row brings in the long-row instances compiled for at most 512 threads
+        assert any(B.addrms_cfg_feasible(c, M, N, dtype)[2].max_threads == 512 for c in cfgs[::5])
     for c in cfgs[::5]:
         st, _, model = B.addrms_cfg_feasible(c, M, N, dtype)
         dev = B.addrms_device_resources(c, M, N, dtype)
