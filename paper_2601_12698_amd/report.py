@@ -177,6 +177,9 @@ def main(argv=None) -> int:
     ap.add_argument("--row-scan", action="store_true",
                     help="time against the number of rows for N = 1000 and N = 1024 (fp16 x, fp32 residual): separates the fixed "
                          "cost of a launch from the per-row rate, and rows that are whole cache lines from rows that are not")
+    ap.add_argument("--width-scan", action="store_true",
+                    help="tuned rate against the row length at constant traffic (1.9 GB, bf16): what holding longer rows costs")
+    ap.add_argument("--only", action="store_true", help="skip the main table; print only the sections asked for")
     ap.add_argument("--audit", action="store_true",
                     help="time what the deriver's efficiency rules prune beside what they retain (three shapes)")
     a = ap.parse_args(argv)
@@ -184,11 +187,12 @@ def main(argv=None) -> int:
         print("needs a GPU", file=sys.stderr)
         return 2
     B.addrms_table_clear()
-    print("| workload | M x N | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tokens/s | copy GB/s | "
-          "row-holding copy GB/s (threads x workgroups per CU) | "
-          "tuned cfg (vec, threads/row, rows/wg, reduce, unroll, flags, cap, walk) | feasible | timed | search ms |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
-    for wl in shapes():
+    if not a.only:
+        print("| workload | M x N | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tokens/s | copy GB/s | "
+              "row-holding copy GB/s (threads x workgroups per CU) | "
+              "tuned cfg (vec, threads/row, rows/wg, reduce, unroll, flags, cap, walk) | feasible | timed | search ms |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    for wl in ([] if a.only else shapes()):
         nbytes = B.addrms_algorithmic_bytes(wl.M, wl.N, wl.dtype)
         t0 = time.perf_counter()
         cfg, rep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
@@ -274,6 +278,17 @@ def main(argv=None) -> int:
             print(f"| {M} x {N} | {dtype} | {rep.default_us:.1f} | {rep.best_us:.1f} | {rep.default_us / rep.best_us:.3f} | "
                   f"{gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | {moved / p * 1e-3:.0f} | {_row_cell(rowp, moved)} | {cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | "
                   f"{wall:.0f} |", flush=True)
+    if a.width_scan:
+        total, dt = 32768 * 7168, "bf16"
+        print("\nTuned rate against the row length at constant traffic (M x N = 32768 x 7168 elements, bf16):\n")
+        print("| M x N | default us | tuned us | % of 8 TB/s | tuned cfg |")
+        print("|---|---|---|---|---|")
+        for N in (512, 1024, 2048, 3584, 4096, 7168, 8192, 14336, 16384, 28672, 32768):
+            M = total // N
+            nbytes = B.addrms_algorithmic_bytes(M, N, dt)
+            cfg, rep = B.addrms_tune(M, N, dt, B.make_budget())
+            print(f"| {M} x {N} | {rep.default_us:.1f} | {rep.best_us:.1f} | "
+                  f"{nbytes / rep.best_us * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | {cfg.as_tuple()} |", flush=True)
     if a.row_scan:
         print("\nTime against the number of rows (fp16 x and weight, fp32 residual; tuned per shape): t = t0 + M * slope by "
               "least squares; t0 is what a launch costs before any row streams, bytes per row / slope the rate the rows "
