@@ -162,6 +162,8 @@ def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--exhaustive-prefill", action="store_true",
                     help="also run the exhaustive search on the prefill shape and report the guided search's regret")
+    ap.add_argument("--exhaustive-large", action="store_true",
+                    help="the same on the large prefill shape (33,000 cfgs at about 50 ms each: half an hour)")
     ap.add_argument("--table", default=None, help="save the specialised table here")
     ap.add_argument("--silumul", action="store_true",
                     help="also tune silu_and_mul (the second kernel behind the same tuner) on three shapes")
@@ -204,8 +206,9 @@ def main(argv=None) -> int:
               f"{rep.default_us / rep.best_us:.3f} | {gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | "
               f"{wl.M / rep.best_us * 1e6:.3g} | {(moved / p * 1e-3) if p else float('nan'):.0f} | {_row_cell(rowp, moved)} | "
               f"{cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
-    if a.exhaustive_prefill:
-        wl = W.PREFILL
+    for asked, wl, label in ((a.exhaustive_prefill, W.PREFILL, "prefill"), (a.exhaustive_large, W.LARGE_PREFILL, "large prefill")):
+        if not asked:
+            continue
         g, grep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
         e, erep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps, strategy=B.SEARCH_EXHAUSTIVE))
         tgs, tes = [], []
@@ -213,11 +216,11 @@ def main(argv=None) -> int:
             tgs.append(B.addrms_measure(g, wl.M, wl.N, wl.dtype))
             tes.append(B.addrms_measure(e, wl.M, wl.N, wl.dtype))
         tg, te = sorted(tgs)[2], sorted(tes)[2]
-        print(f"\nprefill: guided {g.as_tuple()} after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
+        print(f"\n{label}: guided {g.as_tuple()} after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
               f"exhaustive {e.as_tuple()} after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms.  "
               f"Confirmed inside their own searches (2 x (20 + 100) launches): {grep.best_us:.2f} us against {erep.best_us:.2f} us, "
               f"regret {grep.best_us / erep.best_us:.4f}; measured afterwards in alternation on newly allocated buffers "
-              f"(median of 5 each): {tg:.2f} us against {te:.2f} us, regret {tg / te:.4f}")
+              f"(median of 5 each): {tg:.2f} us against {te:.2f} us, regret {tg / te:.4f}", flush=True)
     if a.silumul:
         print("\nsilu_and_mul (out[i,j] = silu(x[i,j]) * x[i,d+j]), tuned vs default:\n")
         print("| workload | M x d | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
