@@ -41,9 +41,12 @@ constexpr int kSpanCptBase = 200;        // aligned-span form: cpt = 200 + chunk
 constexpr int kLdsCacheCptBase = 300;    // forms with the row cache continued in LDS: cpt = 300 + register-held chunks
 constexpr int kLdsCacheRegElems = 48;    // their values per thread kept in registers (a 1024-thread workgroup leaves each lane
                                          // 128 registers; 64 cached values spill)
-constexpr int kLdsCacheBigCptBase = 400; // the same body compiled for workgroups of at most 512 threads (each lane then has 256
-constexpr int kLdsCacheBigRegElems = 144;//   registers): 144 values per thread in registers; vec 4 and 8 only.  Taken where the
-constexpr int kLdsCacheBigMaxThreads = 512; // 48-value instance cannot keep the whole row on the chip at the launch shape asked for.
+// The same body compiled for workgroups of at most 512 threads, where each lane has 256 registers: 144 values per
+// thread stay in registers (vec 4 and 8 only; cpt = 400 + register-held chunks).  No knob selects it: check_cfg takes
+// it where the 48-value instance cannot keep the whole row on the chip at the launch shape asked for.
+constexpr int kLdsCacheBigCptBase = 400;
+constexpr int kLdsCacheBigRegElems = 144;
+constexpr int kLdsCacheBigMaxThreads = 512;
 constexpr int kLineBytes = 128;          // cache line of the L2 / memory side
 constexpr int64_t kMaxTwoPassElemsPerWg = 1ll << 28;   // two-pass form: rows_per_wg * N elements, 32-bit byte offsets
 
