@@ -177,8 +177,9 @@ def main(argv=None) -> int:
     ap.add_argument("--graph-decode", action="store_true",
                     help="decode shapes: per-launch time of a chain of launches issued eagerly vs replayed from a HIP graph")
     ap.add_argument("--row-scan", action="store_true",
-                    help="time against the number of rows for N = 1000 and N = 1024 (fp16 x, fp32 residual): separates the fixed "
-                         "cost of a launch from the per-row rate, and rows that are whole cache lines from rows that are not")
+                    help="time against the number of rows for N = 1000, 1024 and 5120 (fp16 x, fp32 residual) and N = 4096 (bf16): "
+                         "separates the fixed cost of a launch from the per-row rate, and rows that are whole cache lines from "
+                         "rows that are not")
     ap.add_argument("--width-scan", action="store_true",
                     help="tuned rate against the row length at constant traffic (1.9 GB, bf16): what holding longer rows costs")
     ap.add_argument("--only", action="store_true", help="skip the main table; print only the sections asked for")
@@ -293,26 +294,27 @@ def main(argv=None) -> int:
             print(f"| {M} x {N} | {rep.default_us:.1f} | {rep.best_us:.1f} | "
                   f"{nbytes / rep.best_us * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | {cfg.as_tuple()} |", flush=True)
     if a.row_scan:
-        print("\nTime against the number of rows (fp16 x and weight, fp32 residual; tuned per shape): t = t0 + M * slope by "
-              "least squares; t0 is what a launch costs before any row streams, bytes per row / slope the rate the rows "
-              "stream at:\n")
-        print("| N | M | tuned us | GB/s | % of 8 TB/s | tuned cfg |")
-        print("|---|---|---|---|---|---|")
-        for N in (1000, 1024):
+        print("\nTime against the number of rows (tuned per shape): t = t0 + M * slope by least squares; t0 is what a launch "
+              "costs before any row streams, bytes per row / slope the rate the rows stream at:\n")
+        print("| N | storage | M | tuned us | GB/s | % of 8 TB/s | tuned cfg |")
+        print("|---|---|---|---|---|---|---|")
+        for N, dt, ms in ((1000, "fp16_res32", (8192, 16384, 32768, 65536)), (1024, "fp16_res32", (8192, 16384, 32768, 65536)),
+                          (4096, "bf16", (4096, 8192, 16384, 32768)), (5120, "fp16_res32", (8192, 16384, 32768, 65536))):
             pts = []
-            for M in (8192, 16384, 32768, 65536):
-                nbytes = B.addrms_algorithmic_bytes(M, N, "fp16_res32")
-                cfg, rep = B.addrms_tune(M, N, "fp16_res32", B.make_budget())
+            for M in ms:
+                nbytes = B.addrms_algorithmic_bytes(M, N, dt)
+                cfg, rep = B.addrms_tune(M, N, dt, B.make_budget())
                 pts.append((M, rep.best_us))
-                print(f"| {N} | {M} | {rep.best_us:.2f} | {nbytes / rep.best_us * 1e-3:.0f} | "
+                print(f"| {N} | {dt} | {M} | {rep.best_us:.2f} | {nbytes / rep.best_us * 1e-3:.0f} | "
                       f"{nbytes / rep.best_us * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | {cfg.as_tuple()} |", flush=True)
             n = len(pts)
             sx, sy = sum(p[0] for p in pts), sum(p[1] for p in pts)
             sxx, sxy = sum(p[0] * p[0] for p in pts), sum(p[0] * p[1] for p in pts)
             slope = (n * sxy - sx * sy) / (n * sxx - sx * sx)
             t0 = (sy - slope * sx) / n
-            print(f"| {N} | fit | t0 = {t0:.2f} us | {12 * N / slope * 1e-3:.0f} GB/s asymptotic | "
-                  f"{12 * N / slope * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | slope {slope * 1e3:.3f} ns per row |", flush=True)
+            row_bytes = 2 * N * (W.x_bytes(dt) + W.r_bytes(dt))
+            print(f"| {N} | {dt} | fit | t0 = {t0:.2f} us | {row_bytes / slope * 1e-3:.0f} GB/s asymptotic | "
+                  f"{row_bytes / slope * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | slope {slope * 1e3:.3f} ns per row |", flush=True)
     if a.graph_decode:
         print("\nDecode shapes, chain of 64 launches, tuned cfg: microseconds per launch issued eagerly vs from a HIP graph:\n")
         print("| M x N | cfg | eager us | graph us |")
