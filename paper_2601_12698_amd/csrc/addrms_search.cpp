@@ -97,6 +97,7 @@ struct Searcher {
                 warmup, reps, c.res.chunks_per_thread, c.res.vgprs, c.res.agprs, c.res.lds_bytes, c.res.waves_per_wg,
                 c.res.wgs_per_cu, c.res.waves_per_simd, (long long)n_workgroups(c.cfg, M, c.res.wgs_per_cu),
                 (long long)n_measured, elapsed_ms());
+        fflush(log);    // a search that is killed loses at most the line being written
     }
 
     // Gate + screening measurement of candidate i.  Returns true if it now has a time.
@@ -395,6 +396,10 @@ void load_resume(const char* path, int op, int64_t M, int64_t N, int dtype,
             continue;
         }
         if (!active || strcmp(ev, "eval")) continue;
+        {   // a line cut short (the writer was killed) says nothing about its candidate
+            const size_t len = strlen(line);
+            if (len < 2 || line[len - 1] != '\n' || line[len - 2] != '}') continue;
+        }
         char phase[24] = "";
         if (!json_str(line, "phase", phase, sizeof phase) || !strcmp(phase, "confirm")) continue;
         const char* p = strstr(line, "\"cfg\":{");

@@ -164,6 +164,10 @@ def main(argv=None) -> int:
                     help="also run the exhaustive search on the prefill shape and report the guided search's regret")
     ap.add_argument("--exhaustive-large", action="store_true",
                     help="the same on the large prefill shape (33,000 cfgs at about 50 ms each: half an hour)")
+    ap.add_argument("--exhaustive-log", default=None,
+                    help="log of the exhaustive searches; a later run with the same file takes what it holds and measures the rest")
+    ap.add_argument("--exhaustive-wall-ms", type=float, default=0.0,
+                    help="time limit of one exhaustive search (0: none); with a log, several limited runs add up to a whole one")
     ap.add_argument("--table", default=None, help="save the specialised table here")
     ap.add_argument("--silumul", action="store_true",
                     help="also tune silu_and_mul (the second kernel behind the same tuner) on three shapes")
@@ -211,14 +215,21 @@ def main(argv=None) -> int:
         if not asked:
             continue
         g, grep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
-        e, erep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps, strategy=B.SEARCH_EXHAUSTIVE))
+        e, erep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps, strategy=B.SEARCH_EXHAUSTIVE,
+                                                                    log_path=a.exhaustive_log, max_wall_ms=a.exhaustive_wall_ms))
+        if erep.n_measured + erep.n_failed + erep.n_resumed < erep.n_feasible:
+            print(f"\n{label}: the exhaustive search stopped at its time limit after {erep.n_measured + erep.n_resumed} of "
+                  f"{erep.n_feasible} cfgs ({erep.n_resumed} of them taken from the log); run again with the same log to go on",
+                  flush=True)
+            continue
         tgs, tes = [], []
         for _ in range(5):                      # alternating, so that drift after the long search hits both alike
             tgs.append(B.addrms_measure(g, wl.M, wl.N, wl.dtype))
             tes.append(B.addrms_measure(e, wl.M, wl.N, wl.dtype))
         tg, te = sorted(tgs)[2], sorted(tes)[2]
         print(f"\n{label}: guided {g.as_tuple()} after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
-              f"exhaustive {e.as_tuple()} after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms.  "
+              f"exhaustive {e.as_tuple()} after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms"
+              f"{f' (and {erep.n_resumed} taken from the log of earlier runs)' if erep.n_resumed else ''}.  "
               f"Confirmed inside their own searches (2 x (20 + 100) launches): {grep.best_us:.2f} us against {erep.best_us:.2f} us, "
               f"regret {grep.best_us / erep.best_us:.4f}; measured afterwards in alternation on newly allocated buffers "
               f"(median of 5 each): {tg:.2f} us against {te:.2f} us, regret {tg / te:.4f}", flush=True)

@@ -247,6 +247,19 @@ def test_second_search_resumes_from_the_log(tmp_path):
     eighth, rep8 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=part), rec8.measure, rec8.validate)
     assert 0 < rep8.n_resumed < rep2.n_resumed and rep8.n_measured > 0
     assert eighth.as_tuple() == first.as_tuple()
+    # a log whose last line was cut in the middle (the writer was killed): that candidate counts as not yet seen,
+    # not as one that failed the gate
+    cut = str(tmp_path / "cut.jsonl")
+    keep = lines[:first_end // 2]
+    while not ('"event":"eval"' in keep[-1] and '"pass":true' in keep[-1]):
+        keep.pop()
+    with open(cut, "w") as f:
+        f.write("\n".join(keep[:-1]) + "\n" + keep[-1][:keep[-1].index('"pass"')])
+    rec9 = Recorder(lambda c: cost(c, 0.02), fail_validate=bad_output)
+    ninth, rep9 = B.addrms_tune_with_backend(M, N, DT, B.make_budget(log_path=cut), rec9.measure, rec9.validate)
+    n_evals = sum('"event":"eval"' in l for l in keep)
+    assert rep9.n_resumed == n_evals - 1                          # all complete lines, not the cut one
+    assert ninth.as_tuple() == first.as_tuple()
 
 
 def test_default_wins_when_it_confirms_fastest():
