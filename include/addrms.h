@@ -195,7 +195,10 @@ typedef struct addrms_budget {
                                 format made on this architecture by this library version,
                                 candidates it screened are not measured again (their logged
                                 times and gate verdicts stand); only the Top-K confirmation
-                                is repeated.  The search is appended to the file.            */
+                                is repeated.  The search is appended to the file, one line
+                                per candidate, flushed as written; a last line that a killed
+                                search left incomplete is ignored, so searches cut short by
+                                a signal or by max_wall_ms add up to a whole one.            */
     int32_t family_mask;     /* ADDRMS_FAMILY_* bits the search may use; 0 = all of them   */
     int32_t no_resume;       /* nonzero: ignore what log_path already holds, measure anew   */
 } addrms_budget;
