@@ -74,23 +74,28 @@ def measured_traffic(workload_name, cfg=None):
     return found
 
 
-def recorded_regret():
-    """Regret of the guided search against the exhaustive one on prefill 4096 x 4096, as the last run of
-    `python -m paper_2601_12698_amd.report --exhaustive-prefill` recorded it (the exhaustive search takes two
-    minutes of GPU time, too long to repeat in every bench run)."""
+def recorded_regret(label="prefill"):
+    """Regret of the guided search against the exhaustive one on prefill 4096 x 4096 (`label` "prefill") or on the
+    headline shape ("large prefill"), as the last run of `python -m paper_2601_12698_amd.report --exhaustive-prefill`
+    (`--exhaustive-large`) recorded it: the exhaustive searches take two minutes and half an hour of GPU time, too
+    long to repeat in every bench run."""
     import re
     path = os.path.join(ROOT, "profiles", "addrms_tuned_vs_default_all_configs.md")
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("prefill: guided"):
+                if line.startswith(label + ": guided"):
                     r = re.findall(r"regret ([0-9.]+)", line)
                     n = re.findall(r"after (\d+) cfgs / (\d+) ms", line)
                     if len(r) == 2 and len(n) == 2:
-                        return {"confirmed_in_search": float(r[0]), "re_measured_in_alternation": float(r[1]),
-                                "guided_cfgs": int(n[0][0]), "guided_ms": int(n[0][1]),
-                                "exhaustive_cfgs": int(n[1][0]), "exhaustive_ms": int(n[1][1]),
-                                "source": "profiles/" + os.path.basename(path)}
+                        out = {"confirmed_in_search": float(r[0]), "re_measured_in_alternation": float(r[1]),
+                               "guided_cfgs": int(n[0][0]), "guided_ms": int(n[0][1]),
+                               "exhaustive_cfgs": int(n[1][0]), "exhaustive_ms": int(n[1][1]),
+                               "source": "profiles/" + os.path.basename(path)}
+                        earlier = re.search(r"and (\d+) taken from the log of earlier runs", line)
+                        if earlier:
+                            out["exhaustive_cfgs_from_the_log_of_earlier_runs"] = int(earlier.group(1))
+                        return out
     except OSError:
         pass
     return None
@@ -622,6 +627,7 @@ def main():
                      "kernel_us": round(kernel_us, 3), "algorithmic_bytes": nbytes},
     }
     out["tune"]["regret_vs_exhaustive_on_prefill_4096x4096"] = recorded_regret()
+    out["tune"]["regret_vs_exhaustive_on_large_prefill_32768x7168"] = recorded_regret("large prefill")
     headline_entry = None
     if retest is not None:
         out["tune"]["retest_on_workload_buffers"] = retest
