@@ -89,7 +89,7 @@ def probes_us(wl, reps=50):
             chunks = -(-pieces // t)
             if chunks > 16 or (chunks - 1) * t >= pieces:
                 continue
-            for wgs in (1, 2, 3, 4, 6, 8):
+            for wgs in (1, 2, 3, 4, 6, 8, 12, 16):
                 if wgs * t > 2048:
                     continue
                 us = timed(lambda x, r: B.addrms_row_probe(x, r, wl.M, wl.N, wl.dtype, t, wgs), 3, max(6, reps // 4))
@@ -300,14 +300,18 @@ def main(argv=None) -> int:
     if a.width_scan:
         total, dt = 32768 * 7168, "bf16"
         print("\nTuned rate against the row length at constant traffic (M x N = 32768 x 7168 elements, bf16):\n")
-        print("| M x N | default us | tuned us | % of 8 TB/s | tuned cfg |")
-        print("|---|---|---|---|---|")
+        print("| M x N | default us | tuned us | % of 8 TB/s | copy % | row-holding copy % (threads x workgroups per CU) | tuned cfg |")
+        print("|---|---|---|---|---|---|---|")
         for N in (512, 1024, 2048, 3584, 4096, 7168, 8192, 14336, 16384, 28672, 32768):
             M = total // N
             nbytes = B.addrms_algorithmic_bytes(M, N, dt)
             cfg, rep = B.addrms_tune(M, N, dt, B.make_budget())
+            p, rowp = probes_us(_Shape(M, N, dt), reps=24)
+            moved = 2 * M * N * (W.x_bytes(dt) + W.r_bytes(dt))
+            row_cell = "-" if rowp is None else f"{moved / rowp[0] * 1e-3 / HBM_PEAK_GBPS * 100:.1f} ({rowp[1]} x {rowp[2]})"
             print(f"| {M} x {N} | {rep.default_us:.1f} | {rep.best_us:.1f} | "
-                  f"{nbytes / rep.best_us * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | {cfg.as_tuple()} |", flush=True)
+                  f"{nbytes / rep.best_us * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | {moved / p * 1e-3 / HBM_PEAK_GBPS * 100:.1f} | "
+                  f"{row_cell} | {cfg.as_tuple()} |", flush=True)
     if a.row_scan:
         print("\nTime against the number of rows (tuned per shape): t = t0 + M * slope by least squares; t0 is what a launch "
               "costs before any row streams, bytes per row / slope the rate the rows stream at:\n")
