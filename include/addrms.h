@@ -64,7 +64,9 @@ enum { ADDRMS_FLAG_XCD_CONTIG = 1,    /* workgroups of one XCD cover a contiguou
                                          where no single-pass configuration covers N            */
        ADDRMS_FLAG_LDS_CACHE = 16,    /* rows somewhat too long for the registers: still one pass,
                                          the row cache continues in the workgroup's LDS (up to
-                                         160 KB per CU, so about 73 K elements per row).  Together
+                                         160 KB per CU: about 90 K elements per row at 1024 threads,
+                                         about 110 K at 512 threads with 16-bit x, where a thread
+                                         keeps 144 values in registers instead of 48).  Together
                                          with ADDRMS_FLAG_TWO_PASS: the hybrid form for rows beyond
                                          that -- registers and LDS hold what they can, and only the
                                          rest of each row is read twice                           */
