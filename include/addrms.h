@@ -109,7 +109,8 @@ typedef struct addrms_cfg {
  *            (1024 threads x 32 cached values, at most 16 accesses per thread:
  *            even N up to 32768, odd N up to 16384); longer rows continue the
  *            cache in LDS (ADDRMS_FLAG_LDS_CACHE) while it fits and otherwise, up to
- *            2^28 elements, run in the two-pass form (ADDRMS_FLAG_TWO_PASS); the default
+ *            2^28 elements, read what fits neither registers nor LDS twice (both flags)
+ *            or the whole row twice (ADDRMS_FLAG_TWO_PASS); the default
  *            configuration selects these by itself; beyond that UNSUPPORTED_SHAPE
  *   dtype    addrms_dtype
  *   cfg      host; NULL = look (M, N, dtype) up in the specialised table
@@ -186,7 +187,8 @@ typedef struct addrms_budget {
     int32_t strategy;        /* ADDRMS_SEARCH_*                                            */
     int32_t top_k;           /* candidates re-tested at the end; 0 = 5 (max 8)             */
     int32_t warmup;          /* confirmation protocol; 0 = 20 (Section 4, "Performance     */
-    int32_t reps;            /*   Measurement": 20 warm-up runs, mean of 100); 0 = 100     */
+    int32_t reps;            /*   Measurement": 20 warm-up runs, mean of 100); 0 = 100.
+                                The exhaustive strategy times every candidate with it.     */
     int32_t coarse_warmup;   /* screening protocol of the guided search; 0 = 3             */
     int32_t coarse_reps;     /* 0 = 15                                                     */
     int32_t skip_validation; /* nonzero: do not gate candidates on correctness (tests only)*/
