@@ -93,3 +93,17 @@ def test_probe_list_of_the_counters_command():
         S.parse_probes("columns:3")
     spec = S._spec([], 8, 4096, "bf16", 1e-6, S.parse_probes("rows:448,3"))
     assert spec["probes"] == [{"kind": "rows", "threads": 448, "wgs": 3}] and spec["cfgs"] == []
+
+
+def test_report_and_bench_say_that_they_need_a_gpu(capsys):
+    """Neither measures anything without a device, and neither pretends to: no CPU fallback."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    from paper_2601_12698_amd import report
+    assert report.main(["--only", "--width-scan", "--exhaustive-large", "--exhaustive-log", "x.jsonl"]) == 2
+    assert "needs a GPU" in capsys.readouterr().err
+    import bench
+    assert bench.recorded_regret("large prefill")["exhaustive_cfgs"] > 0      # parses the committed profile
+    assert bench.recorded_regret()["guided_cfgs"] > 0
+    assert bench.measured_traffic("large_prefill_32768x7168_bf16_outliers")["over_algorithmic"] < 1.01
