@@ -236,7 +236,8 @@ typedef struct addrms_tune_report {
  *   budget  host, may be NULL (all defaults)
  *   out_cfg host, required;  report host, may be NULL
  * With the environment variable ADDRMS_VERBOSE set (1: one line when a search starts and
- * one when it ends; 2: also one per candidate) every search reports on stderr.
+ * one when it ends; 2: also one per candidate) every search reports on stderr, and the audit every
+ * 500 candidates.
  */
 int addrms_tune(int64_t M, int64_t N, int dtype, const addrms_budget* budget,
                 addrms_cfg* out_cfg, addrms_tune_report* report);

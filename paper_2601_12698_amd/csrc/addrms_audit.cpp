@@ -54,12 +54,17 @@ int run_audit_rules(int64_t M, int64_t N, int dtype, const addrms_budget* budget
     if (cls[0].empty()) return fail(ADDRMS_ERR_UNSUPPORTED_SHAPE, "feasible region is empty");
 
     bool out_of_time = false;
+    const int verbose = verbosity();
+    int64_t n_done = 0;
     auto run_class = [&](const std::vector<addrms_cfg>& v, bool sample, std::vector<double>* times, addrms_cfg* best_cfg,
                          int32_t* n_failed) {
         const size_t stride = (sample && per_class > 0) ? std::max<size_t>(1, (v.size() + per_class - 1) / per_class) : 1;
         double best = 0.0;
         for (size_t i = 0; i < v.size(); i += stride) {
             if (wall_cap > 0.0 && elapsed_ms() >= wall_cap) { out_of_time = true; break; }
+            if (verbose && ++n_done % 500 == 0)
+                fprintf(stderr, "[addrms] audit of %lld x %lld %s: %lld candidates after %.0f ms\n", (long long)M, (long long)N,
+                        dtype_name(dtype), (long long)n_done, elapsed_ms());
             if (gate && be.validate(be.user, &v[i]) != 0) { ++*n_failed; continue; }
             double us = 0.0;
             if (be.measure(be.user, &v[i], warm, reps, &us) != 0 || !(us > 0.0)) { ++*n_failed; continue; }

@@ -142,6 +142,9 @@ int64_t export_enumerate_feasible(int op, int64_t M, int64_t N, int dtype, addrm
 int export_table_lookup(int op, int64_t M, int64_t N, int dtype, addrms_cfg* out);
 int64_t export_algorithmic_bytes(int op, int64_t M, int64_t N, int dtype);
 
+// 0, 1 or 2: what the environment variable ADDRMS_VERBOSE asks the searches and the audit to report on stderr.
+int verbosity();
+
 // ---- error text ------------------------------------------------------------
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();

@@ -328,13 +328,6 @@ struct Searcher {
     }
 };
 
-// Progress on stderr when the environment variable ADDRMS_VERBOSE is set to something other than "0": one line
-// when a search starts and one when it ends (2: also one per candidate).
-int verbosity()
-{
-    static const int v = [] { const char* e = getenv("ADDRMS_VERBOSE"); return (e && *e && strcmp(e, "0") != 0) ? atoi(e) > 1 ? 2 : 1 : 0; }();
-    return v;
-}
 
 // ---- resume: what an earlier run already measured ---------------------------------------
 // The log is a list of searches, each opened by a "begin" line that names architecture, library
@@ -427,6 +420,14 @@ void fill_defaults(addrms_budget* b)
 }
 
 }  // namespace
+
+// Progress on stderr when the environment variable ADDRMS_VERBOSE is set to something other than "0": one line
+// when a search starts and one when it ends (2: also one per candidate); the audit reports every 500 candidates.
+int verbosity()
+{
+    static const int v = [] { const char* e = getenv("ADDRMS_VERBOSE"); return (e && *e && strcmp(e, "0") != 0) ? atoi(e) > 1 ? 2 : 1 : 0; }();
+    return v;
+}
 
 int run_search(int64_t M, int64_t N, int dtype, const addrms_budget* budget, const addrms_backend& be,
                addrms_cfg* out_cfg, addrms_tune_report* report, int op)

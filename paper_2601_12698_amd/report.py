@@ -187,6 +187,8 @@ def main(argv=None) -> int:
     ap.add_argument("--width-scan", action="store_true",
                     help="tuned rate against the row length at constant traffic (1.9 GB, bf16): what holding longer rows costs")
     ap.add_argument("--only", action="store_true", help="skip the main table; print only the sections asked for")
+    ap.add_argument("--audit-large", action="store_true",
+                    help="the audit on the large prefill shape instead (several minutes)")
     ap.add_argument("--audit", action="store_true",
                     help="time what the deriver's efficiency rules prune beside what they retain (three shapes)")
     a = ap.parse_args(argv)
@@ -345,13 +347,16 @@ def main(argv=None) -> int:
             print(f"| {wl.M} x {wl.N} | {cfg.as_tuple()} | {eager:.2f} | {graph:.2f} |", flush=True)
         eager, graph = launch_floor_us()
         print(f"| launch floor | (copy kernel on 16 bytes of each stream) | {eager:.2f} | {graph:.2f} |", flush=True)
-    if a.audit:
+    if a.audit or a.audit_large:
         print("\nAudit of the efficiency rules (every cfg gated and timed, 3 + 15 launches):\n")
         print("| M x N | dtype | retained | best us | decile us | median us | rule | pruned | failed gate | best us | "
               "median us | in top decile | beating best | s |")
         print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
-        for M, N, dtype in ((2048, 1000, "fp16_res32"), (4096, 4096, "bf16"), (1024, 11008, "fp32")):
-            rep = B.addrms_audit_rules(M, N, dtype, B.make_budget())
+        shapes_audited = [(2048, 1000, "fp16_res32", 0), (4096, 4096, "bf16", 0), (1024, 11008, "fp32", 0)]
+        if a.audit_large:       # the retained region in full (33,000 cfgs), 300 sampled cfgs of each pruned class
+            shapes_audited = [(W.LARGE_PREFILL.M, W.LARGE_PREFILL.N, W.LARGE_PREFILL.dtype, 300)]
+        for M, N, dtype, cap in shapes_audited:
+            rep = B.addrms_audit_rules(M, N, dtype, B.make_budget(max_candidates=cap))
             for r in rep.rules:
                 if r.n_pruned:
                     print(f"| {M} x {N} | {dtype} | {rep.n_retained} | {rep.retained_best_us:.2f} | "
