@@ -628,6 +628,7 @@ def main():
     }
     out["tune"]["regret_vs_exhaustive_on_prefill_4096x4096"] = recorded_regret()
     out["tune"]["regret_vs_exhaustive_on_large_prefill_32768x7168"] = recorded_regret("large prefill")
+    out["tune"]["regret_vs_exhaustive_on_odd_widths_8192xN"] = {str(n): recorded_regret(f"odd width N={n}") for n in W.ODD_WIDTH_N}
     headline_entry = None
     if retest is not None:
         out["tune"]["retest_on_workload_buffers"] = retest

@@ -164,6 +164,8 @@ def main(argv=None) -> int:
                     help="also run the exhaustive search on the prefill shape and report the guided search's regret")
     ap.add_argument("--exhaustive-large", action="store_true",
                     help="the same on the large prefill shape (33,000 cfgs at about 50 ms each: half an hour)")
+    ap.add_argument("--exhaustive-odd", action="store_true",
+                    help="the same on the three odd-width mixed-precision shapes (a quarter of an hour)")
     ap.add_argument("--exhaustive-log", default=None,
                     help="log of the exhaustive searches; a later run with the same file takes what it holds and measures the rest")
     ap.add_argument("--exhaustive-wall-ms", type=float, default=0.0,
@@ -213,7 +215,9 @@ def main(argv=None) -> int:
               f"{rep.default_us / rep.best_us:.3f} | {gbps:.0f} | {100 * gbps / HBM_PEAK_GBPS:.1f} | "
               f"{wl.M / rep.best_us * 1e6:.3g} | {(moved / p * 1e-3) if p else float('nan'):.0f} | {_row_cell(rowp, moved)} | "
               f"{cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
-    for asked, wl, label in ((a.exhaustive_prefill, W.PREFILL, "prefill"), (a.exhaustive_large, W.LARGE_PREFILL, "large prefill")):
+    regret_shapes = [(a.exhaustive_prefill, W.PREFILL, "prefill"), (a.exhaustive_large, W.LARGE_PREFILL, "large prefill")]
+    regret_shapes += [(a.exhaustive_odd, W.ODD_WIDTH.with_cols(n), f"odd width N={n}") for n in W.ODD_WIDTH_N]
+    for asked, wl, label in regret_shapes:
         if not asked:
             continue
         g, grep = B.addrms_tune(wl.M, wl.N, wl.dtype, B.make_budget(eps=wl.eps))
