@@ -166,6 +166,8 @@ def main(argv=None) -> int:
                     help="the same on the large prefill shape (33,000 cfgs at about 50 ms each: half an hour)")
     ap.add_argument("--exhaustive-odd", action="store_true",
                     help="the same on the three odd-width mixed-precision shapes (a quarter of an hour)")
+    ap.add_argument("--exhaustive-others", action="store_true",
+                    help="the same for silu_and_mul (4096 x 11008) and merge_attn_states (768 x 32 x 256), bf16")
     ap.add_argument("--exhaustive-log", default=None,
                     help="log of the exhaustive searches; a later run with the same file takes what it holds and measures the rest")
     ap.add_argument("--exhaustive-wall-ms", type=float, default=0.0,
@@ -239,6 +241,23 @@ def main(argv=None) -> int:
               f"Confirmed inside their own searches (2 x (20 + 100) launches): {grep.best_us:.2f} us against {erep.best_us:.2f} us, "
               f"regret {grep.best_us / erep.best_us:.4f}; measured afterwards in alternation on newly allocated buffers "
               f"(median of 5 each): {tg:.2f} us against {te:.2f} us, regret {tg / te:.4f}", flush=True)
+    if a.exhaustive_others:
+        # the two further operators: the same search code, so the same question
+        for label, tune, measure, dims, dt in (
+                ("silu_and_mul 4096 x 11008", B.silumul_tune, B.silumul_measure, (W.SILU_PREFILL.M, W.SILU_PREFILL.d), W.SILU_PREFILL.dtype),
+                ("merge_attn_states 768 x 32 x 256", B.mergestates_tune, B.mergestates_measure, (768 * 32, 256), "bf16")):
+            g, grep = tune(*dims, dt, B.make_budget())
+            e, erep = tune(*dims, dt, B.make_budget(strategy=B.SEARCH_EXHAUSTIVE))
+            tgs, tes = [], []
+            for _ in range(5):
+                tgs.append(measure(g, *dims, dt))
+                tes.append(measure(e, *dims, dt))
+            tg, te = sorted(tgs)[2], sorted(tes)[2]
+            print(f"\n{label} bf16: guided {g.as_tuple()} after {grep.n_measured} cfgs / {grep.wall_ms:.0f} ms; "
+                  f"exhaustive {e.as_tuple()} after {erep.n_measured} cfgs / {erep.wall_ms:.0f} ms.  Confirmed inside their own "
+                  f"searches: {grep.best_us:.2f} us against {erep.best_us:.2f} us, regret {grep.best_us / erep.best_us:.4f}; "
+                  f"measured afterwards in alternation (median of 5 each): {tg:.2f} us against {te:.2f} us, regret "
+                  f"{tg / te:.4f}", flush=True)
     if a.silumul:
         print("\nsilu_and_mul (out[i,j] = silu(x[i,j]) * x[i,d+j]), tuned vs default:\n")
         print("| workload | M x d | default us | tuned us | speedup | tuned GB/s | % of 8 TB/s | tuned cfg | feasible | timed | search ms |")
