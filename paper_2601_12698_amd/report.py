@@ -166,6 +166,8 @@ def main(argv=None) -> int:
                     help="the same on the large prefill shape (33,000 cfgs at about 50 ms each: half an hour)")
     ap.add_argument("--exhaustive-odd", action="store_true",
                     help="the same on the three odd-width mixed-precision shapes (a quarter of an hour)")
+    ap.add_argument("--exhaustive-decode", action="store_true",
+                    help="the same on the nine decode shapes (launch-bound: their times move by a few per cent by themselves)")
     ap.add_argument("--exhaustive-others", action="store_true",
                     help="the same for silu_and_mul (4096 x 11008) and merge_attn_states (768 x 32 x 256), bf16")
     ap.add_argument("--exhaustive-log", default=None,
@@ -219,6 +221,7 @@ def main(argv=None) -> int:
               f"{cfg.as_tuple()} | {rep.n_feasible} | {rep.n_measured} | {wall:.0f} |", flush=True)
     regret_shapes = [(a.exhaustive_prefill, W.PREFILL, "prefill"), (a.exhaustive_large, W.LARGE_PREFILL, "large prefill")]
     regret_shapes += [(a.exhaustive_odd, W.ODD_WIDTH.with_cols(n), f"odd width N={n}") for n in W.ODD_WIDTH_N]
+    regret_shapes += [(a.exhaustive_decode, W.DECODE.with_rows(m), f"decode M={m}") for m in W.DECODE_M]
     for asked, wl, label in regret_shapes:
         if not asked:
             continue
